@@ -1,0 +1,634 @@
+/*
+ * CPU oracle for block-selective mixed-precision attention (ThriftAttention).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is a plain, slow, obviously-correct
+ * restatement of what the method computes, written from the paper, in fp64.
+ * It shares no code, header, table or helper with the HIP library; only the
+ * tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+ *
+ * What follows the paper and where:
+ *   block means, block-pair scores, TopK ........ Sec. 3.2 "Block-importance scoring",
+ *                                                 Alg. 1 steps 3 and 5
+ *   causal restriction of the selection ......... Sec. 3.2, last paragraph
+ *   budget -> k (global-k form) ................. App. B "ThriftAttention settings"
+ *   FP4 block-scaled quantiser .................. Sec. 3.2 "FP4 quantisation", Alg. 1 step 2,
+ *                                                 re-read for MXFP4 (E2M1 elements, one E8M0
+ *                                                 scale per 32 elements, OCP Microscaling rule)
+ *   two score paths, online softmax, P
+ *   quantisation, merge, final normalisation .... Sec. 3.2 "Mixed-precision attention
+ *                                                 computation", Alg. 1 steps 4-23
+ *   exact attention (error reference) ........... Sec. 3.1, Eq. (1)
+ *   first-order error bound ..................... Sec. 3.1, Eq. (4)
+ *
+ * Readings of points the paper leaves open (all listed again in the design notes):
+ *   - scales are E8M0 per 32 elements instead of E4M3 per 16, so the first-level
+ *     P scale s1 = rowmax(P)/(448*6) of Alg. 1 step 19 is identically 1 here;
+ *   - Q and K are grouped along the head dimension, V along the token axis
+ *     (the contraction axis of P.V);
+ *   - the row sum l uses the unquantised P in both branches (Alg. 1 steps 12, 17);
+ *   - on the 16-bit path P is rounded to the input dtype before P.V (that is the
+ *     operand type a 16-bit matrix unit consumes);
+ *   - ties in TopK go to the smaller block index.
+ *
+ * Parity pins live in tests/test_oracle_*.py.  Function without an external pin:
+ * oracle_attn_thrift at real shapes with P quantisation on ("parity unpinned"
+ * beyond the invariants: budget 100% == 16-bit attention, budget 0% == attention
+ * on dequantised tensors when P quantisation is disabled, branch-swap identity).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_F16 0
+#define ORACLE_BF16 1
+
+/* ------------------------------------------------------------------ */
+/* 16-bit float decoding / rounding                                    */
+/* ------------------------------------------------------------------ */
+
+static double half_bits_to_double(uint16_t h) {
+  int sign = (h >> 15) & 1;
+  int ex = (h >> 10) & 31;
+  int man = h & 1023;
+  double v;
+  if (ex == 0) v = ldexp((double)man, -24);            /* subnormal: man * 2^-24 */
+  else if (ex == 31) v = man ? NAN : INFINITY;
+  else v = ldexp((double)(man + 1024), ex - 25);      /* (1 + man/1024) * 2^(ex-15) */
+  return sign ? -v : v;
+}
+
+static double bf16_bits_to_double(uint16_t b) {
+  uint32_t w = (uint32_t)b << 16;
+  float f;
+  memcpy(&f, &w, 4);
+  return (double)f;
+}
+
+static double bits_to_double(uint16_t u, int dtype) {
+  return dtype == ORACLE_F16 ? half_bits_to_double(u) : bf16_bits_to_double(u);
+}
+
+/* Round a double to the nearest value with `mant` explicit mantissa bits and minimum normal
+ * exponent `emin` (subnormals below it), ties to even; no overflow handling beyond returning
+ * infinity.  fp16: mant 10, emin -14, emax 15.  bf16: mant 7, emin -126, emax 127. */
+static double round_to_format(double x, int mant, int emin, int emax) {
+  if (x == 0.0 || isnan(x) || isinf(x)) return x;
+  int ex;
+  double a = fabs(x);
+  frexp(a, &ex);               /* a = f * 2^ex, f in [0.5,1)  ->  floor(log2 a) = ex-1 */
+  int e = ex - 1;
+  if (e < emin) e = emin;      /* subnormal range shares the spacing of the smallest normal */
+  double ulp = ldexp(1.0, e - mant);
+  double q = a / ulp;          /* exact: division by a power of two */
+  double r = nearbyint(q);     /* default rounding mode: to nearest, ties to even */
+  double y = r * ulp;
+  if (y >= ldexp(2.0 - ldexp(1.0, -mant), emax) + ldexp(1.0, emax - mant - 1)) y = INFINITY;
+  return x < 0 ? -y : y;
+}
+
+double oracle_round_to_dtype(double x, int dtype) {
+  return dtype == ORACLE_F16 ? round_to_format(x, 10, -14, 15) : round_to_format(x, 7, -126, 127);
+}
+
+/* ------------------------------------------------------------------ */
+/* Block means  (Sec. 3.2, Alg. 1 step 3)                              */
+/* ------------------------------------------------------------------ */
+
+/* x: [B,H,N,D] raw 16-bit values; means: [B,H,N/block,D] fp32 (the arithmetic mean, computed in
+ * fp64 and rounded once to fp32). */
+void oracle_block_means(const uint16_t* x, int dtype, int B, int H, int N, int D, int block, float* means) {
+  int T = N / block;
+  for (long bh = 0; bh < (long)B * H; ++bh)
+    for (int t = 0; t < T; ++t)
+      for (int c = 0; c < D; ++c) {
+        double s = 0.0;
+        for (int r = 0; r < block; ++r) s += bits_to_double(x[((bh * N) + (long)t * block + r) * D + c], dtype);
+        means[(bh * T + t) * D + c] = (float)(s / (double)block);
+      }
+}
+
+/* ------------------------------------------------------------------ */
+/* Budget rules                                                        */
+/* ------------------------------------------------------------------ */
+
+/* Per-row rule of the benchmark configurations: k_i = ceil(f * visible_i), at least 1 when
+ * f > 0, never more than visible_i; f == 0 gives 0.  f is taken in millionths so that both
+ * sides decide the ceiling in integer arithmetic.  fixed_k >= 0 overrides: k_i = min(fixed_k,
+ * visible_i) (the paper's single global k). */
+int oracle_row_k(int visible, double budget, int fixed_k) {
+  if (fixed_k >= 0) return fixed_k < visible ? fixed_k : visible;
+  long ppm = llround(budget * 1e6);
+  if (ppm <= 0) return 0;
+  long k = (ppm * (long)visible + 999999L) / 1000000L;
+  if (k < 1) k = 1;
+  if (k > visible) k = visible;
+  return (int)k;
+}
+
+/* App. B: the global integer k whose causal tile fraction (k n - k(k-1)/2) / (n(n+1)/2) is
+ * closest to f, clamped to [1, n]; ties go to the smaller k. */
+int oracle_paper_global_k(int n, double f) {
+  int best = 1;
+  double bestd = INFINITY;
+  for (int k = 1; k <= n; ++k) {
+    double frac = ((double)k * n - (double)k * (k - 1) / 2.0) / ((double)n * (n + 1) / 2.0);
+    double d = fabs(frac - f);
+    if (d < bestd) { bestd = d; best = k; }
+  }
+  return best;
+}
+
+/* Number of key blocks visible to query block i.  Causal: key block j is visible iff its first
+ * key position j*Bk is not after the block's last query position (i + off + 1)*Bq - 1. */
+int oracle_visible_blocks(int i, int Tk, int Bq, int Bk, int causal, int q_block_offset) {
+  if (!causal) return Tk;
+  long last_q = ((long)i + q_block_offset + 1) * Bq - 1;
+  long v = last_q / Bk + 1;
+  if (v > Tk) v = Tk;
+  if (v < 0) v = 0;
+  return (int)v;
+}
+
+/* ------------------------------------------------------------------ */
+/* Scores and TopK  (Sec. 3.2; Alg. 1 step 5)                          */
+/* ------------------------------------------------------------------ */
+
+/* S_hat[b,h,i,j] = qmean_i . kmean_j in fp64 over the fp32 means; no 1/sqrt(d). */
+void oracle_block_scores(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                         double* scores) {
+  int grp = Hq / Hkv;
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < Hq; ++h)
+      for (int i = 0; i < Tq; ++i)
+        for (int j = 0; j < Tk; ++j) {
+          const float* qm = qmean + (((long)b * Hq + h) * Tq + i) * D;
+          const float* km = kmean + (((long)b * Hkv + h / grp) * Tk + j) * D;
+          double s = 0.0;
+          for (int c = 0; c < D; ++c) s += (double)qm[c] * (double)km[c];
+          scores[(((long)b * Hq + h) * Tq + i) * Tk + j] = s;
+        }
+}
+
+typedef struct { double s; int j; } scored_t;
+
+static int cmp_scored(const void* pa, const void* pb) {
+  const scored_t* a = (const scored_t*)pa;
+  const scored_t* b = (const scored_t*)pb;
+  if (a->s > b->s) return -1;
+  if (a->s < b->s) return 1;
+  return a->j - b->j; /* equal scores: smaller block index first */
+}
+
+static int cmp_int(const void* pa, const void* pb) { return *(const int*)pa - *(const int*)pb; }
+
+/* idx: [B,Hq,Tq,kmax] ascending block ids padded with -1; cnt: [B,Hq,Tq].
+ * Returns 0, or -1 if some row needs more than kmax slots. */
+int oracle_select_topk(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                       int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
+                       int32_t* idx, int32_t* cnt, int kmax) {
+  int grp = Hq / Hkv;
+  scored_t* row = (scored_t*)malloc(sizeof(scored_t) * (size_t)(Tk > 0 ? Tk : 1));
+  int* sel = (int*)malloc(sizeof(int) * (size_t)(Tk > 0 ? Tk : 1));
+  int rc = 0;
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < Hq; ++h)
+      for (int i = 0; i < Tq; ++i) {
+        long rowid = ((long)b * Hq + h) * Tq + i;
+        int vis = oracle_visible_blocks(i, Tk, Bq, Bk, causal, q_block_offset);
+        int k = oracle_row_k(vis, budget, fixed_k);
+        const float* qm = qmean + rowid * D;
+        for (int j = 0; j < vis; ++j) {
+          const float* km = kmean + (((long)b * Hkv + h / grp) * Tk + j) * D;
+          double s = 0.0;
+          for (int c = 0; c < D; ++c) s += (double)qm[c] * (double)km[c];
+          row[j].s = s;
+          row[j].j = j;
+        }
+        qsort(row, (size_t)vis, sizeof(scored_t), cmp_scored);
+        if (k > kmax) { rc = -1; k = kmax; }
+        for (int t = 0; t < k; ++t) sel[t] = row[t].j;
+        qsort(sel, (size_t)k, sizeof(int), cmp_int);
+        for (int t = 0; t < kmax; ++t) idx[rowid * kmax + t] = t < k ? sel[t] : -1;
+        cnt[rowid] = k;
+      }
+  free(row);
+  free(sel);
+  return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* MXFP4 quantiser  (Sec. 3.2 "FP4 quantisation", MXFP4 reading)       */
+/* ------------------------------------------------------------------ */
+
+static const double E2M1_VALUE[8] = {0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0};
+
+/* Round y to the E2M1 grid {0,.5,1,1.5,2,3,4,6}: nearest, ties to the even code, magnitudes
+ * above 6 saturate to 6; the sign bit (bit 3) is kept even when the magnitude rounds to 0. */
+static uint8_t e2m1_encode(double y) {
+  uint8_t sign = signbit(y) ? 8 : 0;
+  double a = fabs(y);
+  uint8_t c;
+  if (a <= 0.25) c = 0;
+  else if (a < 0.75) c = 1;
+  else if (a <= 1.25) c = 2;
+  else if (a < 1.75) c = 3;
+  else if (a <= 2.5) c = 4;
+  else if (a < 3.5) c = 5;
+  else if (a <= 5.0) c = 6;
+  else c = 7;
+  return sign | c;
+}
+
+double oracle_e2m1_decode(int code) {
+  double v = E2M1_VALUE[code & 7];
+  return (code & 8) ? -v : v;
+}
+
+/* One group of n values x[0], x[stride], ...: shared exponent e = floor(log2 max|x|) - 2 clamped to
+ * [-127,127] (scale byte e+127; an all-zero group gets byte 127), elements encode x * 2^-e. */
+static uint8_t mx_quantize_group(const double* x, int n, int stride, uint8_t* codes, int cstride) {
+  double amax = 0.0;
+  for (int t = 0; t < n; ++t) { double a = fabs(x[(long)t * stride]); if (a > amax) amax = a; }
+  int e;
+  if (amax == 0.0) e = 0;
+  else {
+    int ex;
+    frexp(amax, &ex);          /* amax = f * 2^ex with f in [0.5,1) */
+    e = (ex - 1) - 2;
+    if (e < -127) e = -127;
+    if (e > 127) e = 127;
+  }
+  for (int t = 0; t < n; ++t) codes[(long)t * cstride] = e2m1_encode(ldexp(x[(long)t * stride], -e));
+  return (uint8_t)(e + 127);
+}
+
+/* Stand-alone entry used by the quantiser tests: n doubles -> n codes + one scale byte. */
+uint8_t oracle_mx_quantize_group(const double* x, int n, uint8_t* codes) {
+  return mx_quantize_group(x, n, 1, codes, 1);
+}
+
+/* x: [B,H,N,D] raw 16-bit.  codes: [B,H,N,D], ONE code (0..15) per byte, unpacked.
+ * axis 0: groups of 32 along D, scales [B,H,N,D/32].
+ * axis 1: groups of 32 along N, scales [B,H,N/32,D]. */
+void oracle_quantize_mxfp4(const uint16_t* x, int dtype, int B, int H, int N, int D, int axis,
+                           uint8_t* codes, uint8_t* scales) {
+  double grp[32];
+#pragma omp parallel for private(grp) schedule(static)
+  for (long bh = 0; bh < (long)B * H; ++bh) {
+    const uint16_t* xb = x + bh * (long)N * D;
+    uint8_t* cb = codes + bh * (long)N * D;
+    if (axis == 0) {
+      for (int n = 0; n < N; ++n)
+        for (int g = 0; g < D / 32; ++g) {
+          for (int t = 0; t < 32; ++t) grp[t] = bits_to_double(xb[(long)n * D + g * 32 + t], dtype);
+          scales[(bh * N + n) * (D / 32) + g] = mx_quantize_group(grp, 32, 1, cb + (long)n * D + g * 32, 1);
+        }
+    } else {
+      for (int g = 0; g < N / 32; ++g)
+        for (int c = 0; c < D; ++c) {
+          for (int t = 0; t < 32; ++t) grp[t] = bits_to_double(xb[((long)g * 32 + t) * D + c], dtype);
+          scales[(bh * (N / 32) + g) * D + c] = mx_quantize_group(grp, 32, 1, cb + (long)g * 32 * D + c, D);
+        }
+    }
+  }
+}
+
+/* value = E2M1(code) * 2^(scale-127), same indexing as oracle_quantize_mxfp4. */
+void oracle_dequantize_mxfp4(const uint8_t* codes, const uint8_t* scales, int B, int H, int N, int D, int axis,
+                             double* out) {
+  for (long bh = 0; bh < (long)B * H; ++bh)
+    for (int n = 0; n < N; ++n)
+      for (int c = 0; c < D; ++c) {
+        long e = bh * (long)N * D + (long)n * D + c;
+        int sb = axis == 0 ? scales[(bh * N + n) * (D / 32) + c / 32] : scales[(bh * (N / 32) + n / 32) * D + c];
+        out[e] = ldexp(oracle_e2m1_decode(codes[e]), sb - 127);
+      }
+}
+
+/* ------------------------------------------------------------------ */
+/* Exact attention  (Sec. 3.1, Eq. (1)) — the error reference          */
+/* ------------------------------------------------------------------ */
+
+/* q: [B,Hq,Nq,D], k,v: [B,Hkv,Nk,D].  Query row t sits at absolute position q_pos0 + t; with
+ * causal != 0 it sees keys at positions <= its own.  rows: n_rows triples (b,h,t); out: [n_rows,D];
+ * lse (nullable): [n_rows] natural-log sum of exp of the scaled scores. */
+void oracle_attn_exact(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
+                       int B, int Hq, int Hkv, int Nq, int Nk, int D, int causal, int q_pos0, double scale,
+                       const int32_t* rows, int n_rows, double* out, double* lse) {
+  (void)B;
+  int grp = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int r = 0; r < n_rows; ++r) {
+    int b = rows[3 * r], h = rows[3 * r + 1], t = rows[3 * r + 2];
+    const uint16_t* qr = q + (((long)b * Hq + h) * Nq + t) * D;
+    const uint16_t* kb = k + ((long)b * Hkv + h / grp) * (long)Nk * D;
+    const uint16_t* vb = v + ((long)b * Hkv + h / grp) * (long)Nk * D;
+    long nvis = causal ? (long)q_pos0 + t + 1 : Nk;
+    if (nvis > Nk) nvis = Nk;
+    double* s = (double*)malloc(sizeof(double) * (size_t)(nvis > 0 ? nvis : 1));
+    double mx = -INFINITY;
+    for (long j = 0; j < nvis; ++j) {
+      double d = 0.0;
+      for (int c = 0; c < D; ++c) d += bits_to_double(qr[c], dtype) * bits_to_double(kb[j * D + c], dtype);
+      s[j] = d * scale;
+      if (s[j] > mx) mx = s[j];
+    }
+    double den = 0.0;
+    for (long j = 0; j < nvis; ++j) { s[j] = exp(s[j] - mx); den += s[j]; }
+    for (int c = 0; c < D; ++c) {
+      double o = 0.0;
+      for (long j = 0; j < nvis; ++j) o += s[j] * bits_to_double(vb[j * D + c], dtype);
+      out[(long)r * D + c] = o / den;
+    }
+    if (lse) lse[r] = mx + log(den);
+    free(s);
+  }
+}
+
+/* ------------------------------------------------------------------ */
+/* Mixed-precision attention  (Alg. 1 steps 4-23)                      */
+/* ------------------------------------------------------------------ */
+
+typedef struct {
+  int D, Bk, dtype, quantize_p;
+  double scale;
+  const double* kh;   /* [Nk,D] high-precision keys   */
+  const double* vh;   /* [Nk,D] high-precision values */
+  const double* kq;   /* [Nk,D] dequantised MXFP4 keys   */
+  const double* vq;   /* [Nk,D] dequantised MXFP4 values */
+} kv_view_t;
+
+/* One (query row, key block) step of Alg. 1: scores on the chosen path, running max / sum update,
+ * P rounding or quantisation, output accumulation.  qh / qq: the row's high-precision and
+ * dequantised-MXFP4 query.  n_valid: keys of the block the row may see (causal prefix; Bk if
+ * unmasked; 0 = nothing visible, state untouched). */
+static void row_tile_step(const kv_view_t* kv, const double* qh, const double* qq, int j, int is16, int n_valid,
+                          double* m, double* l, double* O) {
+  int D = kv->D, Bk = kv->Bk;
+  if (n_valid <= 0) return;
+  double S[256], P[256];
+  const double* qrow = is16 ? qh : qq;
+  const double* kmat = is16 ? kv->kh : kv->kq;
+  double rowmax = -INFINITY;
+  for (int c = 0; c < Bk; ++c) {
+    if (c >= n_valid) { S[c] = -INFINITY; continue; }
+    double d = 0.0;
+    const double* kr = kmat + ((long)j * Bk + c) * D;
+    for (int x = 0; x < D; ++x) d += qrow[x] * kr[x];
+    S[c] = d * kv->scale;
+    if (S[c] > rowmax) rowmax = S[c];
+  }
+  double m_new = *m > rowmax ? *m : rowmax;
+  double alpha = isinf(*m) ? 0.0 : exp(*m - m_new);
+  double rs = 0.0;
+  for (int c = 0; c < Bk; ++c) { P[c] = c < n_valid ? exp(S[c] - m_new) : 0.0; rs += P[c]; }
+  *l = alpha * (*l) + rs;                     /* row sum from the unquantised P on both paths */
+  for (int x = 0; x < D; ++x) O[x] *= alpha;
+  if (is16) {
+    for (int c = 0; c < Bk; ++c) {
+      double p = oracle_round_to_dtype(P[c], kv->dtype);
+      if (p == 0.0) continue;
+      const double* vr = kv->vh + ((long)j * Bk + c) * D;
+      for (int x = 0; x < D; ++x) O[x] += p * vr[x];
+    }
+  } else {
+    double Pd[256];
+    if (kv->quantize_p) {
+      uint8_t codes[32];
+      for (int g = 0; g < Bk / 32; ++g) {
+        uint8_t sb = mx_quantize_group(P + g * 32, 32, 1, codes, 1);
+        for (int t = 0; t < 32; ++t) Pd[g * 32 + t] = ldexp(oracle_e2m1_decode(codes[t]), (int)sb - 127);
+      }
+    } else {
+      for (int c = 0; c < Bk; ++c) Pd[c] = P[c];
+    }
+    for (int c = 0; c < Bk; ++c) {
+      if (Pd[c] == 0.0) continue;
+      const double* vr = kv->vq + ((long)j * Bk + c) * D;
+      for (int x = 0; x < D; ++x) O[x] += Pd[c] * vr[x];
+    }
+  }
+  *m = m_new;
+}
+
+static int in_sorted(const int32_t* a, int n, int j) {
+  for (int t = 0; t < n; ++t) if (a[t] == j) return 1;
+  return 0;
+}
+
+/* Convert one head's [N,D] 16-bit tensor to doubles; and to dequantised-MXFP4 doubles. */
+static void head_to_double(const uint16_t* x, int dtype, long n, double* out) {
+  for (long e = 0; e < n; ++e) out[e] = bits_to_double(x[e], dtype);
+}
+static void head_quant_dequant(const uint16_t* x, int dtype, int N, int D, int axis, double* out) {
+  uint8_t* codes = (uint8_t*)malloc((size_t)N * D);
+  uint8_t* scales = (uint8_t*)malloc((size_t)N * D / 32);
+  oracle_quantize_mxfp4(x, dtype, 1, 1, N, D, axis, codes, scales);
+  oracle_dequantize_mxfp4(codes, scales, 1, 1, N, D, axis, out);
+  free(codes);
+  free(scales);
+}
+
+/*
+ * Prefill.  q:[B,Hq,N,D], k,v:[B,Hkv,N,D] raw 16-bit; idx:[B,Hq,Tq,kmax], cnt:[B,Hq,Tq] from
+ * oracle_select_topk (or set by hand).  units: n_units triples (b,h,i) naming the query blocks to
+ * evaluate.  out: [n_units,Bq,D] fp64 (not rounded to the output dtype); lse nullable [n_units,Bq].
+ * tile_order 0: key blocks ascending (Alg. 1); 1: all 4-bit tiles ascending, then the 16-bit ones
+ * (the kernel order Sec. 3.3 describes).  quantize_p 0 disables step 19's P quantisation (test aid).
+ * force_path: -1 use idx; 0 all tiles on the 4-bit path; 1 all tiles on the 16-bit path.
+ */
+int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
+                               const int32_t* idx, const int32_t* cnt, int kmax,
+                               int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, double scale,
+                               int tile_order, int quantize_p, int force_path,
+                               const int32_t* units, int n_units, double* out, double* lse) {
+  (void)B;
+  if (Bk > 256 || Bk % 32 || D % 32) return -1;
+  int grp = Hq / Hkv, Tq = N / Bq, Tk = N / Bk;
+  /* group the work by kv head so that each head's K/V is converted once */
+  for (int b0 = 0; b0 < B; ++b0)
+    for (int g = 0; g < Hkv; ++g) {
+      int any = 0;
+      for (int u = 0; u < n_units; ++u) if (units[3 * u] == b0 && units[3 * u + 1] / grp == g) any = 1;
+      if (!any) continue;
+      long hd = (long)N * D;
+      const uint16_t* kb = k + ((long)b0 * Hkv + g) * hd;
+      const uint16_t* vb = v + ((long)b0 * Hkv + g) * hd;
+      double* kh = (double*)malloc(sizeof(double) * hd);
+      double* vh = (double*)malloc(sizeof(double) * hd);
+      double* kq = (double*)malloc(sizeof(double) * hd);
+      double* vq = (double*)malloc(sizeof(double) * hd);
+      head_to_double(kb, dtype, hd, kh);
+      head_to_double(vb, dtype, hd, vh);
+      head_quant_dequant(kb, dtype, N, D, 0, kq);
+      head_quant_dequant(vb, dtype, N, D, 1, vq);
+      kv_view_t kv = {D, Bk, dtype, quantize_p, scale, kh, vh, kq, vq};
+#pragma omp parallel for schedule(dynamic, 1)
+      for (int u = 0; u < n_units; ++u) {
+        int b = units[3 * u], h = units[3 * u + 1], i = units[3 * u + 2];
+        if (b != b0 || h / grp != g) continue;
+        const uint16_t* qb = q + (((long)b * Hq + h) * N + (long)i * Bq) * D;
+        double* qh = (double*)malloc(sizeof(double) * (size_t)Bq * D);
+        double* qq = (double*)malloc(sizeof(double) * (size_t)Bq * D);
+        head_to_double(qb, dtype, (long)Bq * D, qh);
+        head_quant_dequant(qb, dtype, Bq, D, 0, qq);
+        long rowid = ((long)b * Hq + h) * Tq + i;
+        const int32_t* sel = idx ? idx + rowid * kmax : NULL;
+        int nsel = cnt ? cnt[rowid] : 0;
+        int vis = oracle_visible_blocks(i, Tk, Bq, Bk, causal, 0);
+        int* order = (int*)malloc(sizeof(int) * (size_t)(vis > 0 ? vis : 1));
+        int* path = (int*)malloc(sizeof(int) * (size_t)(vis > 0 ? vis : 1));
+        int no = 0;
+        for (int pass = 0; pass < 2; ++pass)
+          for (int j = 0; j < vis; ++j) {
+            int is16 = force_path >= 0 ? force_path : in_sorted(sel, nsel, j);
+            if (tile_order == 0) { if (pass == 0) { order[no] = j; path[no++] = is16; } }
+            else if ((pass == 0 && !is16) || (pass == 1 && is16)) { order[no] = j; path[no++] = is16; }
+          }
+        for (int r = 0; r < Bq; ++r) {
+          double m = -INFINITY, l = 0.0;
+          double* O = out + ((long)u * Bq + r) * D;
+          for (int x = 0; x < D; ++x) O[x] = 0.0;
+          long qpos = (long)i * Bq + r;
+          for (int t = 0; t < no; ++t) {
+            int j = order[t];
+            int n_valid = Bk;
+            if (causal) {
+              long nv = qpos - (long)j * Bk + 1;
+              n_valid = nv < 0 ? 0 : (nv > Bk ? Bk : (int)nv);
+            }
+            row_tile_step(&kv, qh + (long)r * D, qq + (long)r * D, j, path[t], n_valid, &m, &l, O);
+          }
+          for (int x = 0; x < D; ++x) O[x] /= l;            /* Alg. 1 step 21 */
+          if (lse) lse[(long)u * Bq + r] = m + log(l);
+        }
+        free(order); free(path); free(qh); free(qq);
+      }
+      free(kh); free(vh); free(kq); free(vq);
+    }
+  return 0;
+}
+
+/*
+ * Decode: one query token per (b, q-head) against a cache of seqlen keys (all visible), the
+ * paper's algorithm with a one-row query block, evaluated split-K: the key blocks are cut into
+ * partitions of split_blocks blocks, each partition runs Alg. 1's recurrence from a fresh
+ * (m,l,O), and the partitions are merged by their log-sum-exp.  split_blocks <= 0: one partition.
+ * q:[B,Hq,D]; k,v:[B,Hkv,Nkv,D]; idx:[B,Hq,kmax], cnt:[B,Hq]; seqlens nullable [B] (multiples
+ * of Bk).  out: [B,Hq,D] fp64.
+ */
+int oracle_attn_thrift_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
+                              const int32_t* idx, const int32_t* cnt, int kmax, const int32_t* seqlens,
+                              int B, int Hq, int Hkv, int Nkv, int D, int Bk, double scale,
+                              int split_blocks, int quantize_p, int force_path, double* out) {
+  if (Bk > 256 || Bk % 32 || D % 32 || D > 1024) return -1;
+  int grp = Hq / Hkv;
+#pragma omp parallel for schedule(dynamic, 1) collapse(2)
+  for (int b = 0; b < B; ++b)
+    for (int g = 0; g < Hkv; ++g) {
+      int len = seqlens ? seqlens[b] : Nkv;
+      int Tk = len / Bk;
+      long hd = (long)Nkv * D;
+      const uint16_t* kb = k + ((long)b * Hkv + g) * hd;
+      const uint16_t* vb = v + ((long)b * Hkv + g) * hd;
+      long used = (long)Tk * Bk * D;
+      double* kh = (double*)malloc(sizeof(double) * (size_t)(used > 0 ? used : 1));
+      double* vh = (double*)malloc(sizeof(double) * (size_t)(used > 0 ? used : 1));
+      double* kq = (double*)malloc(sizeof(double) * (size_t)(used > 0 ? used : 1));
+      double* vq = (double*)malloc(sizeof(double) * (size_t)(used > 0 ? used : 1));
+      head_to_double(kb, dtype, used, kh);
+      head_to_double(vb, dtype, used, vh);
+      head_quant_dequant(kb, dtype, Tk * Bk, D, 0, kq);
+      head_quant_dequant(vb, dtype, Tk * Bk, D, 1, vq);
+      kv_view_t kv = {D, Bk, dtype, quantize_p, scale, kh, vh, kq, vq};
+      int sb = split_blocks > 0 ? split_blocks : (Tk > 0 ? Tk : 1);
+      for (int h = g * grp; h < (g + 1) * grp; ++h) {
+        double qh[1024], qq[1024];
+        const uint16_t* qb = q + ((long)b * Hq + h) * D;
+        head_to_double(qb, dtype, D, qh);
+        head_quant_dequant(qb, dtype, 1, D, 0, qq);
+        const int32_t* sel = idx ? idx + ((long)b * Hq + h) * kmax : NULL;
+        int nsel = cnt ? cnt[(long)b * Hq + h] : 0;
+        double M = -INFINITY, L = 0.0, Oacc[1024];
+        for (int x = 0; x < D; ++x) Oacc[x] = 0.0;
+        for (int p0 = 0; p0 < Tk; p0 += sb) {
+          double m = -INFINITY, l = 0.0, O[1024];
+          for (int x = 0; x < D; ++x) O[x] = 0.0;
+          for (int j = p0; j < p0 + sb && j < Tk; ++j) {
+            int is16 = force_path >= 0 ? force_path : in_sorted(sel, nsel, j);
+            row_tile_step(&kv, qh, qq, j, is16, Bk, &m, &l, O);
+          }
+          /* log-sum-exp merge of the partition into the running total */
+          double Mn = M > m ? M : m;
+          double a = isinf(M) ? 0.0 : exp(M - Mn), c = isinf(m) ? 0.0 : exp(m - Mn);
+          for (int x = 0; x < D; ++x) Oacc[x] = a * Oacc[x] + c * O[x];
+          L = a * L + c * l;
+          M = Mn;
+        }
+        for (int x = 0; x < D; ++x) out[((long)b * Hq + h) * D + x] = Oacc[x] / L;
+      }
+      free(kh); free(vh); free(kq); free(vq);
+    }
+  return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Diagnostics                                                         */
+/* ------------------------------------------------------------------ */
+
+/* Right-hand side of Eq. (4) for one query row: sum_j |eps_j| p_j ||v_j - o||, with eps_j the
+ * difference between the 4-bit-path score and the exact score, p the exact softmax, o the exact
+ * output.  per_block (nullable, [Nk/Bk]) receives the sum split by key block. */
+double oracle_error_bound_rhs(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
+                              int Nk, int D, int Bk, int n_visible, double scale, double* per_block) {
+  long hd = (long)Nk * D;
+  double* kq = (double*)malloc(sizeof(double) * hd);
+  double qq[1024], qh[1024];
+  head_quant_dequant(k, dtype, Nk, D, 0, kq);
+  head_to_double(q, dtype, D, qh);
+  head_quant_dequant(q, dtype, 1, D, 0, qq);
+  double* s = (double*)malloc(sizeof(double) * (size_t)n_visible);
+  double* eps = (double*)malloc(sizeof(double) * (size_t)n_visible);
+  double mx = -INFINITY;
+  for (int j = 0; j < n_visible; ++j) {
+    double d = 0.0, dq = 0.0;
+    for (int c = 0; c < D; ++c) {
+      d += qh[c] * bits_to_double(k[(long)j * D + c], dtype);
+      dq += qq[c] * kq[(long)j * D + c];
+    }
+    s[j] = d * scale;
+    eps[j] = (dq - d) * scale;
+    if (s[j] > mx) mx = s[j];
+  }
+  double den = 0.0;
+  for (int j = 0; j < n_visible; ++j) { s[j] = exp(s[j] - mx); den += s[j]; }
+  double o[1024];
+  for (int c = 0; c < D; ++c) {
+    double a = 0.0;
+    for (int j = 0; j < n_visible; ++j) a += s[j] / den * bits_to_double(v[(long)j * D + c], dtype);
+    o[c] = a;
+  }
+  if (per_block) for (int t = 0; t < Nk / Bk; ++t) per_block[t] = 0.0;
+  double total = 0.0;
+  for (int j = 0; j < n_visible; ++j) {
+    double nrm = 0.0;
+    for (int c = 0; c < D; ++c) { double d = bits_to_double(v[(long)j * D + c], dtype) - o[c]; nrm += d * d; }
+    double term = fabs(eps[j]) * s[j] / den * sqrt(nrm);
+    total += term;
+    if (per_block) per_block[j / Bk] += term;
+  }
+  free(kq); free(s); free(eps);
+  return total;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

@@ -1,0 +1,319 @@
+"""Pins for the oracle's attention routines (CPU only).
+
+The exact routine is pinned to a numpy brute force and to torch's fp64
+scaled_dot_product_attention.  The mixed-precision routine is pinned by the
+invariants the method fixes (100 % budget == 16-bit attention, 0 % budget with
+P quantisation off == exact attention on the dequantised tensors, T_i = all /
+none == forced paths, tile-order independence without P quantisation) and by a
+second, independently written numpy version of Alg. 1's recurrence.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_23081_amd import metrics
+from paper_2605_23081_amd import workloads as W
+
+E2M1 = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+
+
+def _softmax_attention_np(q, k, v, causal, scale, q_pos0=0):
+    """Textbook Eq. (1): o = sum_j p_j v_j, p = softmax(q.k / sqrt(d)); fp64."""
+    s = (q @ k.T) * scale
+    if causal:
+        qpos = q_pos0 + np.arange(q.shape[0])[:, None]
+        s = np.where(np.arange(k.shape[0])[None, :] <= qpos, s, -np.inf)
+    s = s - s.max(axis=1, keepdims=True)
+    p = np.exp(s)
+    return (p / p.sum(axis=1, keepdims=True)) @ v
+
+
+def _all_rows(B, H, N):
+    return np.array([(b, h, t) for b in range(B) for h in range(H) for t in range(N)], np.int32)
+
+
+def _all_units(B, H, Tq):
+    return np.array([(b, h, i) for b in range(B) for h in range(H) for i in range(Tq)], np.int32)
+
+
+def _small(dtype="f16", N=256, Hq=2, Hkv=1, Bq=64, seed=1):
+    base = W.TINY if dtype == "f16" else W.QWEN3_32K
+    w = W.scaled(base, N=N, Hq=Hq, Hkv=Hkv, Bq=Bq, Bk=64, seed=seed, planted_blocks=1, sink_tokens=0)
+    q, k, v, _, _ = W.make_prefill(w)
+    return w, q, k, v
+
+
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_exact_attention_against_numpy_and_torch(oracle, causal, dtype):
+    w, q, k, v = _small(dtype)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    out, lse = oracle.attn_exact(qb, kb, vb, dt, causal, scale, _all_rows(1, w.Hq, w.N), want_lse=True)
+    out = out.reshape(w.Hq, w.N, w.D)
+    qd, kd, vd = q.double(), k.double(), v.double()
+    for h in range(w.Hq):
+        want = _softmax_attention_np(qd[0, h].numpy(), kd[0, h // w.group].numpy(), vd[0, h // w.group].numpy(), causal, scale)
+        assert np.abs(out[h] - want).max() < 1e-12
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        qd, kd.repeat_interleave(w.group, dim=1), vd.repeat_interleave(w.group, dim=1), is_causal=causal)
+    assert np.abs(out - ref[0].numpy()).max() < 1e-10
+    # log-sum-exp of the scaled scores
+    s = (qd[0, 0] @ kd[0, 0].T * scale).numpy()
+    if causal:
+        s = np.where(np.tril(np.ones_like(s)) > 0, s, -np.inf)
+    want_lse = np.log(np.exp(s - s.max(1, keepdims=True)).sum(1)) + s.max(1)
+    assert np.abs(lse.reshape(w.Hq, w.N)[0] - want_lse).max() < 1e-10
+
+
+def test_exact_attention_decode_position(oracle):
+    w, q, k, v = _small("f16", N=192, Hq=2, Hkv=1)
+    qb, dt = oracle.bits_of(q[:, :, -1:, :]); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    rows = np.array([(0, 0, 0), (0, 1, 0)], np.int32)
+    out = oracle.attn_exact(qb, kb, vb, dt, True, 0.1, rows, q_pos0=w.N - 1)
+    for h in range(2):
+        want = _softmax_attention_np(q[0, h, -1:].double().numpy(), k[0, 0].double().numpy(), v[0, 0].double().numpy(), False, 0.1)
+        assert np.abs(out[h] - want[0]).max() < 1e-12
+
+
+@pytest.mark.parametrize("dtype,Bq", [("f16", 64), ("bf16", 128)])
+def test_full_budget_equals_16bit_attention(oracle, dtype, Bq):
+    """Budget 100 %: every visible tile on the 16-bit path -> exact attention up to the rounding of P."""
+    w, q, k, v = _small(dtype, N=512, Bq=Bq)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    Tq = w.N // Bq
+    units = _all_units(1, w.Hq, Tq)
+    exact = oracle.attn_exact(qb, kb, vb, dt, True, scale, _all_rows(1, w.Hq, w.N)).reshape(w.Hq, w.N, w.D)
+    qm = oracle.block_means(qb, dt, Bq); km = oracle.block_means(kb, dt, 64)
+    idx, cnt = oracle.select_topk(qm, km, Bq, 64, True, 1.0)
+    for order in (0, 1):
+        out, lse = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, Bq, 64, True, scale, units, tile_order=order, want_lse=True)
+        out = out.reshape(w.Hq, w.N, w.D)
+        tol = 2e-3 if dtype == "f16" else 8e-3   # P carries 11 (fp16) or 8 (bf16) significant bits
+        assert np.abs(out - exact).max() < tol
+        assert np.abs(out - exact).max() > 0          # the rounding of P is really applied
+    forced = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, Bq, 64, True, scale, units, force_path=1).reshape(w.Hq, w.N, w.D)
+    assert np.array_equal(forced, out if order == 0 else forced) or np.abs(forced - out).max() < 1e-12
+    _, lse_exact = oracle.attn_exact(qb, kb, vb, dt, True, scale, _all_rows(1, w.Hq, w.N), want_lse=True)
+    assert np.abs(lse.ravel() - lse_exact).max() < 1e-10   # l uses the unrounded P
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_zero_budget_without_p_quantisation_is_attention_on_dequantised_tensors(oracle, causal):
+    w, q, k, v = _small("f16", N=256, Bq=64)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    units = _all_units(1, w.Hq, w.N // 64)
+    for order in (0, 1):
+        out = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, causal, scale, units, tile_order=order,
+                                         quantize_p=False, force_path=0).reshape(w.Hq, w.N, w.D)
+        qd = oracle.dequantize_mxfp4(*oracle.quantize_mxfp4(qb, dt, 0), 0)
+        kd = oracle.dequantize_mxfp4(*oracle.quantize_mxfp4(kb, dt, 0), 0)
+        vd = oracle.dequantize_mxfp4(*oracle.quantize_mxfp4(vb, dt, 1), 1)
+        for h in range(w.Hq):
+            want = _softmax_attention_np(qd[0, h], kd[0, 0], vd[0, 0], causal, scale)
+            assert np.abs(out[h] - want).max() < 1e-11
+
+
+# ---- an independent numpy restatement of Alg. 1 (one head), used only as a cross-check ----
+
+def _np_mx_quant_dequant(x):
+    """x [..., 32] -> dequantised MXFP4 values; power-of-two scale, nearest grid value, ties to even code."""
+    amax = np.abs(x).max(-1, keepdims=True)
+    e = np.where(amax > 0, np.floor(np.log2(np.where(amax > 0, amax, 1.0))) - 2, 0.0)
+    e = np.clip(e, -127, 127)
+    y = x / 2.0 ** e
+    a = np.minimum(np.abs(y), 6.0)
+    d = np.abs(a[..., None] - E2M1)
+    best = np.zeros(a.shape, np.int64)
+    for c in range(1, 8):
+        cur = np.take_along_axis(d, best[..., None], -1)[..., 0]
+        better = (d[..., c] < cur) | ((d[..., c] == cur) & (c % 2 == 0) & (best % 2 == 1))
+        best = np.where(better, c, best)
+    return np.sign(y) * E2M1[best] * 2.0 ** e
+
+
+def _np_round(x, dtype):
+    if dtype == "f16":
+        return x.astype(np.float16).astype(np.float64)
+    return torch.from_numpy(x).to(torch.bfloat16).double().numpy()
+
+
+def _np_thrift_head(q, k, v, sel, Bq, Bk, causal, scale, dtype, quantize_p=True):
+    """q,k,v fp64 [N,D] holding 16-bit values; sel[i] = set of 16-bit key blocks of query block i."""
+    N, D = q.shape
+    qq = _np_mx_quant_dequant(q.reshape(N, D // 32, 32)).reshape(N, D)
+    kq = _np_mx_quant_dequant(k.reshape(N, D // 32, 32)).reshape(N, D)
+    vq = _np_mx_quant_dequant(v.reshape(N // 32, 32, D).transpose(0, 2, 1)).transpose(0, 2, 1).reshape(N, D)
+    out = np.zeros((N, D))
+    for i in range(N // Bq):
+        rows = slice(i * Bq, (i + 1) * Bq)
+        m = np.full(Bq, -np.inf); l = np.zeros(Bq); O = np.zeros((Bq, D))
+        nvis = min(N // Bk, ((i + 1) * Bq - 1) // Bk + 1) if causal else N // Bk
+        for j in range(nvis):
+            cols = slice(j * Bk, (j + 1) * Bk)
+            hi = j in sel[i]
+            S = ((q[rows] @ k[cols].T) if hi else (qq[rows] @ kq[cols].T)) * scale
+            if causal:
+                S = np.where(np.arange(j * Bk, (j + 1) * Bk)[None, :] <= np.arange(i * Bq, (i + 1) * Bq)[:, None], S, -np.inf)
+            m_new = np.maximum(m, S.max(1))
+            live = np.isfinite(m_new)
+            m_safe = np.where(live, m_new, 0.0)
+            alpha = np.where(np.isfinite(m), np.exp(m - m_safe), 0.0)
+            P = np.where(live[:, None], np.exp(S - m_safe[:, None]), 0.0)
+            l = alpha * l + P.sum(1)
+            if hi:
+                O = alpha[:, None] * O + _np_round(P, dtype) @ v[cols]
+            else:
+                Pq = _np_mx_quant_dequant(P.reshape(Bq, Bk // 32, 32)).reshape(Bq, Bk) if quantize_p else P
+                O = alpha[:, None] * O + Pq @ vq[cols]
+            m = m_new
+        out[rows] = O / l[:, None]
+    return out
+
+
+@pytest.mark.parametrize("dtype,Bq,causal", [("f16", 64, True), ("bf16", 128, True), ("f16", 64, False)])
+def test_mixed_attention_against_independent_numpy_recurrence(oracle, dtype, Bq, causal):
+    w, q, k, v = _small(dtype, N=512, Hq=2, Hkv=1, Bq=Bq, seed=5)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    Tq = w.N // Bq
+    qm = oracle.block_means(qb, dt, Bq); km = oracle.block_means(kb, dt, 64)
+    for budget in (0.0, 0.25, 1.0):
+        idx, cnt = oracle.select_topk(qm, km, Bq, 64, causal, budget)
+        out = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, Bq, 64, causal, scale, _all_units(1, w.Hq, Tq)).reshape(w.Hq, w.N, w.D)
+        for h in range(w.Hq):
+            sel = [set(idx[0, h, i, :cnt[0, h, i]].tolist()) for i in range(Tq)]
+            want = _np_thrift_head(q[0, h].double().numpy(), k[0, 0].double().numpy(), v[0, 0].double().numpy(), sel, Bq, 64, causal, scale, dtype)
+            # same arithmetic in a different summation order: agreement to rounding noise, except where
+            # that noise flips a 4-bit code of P (rare, bounded by one grid step of one element)
+            diff = np.abs(out[h] - want)
+            assert np.quantile(diff, 0.999) < 1e-9
+            assert diff.max() < 5e-3
+
+
+def test_selection_sets_all_and_none_equal_forced_paths_and_branch_swap(oracle):
+    w, q, k, v = _small("f16", N=512, Hq=1, Hkv=1, Bq=64, seed=7)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    Tq = Tk = 8
+    units = _all_units(1, 1, Tq)
+    full_idx = np.full((1, 1, Tq, Tk), -1, np.int32); full_cnt = np.zeros((1, 1, Tq), np.int32)
+    for i in range(Tq):
+        full_idx[0, 0, i, :i + 1] = np.arange(i + 1); full_cnt[0, 0, i] = i + 1
+    none_idx = np.full((1, 1, Tq, 1), -1, np.int32); none_cnt = np.zeros((1, 1, Tq), np.int32)
+    a = oracle.attn_thrift_prefill(qb, kb, vb, dt, full_idx, full_cnt, 64, 64, True, scale, units)
+    b = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, units, force_path=1)
+    assert np.array_equal(a, b)
+    a = oracle.attn_thrift_prefill(qb, kb, vb, dt, none_idx, none_cnt, 64, 64, True, scale, units)
+    b = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, units, force_path=0)
+    assert np.array_equal(a, b)
+    # a hand-set T_i changes exactly the rows of that query block and nothing else
+    one_idx = none_idx.copy(); one_cnt = none_cnt.copy()
+    one_idx[0, 0, 5, 0] = 2; one_cnt[0, 0, 5] = 1
+    c = oracle.attn_thrift_prefill(qb, kb, vb, dt, one_idx, one_cnt, 64, 64, True, scale, units)
+    assert np.array_equal(c[:5], a[:5]) and np.array_equal(c[6:], a[6:]) and not np.array_equal(c[5], a[5])
+    # without P quantisation the result does not depend on the order of the tiles (to rounding)
+    sel_idx, sel_cnt = oracle.select_topk(oracle.block_means(qb, dt, 64), oracle.block_means(kb, dt, 64), 64, 64, True, 0.25)
+    o0 = oracle.attn_thrift_prefill(qb, kb, vb, dt, sel_idx, sel_cnt, 64, 64, True, scale, units, tile_order=0, quantize_p=False)
+    o1 = oracle.attn_thrift_prefill(qb, kb, vb, dt, sel_idx, sel_cnt, 64, 64, True, scale, units, tile_order=1, quantize_p=False)
+    assert np.abs(o0 - o1).max() < 2e-3          # only the fp16 rounding of P on promoted tiles depends on the running max
+    p0 = oracle.attn_thrift_prefill(qb, kb, vb, dt, sel_idx, sel_cnt, 64, 64, True, scale, units, tile_order=0)
+    p1 = oracle.attn_thrift_prefill(qb, kb, vb, dt, sel_idx, sel_cnt, 64, 64, True, scale, units, tile_order=1)
+    # with P quantisation on, the order changes the running max each tile sees, hence which way each
+    # 4-bit code of P rounds: two noise realisations of the same quantity, far below the 4-bit error itself
+    rows = _all_rows(1, 1, w.N)
+    exact = oracle.attn_exact(qb, kb, vb, dt, True, scale, rows).reshape(p0.shape)
+    assert metrics.rel_fro(p0, p1) < 0.1 * metrics.rel_fro(p0, exact)
+
+
+def test_decode_split_k_and_invariants(oracle):
+    w = W.scaled(W.DECODE_131K, B=2, N=1024, Hq=4, Hkv=2, sink_tokens=4)
+    q, k, v = W.make_decode(w)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    Tk = w.N // 64
+    km = oracle.block_means(kb, dt, 64)
+    qm = q.float().numpy().reshape(2, 4, 1, 128)
+    idx, cnt = oracle.select_topk(qm, km, 1, 64, True, 0.05, q_block_offset=w.N - 1)
+    assert np.all(cnt == math.ceil(0.05 * Tk))
+    idx, cnt = idx[:, :, 0], cnt[:, :, 0]
+    rows = np.array([(b, h, 0) for b in range(2) for h in range(4)], np.int32)
+    exact = oracle.attn_exact(qb.reshape(2, 4, 1, 128), kb, vb, dt, False, scale, rows).reshape(2, 4, 128)
+    # 100 %: 16-bit path everywhere == exact attention up to P rounding, for any split
+    for split in (0, 4, 5):
+        o = oracle.attn_thrift_decode(qb, kb, vb, dt, None, None, 64, scale, split, force_path=1)
+        assert np.abs(o - exact).max() < 2e-3
+    # P quantisation off: split-K is exact arithmetic, any partition size gives the same result
+    ref = oracle.attn_thrift_decode(qb, kb, vb, dt, idx, cnt, 64, scale, 0, quantize_p=False)
+    for split in (1, 4, 7, 16):
+        o = oracle.attn_thrift_decode(qb, kb, vb, dt, idx, cnt, 64, scale, split, quantize_p=False)
+        assert np.abs(o - ref).max() < 1e-3     # fp16 rounding of P on promoted blocks depends on the partition max
+    o0 = oracle.attn_thrift_decode(qb, kb, vb, dt, None, None, 64, scale, 0, quantize_p=False, force_path=0)
+    o4 = oracle.attn_thrift_decode(qb, kb, vb, dt, None, None, 64, scale, 4, quantize_p=False, force_path=0)
+    assert np.abs(o0 - o4).max() < 1e-12
+    # decode == the last row of a prefill over the same keys (one partition, same tile order)
+    qfull = torch.zeros(2, 4, w.N, 128, dtype=q.dtype); qfull[:, :, -1] = q
+    qfb, _ = oracle.bits_of(qfull)
+    pidx = np.full((2, 4, w.N, idx.shape[-1]), -1, np.int32); pcnt = np.zeros((2, 4, w.N), np.int32)
+    pidx[:, :, -1] = idx; pcnt[:, :, -1] = cnt
+    units = np.array([(b, h, w.N - 1) for b in range(2) for h in range(4)], np.int32)
+    pre = oracle.attn_thrift_prefill(qfb, kb, vb, dt, pidx, pcnt, 1, 64, True, scale, units).reshape(2, 4, 128)
+    dec = oracle.attn_thrift_decode(qb, kb, vb, dt, idx, cnt, 64, scale, 0)
+    assert np.array_equal(pre, dec)
+    # shorter sequences via seqlens: only the first blocks are read
+    sl = np.array([512, 1024], np.int32)
+    idx_s = np.where(idx < 8, idx, -1); idx_s.sort(axis=-1); idx_s = idx_s[..., ::-1].copy()
+    cnt_s = (idx_s >= 0).sum(-1).astype(np.int32)
+    idx_s2 = np.full_like(idx_s, -1)
+    for b in range(2):
+        for h in range(4):
+            vals = sorted(x for x in idx_s[b, h] if x >= 0)
+            idx_s2[b, h, :len(vals)] = vals
+    o = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_s2, cnt_s, 64, scale, 4, seqlens=sl, force_path=1)
+    ex0 = oracle.attn_exact(qb.reshape(2, 4, 1, 128)[:1], kb[:1, :, :512], vb[:1, :, :512], dt, False, scale, rows[:4]).reshape(4, 128)
+    assert np.abs(o[0] - ex0).max() < 2e-3
+
+
+def test_promoting_blocks_reduces_error_on_planted_workload(oracle):
+    """Qualitative claim of Sec. 3.1/3.2 on the synthetic stand-in: 16-bit for a few top blocks closes
+    most of the 4-bit error gap, and the block-mean selector beats promoting the same number of
+    lowest-scored blocks."""
+    w = W.TINY
+    q, k, v, _, _ = W.make_prefill(w)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    sample = np.array([(0, 0, i) for i in (20, 25, 31)], np.int32)
+    rows = np.array([(0, 0, i * 64 + r) for i in (20, 25, 31) for r in range(64)], np.int32)
+    exact = oracle.attn_exact(qb, kb, vb, dt, True, scale, rows).reshape(3, 64, 128)
+    qm = oracle.block_means(qb, dt, 64); km = oracle.block_means(kb, dt, 64)
+    idx, cnt = oracle.select_topk(qm, km, 64, 64, True, 0.05)
+    e4 = metrics.rel_fro(oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, sample, force_path=0), exact)
+    e16 = metrics.rel_fro(oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, sample, force_path=1), exact)
+    em = metrics.rel_fro(oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, 64, 64, True, scale, sample), exact)
+    assert e16 < em < e4
+    assert metrics.recovery(e16, e4, em) > 0.5
+    # worst-scored blocks instead of best-scored ones recover less
+    scores = oracle.block_scores(qm, km)
+    bad_idx = np.full_like(idx, -1)
+    for i in range(32):
+        order = np.argsort(scores[0, 0, i, :i + 1], kind="stable")[:cnt[0, 0, i]]
+        bad_idx[0, 0, i, :cnt[0, 0, i]] = np.sort(order)
+    eb = metrics.rel_fro(oracle.attn_thrift_prefill(qb, kb, vb, dt, bad_idx, cnt, 64, 64, True, scale, sample), exact)
+    assert em < eb
+
+
+def test_error_bound_diagnostic_bookkeeping(oracle):
+    """Eq. (4) right-hand side, split by key block: non-negative terms that add up to the total and
+    vanish for blocks the (causal) row cannot see."""
+    w = W.TINY
+    q, k, v, _, _ = W.make_prefill(w)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    t = 20 * 64 + 10
+    total, per = oracle.error_bound_rhs(qb[0, 0, t], kb[0, 0], vb[0, 0], dt, 64, t + 1, 1 / math.sqrt(128))
+    assert total > 0 and np.all(per >= 0)
+    assert abs(per.sum() - total) < 1e-12 * max(1, total)
+    assert np.all(per[21:] == 0) and per[20] > 0
