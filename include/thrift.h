@@ -1,0 +1,171 @@
+/*
+ * thrift.h — C ABI of the MI355X (gfx950) library for block-selective mixed-precision attention
+ * (ThriftAttention, arXiv 2605.23081).
+ *
+ * The five compute entry points are the steps of the paper's Algorithm 1:
+ *   thrift_block_means      Alg. 1 step 3   (Sec. 3.2 "Block-importance scoring")
+ *   thrift_select_topk      Alg. 1 step 5   (Sec. 3.2, TopK of  Qbar_i . Kbar_j ; causal restriction
+ *                                            of the last paragraph of Sec. 3.2)
+ *   thrift_quantize_mxfp4   Alg. 1 step 2   (Sec. 3.2 "FP4 quantisation", in MXFP4: E2M1 elements with
+ *                                            one E8M0 scale per 32 elements instead of NVFP4)
+ *   thrift_attn_prefill     Alg. 1 steps 4-23 (Sec. 3.2 "Mixed-precision attention computation", Sec. 3.3)
+ *   thrift_attn_decode      the same algorithm for one query token over a dual 4-bit / 16-bit KV
+ *                           cache (Sec. 4.1, last sentences; Sec. 5), evaluated split-K
+ *
+ * Conventions shared by every call
+ *   - Every pointer is a DEVICE pointer unless the comment says "host".  The caller owns every
+ *     buffer; the library never allocates, frees or synchronises.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Arguments are validated on the host before anything is launched.  On a status other than
+ *     THRIFT_OK nothing has been launched and no output has been touched.
+ *   - No global state: calls on different streams are independent.
+ *   - Tensors are contiguous, last index fastest.  16-bit tensors are IEEE fp16 (THRIFT_F16) or
+ *     bfloat16 (THRIFT_BF16).
+ *   - Shape limits of this version: D == 128, Bk == 64, Bq in {64, 128} (prefill), N a multiple of
+ *     Bq and of Bk, Hq a multiple of Hkv, at most 4096 key blocks per row.  Anything else returns
+ *     THRIFT_ERR_SHAPE.
+ *
+ * MXFP4 as used here (OCP Microscaling v1.0 conversion)
+ *   A group of 32 values with a = max|x| gets the scale byte e+127, e = floor(log2 a) - 2 clamped to
+ *   [-127,127] (an all-zero group gets 127); each element is x * 2^-e rounded to the E2M1 grid
+ *   {0, .5, 1, 1.5, 2, 3, 4, 6} to nearest, ties to the even code, magnitudes above 6 saturating to 6;
+ *   code bit 3 is the sign (kept when the magnitude rounds to zero), bits 2-1 the exponent, bit 0 the
+ *   mantissa.  Two codes share a byte: the element with the even index along the group axis sits in
+ *   the low nibble.  Inf / NaN inputs are not supported.
+ */
+#ifndef THRIFT_H_
+#define THRIFT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  THRIFT_OK = 0,
+  THRIFT_ERR_NULL = 1,      /* a required pointer is NULL */
+  THRIFT_ERR_SHAPE = 2,     /* unsupported or inconsistent sizes */
+  THRIFT_ERR_DTYPE = 3,     /* unknown dtype code */
+  THRIFT_ERR_BUDGET = 4,    /* budget outside [0,1] (and no fixed_k), or kmax too small for it */
+  THRIFT_ERR_WORKSPACE = 5, /* workspace missing or smaller than thrift_*_workspace() */
+  THRIFT_ERR_ARCH = 6,      /* the current device is not gfx950 */
+  THRIFT_ERR_LAUNCH = 7     /* the HIP runtime refused a launch */
+} thrift_status;
+
+typedef enum { THRIFT_F16 = 0, THRIFT_BF16 = 1, THRIFT_F32 = 2 /* outputs only */ } thrift_dtype;
+
+/* Host: static string for a status code. */
+const char* thrift_status_string(thrift_status s);
+
+/* Host: FP16 budget of one query-block row (benchmark rule: ceil(budget * visible), at least 1 when
+ * budget > 0, at most visible; budget is rounded to millionths and the ceiling is taken in integers).
+ * fixed_k >= 0 overrides it: min(fixed_k, visible) — the paper's single global k. */
+int thrift_row_budget(int visible, double budget, int fixed_k);
+
+/* Host: key blocks visible to query block i (+ q_block_offset) under the causal restriction of
+ * Sec. 3.2: block j is visible iff j*Bk <= (i + q_block_offset + 1)*Bq - 1.  Non-causal: Tk. */
+int thrift_visible_blocks(int i, int Tk, int Bq, int Bk, int causal, int q_block_offset);
+
+/* Host: the global k of App. B "ThriftAttention settings": the k in [1,n] whose causal tile fraction
+ * (k n - k(k-1)/2) / (n(n+1)/2) is closest to `fraction` (ties: smaller k). */
+int thrift_budget_to_global_k(int n_blocks, double fraction);
+
+/* Host: the largest per-row count thrift_select_topk will write for these arguments (size of the
+ * last axis the caller must give idx). */
+int thrift_select_kmax(int Tq, int Tk, int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset);
+
+/*
+ * Block token means (Sec. 3.2; Alg. 1 step 3).
+ *   x      [B,H,N,D] 16-bit (dt)
+ *   means  [B,H,N/block,D] fp32: arithmetic mean over the block's tokens, accumulated in fp64 and
+ *          rounded once.  block must divide N (any block >= 1).
+ */
+thrift_status thrift_block_means(const void* x, thrift_dtype dt, int B, int H, int N, int D, int block,
+                                 float* means, void* stream);
+
+/*
+ * Block-pair scores S_ij = Qbar_i . Kbar_j (no 1/sqrt(d); fp64 accumulation) and per-row TopK
+ * (Sec. 3.2; Alg. 1 step 5), restricted to causally visible key blocks when causal != 0.
+ *   qmean [B,Hq,Tq,D], kmean [B,Hkv,Tk,D] fp32; query head h uses KV head h / (Hq/Hkv).
+ *   budget in [0,1] with fixed_k < 0, or fixed_k >= 0 (then budget is ignored); see thrift_row_budget.
+ *   q_block_offset shifts the causal frontier (decode: Bq = 1, offset = position of the token).
+ *   idx [B,Hq,Tq,kmax] int32: the selected block ids of each row in ascending order, padded with -1.
+ *   cnt [B,Hq,Tq] int32: how many were selected.
+ * Equal scores are ordered by the smaller block id.  kmax < thrift_select_kmax(...) is THRIFT_ERR_BUDGET.
+ */
+thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                                 int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
+                                 int32_t* idx, int32_t* cnt, int kmax, void* stream);
+
+/*
+ * MXFP4 quantisation (Sec. 3.2 "FP4 quantisation"; Alg. 1 step 2).
+ *   x [B,H,N,D] 16-bit (dt).
+ *   axis 0 (Q and K: groups of 32 along D):
+ *       codes  [B,H,N,D/2]   byte t of a row holds elements 2t (low nibble) and 2t+1
+ *       scales [B,H,N,D/32]
+ *   axis 1 (V: groups of 32 along the token axis, the contraction axis of P.V; N % 64 == 0):
+ *       codes  [B,H,N/64,D,32]  per 64-token block and channel, byte t holds tokens 2t (low) and 2t+1
+ *       scales [B,H,N/32,D]
+ */
+thrift_status thrift_quantize_mxfp4(const void* x, thrift_dtype dt, int B, int H, int N, int D, int axis,
+                                    uint8_t* codes, uint8_t* scales, void* stream);
+
+/* Host: bytes of workspace thrift_attn_prefill needs (may be 0; then workspace may be NULL). */
+size_t thrift_attn_prefill_workspace(int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int kmax);
+
+/*
+ * Fused mixed-precision flash attention (Alg. 1 steps 4-23).  For each query block i the key blocks
+ * are visited in ascending order; block j runs on the 16-bit matrix path when j is in idx[b,h,i,:cnt]
+ * and on the MXFP4 matrix path otherwise; both update one (m, l, O) online-softmax state per row; l
+ * accumulates the unquantised probabilities on both paths; on the 4-bit path P is quantised per row in
+ * groups of 32 keys (E8M0 scale: the first-level scale of Alg. 1 step 19 is identically 1), on the
+ * 16-bit path P is rounded to dt.
+ *   q [B,Hq,N,D], k,v [B,Hkv,N,D]                 16-bit (dt), read only for the selected tiles
+ *   q4,qs / k4,ks : thrift_quantize_mxfp4(axis 0) of q / k;   v4,vs : axis 1 of v
+ *   idx [B,Hq,N/Bq,kmax], cnt [B,Hq,N/Bq]         from thrift_select_topk (ascending, padded -1)
+ *   softmax_scale <= 0 selects 1/sqrt(D)
+ *   out [B,Hq,N,D] in out_dt (THRIFT_F16, THRIFT_BF16 or THRIFT_F32)
+ *   lse (nullable) [B,Hq,N] fp32: log-sum-exp of the scaled scores of each row
+ */
+thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, thrift_dtype dt,
+                                  const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
+                                  const uint8_t* v4, const uint8_t* vs,
+                                  const int32_t* idx, const int32_t* cnt, int kmax,
+                                  int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, float softmax_scale,
+                                  void* out, thrift_dtype out_dt, float* lse,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Host: bytes of workspace thrift_attn_decode needs. */
+size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int Bk, int split_blocks);
+
+/*
+ * Decode over a dual KV cache: one query token per (sequence, query head) at position seqlen-1, so
+ * every cached key is visible.  The call (i) scores the cached key-block means against the query
+ * (the block mean of a one-token block is the token) and selects ceil(budget * blocks) blocks per
+ * query head (or fixed_k), (ii) runs Alg. 1 per (sequence, KV head, partition of split_blocks key
+ * blocks) for the Hq/Hkv query heads of the group — MXFP4 codes for non-selected blocks, the 16-bit
+ * copy for selected ones — and (iii) merges the partitions by their log-sum-exp.
+ *   q [B,Hq,D] 16-bit (dt)
+ *   k16,v16 [B,Hkv,Nkv,D] 16-bit (dt)             read only for selected blocks
+ *   k4,ks (axis 0) and v4,vs (axis 1) of the same cache; kmean [B,Hkv,Nkv/Bk,D] fp32
+ *   seqlens (nullable, device) [B] int32: valid tokens per sequence, multiples of Bk, <= Nkv; NULL = Nkv
+ *   split_blocks: key blocks per partition (> 0)
+ *   out [B,Hq,D] in out_dt
+ *   idx_out (nullable) [B,Hq,kmax_out], cnt_out (nullable) [B,Hq]: the selection that was used
+ *     (kmax_out >= thrift_select_kmax(1, Nkv/Bk, 1, Bk, 0, budget, fixed_k, 0))
+ *   workspace: thrift_attn_decode_workspace(...) bytes
+ */
+thrift_status thrift_attn_decode(const void* q, thrift_dtype dt, const void* k16, const void* v16,
+                                 const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
+                                 const float* kmean, const int32_t* seqlens,
+                                 int B, int Hq, int Hkv, int Nkv, int D, int Bk,
+                                 double budget, int fixed_k, int split_blocks, float softmax_scale,
+                                 void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* THRIFT_H_ */

@@ -1,0 +1,242 @@
+"""Thin ctypes binding of the C ABI in include/thrift.h: argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libthrift_hip.so; PyTorch is used for device
+memory and for the current stream.  There is no CPU fallback: if the library has not been built
+(``python -m paper_2605_23081_amd.build``) importing a function from here raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libthrift_hip.so")
+
+F16, BF16, F32 = 0, 1, 2
+_DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
+
+EXPORTS = (
+    "thrift_status_string", "thrift_row_budget", "thrift_visible_blocks", "thrift_budget_to_global_k",
+    "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_quantize_mxfp4",
+    "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_decode_workspace", "thrift_attn_decode",
+)
+
+_lib = None
+
+
+class ThriftError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: status {code} ({status_string(code)})")
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_23081_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        i, d, f, p, sz = C.c_int, C.c_double, C.c_float, C.c_void_p, C.c_size_t
+        L.thrift_status_string.restype = C.c_char_p
+        L.thrift_status_string.argtypes = [i]
+        L.thrift_row_budget.argtypes = [i, d, i]
+        L.thrift_visible_blocks.argtypes = [i] * 6
+        L.thrift_budget_to_global_k.argtypes = [i, d]
+        L.thrift_select_kmax.argtypes = [i, i, i, i, i, d, i, i]
+        L.thrift_block_means.argtypes = [p, i, i, i, i, i, i, p, p]
+        L.thrift_select_topk.argtypes = [p, p, i, i, i, i, i, i, i, i, i, d, i, i, p, p, i, p]
+        L.thrift_quantize_mxfp4.argtypes = [p, i, i, i, i, i, i, p, p, p]
+        L.thrift_attn_prefill_workspace.restype = sz
+        L.thrift_attn_prefill_workspace.argtypes = [i] * 8
+        L.thrift_attn_prefill.argtypes = [p, p, p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, i, i, i, f, p, i, p, p, sz, p]
+        L.thrift_attn_decode_workspace.restype = sz
+        L.thrift_attn_decode_workspace.argtypes = [i] * 7
+        L.thrift_attn_decode.argtypes = [p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, d, i, i, f, p, i, p, p, i, p, sz, p]
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().thrift_status_string(int(code)).decode()
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise ThriftError(code, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype=None) -> torch.Tensor:
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    if dtype is not None:
+        assert t.dtype == dtype, (t.dtype, dtype)
+    return t
+
+
+# ---- host helpers ----
+
+def row_budget(visible: int, budget: float, fixed_k: int = -1) -> int:
+    return int(lib().thrift_row_budget(int(visible), float(budget), int(fixed_k)))
+
+
+def visible_blocks(i: int, Tk: int, Bq: int, Bk: int, causal: bool, q_block_offset: int = 0) -> int:
+    return int(lib().thrift_visible_blocks(i, Tk, Bq, Bk, int(causal), q_block_offset))
+
+
+def budget_to_global_k(n_blocks: int, fraction: float) -> int:
+    return int(lib().thrift_budget_to_global_k(int(n_blocks), float(fraction)))
+
+
+def select_kmax(Tq: int, Tk: int, Bq: int, Bk: int, causal: bool, budget: float, fixed_k: int = -1,
+                q_block_offset: int = 0) -> int:
+    return int(lib().thrift_select_kmax(Tq, Tk, Bq, Bk, int(causal), float(budget), int(fixed_k), q_block_offset))
+
+
+# ---- the five compute calls ----
+
+def thrift_block_means(x: torch.Tensor, block: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(x)
+    B, H, N, D = x.shape
+    if out is None:
+        out = torch.empty(B, H, N // max(block, 1), D, dtype=torch.float32, device=x.device)
+    _check(lib().thrift_block_means(_ptr(x), _DT[x.dtype], B, H, N, D, block, _ptr(out), _stream()), "thrift_block_means")
+    return out
+
+
+def thrift_select_topk(qmean: torch.Tensor, kmean: torch.Tensor, Bq: int, Bk: int, causal: bool, budget: float,
+                       fixed_k: int = -1, q_block_offset: int = 0, kmax: Optional[int] = None,
+                       idx: Optional[torch.Tensor] = None, cnt: Optional[torch.Tensor] = None
+                       ) -> Tuple[torch.Tensor, torch.Tensor]:
+    _dev(qmean, torch.float32), _dev(kmean, torch.float32)
+    B, Hq, Tq, D = qmean.shape
+    _, Hkv, Tk, _ = kmean.shape
+    if kmax is None:
+        kmax = max(1, select_kmax(Tq, Tk, Bq, Bk, causal, budget, fixed_k, q_block_offset))
+    if idx is None:
+        idx = torch.empty(B, Hq, Tq, kmax, dtype=torch.int32, device=qmean.device)
+        cnt = torch.empty(B, Hq, Tq, dtype=torch.int32, device=qmean.device)
+    _check(lib().thrift_select_topk(_ptr(qmean), _ptr(kmean), B, Hq, Hkv, Tq, Tk, D, Bq, Bk, int(causal), float(budget),
+                                    int(fixed_k), int(q_block_offset), _ptr(idx), _ptr(cnt), int(kmax), _stream()),
+           "thrift_select_topk")
+    return idx, cnt
+
+
+def thrift_quantize_mxfp4(x: torch.Tensor, axis: int, codes: Optional[torch.Tensor] = None,
+                          scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    _dev(x)
+    B, H, N, D = x.shape
+    if codes is None:
+        if axis == 0:
+            codes = torch.empty(B, H, N, D // 2, dtype=torch.uint8, device=x.device)
+            scales = torch.empty(B, H, N, D // 32, dtype=torch.uint8, device=x.device)
+        else:
+            codes = torch.empty(B, H, max(N // 64, 0), D, 32, dtype=torch.uint8, device=x.device)
+            scales = torch.empty(B, H, max(N // 32, 0), D, dtype=torch.uint8, device=x.device)
+    _check(lib().thrift_quantize_mxfp4(_ptr(x), _DT[x.dtype], B, H, N, D, int(axis), _ptr(codes), _ptr(scales), _stream()),
+           "thrift_quantize_mxfp4")
+    return codes, scales
+
+
+def thrift_attn_prefill(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq: int, Bk: int, causal: bool,
+                        softmax_scale: float = 0.0, out: Optional[torch.Tensor] = None,
+                        out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None) -> torch.Tensor:
+    for t in (q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt):
+        _dev(t)
+    B, Hq, N, D = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        out = torch.empty(B, Hq, N, D, dtype=out_dtype or q.dtype, device=q.device)
+    kmax = idx.shape[-1]
+    ws_bytes = lib().thrift_attn_prefill_workspace(B, Hq, Hkv, N, D, Bq, Bk, kmax)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=q.device) if ws_bytes else None
+    _check(lib().thrift_attn_prefill(_ptr(q), _ptr(k), _ptr(v), _DT[q.dtype], _ptr(q4), _ptr(qs), _ptr(k4), _ptr(ks),
+                                     _ptr(v4), _ptr(vs), _ptr(idx), _ptr(cnt), kmax, B, Hq, Hkv, N, D, Bq, Bk,
+                                     int(causal), float(softmax_scale), _ptr(out), _DT[out.dtype], _ptr(lse), _ptr(ws),
+                                     ws_bytes, _stream()), "thrift_attn_prefill")
+    return out
+
+
+def decode_workspace_bytes(B: int, Hq: int, Hkv: int, Nkv: int, D: int, Bk: int, split_blocks: int) -> int:
+    return int(lib().thrift_attn_decode_workspace(B, Hq, Hkv, Nkv, D, Bk, split_blocks))
+
+
+def thrift_attn_decode(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budget: float, fixed_k: int = -1,
+                       split_blocks: int = 256, softmax_scale: float = 0.0, seqlens: Optional[torch.Tensor] = None,
+                       out: Optional[torch.Tensor] = None, out_dtype: Optional[torch.dtype] = None,
+                       workspace: Optional[torch.Tensor] = None, return_selection: bool = False):
+    for t in (q, k16, v16, k4, ks, v4, vs, kmean):
+        _dev(t)
+    B, Hq, D = q.shape
+    _, Hkv, Nkv, _ = k16.shape
+    if out is None:
+        out = torch.empty(B, Hq, D, dtype=out_dtype or q.dtype, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(max(decode_workspace_bytes(B, Hq, Hkv, Nkv, D, Bk, split_blocks), 16), dtype=torch.uint8,
+                                device=q.device)
+    idx = cnt = None
+    kmax = 0
+    if return_selection:
+        kmax = max(1, row_budget(Nkv // Bk, budget, fixed_k))
+        idx = torch.empty(B, Hq, kmax, dtype=torch.int32, device=q.device)
+        cnt = torch.empty(B, Hq, dtype=torch.int32, device=q.device)
+    _check(lib().thrift_attn_decode(_ptr(q), _DT[q.dtype], _ptr(k16), _ptr(v16), _ptr(k4), _ptr(ks), _ptr(v4), _ptr(vs),
+                                    _ptr(kmean), _ptr(seqlens), B, Hq, Hkv, Nkv, D, Bk, float(budget), int(fixed_k),
+                                    int(split_blocks), float(softmax_scale), _ptr(out), _DT[out.dtype], _ptr(idx), _ptr(cnt),
+                                    kmax, _ptr(workspace), workspace.numel(), _stream()), "thrift_attn_decode")
+    return (out, idx, cnt) if return_selection else out
+
+
+# ---- Alg. 1 end to end: the user-level form of the paper's signature ----
+
+class PrefillPlan:
+    """Buffers of one prefill problem, allocated once so that repeated steps do not allocate."""
+
+    def __init__(self, B, Hq, Hkv, N, D, Bq, Bk, causal, budget, dtype, device, fixed_k=-1, out_dtype=None):
+        self.args = (B, Hq, Hkv, N, D, Bq, Bk, causal, budget, fixed_k)
+        dev = device
+        u8, f32, i32 = torch.uint8, torch.float32, torch.int32
+        self.qmean = torch.empty(B, Hq, N // Bq, D, dtype=f32, device=dev)
+        self.kmean = torch.empty(B, Hkv, N // Bk, D, dtype=f32, device=dev)
+        self.kmax = max(1, select_kmax(N // Bq, N // Bk, Bq, Bk, causal, budget, fixed_k))
+        self.idx = torch.empty(B, Hq, N // Bq, self.kmax, dtype=i32, device=dev)
+        self.cnt = torch.empty(B, Hq, N // Bq, dtype=i32, device=dev)
+        self.q4 = torch.empty(B, Hq, N, D // 2, dtype=u8, device=dev)
+        self.qs = torch.empty(B, Hq, N, D // 32, dtype=u8, device=dev)
+        self.k4 = torch.empty(B, Hkv, N, D // 2, dtype=u8, device=dev)
+        self.ks = torch.empty(B, Hkv, N, D // 32, dtype=u8, device=dev)
+        self.v4 = torch.empty(B, Hkv, N // 64, D, 32, dtype=u8, device=dev)
+        self.vs = torch.empty(B, Hkv, N // 32, D, dtype=u8, device=dev)
+        self.out = torch.empty(B, Hq, N, D, dtype=out_dtype or dtype, device=dev)
+
+    def run(self, q, k, v, softmax_scale: float = 0.0, prepass: bool = True, attention: bool = True) -> torch.Tensor:
+        B, Hq, Hkv, N, D, Bq, Bk, causal, budget, fixed_k = self.args
+        if prepass:
+            thrift_block_means(q, Bq, out=self.qmean)
+            thrift_block_means(k, Bk, out=self.kmean)
+            thrift_select_topk(self.qmean, self.kmean, Bq, Bk, causal, budget, fixed_k, kmax=self.kmax, idx=self.idx, cnt=self.cnt)
+            thrift_quantize_mxfp4(q, 0, self.q4, self.qs)
+            thrift_quantize_mxfp4(k, 0, self.k4, self.ks)
+            thrift_quantize_mxfp4(v, 1, self.v4, self.vs)
+        if attention:
+            thrift_attn_prefill(q, k, v, self.q4, self.qs, self.k4, self.ks, self.v4, self.vs, self.idx, self.cnt, Bq, Bk,
+                                causal, softmax_scale, out=self.out)
+        return self.out
+
+
+def thrift_attention(q, k, v, causal: bool = True, Bq: int = 128, Bk: int = 64, budget: float = 0.05,
+                     fixed_k: int = -1, softmax_scale: float = 0.0, out_dtype=None) -> torch.Tensor:
+    """Alg. 1: Q, K, V, block sizes and FP16 budget in, attention output out (all stages on the GPU)."""
+    B, Hq, N, D = q.shape
+    plan = PrefillPlan(B, Hq, k.shape[1], N, D, Bq, Bk, causal, budget, q.dtype, q.device, fixed_k, out_dtype)
+    return plan.run(q, k, v, softmax_scale)

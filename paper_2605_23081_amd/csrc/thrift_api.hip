@@ -1,0 +1,252 @@
+// C ABI of the library: host-side validation, budget arithmetic and kernel dispatch.
+// Nothing here allocates, frees or synchronises; on any error nothing is launched.
+#include <math.h>
+#include <string.h>
+
+#include "thrift_launch.h"
+
+using namespace thrift;
+
+namespace {
+
+constexpr int kHeadDim = 128;
+constexpr int kKeyBlock = 64;
+constexpr int kMaxKeyBlocks = 4096;
+
+long long budget_ppm(double budget) { return llround(budget * 1e6); }
+
+bool is16(thrift_dtype dt) { return dt == THRIFT_F16 || dt == THRIFT_BF16; }
+bool is_out(thrift_dtype dt) { return dt == THRIFT_F16 || dt == THRIFT_BF16 || dt == THRIFT_F32; }
+
+// gfx950 check, cached per device ordinal (read-mostly; a benign race writes the same value).
+thrift_status check_arch() {
+  static int cache[64] = {0};   // 0 unknown, 1 ok, 2 wrong
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return THRIFT_ERR_ARCH;
+  if (dev >= 0 && dev < 64 && cache[dev] != 0) return cache[dev] == 1 ? THRIFT_OK : THRIFT_ERR_ARCH;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return THRIFT_ERR_ARCH;
+  const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+  if (dev >= 0 && dev < 64) cache[dev] = ok ? 1 : 2;
+  return ok ? THRIFT_OK : THRIFT_ERR_ARCH;
+}
+
+thrift_status after_launch() { return hipGetLastError() == hipSuccess ? THRIFT_OK : THRIFT_ERR_LAUNCH; }
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct DecodeLayout {
+  size_t qf32, q4, qs, idx, cnt, bitmap, part_o, part_ml, total;
+  int nsplit, nparts, words;
+};
+
+DecodeLayout decode_layout(int B, int Hq, int Nkv, int Bk, int split_blocks) {
+  DecodeLayout L;
+  const int Tk = Nkv / Bk;
+  L.nsplit = (Tk + split_blocks - 1) / split_blocks;
+  L.nparts = L.nsplit * 4;                       // one partial per wavefront of a partition's workgroup
+  L.words = (Tk + 63) / 64;
+  size_t off = 0;
+  L.qf32 = off; off += align256((size_t)B * Hq * kHeadDim * sizeof(float));
+  L.q4 = off; off += align256((size_t)B * Hq * (kHeadDim / 2));
+  L.qs = off; off += align256((size_t)B * Hq * (kHeadDim / 32));
+  L.idx = off; off += align256((size_t)B * Hq * Tk * sizeof(int32_t));
+  L.cnt = off; off += align256((size_t)B * Hq * sizeof(int32_t));
+  L.bitmap = off; off += align256((size_t)B * Hq * L.words * sizeof(unsigned long long));
+  L.part_o = off; off += align256((size_t)B * Hq * L.nparts * kHeadDim * sizeof(float));
+  L.part_ml = off; off += align256((size_t)B * Hq * L.nparts * 2 * sizeof(float));
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* thrift_status_string(thrift_status s) {
+  switch (s) {
+    case THRIFT_OK: return "ok";
+    case THRIFT_ERR_NULL: return "null pointer";
+    case THRIFT_ERR_SHAPE: return "unsupported or inconsistent shape";
+    case THRIFT_ERR_DTYPE: return "unknown dtype";
+    case THRIFT_ERR_BUDGET: return "budget out of range or kmax too small";
+    case THRIFT_ERR_WORKSPACE: return "workspace missing or too small";
+    case THRIFT_ERR_ARCH: return "device is not gfx950";
+    case THRIFT_ERR_LAUNCH: return "kernel launch failed";
+  }
+  return "unknown status";
+}
+
+int thrift_row_budget(int visible, double budget, int fixed_k) {
+  if (visible < 0) visible = 0;
+  if (fixed_k >= 0) return fixed_k < visible ? fixed_k : visible;
+  const long long ppm = budget_ppm(budget);
+  if (ppm <= 0) return 0;
+  long long k = (ppm * (long long)visible + 999999LL) / 1000000LL;
+  if (k < 1) k = 1;
+  if (k > visible) k = visible;
+  return (int)k;
+}
+
+int thrift_visible_blocks(int i, int Tk, int Bq, int Bk, int causal, int q_block_offset) {
+  if (!causal) return Tk;
+  const long long last_q = ((long long)i + q_block_offset + 1) * Bq - 1;
+  long long v = last_q / Bk + 1;
+  if (v > Tk) v = Tk;
+  if (v < 0) v = 0;
+  return (int)v;
+}
+
+int thrift_budget_to_global_k(int n, double fraction) {
+  int best = 1;
+  double bestd = INFINITY;
+  for (int k = 1; k <= n; ++k) {
+    const double frac = ((double)k * n - (double)k * (k - 1) / 2.0) / ((double)n * (n + 1) / 2.0);
+    const double d = fabs(frac - fraction);
+    if (d < bestd) { bestd = d; best = k; }
+  }
+  return best;
+}
+
+int thrift_select_kmax(int Tq, int Tk, int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset) {
+  // the row budget grows with the number of visible blocks, which grows with i
+  int kmax = 0;
+  if (Tq <= 0) return 0;
+  const int v_last = thrift_visible_blocks(Tq - 1, Tk, Bq, Bk, causal, q_block_offset);
+  const int v_first = thrift_visible_blocks(0, Tk, Bq, Bk, causal, q_block_offset);
+  kmax = thrift_row_budget(v_last, budget, fixed_k);
+  const int k0 = thrift_row_budget(v_first, budget, fixed_k);
+  return kmax > k0 ? kmax : k0;
+}
+
+thrift_status thrift_block_means(const void* x, thrift_dtype dt, int B, int H, int N, int D, int block,
+                                 float* means, void* stream) {
+  if (!x || !means) return THRIFT_ERR_NULL;
+  if (!is16(dt)) return THRIFT_ERR_DTYPE;
+  if (B <= 0 || H <= 0 || N <= 0 || D != kHeadDim || block <= 0 || N % block != 0) return THRIFT_ERR_SHAPE;
+  const long n_blocks = (long)B * H * (N / block);
+  if (n_blocks > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (thrift_status s = check_arch()) return s;
+  launch_block_means(x, dt, n_blocks, block, means, (hipStream_t)stream);
+  return after_launch();
+}
+
+thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                                 int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
+                                 int32_t* idx, int32_t* cnt, int kmax, void* stream) {
+  if (!qmean || !kmean || !idx || !cnt) return THRIFT_ERR_NULL;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Tq <= 0 || Tk <= 0 || Tk > kMaxKeyBlocks || D != kHeadDim ||
+      Bq <= 0 || Bk <= 0 || q_block_offset < 0 || kmax <= 0)
+    return THRIFT_ERR_SHAPE;
+  if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
+  if (kmax < thrift_select_kmax(Tq, Tk, Bq, Bk, causal, budget, fixed_k, q_block_offset)) return THRIFT_ERR_BUDGET;
+  if ((long)B * Hkv * (((long)Tq * (Hq / Hkv) + 3) / 4) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (thrift_status s = check_arch()) return s;
+  SelectArgs a;
+  a.qmean = qmean; a.kmean = kmean; a.idx = idx; a.cnt = cnt; a.bitmap = nullptr; a.seqlens = nullptr; a.bitmap_words = 0;
+  a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Tq = Tq; a.Tk = Tk; a.Bq = Bq; a.Bk = Bk; a.causal = causal ? 1 : 0;
+  a.fixed_k = fixed_k; a.q_block_offset = q_block_offset; a.kmax = kmax; a.ppm = fixed_k >= 0 ? 0 : budget_ppm(budget);
+  launch_select_topk(a, (hipStream_t)stream);
+  return after_launch();
+}
+
+thrift_status thrift_quantize_mxfp4(const void* x, thrift_dtype dt, int B, int H, int N, int D, int axis,
+                                    uint8_t* codes, uint8_t* scales, void* stream) {
+  if (!x || !codes || !scales) return THRIFT_ERR_NULL;
+  if (!is16(dt)) return THRIFT_ERR_DTYPE;
+  if (B <= 0 || H <= 0 || N <= 0 || D != kHeadDim || (axis != 0 && axis != 1)) return THRIFT_ERR_SHAPE;
+  if (axis == 1 && N % 64 != 0) return THRIFT_ERR_SHAPE;
+  const long bh = (long)B * H;
+  if (axis == 1 && bh * (N / 64) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (axis == 0 && ((size_t)bh * N * (kHeadDim / 32) + 255) / 256 > 0x7fffffffUL) return THRIFT_ERR_SHAPE;
+  if (thrift_status s = check_arch()) return s;
+  launch_quantize(x, dt, bh, N, axis, codes, scales, (hipStream_t)stream);
+  return after_launch();
+}
+
+size_t thrift_attn_prefill_workspace(int, int, int, int, int, int, int, int) { return 0; }
+
+thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, thrift_dtype dt,
+                                  const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
+                                  const uint8_t* v4, const uint8_t* vs,
+                                  const int32_t* idx, const int32_t* cnt, int kmax,
+                                  int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, float softmax_scale,
+                                  void* out, thrift_dtype out_dt, float* lse,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (!q || !k || !v || !q4 || !qs || !k4 || !ks || !v4 || !vs || !idx || !cnt || !out) return THRIFT_ERR_NULL;
+  if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || N <= 0 || D != kHeadDim || Bk != kKeyBlock ||
+      (Bq != 64 && Bq != 128) || N % Bq != 0 || N % Bk != 0 || kmax <= 0 || N / Bk > kMaxKeyBlocks)
+    return THRIFT_ERR_SHAPE;
+  if ((long)B * Hq * (N / Bq) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (thrift_status s = check_arch()) return s;
+  PrefillArgs a;
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
+  a.q4 = q4; a.qs = qs; a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.idx = idx; a.cnt = cnt;
+  a.out = out; a.lse = lse; a.kmax = kmax; a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.N = N; a.Bq = Bq; a.causal = causal ? 1 : 0;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+  a.dt = dt; a.out_dt = out_dt;
+  launch_prefill(a, (hipStream_t)stream);
+  return after_launch();
+}
+
+size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int Bk, int split_blocks) {
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock || split_blocks <= 0 || Nkv % Bk != 0)
+    return 0;
+  return decode_layout(B, Hq, Nkv, Bk, split_blocks).total;
+}
+
+thrift_status thrift_attn_decode(const void* q, thrift_dtype dt, const void* k16, const void* v16,
+                                 const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
+                                 const float* kmean, const int32_t* seqlens,
+                                 int B, int Hq, int Hkv, int Nkv, int D, int Bk,
+                                 double budget, int fixed_k, int split_blocks, float softmax_scale,
+                                 void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (!q || !k16 || !v16 || !k4 || !ks || !v4 || !vs || !kmean || !out) return THRIFT_ERR_NULL;
+  if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Hq / Hkv > 32 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock ||
+      Nkv % Bk != 0 || Nkv / Bk > kMaxKeyBlocks || split_blocks <= 0 || split_blocks % 4 != 0)
+    return THRIFT_ERR_SHAPE;
+  if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
+  const int Tk = Nkv / Bk;
+  const int kneed = thrift_row_budget(Tk, budget, fixed_k);
+  if (idx_out && (kmax_out < kneed || kmax_out <= 0)) return THRIFT_ERR_BUDGET;
+  if (idx_out && !cnt_out) return THRIFT_ERR_NULL;
+  const DecodeLayout L = decode_layout(B, Hq, Nkv, Bk, split_blocks);
+  if (!workspace) return THRIFT_ERR_WORKSPACE;
+  if (workspace_bytes < L.total) return THRIFT_ERR_WORKSPACE;
+  if (((uintptr_t)workspace & 15) != 0) return THRIFT_ERR_WORKSPACE;
+  if (thrift_status s = check_arch()) return s;
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* qf32 = (float*)(ws + L.qf32);
+  int32_t* idx = (int32_t*)(ws + L.idx);
+  int32_t* cnt = (int32_t*)(ws + L.cnt);
+
+  // (i) the query token is its own block mean; score it against the cached key-block means
+  launch_block_means(q, dt, (long)B * Hq, 1, qf32, st);
+  launch_quantize(q, dt, (long)B * Hq, 1, 0, (uint8_t*)(ws + L.q4), (uint8_t*)(ws + L.qs), st);
+  SelectArgs sa;
+  sa.qmean = qf32; sa.kmean = kmean; sa.idx = idx; sa.cnt = cnt;
+  sa.bitmap = (unsigned long long*)(ws + L.bitmap); sa.bitmap_words = L.words; sa.seqlens = seqlens;
+  sa.B = B; sa.Hq = Hq; sa.Hkv = Hkv; sa.Tq = 1; sa.Tk = Tk; sa.Bq = 1; sa.Bk = Bk; sa.causal = 0;
+  sa.fixed_k = fixed_k; sa.q_block_offset = 0; sa.kmax = Tk; sa.ppm = fixed_k >= 0 ? 0 : budget_ppm(budget);
+  launch_select_topk(sa, st);
+  if (idx_out) launch_copy_selection(idx, cnt, Tk, idx_out, cnt_out, kmax_out, (long)B * Hq, st);
+
+  // (ii) split-K partial attention, (iii) log-sum-exp merge
+  DecodeArgs a;
+  a.q = (const uint16_t*)q; a.q4 = (const uint8_t*)(ws + L.q4); a.qs = (const uint8_t*)(ws + L.qs); a.k16 = (const uint16_t*)k16; a.v16 = (const uint16_t*)v16;
+  a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.seqlens = seqlens;
+  a.bitmap = sa.bitmap; a.bitmap_words = L.words;
+  a.out = out; a.part_o = (float*)(ws + L.part_o); a.part_ml = (float*)(ws + L.part_ml);
+  a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Nkv = Nkv; a.split_blocks = split_blocks; a.nsplit = L.nsplit; a.nparts = L.nparts;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+  a.dt = dt; a.out_dt = out_dt;
+  launch_decode(a, st);
+  return after_launch();
+}
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+// Host-side launch interface between the C ABI layer and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "thrift.h"
+
+namespace thrift {
+
+void launch_block_means(const void* x, thrift_dtype dt, long n_blocks, int block, float* means, hipStream_t st);
+void launch_quantize(const void* x, thrift_dtype dt, long bh, int N, int axis, uint8_t* codes, uint8_t* scales, hipStream_t st);
+
+struct SelectArgs {
+  const float* qmean;
+  const float* kmean;
+  int32_t* idx;
+  int32_t* cnt;
+  unsigned long long* bitmap;   // nullable: [rows][bitmap_words], bit j%64 of word j/64 = block j selected
+  const int32_t* seqlens;       // nullable: [B] valid tokens; caps the visible blocks of batch b
+  int bitmap_words;
+  int B, Hq, Hkv, Tq, Tk, Bq, Bk, causal, fixed_k, q_block_offset, kmax;
+  long long ppm;                // budget in millionths
+};
+void launch_select_topk(const SelectArgs& a, hipStream_t st);
+// idx [rows][kmax_in] -> idx_out [rows][kmax_out] (padded -1), cnt copied
+void launch_copy_selection(const int32_t* idx, const int32_t* cnt, int kmax_in, int32_t* idx_out, int32_t* cnt_out,
+                           int kmax_out, long rows, hipStream_t st);
+
+struct PrefillArgs {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  const uint8_t* q4;
+  const uint8_t* qs;
+  const uint8_t* k4;
+  const uint8_t* ks;
+  const uint8_t* v4;
+  const uint8_t* vs;
+  const int32_t* idx;
+  const int32_t* cnt;
+  void* out;
+  float* lse;
+  int kmax, B, Hq, Hkv, N, Bq, causal;
+  float scale;            // softmax scale (already defaulted)
+  thrift_dtype dt, out_dt;
+};
+void launch_prefill(const PrefillArgs& a, hipStream_t st);
+
+struct DecodeArgs {
+  const uint16_t* q;
+  const uint8_t* q4;      // MXFP4 codes / scales of q (axis 0), [B,Hq,64] and [B,Hq,4]
+  const uint8_t* qs;
+  const uint16_t* k16;
+  const uint16_t* v16;
+  const uint8_t* k4;
+  const uint8_t* ks;
+  const uint8_t* v4;
+  const uint8_t* vs;
+  const int32_t* seqlens;
+  const unsigned long long* bitmap;   // [B,Hq,bitmap_words] selected key blocks per query head
+  void* out;
+  float* part_o;          // [B,Hq,nparts,D] unnormalised partial outputs
+  float* part_ml;         // [B,Hq,nparts,2] running max (raw score units) and row sum of each partial
+  int bitmap_words, B, Hq, Hkv, Nkv, split_blocks, nsplit, nparts;
+  float scale;
+  thrift_dtype dt, out_dt;
+};
+void launch_decode(const DecodeArgs& a, hipStream_t st);
+
+}  // namespace thrift

@@ -1,0 +1,187 @@
+// Fused mixed-precision flash attention for prefill (Algorithm 1 steps 4-23; Sec. 3.3).
+//
+// One workgroup = one (batch, query head, query block); wavefront w owns query rows 32w .. 32w+31 of
+// the block and keeps Q (4-bit and 16-bit fragments), the online-softmax state and the O^T accumulators
+// in registers.  Key blocks are visited in ascending order (the order of Alg. 1); each block is staged
+// once into LDS for all wavefronts — MXFP4 codes + scales for ordinary blocks, the 16-bit K/V tile for
+// blocks listed in the row's TopK set — and dispatched per tile to the scaled-FP4 or the 16-bit MFMA
+// path.  4-bit tiles are prefetched into registers one block ahead so that their global latency hides
+// behind the current tile's arithmetic.
+//
+// Differences from the kernel the paper sketches for Blackwell (Sec. 3.3): no two-phase split (4-bit
+// tiles first, 16-bit helper afterwards) — on gfx950 both Q fragment sets fit in the 512-entry register
+// file at two wavefronts per SIMD, and ascending order keeps the result independent of the schedule;
+// LDS aliasing of the two tile formats is kept.
+#include "thrift_launch.h"
+#include "thrift_tile.h"
+
+namespace thrift {
+
+template <typename T, int NW>
+__global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
+  constexpr int NT = NW * 64;
+  constexpr int CH = 256 / NT;                         // 16-byte chunks of a 4 KiB tile per thread
+  __shared__ __align__(16) unsigned char lds[kLdsBytes16];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, r = lane & 31;
+  const int N = a.N, Bq = NW * 32, Tq = N / Bq, Tk = N / kBk, G = a.Hq / a.Hkv;
+
+  // ---- work item: heavy (late) query blocks first; KV heads spread over the 8 XCDs so that the query
+  // heads and neighbouring query blocks that share a KV head also share an L2 ----
+  const int units = a.B * a.Hkv, per_unit = G * Tq;
+  int unit, within;
+  if ((units & 7) == 0) {
+    const int xcd = blockIdx.x & 7, t = blockIdx.x >> 3;
+    unit = xcd + 8 * (t / per_unit);
+    within = t % per_unit;
+  } else {
+    unit = blockIdx.x / per_unit;
+    within = blockIdx.x % per_unit;
+  }
+  const int b = unit / a.Hkv, kvh = unit % a.Hkv;
+  const int i = Tq - 1 - within / G;
+  const int hq = kvh * G + within % G;
+  const size_t qh = (size_t)b * a.Hq + hq, kh = (size_t)b * a.Hkv + kvh;
+  const int q0 = i * Bq + wave * 32;                    // first query row of this wavefront
+  const size_t qrow = qh * N + q0 + r;
+
+  // ---- Q fragments ----
+  v4i qf4[2];
+  qf4[0] = *reinterpret_cast<const v4i*>(a.q4 + qrow * 64 + half * 16);
+  qf4[1] = *reinterpret_cast<const v4i*>(a.q4 + qrow * 64 + 32 + half * 16);
+  const uint32_t qsc = *reinterpret_cast<const uint32_t*>(a.qs + qrow * 4) >> (8 * half);
+  const uint16_t* q16row = a.q + qrow * kD;
+
+  const int vis = a.causal ? min(Tk, ((i + 1) * Bq - 1) / kBk + 1) : Tk;
+  const int32_t* sel = a.idx + (qh * Tq + i) * a.kmax;
+  const int nsel = a.cnt[qh * Tq + i];
+  int ps = 0;
+  int next16 = nsel > 0 ? sel[0] : 0x7fffffff;
+
+  const uint8_t* k4base = a.k4 + kh * N * 64;
+  const uint8_t* v4base = a.v4 + kh * (size_t)(N / 64) * 4096;
+  const uint8_t* ksbase = a.ks + kh * N * 4;
+  const uint8_t* vsbase = a.vs + kh * (size_t)(N / 32) * kD;
+  const uint16_t* k16base = a.k + kh * N * kD;
+  const uint16_t* v16base = a.v + kh * N * kD;
+
+  // ---- register prefetch of a 4-bit tile: each thread carries CH 16-byte chunks of K and of V and
+  // (threads 0-127) one dword of scale bytes ----
+  uint4 pk0 = make_uint4(0, 0, 0, 0), pk1 = pk0, pv0 = pk0, pv1 = pk0;
+  uint32_t psc = 0;
+#define THRIFT_PREFETCH4(J)                                                                                    \
+  do {                                                                                                         \
+    const uint8_t* kt_ = k4base + (size_t)(J) * 4096 + tid * 16;                                               \
+    const uint8_t* vt_ = v4base + (size_t)(J) * 4096 + tid * 16;                                               \
+    pk0 = *reinterpret_cast<const uint4*>(kt_);                                                                \
+    pv0 = *reinterpret_cast<const uint4*>(vt_);                                                                \
+    if (CH == 2) {                                                                                             \
+      pk1 = *reinterpret_cast<const uint4*>(kt_ + NT * 16);                                                    \
+      pv1 = *reinterpret_cast<const uint4*>(vt_ + NT * 16);                                                    \
+    }                                                                                                          \
+    if (tid < 64) psc = *reinterpret_cast<const uint32_t*>(ksbase + (size_t)(J) * 256 + tid * 4);              \
+    else if (tid < 128) psc = *reinterpret_cast<const uint32_t*>(vsbase + (size_t)(J) * 256 + (tid - 64) * 4); \
+  } while (0)
+
+  RowState st = {-INFINITY, 0.f};
+  v16f o[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n) o[n] = (v16f){0.f};
+  const float c = a.scale * 1.4426950408889634f;
+
+  if (vis > 0 && next16 != 0) THRIFT_PREFETCH4(0);
+  for (int j = 0; j < vis; ++j) {
+    const bool is16 = j == next16;
+    __syncthreads();                                    // every wavefront is done with the previous tile
+    if (is16) {
+      // 16-bit K and V tiles, row-major with padded rows
+#pragma unroll
+      for (int u = 0; u < 1024 / NT; ++u) {
+        const int chunk = tid + NT * u, row = chunk >> 4, col = chunk & 15;
+        const uint4 kk = *reinterpret_cast<const uint4*>(k16base + ((size_t)j * kBk + row) * kD + col * 8);
+        const uint4 vv = *reinterpret_cast<const uint4*>(v16base + ((size_t)j * kBk + row) * kD + col * 8);
+        *reinterpret_cast<uint4*>(lds + kLdsK16 + row * kRow16 + col * 16) = kk;
+        *reinterpret_cast<uint4*>(lds + kLdsV16 + row * kRow16 + col * 16) = vv;
+      }
+      ++ps;
+      next16 = ps < nsel ? sel[ps] : 0x7fffffff;
+    } else {
+      // K codes in MFMA fragment order, V codes as they are, scale bytes
+      *reinterpret_cast<uint4*>(lds + kLdsK4 + k4_fragment_offset(tid >> 2, tid & 3)) = pk0;
+      *reinterpret_cast<uint4*>(lds + kLdsV4 + tid * 16) = pv0;
+      if (CH == 2) {
+        *reinterpret_cast<uint4*>(lds + kLdsK4 + k4_fragment_offset((tid + NT) >> 2, (tid + NT) & 3)) = pk1;
+        *reinterpret_cast<uint4*>(lds + kLdsV4 + (tid + NT) * 16) = pv1;
+      }
+      if (tid < 64) {
+        *reinterpret_cast<uint32_t*>(lds + kLdsKS + tid * 4) = psc;
+      } else if (tid < 128) {
+        // bytes 4w .. 4w+3 of the [2 groups][128 channels] scale rows -> [group][r][n], channel = 32n + r
+        const int w = tid - 64, grp = w >> 5, ch = (4 * w) & 127, n = ch >> 5, rr = ch & 31;
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb) lds[kLdsVS + (grp * 32 + rr + bb) * 4 + n] = (unsigned char)(psc >> (8 * bb));
+      }
+    }
+    __syncthreads();
+    if (j + 1 < vis && j + 1 != next16) THRIFT_PREFETCH4(j + 1);
+
+    const int first_key = j * kBk;
+    if (a.causal && first_key > q0 + 31) continue;      // nothing of this block is visible to this wavefront
+    const bool mask = a.causal && first_key + kBk - 1 > q0;
+    const int n_valid = q0 + r - first_key + 1;         // keys of the block at positions <= the query's
+    v16f s[2];
+    float gmax;
+    if (is16) {
+      scores_16<T>(lds, lane, q16row, s);
+      const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+      rescale(o, alpha);
+      pv_16<T>(lds + kLdsV16, lane, s, o);
+    } else {
+      scores_fp4(lds, lane, qf4, qsc, s);
+      const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+      rescale(o, alpha);
+      pv_fp4(lds, lane, s, gmax, o);
+    }
+  }
+
+  // ---- epilogue (Alg. 1 step 21): O / l; accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
+  const float l = st.l + other_half(st.l);
+  const float inv = l > 0.f ? 1.0f / l : 0.f;
+  const size_t orow = qrow * kD;
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int q4i = 0; q4i < 4; ++q4i) {
+      const int ch = 32 * n + 8 * q4i + 4 * half;
+      const float x0 = o[n][4 * q4i] * inv, x1 = o[n][4 * q4i + 1] * inv, x2 = o[n][4 * q4i + 2] * inv, x3 = o[n][4 * q4i + 3] * inv;
+      if (a.out_dt == THRIFT_F32) {
+        *reinterpret_cast<float4*>((float*)a.out + orow + ch) = make_float4(x0, x1, x2, x3);
+      } else if (a.out_dt == THRIFT_F16) {
+        uint2 w;
+        w.x = (uint32_t)F16::from_float(x0) | ((uint32_t)F16::from_float(x1) << 16);
+        w.y = (uint32_t)F16::from_float(x2) | ((uint32_t)F16::from_float(x3) << 16);
+        *reinterpret_cast<uint2*>((uint16_t*)a.out + orow + ch) = w;
+      } else {
+        uint2 w;
+        w.x = (uint32_t)BF16::from_float(x0) | ((uint32_t)BF16::from_float(x1) << 16);
+        w.y = (uint32_t)BF16::from_float(x2) | ((uint32_t)BF16::from_float(x3) << 16);
+        *reinterpret_cast<uint2*>((uint16_t*)a.out + orow + ch) = w;
+      }
+    }
+  if (a.lse != nullptr && half == 0) a.lse[qrow] = st.m * a.scale + __logf(l);
+}
+
+#undef THRIFT_PREFETCH4
+
+void launch_prefill(const PrefillArgs& a, hipStream_t st) {
+  const unsigned grid = (unsigned)((long)a.B * a.Hq * (a.N / a.Bq));
+  if (a.Bq == 128) {
+    if (a.dt == THRIFT_F16) prefill_kernel<F16, 4><<<dim3(grid), dim3(256), 0, st>>>(a);
+    else prefill_kernel<BF16, 4><<<dim3(grid), dim3(256), 0, st>>>(a);
+  } else {
+    if (a.dt == THRIFT_F16) prefill_kernel<F16, 2><<<dim3(grid), dim3(128), 0, st>>>(a);
+    else prefill_kernel<BF16, 2><<<dim3(grid), dim3(128), 0, st>>>(a);
+  }
+}
+
+}  // namespace thrift

@@ -1,0 +1,326 @@
+// Pre-pass kernels of Algorithm 1: block token means (step 3), MXFP4 quantisation (step 2) and
+// block-pair scoring + per-row TopK (step 5).  All three are streaming / latency kernels: coalesced
+// 16-byte loads, wavefront shuffles and ballots for the reductions, no matrix units.
+#include "thrift_device.h"
+#include "thrift_launch.h"
+
+namespace thrift {
+
+// ------------------------------------------------------------------------------------------------
+// Block means (Sec. 3.2): one workgroup per (b, h, block).  256 threads = 16 row slices x 16 column
+// groups of 8 channels; each thread streams rows slice, slice+16, ... with 16-byte loads and adds
+// in fp64 (the sum of a block of 16-bit values is then exact, so the result does not depend on the
+// order of the additions and matches a serial fp64 mean bit for bit).
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) block_means_kernel(const uint16_t* __restrict__ x, float* __restrict__ means,
+                                                          int block) {
+  const int tid = threadIdx.x;
+  const int cg = tid & 15, rs = tid >> 4;
+  const uint16_t* base = x + (size_t)blockIdx.x * block * kD + cg * 8;
+  double acc[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = 0.0;
+  for (int r = rs; r < block; r += 16) {
+    uint4 w = *reinterpret_cast<const uint4*>(base + (size_t)r * kD);
+    uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      acc[2 * c] += (double)T::to_float((uint16_t)(ww[c] & 0xffffu));
+      acc[2 * c + 1] += (double)T::to_float((uint16_t)(ww[c] >> 16));
+    }
+  }
+  // row slices rs and rs^1, rs^2 sit 16 and 32 lanes apart inside a wavefront
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    acc[c] += __shfl_xor(acc[c], 16);
+    acc[c] += __shfl_xor(acc[c], 32);
+  }
+  __shared__ double part[4][16][8];
+  const int wave = tid >> 6;
+  if ((tid & 63) < 16) {
+#pragma unroll
+    for (int c = 0; c < 8; ++c) part[wave][cg][c] = acc[c];
+  }
+  __syncthreads();
+  if (tid < kD) {
+    const int g = tid >> 3, c = tid & 7;
+    double s = part[0][g][c] + part[1][g][c] + part[2][g][c] + part[3][g][c];
+    means[(size_t)blockIdx.x * kD + tid] = (float)(s / (double)block);
+  }
+}
+
+void launch_block_means(const void* x, thrift_dtype dt, long n_blocks, int block, float* means, hipStream_t st) {
+  if (dt == THRIFT_F16)
+    block_means_kernel<F16><<<dim3((unsigned)n_blocks), dim3(256), 0, st>>>((const uint16_t*)x, means, block);
+  else
+    block_means_kernel<BF16><<<dim3((unsigned)n_blocks), dim3(256), 0, st>>>((const uint16_t*)x, means, block);
+}
+
+// ------------------------------------------------------------------------------------------------
+// MXFP4 quantisation of one 32-element group held as 16 packed pairs (pair u = elements 2u, 2u+1).
+// Returns the 16 code bytes in out[0..3] and the E8M0 byte.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ uint32_t quantize_group32(const uint32_t (&pair)[16], uint32_t (&out)[4]) {
+  // magnitudes of 16-bit floats order like their bit patterns without the sign
+  uint32_t amax16 = 0;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    uint32_t lo = pair[u] & 0x7fffu, hi = (pair[u] >> 16) & 0x7fffu;
+    amax16 = max(amax16, max(lo, hi));
+  }
+  const uint32_t abits = __float_as_uint(T::to_float((uint16_t)amax16));
+  const uint32_t sb = e8m0_from_amax_bits(abits);
+  out[0] = out[1] = out[2] = out[3] = 0u;
+  if (sb >= 1u || abits == 0u) {
+    // the hardware converter divides by a power-of-two scale given as a normal float
+    const float scale = __uint_as_float(sb << 23);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      uint32_t& o = out[u >> 2];
+      switch (u & 3) {
+        case 0: o = T::template cvt_pk_fp4<0>(o, pair[u], scale); break;
+        case 1: o = T::template cvt_pk_fp4<1>(o, pair[u], scale); break;
+        case 2: o = T::template cvt_pk_fp4<2>(o, pair[u], scale); break;
+        default: o = T::template cvt_pk_fp4<3>(o, pair[u], scale); break;
+      }
+    }
+  } else {
+    // scale 2^-127 is a subnormal float: encode x * 2^127 in software (bf16 groups below 2^-124 only)
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      float lo = T::to_float((uint16_t)(pair[u] & 0xffffu)) * 0x1p64f * 0x1p63f;
+      float hi = T::to_float((uint16_t)(pair[u] >> 16)) * 0x1p64f * 0x1p63f;
+      out[u >> 2] |= (e2m1_encode_sw(lo) | (e2m1_encode_sw(hi) << 4)) << (8 * (u & 3));
+    }
+  }
+  return sb;
+}
+
+// axis 0: one thread per group of 32 consecutive channels (64 bytes in, 16 code bytes + 1 scale out).
+template <typename T>
+__global__ void __launch_bounds__(256) quantize_axis0_kernel(const uint16_t* __restrict__ x, uint8_t* __restrict__ codes,
+                                                             uint8_t* __restrict__ scales, size_t n_groups) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= n_groups) return;
+  const uint4* src = reinterpret_cast<const uint4*>(x + g * 32);
+  uint32_t pair[16];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    uint4 w = src[t];
+    pair[4 * t] = w.x; pair[4 * t + 1] = w.y; pair[4 * t + 2] = w.z; pair[4 * t + 3] = w.w;
+  }
+  uint32_t out[4];
+  const uint32_t sb = quantize_group32<T>(pair, out);
+  *reinterpret_cast<uint4*>(codes + g * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+  scales[g] = (uint8_t)sb;
+}
+
+// axis 1: one workgroup per (b, h, 64-token block).  The 64 x 128 tile is staged through LDS with
+// coalesced 16-byte loads; thread (token group g, channel c) then walks its 32 tokens down a column.
+// Output tile: [channel][32 bytes] (tokens 2t, 2t+1 in byte t), scales [2 groups][128 channels].
+template <typename T>
+__global__ void __launch_bounds__(256) quantize_axis1_kernel(const uint16_t* __restrict__ x, uint8_t* __restrict__ codes,
+                                                             uint8_t* __restrict__ scales) {
+  constexpr int kRow = kD + 8;  // padded row (in 16-bit elements): keeps 16-byte alignment, spreads banks
+  __shared__ __align__(16) uint16_t tile[64 * kRow];
+  const int tid = threadIdx.x;
+  const uint16_t* src = x + (size_t)blockIdx.x * 64 * kD;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int chunk = tid + 256 * u;           // 1024 chunks of 8 elements
+    const int row = chunk >> 4, col = (chunk & 15) * 8;
+    *reinterpret_cast<uint4*>(&tile[row * kRow + col]) = *reinterpret_cast<const uint4*>(src + row * kD + col);
+  }
+  __syncthreads();
+  const int g = tid >> 7, c = tid & 127;
+  uint32_t pair[16];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    uint32_t lo = tile[(32 * g + 2 * u) * kRow + c], hi = tile[(32 * g + 2 * u + 1) * kRow + c];
+    pair[u] = lo | (hi << 16);
+  }
+  uint32_t out[4];
+  const uint32_t sb = quantize_group32<T>(pair, out);
+  *reinterpret_cast<uint4*>(codes + ((size_t)blockIdx.x * kD + c) * 32 + g * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+  scales[((size_t)blockIdx.x * 2 + g) * kD + c] = (uint8_t)sb;
+}
+
+void launch_quantize(const void* x, thrift_dtype dt, long bh, int N, int axis, uint8_t* codes, uint8_t* scales, hipStream_t st) {
+  const uint16_t* xs = (const uint16_t*)x;
+  if (axis == 0) {
+    size_t n_groups = (size_t)bh * N * (kD / 32);
+    unsigned grid = (unsigned)((n_groups + 255) / 256);
+    if (dt == THRIFT_F16) quantize_axis0_kernel<F16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales, n_groups);
+    else quantize_axis0_kernel<BF16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales, n_groups);
+  } else {
+    unsigned grid = (unsigned)(bh * (N / 64));
+    if (dt == THRIFT_F16) quantize_axis1_kernel<F16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales);
+    else quantize_axis1_kernel<BF16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Scores + TopK (Sec. 3.2; Alg. 1 step 5).  A workgroup of 4 wavefronts serves 4 consecutive rows of
+// one (b, kv head) in the order (query block, head of the group): they share the staged key-block
+// means.  Each wavefront owns one row: lane l scores key blocks l, l+64, ... in fp64, keeps them in
+// registers as order-preserving 64-bit keys, finds the k-th largest key by a bitwise search with
+// ballot/popcount counting, and emits the selected ids in ascending order.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int visible_blocks_dev(int i, int Tk, int Bq, int Bk, int causal, int off) {
+  if (!causal) return Tk;
+  long long last_q = ((long long)i + off + 1) * Bq - 1;
+  long long v = last_q / Bk + 1;
+  return (int)(v > Tk ? Tk : (v < 0 ? 0 : v));
+}
+
+__device__ __forceinline__ int row_budget_dev(int visible, long long ppm, int fixed_k) {
+  if (fixed_k >= 0) return fixed_k < visible ? fixed_k : visible;
+  if (ppm <= 0) return 0;
+  long long k = (ppm * (long long)visible + 999999LL) / 1000000LL;
+  if (k < 1) k = 1;
+  if (k > visible) k = visible;
+  return (int)k;
+}
+
+__device__ __forceinline__ uint64_t order_key(double s) {
+  uint64_t u = (uint64_t)__double_as_longlong(s);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);   // larger double <=> larger key
+}
+
+template <int MAXC>
+__global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
+  constexpr int kStride = kD + 4;                       // padded fp32 row of a staged key mean
+  __shared__ __align__(16) float kst[64 * kStride];
+  __shared__ __align__(16) float qst[4][kD];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int G = p.Hq / p.Hkv;
+  const int rows_per_unit = p.Tq * G;                   // rows of one (b, kv head), ordered (i, head in group)
+  const int wgs_per_unit = (rows_per_unit + 3) / 4;
+  const int unit = blockIdx.x / wgs_per_unit;
+  const int row0 = (blockIdx.x % wgs_per_unit) * 4;
+  const int b = unit / p.Hkv, kvh = unit % p.Hkv;
+  const int row = row0 + wave;
+  const bool active = row < rows_per_unit;
+  const int i = active ? row / G : 0;
+  const int hq = kvh * G + (active ? row % G : 0);
+  const int cap = p.seqlens ? min(p.Tk, max(0, p.seqlens[b]) / p.Bk) : p.Tk;
+  const int vis = active ? min(cap, visible_blocks_dev(i, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset)) : 0;
+  const int k = row_budget_dev(vis, p.ppm, p.fixed_k);
+  const int last_row = min(row0 + 3, rows_per_unit - 1);
+  const int vis_max = min(cap, visible_blocks_dev(last_row / G, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset));
+  const size_t rowid = ((size_t)b * p.Hq + hq) * p.Tq + i;
+
+  if (active) {
+    const float* qm = p.qmean + rowid * kD;
+    qst[wave][lane] = qm[lane];
+    qst[wave][lane + 64] = qm[lane + 64];
+  }
+  const float* kbase = p.kmean + ((size_t)b * p.Hkv + kvh) * p.Tk * kD;
+
+  uint64_t key[MAXC];
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    key[c] = 0;
+    if (c * 64 < vis_max) {                              // uniform over the workgroup
+      __syncthreads();
+      // stage 64 key means (rows beyond Tk are not read)
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int chunk = tid + 256 * u;                 // 2048 chunks of 4 floats
+        const int r = chunk >> 5, col = (chunk & 31) * 4;
+        if (c * 64 + r < p.Tk)
+          *reinterpret_cast<float4*>(&kst[r * kStride + col]) =
+              *reinterpret_cast<const float4*>(kbase + (size_t)(c * 64 + r) * kD + col);
+      }
+      __syncthreads();
+      const int j = c * 64 + lane;
+      if (j < vis) {
+        double s = 0.0;
+#pragma unroll 8
+        for (int d = 0; d < kD; d += 4) {
+          float4 kv = *reinterpret_cast<const float4*>(&kst[lane * kStride + d]);
+          float4 qv = *reinterpret_cast<const float4*>(&qst[wave][d]);
+          s = fma((double)qv.x, (double)kv.x, s);
+          s = fma((double)qv.y, (double)kv.y, s);
+          s = fma((double)qv.z, (double)kv.z, s);
+          s = fma((double)qv.w, (double)kv.w, s);
+        }
+        key[c] = order_key(s);
+      }
+    }
+  }
+  if (!active) return;
+
+  int32_t* out = p.idx + rowid * p.kmax;
+  if (lane == 0) p.cnt[rowid] = k;
+  unsigned long long* bm = p.bitmap ? p.bitmap + rowid * p.bitmap_words : nullptr;
+  if (k <= 0) {
+    for (int t = lane; t < p.kmax; t += 64) out[t] = -1;
+    if (bm) for (int t = lane; t < p.bitmap_words; t += 64) bm[t] = 0ULL;
+    return;
+  }
+  // k-th largest key: greatest T with |{key >= T}| >= k, built bit by bit from the top
+  uint64_t T = 0;
+  for (int bit = 63; bit >= 0; --bit) {
+    const uint64_t cand = T | (1ULL << bit);
+    int n = 0;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c)
+      if (c * 64 < vis) n += __popcll(__ballot((c * 64 + lane < vis) && key[c] >= cand));
+    if (n >= k) T = cand;
+  }
+  int n_gt = 0;
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c)
+    if (c * 64 < vis) n_gt += __popcll(__ballot((c * 64 + lane < vis) && key[c] > T));
+  const int need_ties = k - n_gt;                        // >= 1: ties at T, taken from the smallest id up
+  const uint64_t lt_mask = (1ULL << lane) - 1ULL;
+  int written = 0, ties_seen = 0;
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    if (c * 64 < vis) {
+      const bool valid = c * 64 + lane < vis;
+      const bool tie = valid && key[c] == T;
+      const uint64_t tie_b = __ballot(tie);
+      const bool sel = valid && (key[c] > T || (tie && ties_seen + __popcll(tie_b & lt_mask) < need_ties));
+      const uint64_t sel_b = __ballot(sel);
+      if (sel) out[written + __popcll(sel_b & lt_mask)] = c * 64 + lane;
+      written += __popcll(sel_b);
+      ties_seen += __popcll(tie_b);
+      if (bm && lane == 0) bm[c] = sel_b;
+    } else if (bm && lane == 0 && c < p.bitmap_words) {
+      bm[c] = 0ULL;
+    }
+  }
+  for (int t = k + lane; t < p.kmax; t += 64) out[t] = -1;
+}
+
+__global__ void __launch_bounds__(256) copy_selection_kernel(const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
+                                                             int kmax_in, int32_t* __restrict__ idx_out,
+                                                             int32_t* __restrict__ cnt_out, int kmax_out, long rows) {
+  const long row = blockIdx.x;
+  if (row >= rows) return;
+  const int n = cnt[row];
+  for (int t = threadIdx.x; t < kmax_out; t += 256) idx_out[row * kmax_out + t] = t < n && t < kmax_in ? idx[row * kmax_in + t] : -1;
+  if (threadIdx.x == 0) cnt_out[row] = n;
+}
+
+void launch_copy_selection(const int32_t* idx, const int32_t* cnt, int kmax_in, int32_t* idx_out, int32_t* cnt_out,
+                           int kmax_out, long rows, hipStream_t st) {
+  copy_selection_kernel<<<dim3((unsigned)rows), dim3(256), 0, st>>>(idx, cnt, kmax_in, idx_out, cnt_out, kmax_out, rows);
+}
+
+void launch_select_topk(const SelectArgs& p, hipStream_t st) {
+  const int G = p.Hq / p.Hkv;
+  const int wgs_per_unit = (p.Tq * G + 3) / 4;
+  const unsigned grid = (unsigned)((long)p.B * p.Hkv * wgs_per_unit);
+  const int chunks = (p.Tk + 63) / 64;
+  if (chunks <= 8) select_topk_kernel<8><<<dim3(grid), dim3(256), 0, st>>>(p);
+  else if (chunks <= 16) select_topk_kernel<16><<<dim3(grid), dim3(256), 0, st>>>(p);
+  else if (chunks <= 32) select_topk_kernel<32><<<dim3(grid), dim3(256), 0, st>>>(p);
+  else select_topk_kernel<64><<<dim3(grid), dim3(256), 0, st>>>(p);
+}
+
+}  // namespace thrift

@@ -1,0 +1,204 @@
+// Per-wavefront tile arithmetic of Algorithm 1 on gfx950 matrix units, shared by the prefill and the
+// decode kernels.
+//
+// One wavefront owns 32 query rows and walks 64-key blocks.  Everything is computed transposed, so
+// that each query lives in one lane column and no cross-lane traffic is needed inside a row:
+//
+//   S^T (keys x queries) = K_j . Q^T        two 32x32 MFMA tiles (keys 0-31 / 32-63 after the row
+//                                           permutation below), accumulated over D = 128
+//   O^T (channels x queries) += V_j^T . P^T  four 32x32 MFMA tiles (32 channels each)
+//
+// 32x32 MFMA register layouts (64 lanes; lane = 32*half + r):
+//   A operand: row r, contraction slots [G*half, G*half + G)     (G = 32 for MXFP4 K=64, 8 for 16-bit K=16)
+//   B operand: column r, same contraction slots
+//   C/D: column r, rows 8*(i/4) + 4*half + i%4 for accumulator register i = 0..15
+// Row permutation of the S^T tiles: MFMA row rho of sub-tile t is fed key
+//   pi_t(rho) = 32*((rho>>2)&1) + 16*t + 4*(rho>>3) + (rho&3),
+// so lane (half, r) ends up holding, for query r, the 32 consecutive keys 32*half + (16*t + i): exactly
+// the 32-slot group it must supply as the B operand of the P.V MFMA, and exactly one MXFP4 scale group
+// of P and of V.  Row max / row sum combine the two halves with one lane swap.
+#pragma once
+
+#include "thrift_device.h"
+
+namespace thrift {
+
+// LDS layout of one staged key block (bytes).  The 4-bit and 16-bit tiles alias the same region.
+constexpr int kRow16 = 2 * kD + 16;          // padded 16-bit row
+constexpr int kLdsK16 = 0;
+constexpr int kLdsV16 = kBk * kRow16;
+constexpr int kLdsBytes16 = 2 * kBk * kRow16;   // 34816
+constexpr int kLdsK4 = 0;                    // 4096 B, stored in MFMA fragment order
+constexpr int kLdsV4 = 4096;                 // 4096 B, [channel][32 B]
+constexpr int kLdsKS = 8192;                 // 64 x 4 scale bytes of K, [key][d-group]
+constexpr int kLdsVS = 8448;                 // 256 scale bytes of V, [token group][r][n] for channel 32n + r
+constexpr int kLdsBytes4 = 8704;
+
+__device__ __forceinline__ int key_of_row(int rho, int t) {
+  return 32 * ((rho >> 2) & 1) + 16 * t + 4 * (rho >> 3) + (rho & 3);
+}
+
+// Byte offset inside the K4 LDS region of the 16-byte chunk (key, c4) of the global [64 keys][64 B] tile:
+// fragment (t, kk) is the contiguous 1 KiB that one MFMA reads, lane-major.
+__device__ __forceinline__ int k4_fragment_offset(int key, int c4) {
+  const int t = (key >> 4) & 1, hp = key >> 5, a = (key >> 2) & 3, c = key & 3;
+  const int rho = 8 * a + 4 * hp + c;
+  const int kk = c4 >> 1, hk = c4 & 1;
+  return ((t * 2 + kk) * 64 + 32 * hk + rho) * 16;
+}
+
+__device__ __forceinline__ v8i widen(v4i x) { return __builtin_shufflevector(x, x, 0, 1, 2, 3, -1, -1, -1, -1); }
+
+struct RowState {
+  float m;      // running maximum of the raw (unscaled) scores of this lane's query
+  float l;      // this lane's partial row sum (the two halves of a query add up at the end)
+};
+
+// S^T for a 4-bit tile.  qf: the lane's two Q fragments (D halves), qsc: its Q scale bytes already
+// shifted so that byte 2*kk belongs to fragment kk.
+__device__ __forceinline__ void scores_fp4(const unsigned char* lds, int lane, const v4i (&qf)[2], uint32_t qsc, v16f (&s)[2]) {
+  const int half = lane >> 5, r = lane & 31;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const uint32_t ksw = *reinterpret_cast<const uint32_t*>(lds + kLdsKS + 4 * key_of_row(r, t)) >> (8 * half);
+    const v4i a0 = *reinterpret_cast<const v4i*>(lds + kLdsK4 + ((t * 2 + 0) * 64 + lane) * 16);
+    const v4i a1 = *reinterpret_cast<const v4i*>(lds + kLdsK4 + ((t * 2 + 1) * 64 + lane) * 16);
+    v16f acc = {0.f};
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a0), widen(qf[0]), acc, 4, 4, 0, ksw, 0, qsc);
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a1), widen(qf[1]), acc, 4, 4, 2, ksw, 2, qsc);
+    s[t] = acc;
+  }
+}
+
+// S^T for a 16-bit tile.  qrow: the lane's 16-bit query row in global memory; fragment s8 holds its
+// elements d = 16*s8 + 8*half + [0,8).  The fragments are fetched per promoted tile (a small share of
+// all tiles) instead of being pinned in 32 registers for the whole kernel.
+template <typename T>
+__device__ __forceinline__ void scores_16(const unsigned char* lds, int lane, const uint16_t* qrow, v16f (&s)[2]) {
+  const int half = lane >> 5, r = lane & 31;
+  v8s qf[8];
+#pragma unroll
+  for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(qrow + 16 * s8 + 8 * half);
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const unsigned char* krow = lds + kLdsK16 + key_of_row(r, t) * kRow16 + 16 * half;
+    v16f acc = {0.f};
+#pragma unroll
+    for (int s8 = 0; s8 < 8; ++s8) {
+      const v8s a = *reinterpret_cast<const v8s*>(krow + 32 * s8);
+      acc = T::mfma(a, qf[s8], acc);
+    }
+    s[t] = acc;
+  }
+}
+
+// Online-softmax update for the lane's 32 scores (Alg. 1 steps 10-12 / 16-17): masks, raises the
+// running maximum, turns s into the unnormalised probabilities exp(scale*(s - m_new)) in place, adds
+// them to the partial row sum and returns alpha = exp(scale*(m_old - m_new)).  group_max receives the
+// largest probability of the lane's 32-key group (the MXFP4 scale of P derives from it).
+//   c = softmax_scale * log2(e);  n_valid = number of leading keys of the block this query may see.
+__device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mask, int n_valid, float c, RowState& st,
+                                                float& group_max) {
+  const int half = lane >> 5;
+  if (mask) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (32 * half + 16 * t + i >= n_valid) s[t][i] = -INFINITY;
+  }
+  float mloc = s[0][0];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, s[0][i]);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, s[1][i]);
+  const float m_new = fmaxf(st.m, fmaxf(mloc, other_half(mloc)));
+  const float m_safe = m_new == -INFINITY ? 0.f : m_new;       // a row that has seen nothing stays empty
+  const float alpha = fast_exp2((st.m - m_safe) * c);
+  float sum = 0.f;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float p = fast_exp2((s[t][i] - m_safe) * c);
+      s[t][i] = p;
+      sum += p;
+    }
+  group_max = fast_exp2((mloc - m_safe) * c);
+  st.l = st.l * alpha + sum;
+  st.m = m_new;
+  return alpha;
+}
+
+__device__ __forceinline__ void rescale(v16f (&o)[4], float alpha) {
+  // skipping is exact: alpha == 1 leaves every accumulator unchanged
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ULL) {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) o[n] *= alpha;
+  }
+}
+
+// 4-bit P.V (Alg. 1 steps 19-20 with the first-level scale equal to 1): quantise the lane's 32
+// probabilities as one MXFP4 group and accumulate O^T += V^T . P^T on the scaled MFMA.  v0..v3: the
+// lane's V^T fragments (channel 32n + r, tokens 32*half .. +31), vsw: their four scale bytes (byte n).
+__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], float group_max, uint32_t vsw, v4i v0, v4i v1, v4i v2, v4i v3,
+                                            v16f (&o)[4]) {
+  uint32_t ef = __float_as_uint(group_max) >> 23;
+  const uint32_t pb = ef >= 3u ? ef - 2u : 1u;                 // E8M0 byte, kept >= 1 so the scale is a normal float
+  const float pscale = __uint_as_float(pb << 23);
+  v4i pq;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    uint32_t o32 = 0;
+    const int t = w >> 1, i0 = 8 * (w & 1);                    // slots 8w .. 8w+7 = p[t][i0 .. i0+7]
+    o32 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o32, p[t][i0 + 0], p[t][i0 + 1], pscale, 0);
+    o32 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o32, p[t][i0 + 2], p[t][i0 + 3], pscale, 1);
+    o32 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o32, p[t][i0 + 4], p[t][i0 + 5], pscale, 2);
+    o32 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o32, p[t][i0 + 6], p[t][i0 + 7], pscale, 3);
+    pq[w] = (int)o32;
+  }
+  const v8i pb8 = widen(pq);
+  o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v0), pb8, o[0], 4, 4, 0, vsw, 0, pb);
+  o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v1), pb8, o[1], 4, 4, 1, vsw, 0, pb);
+  o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v2), pb8, o[2], 4, 4, 2, vsw, 0, pb);
+  o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v3), pb8, o[3], 4, 4, 3, vsw, 0, pb);
+}
+
+// The same with V^T fragments and scales taken from the staged LDS tile.
+__device__ __forceinline__ void pv_fp4(const unsigned char* lds, int lane, const v16f (&p)[2], float group_max, v16f (&o)[4]) {
+  const int half = lane >> 5, r = lane & 31;
+  const uint32_t vsw = *reinterpret_cast<const uint32_t*>(lds + kLdsVS + (half * 32 + r) * 4);
+  const unsigned char* vbase = lds + kLdsV4 + r * 32 + half * 16;
+  pv_fp4_regs(p, group_max, vsw, *reinterpret_cast<const v4i*>(vbase), *reinterpret_cast<const v4i*>(vbase + 1024),
+              *reinterpret_cast<const v4i*>(vbase + 2048), *reinterpret_cast<const v4i*>(vbase + 3072), o);
+}
+
+// 16-bit P.V (Alg. 1 step 13): P rounded to the input dtype; V^T fragments come straight out of the
+// row-major LDS tile `vtile` ([64 keys][kRow16 bytes]) through the transposing 64-bit LDS read (each
+// 16-lane group turns a 4-key x 16-channel patch into 4 consecutive keys of one channel per lane).
+template <typename T>
+__device__ __forceinline__ void pv_16(const unsigned char* vtile, int lane, const v16f (&p)[2], v16f (&o)[4]) {
+  const int half = lane >> 5, r = lane & 31, g = r >> 4, i16 = r & 15;
+  v8s pf[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int t = s >> 1, i0 = 8 * (s & 1);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pf[s][e] = (short)T::from_float(p[t][i0 + e]);
+  }
+  typedef v4s __attribute__((address_space(3))) * lds_v4s_ptr;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    // keys 32*half + 8*s + 4*u + (i16>>2), channels 32*n + 16*g + 4*(i16&3)
+    const unsigned char* base = vtile + (32 * half + 8 * s + (i16 >> 2)) * kRow16 + (16 * g + 4 * (i16 & 3)) * 2;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(base + n * 64));
+      const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(base + n * 64 + 4 * kRow16));
+      const v8s a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      o[n] = T::mfma(a, pf[s], o[n]);
+    }
+  }
+}
+
+}  // namespace thrift

@@ -79,8 +79,8 @@ def scaled(w: Workload, **kw) -> Workload:
     return dataclasses.replace(w, **kw)
 
 
-def _gen(seed: int, stream: int, head: int) -> torch.Generator:
-    g = torch.Generator(device="cpu")
+def _gen(seed: int, stream: int, head: int, device="cpu") -> torch.Generator:
+    g = torch.Generator(device=device)
     g.manual_seed(seed * 1000003 + stream * 4099 + head)
     return g
 
@@ -88,6 +88,10 @@ def _gen(seed: int, stream: int, head: int) -> torch.Generator:
 def _unit(g: torch.Generator, D: int) -> torch.Tensor:
     u = torch.randn(D, generator=g, dtype=torch.float32)
     return u / u.norm()
+
+
+def _randn(n, d, g: torch.Generator) -> torch.Tensor:
+    return torch.randn(n, d, generator=g, dtype=torch.float32, device=g.device)
 
 
 def group_direction(w: Workload, b: int, kvh: int) -> torch.Tensor:
@@ -110,33 +114,38 @@ def _outlier_idx(w: Workload, stream: int, b: int, head: int) -> torch.Tensor:
     return torch.randperm(w.D, generator=g)[: w.outlier_channels]
 
 
-def make_q_head(w: Workload, b: int, h: int, n_rows: Optional[int] = None) -> torch.Tensor:
-    """Queries of one head: [N, D] (or [n_rows, D]) in the workload's dtype."""
+def make_q_head(w: Workload, b: int, h: int, n_rows: Optional[int] = None, device="cpu") -> torch.Tensor:
+    """Queries of one head: [N, D] (or [n_rows, D]) in the workload's dtype.
+
+    ``device``: where the normal draws are made.  The CPU and the GPU generators give different
+    (equally distributed) bits, so parity checks draw on the CPU and copy; the throughput runs may
+    draw on the GPU.  The planted structure (directions, channels, block ids) is always drawn on the CPU.
+    """
     n = w.N if n_rows is None else n_rows
-    g = _gen(w.seed, 1, b * w.Hq + h)
-    q = torch.randn(n, w.D, generator=g, dtype=torch.float32)
-    q += w.query_mean_gain * group_direction(w, b, h // w.group)
+    g = _gen(w.seed, 1, b * w.Hq + h, device)
+    q = _randn(n, w.D, g)
+    q += w.query_mean_gain * group_direction(w, b, h // w.group).to(q.device)
     if w.outlier_channels:
-        q[:, _outlier_idx(w, 3, b, h)] *= w.outlier_scale
+        q[:, _outlier_idx(w, 3, b, h).to(q.device)] *= w.outlier_scale
     return q.to(w.torch_dtype)
 
 
-def make_kv_head(w: Workload, b: int, kvh: int) -> Tuple[torch.Tensor, torch.Tensor]:
+def make_kv_head(w: Workload, b: int, kvh: int, device="cpu") -> Tuple[torch.Tensor, torch.Tensor]:
     """Keys and values of one KV head: two [N, D] tensors in the workload's dtype."""
-    g = _gen(w.seed, 2, b * w.Hkv + kvh)
+    g = _gen(w.seed, 2, b * w.Hkv + kvh, device)
     if w.heavy_tail_nu > 0:
         nu = int(w.heavy_tail_nu)
-        z = torch.randn(w.N, w.D, generator=g, dtype=torch.float32)
-        chi = torch.zeros(w.N, w.D, dtype=torch.float32)
+        z = _randn(w.N, w.D, g)
+        chi = torch.zeros_like(z)
         for _ in range(nu):
-            chi += torch.randn(w.N, w.D, generator=g, dtype=torch.float32) ** 2
+            chi += _randn(w.N, w.D, g) ** 2
         k = z / torch.sqrt(chi / nu) / math.sqrt(nu / (nu - 2.0))
     else:
-        k = torch.randn(w.N, w.D, generator=g, dtype=torch.float32)
-    v = torch.randn(w.N, w.D, generator=g, dtype=torch.float32)
+        k = _randn(w.N, w.D, g)
+    v = _randn(w.N, w.D, g)
     if w.outlier_channels:
-        k[:, _outlier_idx(w, 5, b, kvh)] *= w.outlier_scale
-    u = group_direction(w, b, kvh)
+        k[:, _outlier_idx(w, 5, b, kvh).to(k.device)] *= w.outlier_scale
+    u = group_direction(w, b, kvh).to(k.device)
     for blk in planted_block_ids(w, b, kvh):
         k[blk * w.Bk:(blk + 1) * w.Bk] += w.planted_gain * u
     if w.sink_tokens:
@@ -144,7 +153,7 @@ def make_kv_head(w: Workload, b: int, kvh: int) -> Tuple[torch.Tensor, torch.Ten
     return k.to(w.torch_dtype), v.to(w.torch_dtype)
 
 
-def make_prefill(w: Workload, q_heads: Optional[Sequence[int]] = None):
+def make_prefill(w: Workload, q_heads: Optional[Sequence[int]] = None, device="cpu"):
     """Full prefill tensors: q [B,Hq',N,D], k,v [B,Hkv',N,D] on the CPU.
 
     ``q_heads`` restricts generation to some query heads (and the KV heads they
@@ -157,29 +166,29 @@ def make_prefill(w: Workload, q_heads: Optional[Sequence[int]] = None):
     if q_heads is not None:
         # a subset must keep whole groups so that the GQA mapping h -> h // group survives
         assert all(sorted(h for h in qh if h // w.group == g) == list(range(g * w.group, (g + 1) * w.group)) for g in kvh)
-    q = torch.empty(w.B, len(qh), w.N, w.D, dtype=w.torch_dtype)
-    k = torch.empty(w.B, len(kvh), w.N, w.D, dtype=w.torch_dtype)
+    q = torch.empty(w.B, len(qh), w.N, w.D, dtype=w.torch_dtype, device=device)
+    k = torch.empty(w.B, len(kvh), w.N, w.D, dtype=w.torch_dtype, device=device)
     v = torch.empty_like(k)
     for b in range(w.B):
         for i, h in enumerate(qh):
-            q[b, i] = make_q_head(w, b, h)
+            q[b, i] = make_q_head(w, b, h, device=device)
         for i, g in enumerate(kvh):
-            k[b, i], v[b, i] = make_kv_head(w, b, g)
+            k[b, i], v[b, i] = make_kv_head(w, b, g, device=device)
     return q, k, v, qh, kvh
 
 
-def make_decode(w: Workload, batch: Optional[int] = None):
+def make_decode(w: Workload, batch: Optional[int] = None, device="cpu"):
     """Decode tensors: q [B,Hq,D] (the query at the last position) and the
     high-precision cache k,v [B,Hkv,N,D]; quantised copies and block means are
     produced by the library under test (or by the oracle), not here."""
     assert w.decode
     B = w.B if batch is None else batch
-    q = torch.empty(B, w.Hq, w.D, dtype=w.torch_dtype)
-    k = torch.empty(B, w.Hkv, w.N, w.D, dtype=w.torch_dtype)
+    q = torch.empty(B, w.Hq, w.D, dtype=w.torch_dtype, device=device)
+    k = torch.empty(B, w.Hkv, w.N, w.D, dtype=w.torch_dtype, device=device)
     v = torch.empty_like(k)
     for b in range(B):
         for h in range(w.Hq):
-            q[b, h] = make_q_head(w, b, h, n_rows=1)[0]
+            q[b, h] = make_q_head(w, b, h, n_rows=1, device=device)[0]
         for g in range(w.Hkv):
-            k[b, g], v[b, g] = make_kv_head(w, b, g)
+            k[b, g], v[b, g] = make_kv_head(w, b, g, device=device)
     return q, k, v

@@ -1,0 +1,82 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol, and its host
+logic (budget rules, validation, error codes) behaves as include/thrift.h says.  No kernel runs."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_23081_amd import binding as T
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "thrift.h")).read()
+    declared = set(re.findall(r"\b(thrift_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(T.EXPORTS), declared ^ set(T.EXPORTS)
+    L = T.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_host_budget_helpers_match_the_oracle(oracle):
+    for vis in (0, 1, 19, 20, 21, 64, 2048):
+        for f in (0.0, 1e-7, 0.01, 0.05, 0.1, 0.25, 0.999999, 1.0):
+            assert T.row_budget(vis, f) == oracle.row_k(vis, f)
+        assert T.row_budget(vis, 0.5, fixed_k=7) == oracle.row_k(vis, 0.5, 7)
+    for Bq, Bk, Tk in ((64, 64, 32), (128, 64, 64), (1, 64, 16)):
+        for i in range(0, 16):
+            assert T.visible_blocks(i, Tk, Bq, Bk, True) == oracle.visible_blocks(i, Tk, Bq, Bk, True)
+    assert T.visible_blocks(0, 2048, 1, 64, True, 131071) == 2048
+    for n, f in ((32, 0.05), (512, 0.05), (2048, 0.25)):
+        assert T.budget_to_global_k(n, f) == oracle.paper_global_k(n, f)
+    assert T.select_kmax(32, 32, 64, 64, True, 0.05) == 2
+    assert T.select_kmax(1024, 2048, 128, 64, True, 0.05) == 103
+    assert T.select_kmax(8, 8, 64, 64, False, 0.0, fixed_k=3) == 3
+
+
+def test_validation_errors_come_before_any_launch():
+    L = T.lib()
+    fake = C.c_void_p(0x1000)   # never dereferenced: every call below must fail validation first
+    NULL, SHAPE, DTYPE, BUDGET, WORKSPACE = 1, 2, 3, 4, 5
+    assert L.thrift_block_means(None, 0, 1, 1, 64, 128, 64, fake, None) == NULL
+    assert L.thrift_block_means(fake, 0, 1, 1, 64, 64, 64, fake, None) == SHAPE      # D != 128
+    assert L.thrift_block_means(fake, 0, 1, 1, 100, 128, 64, fake, None) == SHAPE    # N % block
+    assert L.thrift_block_means(fake, 7, 1, 1, 64, 128, 64, fake, None) == DTYPE
+    assert L.thrift_block_means(fake, 2, 1, 1, 64, 128, 64, fake, None) == DTYPE     # fp32 is output-only
+    assert L.thrift_quantize_mxfp4(fake, 0, 1, 1, 96, 128, 1, fake, fake, None) == SHAPE   # axis 1 needs N % 64
+    assert L.thrift_quantize_mxfp4(fake, 0, 1, 1, 64, 128, 2, fake, fake, None) == SHAPE
+    sel = lambda **kw: L.thrift_select_topk(fake, fake, 1, kw.get("Hq", 4), kw.get("Hkv", 2), 8, kw.get("Tk", 8), 128, 64, 64, 1,
+                                            C.c_double(kw.get("budget", 0.05)), kw.get("fixed_k", -1), 0, fake, fake,
+                                            kw.get("kmax", 8), None)
+    assert sel(Hq=3) == SHAPE
+    assert sel(Tk=5000) == SHAPE
+    assert sel(budget=1.5) == BUDGET
+    assert sel(budget=-0.1) == BUDGET
+    assert sel(budget=1.0, kmax=4) == BUDGET           # kmax too small for a 100 % budget
+    pre = lambda **kw: L.thrift_attn_prefill(fake, fake, fake, kw.get("dt", 0), fake, fake, fake, fake, fake, fake, fake, fake, 4,
+                                             1, 4, kw.get("Hkv", 2), kw.get("N", 256), kw.get("D", 128), kw.get("Bq", 64),
+                                             kw.get("Bk", 64), 1, C.c_float(0.0), kw.get("out", fake), kw.get("odt", 0), None,
+                                             None, 0, None)
+    assert pre(Bq=32) == SHAPE and pre(Bk=128) == SHAPE and pre(D=64) == SHAPE and pre(N=200) == SHAPE and pre(Hkv=3) == SHAPE
+    assert pre(out=None) == NULL
+    assert pre(odt=5) == DTYPE and pre(dt=2) == DTYPE
+    dec = lambda **kw: L.thrift_attn_decode(fake, 0, fake, fake, fake, fake, fake, fake, fake, None, 1, 4, 2, kw.get("N", 1024), 128, 64,
+                                            C.c_double(kw.get("budget", 0.05)), -1, kw.get("split", 8), C.c_float(0.0), fake, 0,
+                                            None, None, 0, kw.get("ws", fake), kw.get("wsb", 1 << 30), None)
+    assert dec(split=0) == SHAPE and dec(split=6) == SHAPE and dec(N=1000) == SHAPE
+    assert dec(budget=2.0) == BUDGET
+    assert dec(ws=None) == WORKSPACE and dec(wsb=16) == WORKSPACE
+    need = T.decode_workspace_bytes(16, 32, 8, 131072, 128, 64, 256)
+    assert 0 < need < (64 << 20)
+    assert T.decode_workspace_bytes(16, 32, 8, 131072, 64, 64, 256) == 0
+    assert "gfx950" in T.status_string(6)
+
+
+def test_without_a_gpu_valid_calls_fail_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    fake = C.c_void_p(0x1000)
+    assert T.lib().thrift_block_means(fake, 0, 1, 1, 64, 128, 64, fake, None) == 6   # THRIFT_ERR_ARCH, nothing launched

@@ -1,0 +1,269 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on identical seeded inputs.
+
+Bars (from the build's target): selected block ids exact wherever neighbouring scores differ by more
+than 1e-6 relative; MXFP4 codes and scales bit-exact; block means bit-exact; outputs of all-16-bit
+runs within 2e-3 max abs; mixed outputs within 3e-2 max abs.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_23081_amd import workloads as W
+from tests.gpu_util import check_selection, to_np, unpack_axis0, unpack_axis1
+
+pytestmark = pytest.mark.gpu
+
+TOL16 = 2e-3
+TOLMIX = 3e-2
+
+
+@pytest.fixture(scope="module")
+def T():
+    from paper_2605_23081_amd import binding
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.lib()
+    return binding
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _small_bf16(N=1024, Hq=4, Hkv=2, Bq=128, seed=3, **kw):
+    return W.scaled(W.QWEN3_32K, N=N, Hq=Hq, Hkv=Hkv, Bq=Bq, seed=seed, **kw)
+
+
+def _units(B, H, Tq):
+    return np.array([(b, h, i) for b in range(B) for h in range(H) for i in range(Tq)], np.int32)
+
+
+# ------------------------------------------------------------------ block means
+
+@pytest.mark.parametrize("wl,block", [(W.TINY, 64), (_small_bf16(), 128), (_small_bf16(), 64), (_small_bf16(N=384, Bq=64), 96)])
+def test_block_means_bit_exact(T, oracle, wl, block):
+    _say(f"block_means {wl.name} N={wl.N} block={block}")
+    q, k, v, _, _ = W.make_prefill(wl)
+    for t in (q, k):
+        bits, dt = oracle.bits_of(t)
+        want = oracle.block_means(bits, dt, block)
+        got = to_np(T.thrift_block_means(t.cuda(), block))
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+# ------------------------------------------------------------------ quantiser
+
+def _edge_tensor(dtype):
+    """[1,1,64,128] with groups that exercise zeros, signed zeros, saturation, ties, tiny and huge magnitudes."""
+    g = torch.Generator().manual_seed(11)
+    x = torch.randn(1, 1, 64, 128, generator=g)
+    x[0, 0, 0, :32] = 0.0
+    x[0, 0, 1, :32] = -0.0
+    x[0, 0, 2, :32] = torch.tensor([7.0] + [0.25 * i for i in range(31)])           # ties at every half step, max in (6,8)
+    x[0, 0, 3, :32] = torch.tensor([4.0, 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0] * 4) * torch.tensor([1, -1] * 16)
+    x[0, 0, 4, :32] = 60000.0 if dtype == torch.float16 else 3.0e38
+    x[0, 0, 5, :32] = 6.0e-8 if dtype == torch.float16 else 1.0e-30
+    x[0, 0, 6, :32] = torch.linspace(-1e-3, 1e-3, 32)
+    x[0, 0, 7, 32:64] = torch.tensor([1e4] + [1e-4] * 31)                             # everything but the max underflows to 0
+    if dtype == torch.bfloat16:
+        x[0, 0, 8, :32] = 1.0e-38                                                    # scale byte would be < 1
+        x[0, 0, 9, :32] = torch.tensor([2.0 ** -126 * (i + 1) / 8 for i in range(32)])
+    x[0, 0, 32:, 64:] *= 100.0
+    return x.to(dtype)
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
+def test_quantize_bit_exact_edges_and_random(T, oracle, dtype):
+    _say(f"quantize edges {dtype}")
+    wl = W.TINY if dtype == torch.float16 else _small_bf16()
+    q, k, v, _, _ = W.make_prefill(W.scaled(wl, N=512))
+    for name, x in (("edges", _edge_tensor(dtype)), ("q", q), ("k", k), ("v", v)):
+        bits, dt = oracle.bits_of(x)
+        for axis in (0, 1):
+            want_c, want_s = oracle.quantize_mxfp4(bits, dt, axis)
+            codes, scales = T.thrift_quantize_mxfp4(x.cuda(), axis)
+            got_c = unpack_axis0(to_np(codes)) if axis == 0 else unpack_axis1(to_np(codes))
+            assert np.array_equal(to_np(scales), want_s), (name, axis)
+            bad = np.argwhere(got_c != want_c)
+            assert bad.size == 0, (name, axis, bad[:5], got_c[tuple(bad[0])], want_c[tuple(bad[0])])
+
+
+# ------------------------------------------------------------------ selection
+
+def _select_case(T, oracle, wl, budget, causal=True, fixed_k=-1):
+    q, k, v, _, _ = W.make_prefill(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k)
+    qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    idx_r, cnt_r = oracle.select_topk(qm, km, wl.Bq, wl.Bk, causal, budget, fixed_k)
+    qm_g = T.thrift_block_means(q.cuda(), wl.Bq); km_g = T.thrift_block_means(k.cuda(), wl.Bk)
+    idx_g, cnt_g = T.thrift_select_topk(qm_g, km_g, wl.Bq, wl.Bk, causal, budget, fixed_k)
+    assert idx_g.shape[-1] == max(1, idx_r.shape[-1]) or idx_g.shape[-1] >= idx_r.shape[-1]
+    ig = to_np(idx_g)[..., :idx_r.shape[-1]] if idx_r.shape[-1] <= idx_g.shape[-1] else to_np(idx_g)
+    assert np.all(to_np(idx_g)[..., idx_r.shape[-1]:] == -1)
+    return check_selection(ig, to_np(cnt_g), idx_r, cnt_r, oracle.block_scores(qm, km))
+
+
+@pytest.mark.parametrize("budget", [0.0, 0.05, 0.25, 1.0])
+def test_select_topk_sets(T, oracle, budget):
+    _say(f"select tiny budget={budget}")
+    assert _select_case(T, oracle, W.TINY, budget) == 0
+    _say(f"select bf16 GQA budget={budget}")
+    assert _select_case(T, oracle, _small_bf16(N=4096, Hq=4, Hkv=2), budget) == 0
+
+
+def test_select_topk_variants(T, oracle):
+    _say("select non-causal / fixed_k / 80 blocks (two chunks, ragged) / odd group size")
+    assert _select_case(T, oracle, _small_bf16(N=2048), 0.1, causal=False) == 0
+    assert _select_case(T, oracle, _small_bf16(N=2048), 0.0, fixed_k=5) == 0
+    assert _select_case(T, oracle, _small_bf16(N=5120, Hq=3, Hkv=1, Bq=64), 0.05) == 0
+    assert _select_case(T, oracle, _small_bf16(N=5120, Hq=6, Hkv=2, Bq=128), 0.3) == 0
+
+
+def test_select_topk_ties(T, oracle):
+    _say("select with exact ties")
+    g = torch.Generator().manual_seed(5)
+    qm = torch.randint(-2, 3, (1, 2, 8, 128), generator=g).float()
+    km = torch.randint(-2, 3, (1, 1, 96, 128), generator=g).float()
+    km[0, 0, 70] = km[0, 0, 3]; km[0, 0, 71] = km[0, 0, 3]
+    for fixed_k in (1, 4, 17, 96):
+        idx_r, cnt_r = oracle.select_topk(qm.numpy(), km.numpy(), 64, 64, False, 0.0, fixed_k)
+        idx_g, cnt_g = T.thrift_select_topk(qm.cuda(), km.cuda(), 64, 64, False, 0.0, fixed_k)
+        assert np.array_equal(to_np(idx_g), idx_r) and np.array_equal(to_np(cnt_g), cnt_r)
+
+
+# ------------------------------------------------------------------ prefill
+
+def _prefill_both(T, oracle, wl, budget, causal=True, force_sel=None, out_dtype=torch.float32):
+    """Runs GPU and oracle with the ORACLE's selection fed to both; returns (gpu out, oracle out)."""
+    q, k, v, _, _ = W.make_prefill(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(wl.D)
+    Tq = wl.N // wl.Bq
+    qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    idx, cnt = oracle.select_topk(qm, km, wl.Bq, wl.Bk, causal, budget) if force_sel is None else force_sel
+    want, want_lse = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, wl.Bq, wl.Bk, causal, scale,
+                                                _units(wl.B, wl.Hq, Tq), want_lse=True)
+    want = want.reshape(wl.B, wl.Hq, wl.N, wl.D)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    lse = torch.empty(wl.B, wl.Hq, wl.N, dtype=torch.float32, device="cuda")
+    got = T.thrift_attn_prefill(qg, kg, vg, q4, qs, k4, ks, v4, vs, torch.from_numpy(idx).cuda(), torch.from_numpy(cnt).cuda(),
+                                wl.Bq, wl.Bk, causal, 0.0, out_dtype=out_dtype, lse=lse)
+    torch.cuda.synchronize()
+    return to_np(got.float()), want, to_np(lse), want_lse.reshape(wl.B, wl.Hq, wl.N)
+
+
+@pytest.mark.parametrize("wl", [W.TINY, _small_bf16(N=1024), _small_bf16(N=640, Hq=2, Hkv=1, Bq=64)])
+def test_prefill_all_16bit_tiles(T, oracle, wl):
+    _say(f"prefill 100% {wl.name} N={wl.N} Bq={wl.Bq}")
+    got, want, lse, want_lse = _prefill_both(T, oracle, wl, 1.0)
+    err = np.abs(got - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert err <= TOL16
+    assert np.abs(lse - want_lse).max() <= 1e-3
+
+
+@pytest.mark.parametrize("wl", [W.TINY, _small_bf16(N=1024)])
+def test_prefill_all_4bit_tiles(T, oracle, wl):
+    _say(f"prefill 0% {wl.name} N={wl.N} Bq={wl.Bq}")
+    got, want, _, _ = _prefill_both(T, oracle, wl, 0.0)
+    err = np.abs(got - want)
+    _say(f"  max abs err {err.max():.3e}  p99.9 {np.quantile(err, 0.999):.3e}")
+    assert err.max() <= TOLMIX
+
+
+@pytest.mark.parametrize("budget", [0.05, 0.10, 0.25])
+@pytest.mark.parametrize("wl", [W.TINY, _small_bf16(N=2048)])
+def test_prefill_mixed(T, oracle, wl, budget):
+    _say(f"prefill mixed {wl.name} N={wl.N} Bq={wl.Bq} budget={budget}")
+    got, want, lse, want_lse = _prefill_both(T, oracle, wl, budget)
+    err = np.abs(got - want)
+    _say(f"  max abs err {err.max():.3e}  p99.9 {np.quantile(err, 0.999):.3e}")
+    assert err.max() <= TOLMIX
+
+
+def test_prefill_non_causal_and_output_dtypes(T, oracle):
+    wl = _small_bf16(N=512, Hq=2, Hkv=1)
+    _say("prefill non-causal, bf16/f32 outputs")
+    got, want, _, _ = _prefill_both(T, oracle, wl, 0.25, causal=False)
+    assert np.abs(got - want).max() <= TOLMIX
+    got16, want, _, _ = _prefill_both(T, oracle, wl, 0.25, causal=False, out_dtype=torch.bfloat16)
+    # bf16 output: one rounding of the fp32 result
+    assert np.abs(got16 - torch.from_numpy(got).to(torch.bfloat16).float().numpy()).max() == 0
+    wl = W.scaled(W.TINY, N=512)
+    got, want, _, _ = _prefill_both(T, oracle, wl, 0.25, out_dtype=torch.float16)
+    assert np.abs(got - want).max() <= TOLMIX
+
+
+def test_prefill_end_to_end_alg1(T, oracle):
+    """Q, K, V in, output out, every stage on the GPU (means, TopK, quantisation, attention)."""
+    wl = _small_bf16(N=2048)
+    _say("prefill end-to-end Alg. 1")
+    q, k, v, _, _ = W.make_prefill(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    idx, cnt = oracle.select_topk(qm, km, wl.Bq, wl.Bk, True, 0.05)
+    want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, wl.Bq, wl.Bk, True, 1 / math.sqrt(wl.D),
+                                      _units(1, wl.Hq, wl.N // wl.Bq)).reshape(1, wl.Hq, wl.N, wl.D)
+    got = T.thrift_attention(q.cuda(), k.cuda(), v.cuda(), True, wl.Bq, wl.Bk, 0.05, out_dtype=torch.float32)
+    assert np.abs(to_np(got) - want).max() <= TOLMIX
+    # determinism: a second run gives the same bits
+    got2 = T.thrift_attention(q.cuda(), k.cuda(), v.cuda(), True, wl.Bq, wl.Bk, 0.05, out_dtype=torch.float32)
+    assert torch.equal(got, got2)
+
+
+# ------------------------------------------------------------------ decode
+
+def _decode_case(T, oracle, wl, budget, split_blocks, seqlens=None, fixed_k=-1):
+    q, k, v = W.make_decode(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(wl.D)
+    B, Hq, Tk = wl.B, wl.Hq, wl.N // wl.Bk
+    km = oracle.block_means(kb, dt, wl.Bk)
+    qm = q.float().numpy().reshape(B, Hq, 1, wl.D)
+    sl = None if seqlens is None else np.asarray(seqlens, np.int32)
+    kmax = max(1, oracle.row_k(Tk, budget, fixed_k))
+    idx_r = np.full((B, Hq, kmax), -1, np.int32); cnt_r = np.zeros((B, Hq), np.int32)
+    for b in range(B):
+        tkb = Tk if sl is None else sl[b] // wl.Bk
+        i_b, c_b = oracle.select_topk(qm[b:b + 1], km[b:b + 1, :, :tkb], 1, wl.Bk, False, budget, fixed_k)
+        idx_r[b, :, :i_b.shape[-1]] = i_b[0, :, 0]; cnt_r[b] = c_b[0, :, 0]
+    # the library runs each partition as four consecutive sub-partitions (one per wavefront): split-K
+    # with partitions of split_blocks / 4 key blocks
+    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, scale, split_blocks // 4, seqlens=sl)
+    kg, vg = k.cuda(), v.cuda()
+    k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    kmean = T.thrift_block_means(kg, wl.Bk)
+    got, idx_g, cnt_g = T.thrift_attn_decode(q.cuda(), kg, vg, k4, ks, v4, vs, kmean, wl.Bk, budget, fixed_k, split_blocks,
+                                             seqlens=None if sl is None else torch.from_numpy(sl).cuda(),
+                                             out_dtype=torch.float32, return_selection=True)
+    torch.cuda.synchronize()
+    scores = np.zeros((B, Hq, Tk))
+    for b in range(B):
+        scores[b] = oracle.block_scores(qm[b:b + 1], km[b:b + 1])[0, :, 0]
+    swaps = check_selection(to_np(idx_g), to_np(cnt_g), idx_r, cnt_r, scores)
+    return to_np(got), want, swaps
+
+
+@pytest.mark.parametrize("budget", [0.0, 0.05, 0.25, 1.0])
+def test_decode_parity(T, oracle, budget):
+    wl = W.scaled(W.DECODE_131K, B=2, N=4096, Hq=8, Hkv=2)
+    _say(f"decode B=2 N=4096 budget={budget}")
+    got, want, swaps = _decode_case(T, oracle, wl, budget, 16)
+    err = np.abs(got - want).max()
+    _say(f"  max abs err {err:.3e} swaps {swaps}")
+    assert swaps == 0
+    assert err <= (TOL16 if budget == 1.0 else TOLMIX)
+
+
+def test_decode_variants(T, oracle):
+    _say("decode bf16, group of 1, ragged partition, seqlens, fixed_k")
+    wl = W.scaled(W.DECODE_131K, B=2, N=2560, Hq=4, Hkv=4, dtype="bf16")
+    got, want, swaps = _decode_case(T, oracle, wl, 0.1, 16)          # 40 blocks: partitions of 16,16,8
+    assert swaps == 0 and np.abs(got - want).max() <= TOLMIX
+    wl = W.scaled(W.DECODE_131K, B=3, N=2048, Hq=8, Hkv=2)
+    got, want, swaps = _decode_case(T, oracle, wl, 0.05, 8, seqlens=[2048, 640, 64])
+    assert swaps == 0 and np.abs(got - want).max() <= TOLMIX
+    got, want, swaps = _decode_case(T, oracle, wl, 0.0, 32, fixed_k=3)
+    assert swaps == 0 and np.abs(got - want).max() <= TOLMIX
