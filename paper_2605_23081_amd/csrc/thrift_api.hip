@@ -36,7 +36,7 @@ thrift_status after_launch() { return hipGetLastError() == hipSuccess ? THRIFT_O
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct DecodeLayout {
-  size_t qf32, q4, qs, idx, cnt, bitmap, part_o, part_ml, total;
+  size_t qf32, q4, qs, keys, bitmap, part_o, part_ml, total;
   int nsplit, nparts, words;
 };
 
@@ -50,8 +50,7 @@ DecodeLayout decode_layout(int B, int Hq, int Nkv, int Bk, int split_blocks) {
   L.qf32 = off; off += align256((size_t)B * Hq * kHeadDim * sizeof(float));
   L.q4 = off; off += align256((size_t)B * Hq * (kHeadDim / 2));
   L.qs = off; off += align256((size_t)B * Hq * (kHeadDim / 32));
-  L.idx = off; off += align256((size_t)B * Hq * Tk * sizeof(int32_t));
-  L.cnt = off; off += align256((size_t)B * Hq * sizeof(int32_t));
+  L.keys = off; off += align256((size_t)B * Hq * Tk * sizeof(uint64_t));
   L.bitmap = off; off += align256((size_t)B * Hq * L.words * sizeof(unsigned long long));
   L.part_o = off; off += align256((size_t)B * Hq * L.nparts * kHeadDim * sizeof(float));
   L.part_ml = off; off += align256((size_t)B * Hq * L.nparts * 2 * sizeof(float));
@@ -222,25 +221,19 @@ thrift_status thrift_attn_decode(const void* q, thrift_dtype dt, const void* k16
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
   float* qf32 = (float*)(ws + L.qf32);
-  int32_t* idx = (int32_t*)(ws + L.idx);
-  int32_t* cnt = (int32_t*)(ws + L.cnt);
+  unsigned long long* bitmap = (unsigned long long*)(ws + L.bitmap);
 
-  // (i) the query token is its own block mean; score it against the cached key-block means
+  // (i) the query token is its own block mean; score it against the cached key-block means and select
   launch_block_means(q, dt, (long)B * Hq, 1, qf32, st);
   launch_quantize(q, dt, (long)B * Hq, 1, 0, (uint8_t*)(ws + L.q4), (uint8_t*)(ws + L.qs), st);
-  SelectArgs sa;
-  sa.qmean = qf32; sa.kmean = kmean; sa.idx = idx; sa.cnt = cnt;
-  sa.bitmap = (unsigned long long*)(ws + L.bitmap); sa.bitmap_words = L.words; sa.seqlens = seqlens;
-  sa.B = B; sa.Hq = Hq; sa.Hkv = Hkv; sa.Tq = 1; sa.Tk = Tk; sa.Bq = 1; sa.Bk = Bk; sa.causal = 0;
-  sa.fixed_k = fixed_k; sa.q_block_offset = 0; sa.kmax = Tk; sa.ppm = fixed_k >= 0 ? 0 : budget_ppm(budget);
-  launch_select_topk(sa, st);
-  if (idx_out) launch_copy_selection(idx, cnt, Tk, idx_out, cnt_out, kmax_out, (long)B * Hq, st);
+  launch_decode_select(qf32, kmean, seqlens, (uint64_t*)(ws + L.keys), bitmap, L.words, idx_out, cnt_out, kmax_out,
+                       B, Hq, Hkv, Tk, fixed_k, fixed_k >= 0 ? 0 : budget_ppm(budget), st);
 
   // (ii) split-K partial attention, (iii) log-sum-exp merge
   DecodeArgs a;
   a.q = (const uint16_t*)q; a.q4 = (const uint8_t*)(ws + L.q4); a.qs = (const uint8_t*)(ws + L.qs); a.k16 = (const uint16_t*)k16; a.v16 = (const uint16_t*)v16;
   a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.seqlens = seqlens;
-  a.bitmap = sa.bitmap; a.bitmap_words = L.words;
+  a.bitmap = bitmap; a.bitmap_words = L.words;
   a.out = out; a.part_o = (float*)(ws + L.part_o); a.part_ml = (float*)(ws + L.part_ml);
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Nkv = Nkv; a.split_blocks = split_blocks; a.nsplit = L.nsplit; a.nparts = L.nparts;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);

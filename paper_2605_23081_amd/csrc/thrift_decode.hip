@@ -154,6 +154,168 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Decode-time block selection (Alg. 1 step 5 for one-token query blocks).  Two kernels, so that the
+// whole chip works on the B*Hq short rows:
+//   decode_scores_kernel  one workgroup per (sequence, KV head, 64 key blocks): stages the 64 cached
+//                         key-block means once and scores them against the G query heads of the group
+//                         (fp64, channels in ascending order), storing order-preserving 64-bit keys;
+//   decode_select_kernel  one workgroup per (sequence, query head): finds the k-th largest key by a
+//                         bitwise search with workgroup-wide counting and writes the selection as a
+//                         bitmap (and, on request, as an ascending id list).
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t order_key64(double s) {
+  uint64_t u = (uint64_t)__double_as_longlong(s);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);   // larger double <=> larger key
+}
+
+__global__ void __launch_bounds__(256) decode_scores_kernel(const float* __restrict__ qf32, const float* __restrict__ kmean,
+                                                            const int32_t* __restrict__ seqlens, uint64_t* __restrict__ keys,
+                                                            int Hq, int Hkv, int Tk) {
+  constexpr int kStride = kD + 4;
+  __shared__ __align__(16) float kst[64 * kStride];
+  __shared__ __align__(16) float qst[32 * kD];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int G = Hq / Hkv, chunks = (Tk + 63) / 64;
+  const int chunk = blockIdx.x % chunks, unit = blockIdx.x / chunks;
+  const int b = unit / Hkv, kvh = unit % Hkv;
+  const int cap = seqlens ? min(Tk, max(0, seqlens[b]) / kBk) : Tk;
+  if (chunk * 64 >= cap) return;                            // uniform: nothing of this chunk is valid
+  const float* kbase = kmean + ((size_t)unit * Tk + (size_t)chunk * 64) * kD;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const int c4 = tid + 256 * u, row = c4 >> 5, col = (c4 & 31) * 4;
+    if (chunk * 64 + row < Tk)
+      *reinterpret_cast<float4*>(&kst[row * kStride + col]) = *reinterpret_cast<const float4*>(kbase + (size_t)row * kD + col);
+  }
+  const float* qbase = qf32 + ((size_t)b * Hq + (size_t)kvh * G) * kD;
+  for (int e = tid; e < G * kD; e += 256) qst[e] = qbase[e];
+  __syncthreads();
+  const int j = chunk * 64 + lane;
+  if (j >= cap) return;
+  for (int g = wave; g < G; g += 4) {
+    double s = 0.0;
+#pragma unroll 8
+    for (int d = 0; d < kD; d += 4) {
+      const float4 kv = *reinterpret_cast<const float4*>(&kst[lane * kStride + d]);
+      const float4 qv = *reinterpret_cast<const float4*>(&qst[g * kD + d]);
+      s = fma((double)qv.x, (double)kv.x, s);
+      s = fma((double)qv.y, (double)kv.y, s);
+      s = fma((double)qv.z, (double)kv.z, s);
+      s = fma((double)qv.w, (double)kv.w, s);
+    }
+    keys[((size_t)b * Hq + kvh * G + g) * Tk + j] = order_key64(s);
+  }
+}
+
+struct DecodeSelectArgs {
+  const uint64_t* keys;       // [B*Hq][Tk]
+  const int32_t* seqlens;
+  unsigned long long* bitmap; // [B*Hq][words]
+  int32_t* idx_out;           // nullable [B*Hq][kmax_out]
+  int32_t* cnt_out;           // nullable [B*Hq]
+  int Hq, Tk, words, kmax_out, fixed_k;
+  long long ppm;
+};
+
+__global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p) {
+  constexpr int MAXS = 16;                                  // 16 slices of 256 key blocks: Tk <= 4096
+  __shared__ int part[2][4];
+  __shared__ int scan[2][4];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const size_t row = blockIdx.x;
+  const int b = (int)(row / p.Hq);
+  const int vis = p.seqlens ? min(p.Tk, max(0, p.seqlens[b]) / kBk) : p.Tk;
+  int k;
+  if (p.fixed_k >= 0) k = min(p.fixed_k, vis);
+  else if (p.ppm <= 0) k = 0;
+  else {
+    long long kk = (p.ppm * (long long)vis + 999999LL) / 1000000LL;
+    k = (int)max(1LL, min(kk, (long long)vis));
+    if (vis == 0) k = 0;
+  }
+  const int slices = (vis + 255) / 256;
+  uint64_t key[MAXS];
+#pragma unroll
+  for (int t = 0; t < MAXS; ++t) {
+    const int j = t * 256 + tid;
+    key[t] = (t < slices && j < vis) ? p.keys[row * p.Tk + j] : 0ULL;
+  }
+  unsigned long long* bm = p.bitmap + row * p.words;
+  int32_t* out = p.idx_out ? p.idx_out + row * p.kmax_out : nullptr;
+  if (p.cnt_out && tid == 0) p.cnt_out[row] = k;
+  if (k <= 0) {
+    for (int w = tid; w < p.words; w += 256) bm[w] = 0ULL;
+    if (out) for (int t = tid; t < p.kmax_out; t += 256) out[t] = -1;
+    return;
+  }
+  // workgroup-wide count of valid keys satisfying a predicate: ballots per slice, then 4 wave partials
+  int round = 0;
+  auto count_ge = [&](uint64_t cand, bool strict) -> int {
+    int n = 0;
+#pragma unroll
+    for (int t = 0; t < MAXS; ++t)
+      if (t < slices) {
+        const bool valid = t * 256 + tid < vis;
+        n += __popcll(__ballot(valid && (strict ? key[t] > cand : key[t] >= cand)));
+      }
+    int* slot = part[round & 1];
+    ++round;
+    if (lane == 0) slot[wave] = n;
+    __syncthreads();
+    return slot[0] + slot[1] + slot[2] + slot[3];
+  };
+  uint64_t T = 0;
+  for (int bit = 63; bit >= 0; --bit) {
+    const uint64_t cand = T | (1ULL << bit);
+    if (count_ge(cand, false) >= k) T = cand;
+  }
+  const int need_ties = k - count_ge(T, true);              // >= 1: keys equal to T, taken from the smallest id up
+  const uint64_t lt_mask = (1ULL << lane) - 1ULL;
+  int written = 0, ties_seen = 0;
+#pragma unroll
+  for (int t = 0; t < MAXS; ++t) {
+    if (t < slices) {                                       // uniform
+      const int j = t * 256 + tid;
+      const bool valid = j < vis;
+      const bool tie = valid && key[t] == T;
+      const uint64_t tie_b = __ballot(tie);
+      int* ps = scan[0];
+      if (lane == 0) ps[wave] = __popcll(tie_b);
+      __syncthreads();
+      int tie_before = ties_seen;
+      for (int w = 0; w < wave; ++w) tie_before += ps[w];
+      const int tie_total = ps[0] + ps[1] + ps[2] + ps[3];
+      const bool sel = valid && (key[t] > T || (tie && tie_before + __popcll(tie_b & lt_mask) < need_ties));
+      const uint64_t sel_b = __ballot(sel);
+      int* ss = scan[1];
+      if (lane == 0) ss[wave] = __popcll(sel_b);
+      __syncthreads();
+      int sel_before = written;
+      for (int w = 0; w < wave; ++w) sel_before += ss[w];
+      const int sel_total = ss[0] + ss[1] + ss[2] + ss[3];
+      if (sel && out) out[sel_before + __popcll(sel_b & lt_mask)] = j;
+      if (lane == 0 && t * 4 + wave < p.words) bm[t * 4 + wave] = sel_b;
+      written += sel_total;
+      ties_seen += tie_total;
+      __syncthreads();                                      // scan[] is reused by the next slice
+    }
+  }
+  for (int w = slices * 4 + tid; w < p.words; w += 256) bm[w] = 0ULL;
+  if (out) for (int t = k + tid; t < p.kmax_out; t += 256) out[t] = -1;
+}
+
+void launch_decode_select(const float* qf32, const float* kmean, const int32_t* seqlens, uint64_t* keys,
+                          unsigned long long* bitmap, int words, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                          int B, int Hq, int Hkv, int Tk, int fixed_k, long long ppm, hipStream_t st) {
+  const int chunks = (Tk + 63) / 64;
+  decode_scores_kernel<<<dim3((unsigned)((long)B * Hkv * chunks)), dim3(256), 0, st>>>(qf32, kmean, seqlens, keys, Hq, Hkv, Tk);
+  DecodeSelectArgs p;
+  p.keys = keys; p.seqlens = seqlens; p.bitmap = bitmap; p.idx_out = idx_out; p.cnt_out = cnt_out;
+  p.Hq = Hq; p.Tk = Tk; p.words = words; p.kmax_out = kmax_out; p.fixed_k = fixed_k; p.ppm = ppm;
+  decode_select_kernel<<<dim3((unsigned)((long)B * Hq)), dim3(256), 0, st>>>(p);
+}
+
 // Log-sum-exp merge of the partials of one (sequence, query head): 128 threads, one per channel.
 __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
   const size_t qh = blockIdx.x;

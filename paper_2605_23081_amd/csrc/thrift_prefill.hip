@@ -5,8 +5,9 @@
 // in registers.  Key blocks are visited in ascending order (the order of Alg. 1); each block is staged
 // once into LDS for all wavefronts — MXFP4 codes + scales for ordinary blocks, the 16-bit K/V tile for
 // blocks listed in the row's TopK set — and dispatched per tile to the scaled-FP4 or the 16-bit MFMA
-// path.  4-bit tiles are prefetched into registers one block ahead so that their global latency hides
-// behind the current tile's arithmetic.
+// path.  4-bit tiles are prefetched into registers two blocks ahead and written to the other of two LDS
+// buffers one block ahead, so their global latency hides behind arithmetic and one barrier per block
+// suffices.
 //
 // Differences from the kernel the paper sketches for Blackwell (Sec. 3.3): no two-phase split (4-bit
 // tiles first, 16-bit helper afterwards) — on gfx950 both Q fragment sets fit in the 512-entry register
@@ -21,7 +22,7 @@ template <typename T, int NW>
 __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   constexpr int NT = NW * 64;
   constexpr int CH = 256 / NT;                         // 16-byte chunks of a 4 KiB tile per thread
-  __shared__ __align__(16) unsigned char lds[kLdsBytes16];
+  __shared__ __align__(16) unsigned char lds[2 * kLdsBytes16];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int N = a.N, Bq = NW * 32, Tq = N / Bq, Tk = N / kBk, G = a.Hq / a.Hkv;
@@ -55,8 +56,9 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   const int vis = a.causal ? min(Tk, ((i + 1) * Bq - 1) / kBk + 1) : Tk;
   const int32_t* sel = a.idx + (qh * Tq + i) * a.kmax;
   const int nsel = a.cnt[qh * Tq + i];
+  // the next three promoted block ids at or after the current block (ascending list)
   int ps = 0;
-  int next16 = nsel > 0 ? sel[0] : 0x7fffffff;
+  int n0 = nsel > 0 ? sel[0] : 0x7fffffff, n1 = nsel > 1 ? sel[1] : 0x7fffffff, n2 = nsel > 2 ? sel[2] : 0x7fffffff;
 
   const uint8_t* k4base = a.k4 + kh * N * 64;
   const uint8_t* v4base = a.v4 + kh * (size_t)(N / 64) * 4096;
@@ -65,8 +67,9 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   const uint16_t* k16base = a.k + kh * N * kD;
   const uint16_t* v16base = a.v + kh * N * kD;
 
-  // ---- register prefetch of a 4-bit tile: each thread carries CH 16-byte chunks of K and of V and
-  // (threads 0-127) one dword of scale bytes ----
+  // ---- staging.  A 4-bit tile travels global -> registers (one block ahead) -> LDS; each thread carries
+  // CH 16-byte chunks of K and of V and (threads 0-127) one dword of scale bytes.  A 16-bit tile is copied
+  // global -> LDS in place.  Two LDS buffers alternate, so one barrier per key block is enough. ----
   uint4 pk0 = make_uint4(0, 0, 0, 0), pk1 = pk0, pv0 = pk0, pv1 = pk0;
   uint32_t psc = 0;
 #define THRIFT_PREFETCH4(J)                                                                                    \
@@ -82,6 +85,34 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
     if (tid < 64) psc = *reinterpret_cast<const uint32_t*>(ksbase + (size_t)(J) * 256 + tid * 4);              \
     else if (tid < 128) psc = *reinterpret_cast<const uint32_t*>(vsbase + (size_t)(J) * 256 + (tid - 64) * 4); \
   } while (0)
+#define THRIFT_COMMIT4(BUF)                                                                                    \
+  do {                                                                                                         \
+    unsigned char* b_ = (BUF);                                                                                 \
+    *reinterpret_cast<uint4*>(b_ + kLdsK4 + k4_fragment_offset(tid >> 2, tid & 3)) = pk0;                      \
+    *reinterpret_cast<uint4*>(b_ + kLdsV4 + tid * 16) = pv0;                                                   \
+    if (CH == 2) {                                                                                             \
+      *reinterpret_cast<uint4*>(b_ + kLdsK4 + k4_fragment_offset((tid + NT) >> 2, (tid + NT) & 3)) = pk1;      \
+      *reinterpret_cast<uint4*>(b_ + kLdsV4 + (tid + NT) * 16) = pv1;                                          \
+    }                                                                                                          \
+    if (tid < 64) {                                                                                            \
+      *reinterpret_cast<uint32_t*>(b_ + kLdsKS + tid * 4) = psc;                                               \
+    } else if (tid < 128) {                                                                                    \
+      /* bytes 4w..4w+3 of the [2 groups][128 channels] scale rows -> [group][r][n], channel = 32n + r */      \
+      const int w_ = tid - 64, grp_ = w_ >> 5, ch_ = (4 * w_) & 127, n_ = ch_ >> 5, rr_ = ch_ & 31;            \
+      for (int bb = 0; bb < 4; ++bb) b_[kLdsVS + (grp_ * 32 + rr_ + bb) * 4 + n_] = (unsigned char)(psc >> (8 * bb)); \
+    }                                                                                                          \
+  } while (0)
+#define THRIFT_STAGE16(J, BUF)                                                                                 \
+  do {                                                                                                         \
+    unsigned char* b_ = (BUF);                                                                                 \
+    _Pragma("unroll") for (int u = 0; u < 1024 / NT; ++u) {                                                    \
+      const int chunk = tid + NT * u, row = chunk >> 4, col = chunk & 15;                                      \
+      const uint4 kk = *reinterpret_cast<const uint4*>(k16base + ((size_t)(J) * kBk + row) * kD + col * 8);    \
+      const uint4 vv = *reinterpret_cast<const uint4*>(v16base + ((size_t)(J) * kBk + row) * kD + col * 8);    \
+      *reinterpret_cast<uint4*>(b_ + kLdsK16 + row * kRow16 + col * 16) = kk;                                  \
+      *reinterpret_cast<uint4*>(b_ + kLdsV16 + row * kRow16 + col * 16) = vv;                                  \
+    }                                                                                                          \
+  } while (0)
 
   RowState st = {-INFINITY, 0.f};
   v16f o[4];
@@ -89,41 +120,34 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   for (int n = 0; n < 4; ++n) o[n] = (v16f){0.f};
   const float c = a.scale * 1.4426950408889634f;
 
-  if (vis > 0 && next16 != 0) THRIFT_PREFETCH4(0);
-  for (int j = 0; j < vis; ++j) {
-    const bool is16 = j == next16;
-    __syncthreads();                                    // every wavefront is done with the previous tile
-    if (is16) {
-      // 16-bit K and V tiles, row-major with padded rows
-#pragma unroll
-      for (int u = 0; u < 1024 / NT; ++u) {
-        const int chunk = tid + NT * u, row = chunk >> 4, col = chunk & 15;
-        const uint4 kk = *reinterpret_cast<const uint4*>(k16base + ((size_t)j * kBk + row) * kD + col * 8);
-        const uint4 vv = *reinterpret_cast<const uint4*>(v16base + ((size_t)j * kBk + row) * kD + col * 8);
-        *reinterpret_cast<uint4*>(lds + kLdsK16 + row * kRow16 + col * 16) = kk;
-        *reinterpret_cast<uint4*>(lds + kLdsV16 + row * kRow16 + col * 16) = vv;
-      }
-      ++ps;
-      next16 = ps < nsel ? sel[ps] : 0x7fffffff;
+  // prologue: block 0 into buffer 0, block 1 (if 4-bit) into the prefetch registers
+  if (vis > 0) {
+    if (n0 == 0) {
+      THRIFT_STAGE16(0, lds);
     } else {
-      // K codes in MFMA fragment order, V codes as they are, scale bytes
-      *reinterpret_cast<uint4*>(lds + kLdsK4 + k4_fragment_offset(tid >> 2, tid & 3)) = pk0;
-      *reinterpret_cast<uint4*>(lds + kLdsV4 + tid * 16) = pv0;
-      if (CH == 2) {
-        *reinterpret_cast<uint4*>(lds + kLdsK4 + k4_fragment_offset((tid + NT) >> 2, (tid + NT) & 3)) = pk1;
-        *reinterpret_cast<uint4*>(lds + kLdsV4 + (tid + NT) * 16) = pv1;
-      }
-      if (tid < 64) {
-        *reinterpret_cast<uint32_t*>(lds + kLdsKS + tid * 4) = psc;
-      } else if (tid < 128) {
-        // bytes 4w .. 4w+3 of the [2 groups][128 channels] scale rows -> [group][r][n], channel = 32n + r
-        const int w = tid - 64, grp = w >> 5, ch = (4 * w) & 127, n = ch >> 5, rr = ch & 31;
-#pragma unroll
-        for (int bb = 0; bb < 4; ++bb) lds[kLdsVS + (grp * 32 + rr + bb) * 4 + n] = (unsigned char)(psc >> (8 * bb));
-      }
+      THRIFT_PREFETCH4(0);
+      THRIFT_COMMIT4(lds);
     }
-    __syncthreads();
-    if (j + 1 < vis && j + 1 != next16) THRIFT_PREFETCH4(j + 1);
+    const int t1 = n0 == 0 ? n1 : n0;
+    if (vis > 1 && t1 != 1) THRIFT_PREFETCH4(1);
+  }
+  for (int j = 0; j < vis; ++j) {
+    const bool is16 = j == n0;
+    const int t1 = is16 ? n1 : n0;                      // first promoted id >= j+1
+    const bool next16 = j + 1 == t1;
+    const int t2 = next16 ? (is16 ? n2 : n1) : t1;      // first promoted id >= j+2
+    unsigned char* cur = lds + (j & 1) * kLdsBytes16;
+    unsigned char* nxt = lds + ((j + 1) & 1) * kLdsBytes16;
+    __syncthreads();            // block j is complete in `cur`; everyone has finished block j-1, which used `nxt`
+    if (j + 1 < vis) {
+      if (next16) THRIFT_STAGE16(j + 1, nxt);
+      else THRIFT_COMMIT4(nxt);
+      if (j + 2 < vis && j + 2 != t2) THRIFT_PREFETCH4(j + 2);
+    }
+    if (is16) {
+      ++ps;
+      n0 = n1; n1 = n2; n2 = ps + 2 < nsel ? sel[ps + 2] : 0x7fffffff;
+    }
 
     const int first_key = j * kBk;
     if (a.causal && first_key > q0 + 31) continue;      // nothing of this block is visible to this wavefront
@@ -131,17 +155,12 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
     const int n_valid = q0 + r - first_key + 1;         // keys of the block at positions <= the query's
     v16f s[2];
     float gmax;
-    if (is16) {
-      scores_16<T>(lds, lane, q16row, s);
-      const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-      rescale(o, alpha);
-      pv_16<T>(lds + kLdsV16, lane, s, o);
-    } else {
-      scores_fp4(lds, lane, qf4, qsc, s);
-      const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-      rescale(o, alpha);
-      pv_fp4(lds, lane, s, gmax, o);
-    }
+    if (is16) scores_16<T>(cur, lane, q16row, s);
+    else scores_fp4(cur, lane, qf4, qsc, s);
+    const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+    rescale(o, alpha);
+    if (is16) pv_16<T>(cur + kLdsV16, lane, s, o);
+    else pv_fp4(cur, lane, s, gmax, o);
   }
 
   // ---- epilogue (Alg. 1 step 21): O / l; accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
@@ -172,6 +191,8 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
 }
 
 #undef THRIFT_PREFETCH4
+#undef THRIFT_COMMIT4
+#undef THRIFT_STAGE16
 
 void launch_prefill(const PrefillArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((long)a.B * a.Hq * (a.N / a.Bq));

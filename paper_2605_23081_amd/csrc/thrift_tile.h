@@ -115,6 +115,8 @@ __device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mas
   const float m_new = fmaxf(st.m, fmaxf(mloc, other_half(mloc)));
   const float m_safe = m_new == -INFINITY ? 0.f : m_new;       // a row that has seen nothing stays empty
   const float alpha = fast_exp2((st.m - m_safe) * c);
+  // (s - m) first: the row maximum then maps to exactly 2^0, which the power-of-two scale rule of the
+  // P quantiser depends on (a fused s*c - m*c leaves a rounding residue that moves it across the binade).
   float sum = 0.f;
 #pragma unroll
   for (int t = 0; t < 2; ++t)
