@@ -131,37 +131,70 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
     const int t1 = n0 == 0 ? n1 : n0;
     if (vis > 1 && t1 != 1) THRIFT_PREFETCH4(1);
   }
-  for (int j = 0; j < vis; ++j) {
-    const bool is16 = j == n0;
-    const int t1 = is16 ? n1 : n0;                      // first promoted id >= j+1
-    const bool next16 = j + 1 == t1;
-    const int t2 = next16 ? (is16 ? n2 : n1) : t1;      // first promoted id >= j+2
-    unsigned char* cur = lds + (j & 1) * kLdsBytes16;
-    unsigned char* nxt = lds + ((j + 1) & 1) * kLdsBytes16;
-    __syncthreads();            // block j is complete in `cur`; everyone has finished block j-1, which used `nxt`
-    if (j + 1 < vis) {
-      if (next16) THRIFT_STAGE16(j + 1, nxt);
-      else THRIFT_COMMIT4(nxt);
-      if (j + 2 < vis && j + 2 != t2) THRIFT_PREFETCH4(j + 2);
+  // Blocks this wavefront computes: those with at least one key at or before its last query row.  The
+  // later blocks of the workgroup (visible only to wavefronts with later rows) are still staged and
+  // synchronised on, in a final loop without arithmetic.
+  const int vis_wave = a.causal ? min(vis, (q0 + 31) / kBk + 1) : vis;
+
+  // One step of the staging pipeline at block J: wait until block J is complete in `cur`, then move block
+  // J+1 into the other buffer and start the global loads of block J+2.  T1 / T2: the first promoted ids at
+  // or after J+1 / J+2.
+#define THRIFT_STEP(J, T1, T2)                                                                                 \
+  unsigned char* cur = lds + ((J) & 1) * kLdsBytes16;                                                          \
+  {                                                                                                            \
+    unsigned char* nxt = lds + (((J) + 1) & 1) * kLdsBytes16;                                                  \
+    __syncthreads(); /* everyone has finished block J-1, which used `nxt` */                                   \
+    if ((J) + 1 < vis) {                                                                                       \
+      if ((J) + 1 == (T1)) THRIFT_STAGE16((J) + 1, nxt);                                                       \
+      else THRIFT_COMMIT4(nxt);                                                                                \
+      if ((J) + 2 < vis && (J) + 2 != (T2)) THRIFT_PREFETCH4((J) + 2);                                         \
+    }                                                                                                          \
+  }
+#define THRIFT_MASK(J)                                                                                         \
+  const bool mask = a.causal && (J) * kBk + kBk - 1 > q0;                                                      \
+  const int n_valid = q0 + r - (J) * kBk + 1; /* keys of the block at positions <= the query's */
+
+  // The walk alternates between runs of 4-bit blocks (tight loop: only the scaled-FP4 path, accumulators
+  // updated in place) and single promoted blocks.
+  int j = 0;
+  while (j < vis_wave) {
+    const int run_end = min(vis_wave, n0);
+    for (; j < run_end; ++j) {
+      THRIFT_STEP(j, n0, (j + 1 == n0 ? n1 : n0))
+      THRIFT_MASK(j)
+      v16f s[2];
+      float gmax;
+      scores_fp4(cur, lane, qf4, qsc, s);
+      const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+      rescale(o, alpha);
+      pv_fp4(cur, lane, s, gmax, o);
     }
+    if (j < vis_wave) {                                 // j == n0: a promoted block
+      THRIFT_STEP(j, n1, (j + 1 == n1 ? n2 : n1))
+      THRIFT_MASK(j)
+      v16f s[2];
+      float gmax;
+      scores_16<T>(cur, lane, q16row, s);
+      const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+      rescale(o, alpha);
+      pv_16<T>(cur + kLdsV16, lane, s, o);
+      ++ps;
+      n0 = n1; n1 = n2; n2 = ps + 2 < nsel ? sel[ps + 2] : 0x7fffffff;
+      ++j;
+    }
+  }
+  for (; j < vis; ++j) {                                // staging only
+    const bool is16 = j == n0;
+    const int t1 = is16 ? n1 : n0;
+    THRIFT_STEP(j, t1, (j + 1 == t1 ? (is16 ? n2 : n1) : t1))
+    (void)cur;
     if (is16) {
       ++ps;
       n0 = n1; n1 = n2; n2 = ps + 2 < nsel ? sel[ps + 2] : 0x7fffffff;
     }
-
-    const int first_key = j * kBk;
-    if (a.causal && first_key > q0 + 31) continue;      // nothing of this block is visible to this wavefront
-    const bool mask = a.causal && first_key + kBk - 1 > q0;
-    const int n_valid = q0 + r - first_key + 1;         // keys of the block at positions <= the query's
-    v16f s[2];
-    float gmax;
-    if (is16) scores_16<T>(cur, lane, q16row, s);
-    else scores_fp4(cur, lane, qf4, qsc, s);
-    const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-    rescale(o, alpha);
-    if (is16) pv_16<T>(cur + kLdsV16, lane, s, o);
-    else pv_fp4(cur, lane, s, gmax, o);
   }
+#undef THRIFT_STEP
+#undef THRIFT_MASK
 
   // ---- epilogue (Alg. 1 step 21): O / l; accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
   const float l = st.l + other_half(st.l);

@@ -133,10 +133,19 @@ __device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mas
 }
 
 __device__ __forceinline__ void rescale(v16f (&o)[4], float alpha) {
-  // skipping is exact: alpha == 1 leaves every accumulator unchanged
+  // Skipping is exact: alpha == 1 leaves every accumulator unchanged.  The multiplies are written as
+  // in-place instructions so that the accumulators keep their registers on both sides of the branch
+  // (otherwise the skip path pays 64 register copies per key block).
   if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ULL) {
 #pragma unroll
-    for (int n = 0; n < 4; ++n) o[n] *= alpha;
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float x = o[n][i];
+        asm volatile("v_mul_f32 %0, %1, %0" : "+v"(x) : "v"(alpha));
+        o[n][i] = x;
+      }
+    asm volatile("s_nop 4");     // keep the matrix unit's read of the accumulators clear of the writes above
   }
 }
 
