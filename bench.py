@@ -70,6 +70,15 @@ def main() -> int:
     q, k, v, _, _ = W.make_prefill(wl, device=dev)
     torch.cuda.synchronize()
 
+    # A plain device-to-device copy of known size (1 GiB read + 1 GiB written), outside every timed region:
+    # hardware-counter runs (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) scale their readings by what the same
+    # counter reports for this kernel.
+    cal_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     # ------------------------------------------------------------------ prefill: timed steps
     plan = T.PrefillPlan(B, Hq, Hkv, N, D, Bq, Bk, True, args.budget, q.dtype, dev)
     for _ in range(args.warmup):
