@@ -142,7 +142,7 @@ thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, 
   if ((long)B * Hkv * (((long)Tq * (Hq / Hkv) + 3) / 4) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   SelectArgs a;
-  a.qmean = qmean; a.kmean = kmean; a.idx = idx; a.cnt = cnt; a.bitmap = nullptr; a.seqlens = nullptr; a.bitmap_words = 0;
+  a.qmean = qmean; a.kmean = kmean; a.idx = idx; a.cnt = cnt;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Tq = Tq; a.Tk = Tk; a.Bq = Bq; a.Bk = Bk; a.causal = causal ? 1 : 0;
   a.fixed_k = fixed_k; a.q_block_offset = q_block_offset; a.kmax = kmax; a.ppm = fixed_k >= 0 ? 0 : budget_ppm(budget);
   launch_select_topk(a, (hipStream_t)stream);

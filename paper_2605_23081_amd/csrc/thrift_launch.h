@@ -16,16 +16,10 @@ struct SelectArgs {
   const float* kmean;
   int32_t* idx;
   int32_t* cnt;
-  unsigned long long* bitmap;   // nullable: [rows][bitmap_words], bit j%64 of word j/64 = block j selected
-  const int32_t* seqlens;       // nullable: [B] valid tokens; caps the visible blocks of batch b
-  int bitmap_words;
   int B, Hq, Hkv, Tq, Tk, Bq, Bk, causal, fixed_k, q_block_offset, kmax;
   long long ppm;                // budget in millionths
 };
 void launch_select_topk(const SelectArgs& a, hipStream_t st);
-// idx [rows][kmax_in] -> idx_out [rows][kmax_out] (padded -1), cnt copied
-void launch_copy_selection(const int32_t* idx, const int32_t* cnt, int kmax_in, int32_t* idx_out, int32_t* cnt_out,
-                           int kmax_out, long rows, hipStream_t st);
 
 struct PrefillArgs {
   const uint16_t* q;

@@ -205,7 +205,7 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
   const bool active = row < rows_per_unit;
   const int i = active ? row / G : 0;
   const int hq = kvh * G + (active ? row % G : 0);
-  const int cap = p.seqlens ? min(p.Tk, max(0, p.seqlens[b]) / p.Bk) : p.Tk;
+  const int cap = p.Tk;
   const int vis = active ? min(cap, visible_blocks_dev(i, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset)) : 0;
   const int k = row_budget_dev(vis, p.ppm, p.fixed_k);
   const int last_row = min(row0 + 3, rows_per_unit - 1);
@@ -255,10 +255,8 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
 
   int32_t* out = p.idx + rowid * p.kmax;
   if (lane == 0) p.cnt[rowid] = k;
-  unsigned long long* bm = p.bitmap ? p.bitmap + rowid * p.bitmap_words : nullptr;
   if (k <= 0) {
     for (int t = lane; t < p.kmax; t += 64) out[t] = -1;
-    if (bm) for (int t = lane; t < p.bitmap_words; t += 64) bm[t] = 0ULL;
     return;
   }
   // k-th largest key: greatest T with |{key >= T}| >= k, built bit by bit from the top
@@ -289,27 +287,9 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
       if (sel) out[written + __popcll(sel_b & lt_mask)] = c * 64 + lane;
       written += __popcll(sel_b);
       ties_seen += __popcll(tie_b);
-      if (bm && lane == 0) bm[c] = sel_b;
-    } else if (bm && lane == 0 && c < p.bitmap_words) {
-      bm[c] = 0ULL;
     }
   }
   for (int t = k + lane; t < p.kmax; t += 64) out[t] = -1;
-}
-
-__global__ void __launch_bounds__(256) copy_selection_kernel(const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt,
-                                                             int kmax_in, int32_t* __restrict__ idx_out,
-                                                             int32_t* __restrict__ cnt_out, int kmax_out, long rows) {
-  const long row = blockIdx.x;
-  if (row >= rows) return;
-  const int n = cnt[row];
-  for (int t = threadIdx.x; t < kmax_out; t += 256) idx_out[row * kmax_out + t] = t < n && t < kmax_in ? idx[row * kmax_in + t] : -1;
-  if (threadIdx.x == 0) cnt_out[row] = n;
-}
-
-void launch_copy_selection(const int32_t* idx, const int32_t* cnt, int kmax_in, int32_t* idx_out, int32_t* cnt_out,
-                           int kmax_out, long rows, hipStream_t st) {
-  copy_selection_kernel<<<dim3((unsigned)rows), dim3(256), 0, st>>>(idx, cnt, kmax_in, idx_out, cnt_out, kmax_out, rows);
 }
 
 void launch_select_topk(const SelectArgs& p, hipStream_t st) {

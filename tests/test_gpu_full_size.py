@@ -1,0 +1,138 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot evaluate 10^14 flops, so the GPU runs the whole problem and the oracle recomputes
+sampled units one by one: whole query blocks (first, middle, last) of heads from different KV groups
+for prefill, whole sequences for decode.  Inputs of the sampled heads are drawn on the CPU (the same
+bits go to both sides); for decode the other sequences of the batch are drawn on the GPU.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_23081_amd import workloads as W
+from tests.gpu_util import check_selection, to_np
+
+pytestmark = pytest.mark.gpu
+
+TOL16 = 2e-3
+TOLMIX = 3e-2
+
+
+@pytest.fixture(scope="module")
+def T():
+    from paper_2605_23081_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()
+    return binding
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _prefill_sampled(T, oracle, wl, budgets, heads, blocks, tol_for):
+    """Whole-problem GPU run per budget; oracle on (head, query block) samples."""
+    _say(f"{wl.name}: drawing N={wl.N} Hq={wl.Hq} Hkv={wl.Hkv} on the CPU")
+    q, k, v, _, _ = W.make_prefill(wl)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    scale = 1 / math.sqrt(wl.D)
+    Tq = wl.N // wl.Bq
+    # the oracle works on the KV groups of the sampled heads only (re-indexed densely)
+    groups = sorted({h // wl.group for h in heads})
+    qh_ids = [g * wl.group + t for g in groups for t in range(wl.group)]
+    q_sub = q[:, qh_ids].contiguous(); k_sub = k[:, groups].contiguous(); v_sub = v[:, groups].contiguous()
+    qb, dt = oracle.bits_of(q_sub); kb, _ = oracle.bits_of(k_sub); vb, _ = oracle.bits_of(v_sub)
+    qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    scores = None
+    units = np.array([(0, qh_ids.index(h), i) for h in heads for i in blocks], np.int32)
+    for f in budgets:
+        _say(f"  budget {f}: GPU run of the whole problem")
+        plan = T.PrefillPlan(wl.B, wl.Hq, wl.Hkv, wl.N, wl.D, wl.Bq, wl.Bk, True, f, q.dtype, qg.device, out_dtype=torch.float32)
+        out = plan.run(qg, kg, vg)
+        torch.cuda.synchronize()
+        idx_r, cnt_r = oracle.select_topk(qm, km, wl.Bq, wl.Bk, True, f)
+        idx_g = to_np(plan.idx[:, qh_ids]); cnt_g = to_np(plan.cnt[:, qh_ids])
+        assert np.array_equal(to_np(plan.qmean[:, qh_ids]).view(np.uint32), qm.view(np.uint32))
+        assert np.array_equal(to_np(plan.kmean[:, groups]).view(np.uint32), km.view(np.uint32))
+        if not np.array_equal(idx_g[..., :idx_r.shape[-1]], idx_r):
+            if scores is None:
+                scores = oracle.block_scores(qm, km)
+            swaps = check_selection(idx_g[..., :idx_r.shape[-1]], cnt_g, idx_r, cnt_r, scores)
+            _say(f"    selection differs by {swaps} near-tie swaps")
+        assert np.array_equal(cnt_g, cnt_r)
+        if f == 0.0:
+            assert int(plan.cnt.sum().item()) == 0                      # 0 % == every tile on the 4-bit path
+        if f == 1.0:
+            assert int(plan.cnt.sum().item()) == wl.B * wl.Hq * sum(T.visible_blocks(i, wl.N // wl.Bk, wl.Bq, wl.Bk, True) for i in range(Tq))
+        want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx_r, cnt_r, wl.Bq, wl.Bk, True, scale, units)
+        got = to_np(out)[0].reshape(wl.Hq, Tq, wl.Bq, wl.D)
+        got = np.stack([got[h, i] for h in heads for i in blocks])
+        err = np.abs(got - want)
+        _say(f"    sampled {len(units)} query blocks: max abs err {err.max():.3e}, p99.9 {np.quantile(err, 0.999):.3e}")
+        assert err.max() <= tol_for(f)
+        del plan, out
+
+
+def test_qwen3_131k_budget_sweep(T, oracle):
+    wl = W.QWEN3_131K
+    _prefill_sampled(T, oracle, wl, wl.budgets, heads=[0, 21], blocks=[0, 517, 1023], tol_for=lambda f: TOLMIX)
+
+
+def test_qwen3_32k(T, oracle):
+    wl = W.QWEN3_32K
+    _prefill_sampled(T, oracle, wl, (0.05,), heads=[3, 12, 31], blocks=[0, 1, 100, 255], tol_for=lambda f: TOLMIX)
+
+
+def test_skewed_64k_recovery_curve_and_invariants(T, oracle):
+    wl = W.SKEWED_64K
+    _prefill_sampled(T, oracle, wl, wl.budgets, heads=[5, 40], blocks=[0, 300, 511],
+                     tol_for=lambda f: TOL16 if f == 1.0 else TOLMIX)
+
+
+def test_decode_131k_batch16(T, oracle):
+    wd = W.DECODE_131K
+    sampled = [0, wd.B - 1]
+    _say(f"{wd.name}: B={wd.B}; sequences {sampled} drawn on the CPU, the rest on the GPU")
+    dev = torch.device("cuda:0")
+    qg = torch.empty(wd.B, wd.Hq, wd.D, dtype=wd.torch_dtype, device=dev)
+    kg = torch.empty(wd.B, wd.Hkv, wd.N, wd.D, dtype=wd.torch_dtype, device=dev)
+    vg = torch.empty_like(kg)
+    host = {}
+    for b in range(wd.B):
+        on_cpu = b in sampled
+        d = "cpu" if on_cpu else dev
+        qb_ = torch.stack([W.make_q_head(wd, b, h, n_rows=1, device=d)[0] for h in range(wd.Hq)])
+        kv = [W.make_kv_head(wd, b, g, device=d) for g in range(wd.Hkv)]
+        kb_ = torch.stack([x[0] for x in kv]); vb_ = torch.stack([x[1] for x in kv])
+        if on_cpu:
+            host[b] = (qb_, kb_, vb_)
+        qg[b], kg[b], vg[b] = qb_.to(dev), kb_.to(dev), vb_.to(dev)
+        del kv, kb_, vb_
+    k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    kmean = T.thrift_block_means(kg, wd.Bk)
+    out, idx_g, cnt_g = T.thrift_attn_decode(qg, kg, vg, k4, ks, v4, vs, kmean, wd.Bk, 0.05, split_blocks=wd.split_blocks,
+                                             out_dtype=torch.float32, return_selection=True)
+    torch.cuda.synchronize()
+    scale = 1 / math.sqrt(wd.D)
+    for b in sampled:
+        qc, kc, vc = host[b]
+        qb, dt = oracle.bits_of(qc[None]); kb, _ = oracle.bits_of(kc[None]); vb, _ = oracle.bits_of(vc[None])
+        km = oracle.block_means(kb, dt, wd.Bk)
+        assert np.array_equal(to_np(kmean[b:b + 1]).view(np.uint32), km.view(np.uint32))
+        # codes and scales of the cache, bit-exact on one KV head
+        c0, s0 = oracle.quantize_mxfp4(kb[:, :1], dt, 0)
+        from tests.gpu_util import unpack_axis0, unpack_axis1
+        assert np.array_equal(unpack_axis0(to_np(k4[b:b + 1, :1])), c0) and np.array_equal(to_np(ks[b:b + 1, :1]), s0)
+        c1, s1 = oracle.quantize_mxfp4(vb[:, :1], dt, 1)
+        assert np.array_equal(unpack_axis1(to_np(v4[b:b + 1, :1])), c1) and np.array_equal(to_np(vs[b:b + 1, :1]), s1)
+        qm = qc.float().numpy().reshape(1, wd.Hq, 1, wd.D)
+        idx_r, cnt_r = oracle.select_topk(qm, km, 1, wd.Bk, False, 0.05)
+        idx_r, cnt_r = idx_r[:, :, 0], cnt_r[:, :, 0]
+        swaps = check_selection(to_np(idx_g[b:b + 1]), to_np(cnt_g[b:b + 1]), idx_r, cnt_r, oracle.block_scores(qm, km)[:, :, 0])
+        # four wavefronts per partition: split-K with partitions of split_blocks / 4 key blocks
+        want = oracle.attn_thrift_decode(qb[0][None], kb, vb, dt, idx_r, cnt_r, wd.Bk, scale, wd.split_blocks // 4)
+        err = np.abs(to_np(out[b:b + 1]) - want).max()
+        _say(f"  sequence {b}: selection swaps {swaps}, max abs err {err:.3e}")
+        assert swaps == 0 and err <= TOLMIX
