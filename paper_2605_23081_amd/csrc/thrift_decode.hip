@@ -22,7 +22,8 @@ constexpr int kDecodeLdsPerWave = kBk * kRow16;   // one 16-bit V tile per wavef
 template <typename T>
 __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   __shared__ __align__(16) unsigned char lds_all[4 * kDecodeLdsPerWave];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, r = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
   unsigned char* lds = lds_all + wave * kDecodeLdsPerWave;
   const int G = a.Hq / a.Hkv, Tk_all = a.Nkv / kBk;
   const int part = blockIdx.x % a.nsplit;

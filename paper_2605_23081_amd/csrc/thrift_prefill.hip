@@ -24,7 +24,8 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   constexpr int CH = 256 / NT;                         // 16-byte chunks of a 4 KiB tile per thread
   __shared__ __align__(16) unsigned char lds[2 * kLdsBytes16];
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, r = lane & 31;
+  const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
   const int N = a.N, Bq = NW * 32, Tq = N / Bq, Tk = N / kBk, G = a.Hq / a.Hkv;
 
   // ---- work item: heavy (late) query blocks first; KV heads spread over the 8 XCDs so that the query
