@@ -161,9 +161,9 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
 //   decode_scores_kernel  one workgroup per (sequence, KV head, 64 key blocks): stages the 64 cached
 //                         key-block means once and scores them against the G query heads of the group
 //                         (fp64, channels in ascending order), storing order-preserving 64-bit keys;
-//   decode_select_kernel  one workgroup per (sequence, query head): finds the k-th largest key by a
-//                         bitwise search with workgroup-wide counting and writes the selection as a
-//                         bitmap (and, on request, as an ascending id list).
+//   decode_select_kernel  one wavefront per (sequence, query head): finds the k-th largest key by a
+//                         bitwise search with ballot counting and writes the selection as a bitmap
+//                         (and, on request, as an ascending id list).
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t order_key64(double s) {
   uint64_t u = (uint64_t)__double_as_longlong(s);
@@ -219,91 +219,80 @@ struct DecodeSelectArgs {
   long long ppm;
 };
 
-__global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p) {
-  constexpr int MAXS = 16;                                  // 16 slices of 256 key blocks: Tk <= 4096
-  __shared__ int part[2][4];
-  __shared__ int scan[2][4];
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const size_t row = blockIdx.x;
+// One wavefront per row, no barriers: lane l keeps key blocks l, l+64, ... in registers; the k-th largest
+// key is found by a 64-step bitwise search whose counts are ballots + scalar popcounts.
+template <int MAXC>
+__global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, long n_rows) {
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (row >= n_rows) return;
   const int b = (int)(row / p.Hq);
   const int vis = p.seqlens ? min(p.Tk, max(0, p.seqlens[b]) / kBk) : p.Tk;
   int k;
   if (p.fixed_k >= 0) k = min(p.fixed_k, vis);
-  else if (p.ppm <= 0) k = 0;
+  else if (p.ppm <= 0 || vis == 0) k = 0;
   else {
     long long kk = (p.ppm * (long long)vis + 999999LL) / 1000000LL;
     k = (int)max(1LL, min(kk, (long long)vis));
-    if (vis == 0) k = 0;
   }
-  const int slices = (vis + 255) / 256;
-  uint64_t key[MAXS];
+  uint64_t key[MAXC];
 #pragma unroll
-  for (int t = 0; t < MAXS; ++t) {
-    const int j = t * 256 + tid;
-    key[t] = (t < slices && j < vis) ? p.keys[row * p.Tk + j] : 0ULL;
+  for (int c = 0; c < MAXC; ++c) {
+    const int j = c * 64 + lane;
+    key[c] = j < vis ? p.keys[row * p.Tk + j] : 0ULL;
   }
   unsigned long long* bm = p.bitmap + row * p.words;
   int32_t* out = p.idx_out ? p.idx_out + row * p.kmax_out : nullptr;
-  if (p.cnt_out && tid == 0) p.cnt_out[row] = k;
+  if (p.cnt_out && lane == 0) p.cnt_out[row] = k;
   if (k <= 0) {
-    for (int w = tid; w < p.words; w += 256) bm[w] = 0ULL;
-    if (out) for (int t = tid; t < p.kmax_out; t += 256) out[t] = -1;
+    for (int w = lane; w < p.words; w += 64) bm[w] = 0ULL;
+    if (out) for (int t = lane; t < p.kmax_out; t += 64) out[t] = -1;
     return;
   }
-  // workgroup-wide count of valid keys satisfying a predicate: ballots per slice, then 4 wave partials
-  int round = 0;
-  auto count_ge = [&](uint64_t cand, bool strict) -> int {
-    int n = 0;
+  // Invalid slots hold key 0, and every candidate below is >= 1, so they never count.  Each lane counts
+  // its own keys (at most MAXC <= 64, seven bits); the wavefront total is the weighted popcount of the
+  // ballots of those seven bits.
+  auto wave_total = [&](int n_lane) -> int {
+    int tot = 0;
 #pragma unroll
-    for (int t = 0; t < MAXS; ++t)
-      if (t < slices) {
-        const bool valid = t * 256 + tid < vis;
-        n += __popcll(__ballot(valid && (strict ? key[t] > cand : key[t] >= cand)));
-      }
-    int* slot = part[round & 1];
-    ++round;
-    if (lane == 0) slot[wave] = n;
-    __syncthreads();
-    return slot[0] + slot[1] + slot[2] + slot[3];
+    for (int b7 = 0; b7 < 7; ++b7) tot += __popcll(__ballot((n_lane >> b7) & 1)) << b7;
+    return tot;
   };
   uint64_t T = 0;
   for (int bit = 63; bit >= 0; --bit) {
     const uint64_t cand = T | (1ULL << bit);
-    if (count_ge(cand, false) >= k) T = cand;
+    int n_lane = 0;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) n_lane += key[c] >= cand ? 1 : 0;
+    if (wave_total(n_lane) >= k) T = cand;
   }
-  const int need_ties = k - count_ge(T, true);              // >= 1: keys equal to T, taken from the smallest id up
+  int n_gt;
+  {
+    int n_lane = 0;
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) n_lane += key[c] > T ? 1 : 0;
+    n_gt = wave_total(n_lane);
+  }
+  const int need_ties = k - n_gt;                            // >= 1: keys equal to T, taken from the smallest id up
   const uint64_t lt_mask = (1ULL << lane) - 1ULL;
   int written = 0, ties_seen = 0;
 #pragma unroll
-  for (int t = 0; t < MAXS; ++t) {
-    if (t < slices) {                                       // uniform
-      const int j = t * 256 + tid;
-      const bool valid = j < vis;
-      const bool tie = valid && key[t] == T;
+  for (int c = 0; c < MAXC; ++c) {
+    if (c * 64 < vis) {
+      const bool valid = c * 64 + lane < vis;
+      const bool tie = valid && key[c] == T;
       const uint64_t tie_b = __ballot(tie);
-      int* ps = scan[0];
-      if (lane == 0) ps[wave] = __popcll(tie_b);
-      __syncthreads();
-      int tie_before = ties_seen;
-      for (int w = 0; w < wave; ++w) tie_before += ps[w];
-      const int tie_total = ps[0] + ps[1] + ps[2] + ps[3];
-      const bool sel = valid && (key[t] > T || (tie && tie_before + __popcll(tie_b & lt_mask) < need_ties));
+      const bool sel = valid && (key[c] > T || (tie && ties_seen + __popcll(tie_b & lt_mask) < need_ties));
       const uint64_t sel_b = __ballot(sel);
-      int* ss = scan[1];
-      if (lane == 0) ss[wave] = __popcll(sel_b);
-      __syncthreads();
-      int sel_before = written;
-      for (int w = 0; w < wave; ++w) sel_before += ss[w];
-      const int sel_total = ss[0] + ss[1] + ss[2] + ss[3];
-      if (sel && out) out[sel_before + __popcll(sel_b & lt_mask)] = j;
-      if (lane == 0 && t * 4 + wave < p.words) bm[t * 4 + wave] = sel_b;
-      written += sel_total;
-      ties_seen += tie_total;
-      __syncthreads();                                      // scan[] is reused by the next slice
+      if (sel && out) out[written + __popcll(sel_b & lt_mask)] = c * 64 + lane;
+      written += __popcll(sel_b);
+      ties_seen += __popcll(tie_b);
+      if (lane == 0) bm[c] = sel_b;
+    } else if (lane == 0 && c < p.words) {
+      bm[c] = 0ULL;
     }
   }
-  for (int w = slices * 4 + tid; w < p.words; w += 256) bm[w] = 0ULL;
-  if (out) for (int t = k + tid; t < p.kmax_out; t += 256) out[t] = -1;
+  if (out) for (int t = k + lane; t < p.kmax_out; t += 64) out[t] = -1;
 }
 
 void launch_decode_select(const float* qf32, const float* kmean, const int32_t* seqlens, uint64_t* keys,
@@ -314,7 +303,12 @@ void launch_decode_select(const float* qf32, const float* kmean, const int32_t* 
   DecodeSelectArgs p;
   p.keys = keys; p.seqlens = seqlens; p.bitmap = bitmap; p.idx_out = idx_out; p.cnt_out = cnt_out;
   p.Hq = Hq; p.Tk = Tk; p.words = words; p.kmax_out = kmax_out; p.fixed_k = fixed_k; p.ppm = ppm;
-  decode_select_kernel<<<dim3((unsigned)((long)B * Hq)), dim3(256), 0, st>>>(p);
+  const long n_rows = (long)B * Hq;
+  const dim3 grid((unsigned)((n_rows + 3) / 4)), block(256);
+  if (chunks <= 8) decode_select_kernel<8><<<grid, block, 0, st>>>(p, n_rows);
+  else if (chunks <= 16) decode_select_kernel<16><<<grid, block, 0, st>>>(p, n_rows);
+  else if (chunks <= 32) decode_select_kernel<32><<<grid, block, 0, st>>>(p, n_rows);
+  else decode_select_kernel<64><<<grid, block, 0, st>>>(p, n_rows);
 }
 
 // Log-sum-exp merge of the partials of one (sequence, query head): 128 threads, one per channel.
@@ -327,10 +321,11 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
   for (int p = 0; p < a.nparts; ++p) M = fmaxf(M, ml[2 * p]);
   float L = 0.f, O = 0.f;
   if (M > -INFINITY) {
+    // an empty partial has m = -inf, l = 0, O = 0: its weight exp2(-inf) is 0, no branch needed, and the
+    // loads of all partials can be in flight together
+#pragma unroll 8
     for (int p = 0; p < a.nparts; ++p) {
-      const float m = ml[2 * p];
-      if (m == -INFINITY) continue;
-      const float w = fast_exp2((m - M) * c);
+      const float w = fast_exp2((ml[2 * p] - M) * c);
       L += w * ml[2 * p + 1];
       O += w * a.part_o[(qh * a.nparts + p) * kD + ch];
     }
