@@ -267,3 +267,86 @@ def test_decode_variants(T, oracle):
     assert swaps == 0 and np.abs(got - want).max() <= TOLMIX
     got, want, swaps = _decode_case(T, oracle, wl, 0.0, 32, fixed_k=3)
     assert swaps == 0 and np.abs(got - want).max() <= TOLMIX
+
+
+# ------------------------------------------------------------------ edge cases
+
+@pytest.mark.parametrize("wl,budget", [
+    (W.scaled(W.TINY, N=64), 1.0),                                  # one query block, one key block
+    (W.scaled(W.TINY, N=64), 0.0),
+    (_small_bf16(N=128, Hq=1, Hkv=1), 0.5),                         # Bq=128 over two key blocks, diagonal only
+    (_small_bf16(N=512, Hq=16, Hkv=8, B=2), 0.1),                   # batch 2, 16 (b, kv head) units: XCD-spread mapping
+    (W.scaled(W.TINY, N=1024, Hq=8, Hkv=8, B=1), 0.25),             # 8 units, group of 1, Bq=64
+    (_small_bf16(N=768, Hq=6, Hkv=2), 0.05),                        # group of 3, 6 query blocks
+])
+def test_prefill_edge_shapes(T, oracle, wl, budget):
+    _say(f"prefill edge {wl.name} B={wl.B} N={wl.N} Hq={wl.Hq} Hkv={wl.Hkv} Bq={wl.Bq} budget={budget}")
+    got, want, lse, want_lse = _prefill_both(T, oracle, wl, budget)
+    err = np.abs(got - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert err <= (TOL16 if budget == 1.0 else TOLMIX)
+    assert np.abs(lse - want_lse).max() <= 1e-3
+
+
+def test_prefill_padded_selection_scale_and_guards(T, oracle):
+    """idx wider than needed (padding -1), explicit softmax scale, and canaries around the output."""
+    wl = _small_bf16(N=1024, Hq=4, Hkv=2)
+    _say("prefill with padded idx, explicit scale, guarded output")
+    q, k, v, _, _ = W.make_prefill(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 0.07
+    Tq = wl.N // wl.Bq
+    qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    idx, cnt = oracle.select_topk(qm, km, wl.Bq, wl.Bk, True, 0.1, kmax=7)
+    want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, wl.Bq, wl.Bk, True, scale, _units(1, wl.Hq, Tq)).reshape(1, wl.Hq, wl.N, wl.D)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    n = wl.Hq * wl.N * wl.D
+    guard = 4096
+    buf = torch.full((n + 2 * guard,), 12345.0, dtype=torch.float32, device="cuda")
+    out = buf[guard:guard + n].view(1, wl.Hq, wl.N, wl.D)
+    T.thrift_attn_prefill(qg, kg, vg, q4, qs, k4, ks, v4, vs, torch.from_numpy(idx).cuda(), torch.from_numpy(cnt).cuda(),
+                          wl.Bq, wl.Bk, True, scale, out=out)
+    torch.cuda.synchronize()
+    assert torch.all(buf[:guard] == 12345.0) and torch.all(buf[guard + n:] == 12345.0)
+    assert np.abs(to_np(out) - want).max() <= TOLMIX
+    # the GPU selection with a wider idx gives the same lists, padded with -1
+    idx_g, cnt_g = T.thrift_select_topk(T.thrift_block_means(qg, wl.Bq), T.thrift_block_means(kg, wl.Bk), wl.Bq, wl.Bk, True, 0.1, kmax=7)
+    assert np.array_equal(to_np(idx_g), idx) and np.array_equal(to_np(cnt_g), cnt)
+
+
+def test_select_single_row_and_offset(T, oracle):
+    _say("select: one query block, decode-style offset")
+    g = torch.Generator().manual_seed(9)
+    qm = torch.randn(2, 4, 1, 128, generator=g)
+    km = torch.randn(2, 2, 200, 128, generator=g)
+    for causal, off, budget in ((False, 0, 0.05), (True, 12799, 0.05), (True, 6399, 0.3)):
+        idx_r, cnt_r = oracle.select_topk(qm.numpy(), km.numpy(), 1, 64, causal, budget, q_block_offset=off)
+        idx_g, cnt_g = T.thrift_select_topk(qm.cuda(), km.cuda(), 1, 64, causal, budget, q_block_offset=off)
+        assert np.array_equal(to_np(idx_g)[..., :idx_r.shape[-1]], idx_r) and np.array_equal(to_np(cnt_g), cnt_r)
+
+
+@pytest.mark.parametrize("Hq,Hkv,B,N,split", [(32, 1, 1, 1024, 16), (4, 4, 1, 640, 64), (16, 2, 2, 1536, 4)])
+def test_decode_edge_shapes(T, oracle, Hq, Hkv, B, N, split):
+    wl = W.scaled(W.DECODE_131K, B=B, N=N, Hq=Hq, Hkv=Hkv)
+    _say(f"decode edge B={B} N={N} Hq={Hq} Hkv={Hkv} split={split}")
+    got, want, swaps = _decode_case(T, oracle, wl, 0.1, split)
+    err = np.abs(got - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert swaps == 0 and err <= TOLMIX
+
+
+def test_decode_is_deterministic_and_keeps_guards(T, oracle):
+    wl = W.scaled(W.DECODE_131K, B=2, N=2048, Hq=8, Hkv=2)
+    q, k, v = W.make_decode(wl)
+    kg, vg = k.cuda(), v.cuda()
+    k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    kmean = T.thrift_block_means(kg, 64)
+    n = wl.B * wl.Hq * wl.D
+    buf = torch.full((n + 512,), 777.0, dtype=torch.float32, device="cuda")
+    out = buf[256:256 + n].view(wl.B, wl.Hq, wl.D)
+    a = T.thrift_attn_decode(q.cuda(), kg, vg, k4, ks, v4, vs, kmean, 64, 0.05, split_blocks=8, out=out).clone()
+    b = T.thrift_attn_decode(q.cuda(), kg, vg, k4, ks, v4, vs, kmean, 64, 0.05, split_blocks=8, out=out).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + n:] == 777.0)
