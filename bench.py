@@ -28,6 +28,12 @@ if ROOT not in sys.path:
 PEAK_16 = 2500.0     # TFLOP/s, dense bf16 / fp16 MFMA, MI355X datasheet
 PEAK_FP4 = 10100.0   # TFLOP/s, dense MXFP4 MFMA
 PEAK_HBM = 8000.0    # GB/s
+# Vector-ALU ceiling of the fused kernel: each score of a 4-bit tile needs at least one subtract, one
+# multiply, one v_exp_f32 (2 issue slots), one add (row sum), half a v_max3 and one half-rate FP4 convert
+# slot = 6.5 issue slots; a wave-tile (32 queries x 64 keys, 1.05 MFLOP) holds 32 scores per lane; a SIMD
+# issues one wavefront instruction per 4 cycles; 1024 SIMDs at the 2.4 GHz nominal clock.
+ALU_SLOTS_PER_SCORE = 6.5
+ALU_PEAK = 1024 * 2.4e9 / (ALU_SLOTS_PER_SCORE * 32 * 4) * (2 * 2 * 32 * 64 * 128) / 1e12   # TFLOP/s
 PAPER_CONTEXT = {"gap_recovery_pct_at_5_10_25": [89.1, 91.8, 92.4], "e2e_speedup_at_131k": 2.0,
                  "hardware": "RTX PRO 6000 Blackwell, NVFP4+FP16 (context only, not a target)"}
 
@@ -123,7 +129,10 @@ def main() -> int:
         "prefill": {"ms_prepass": round(ms_pre, 4), "ms_fused_kernel": round(ms_attn, 3),
                     "kernel_tflops": round(achieved, 2)},
         "roofline": {"bound": "mfma", "kernel": "prefill_kernel<BF16,4>", "achieved": round(achieved, 2), "peak": round(peak, 1),
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None},
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                     "note": "the kernel is limited by softmax / quantisation VALU work, not by the MFMA rate",
+                     "alu": {"peak": round(ALU_PEAK, 1), "unit": "TFLOP/s", "frac": round(achieved / ALU_PEAK, 4),
+                             "slots_per_score": ALU_SLOTS_PER_SCORE}},
         "paper_context": PAPER_CONTEXT,
     }
 
