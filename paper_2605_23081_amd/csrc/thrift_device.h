@@ -50,10 +50,9 @@ struct BF16 {
   typedef __bf16 scalar;
   typedef v8bf vec8;
   static __device__ __forceinline__ float to_float(uint16_t u) { return __uint_as_float((uint32_t)u << 16); }
-  static __device__ __forceinline__ uint16_t from_float(float f) {  // round to nearest even
-    uint32_t w = __float_as_uint(f);
-    w += 0x7fffu + ((w >> 16) & 1u);
-    return (uint16_t)(w >> 16);
+  static __device__ __forceinline__ uint16_t from_float(float f) {  // round to nearest even (hardware convert)
+    __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, h);
   }
   template <int SEL>
   static __device__ __forceinline__ uint32_t cvt_pk_fp4(uint32_t old, uint32_t pair, float scale) {

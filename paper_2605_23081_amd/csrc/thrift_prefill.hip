@@ -18,6 +18,11 @@
 
 namespace thrift {
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
+// load (a full fence), which would wait for the 4-bit tile prefetched two blocks ahead at every key
+// block; here only this wavefront's LDS reads and writes must have completed before the rendezvous.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 template <typename T, int NW>
 __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   constexpr int NT = NW * 64;
@@ -144,7 +149,7 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   unsigned char* cur = lds + ((J) & 1) * kLdsBytes16;                                                          \
   {                                                                                                            \
     unsigned char* nxt = lds + (((J) + 1) & 1) * kLdsBytes16;                                                  \
-    __syncthreads(); /* everyone has finished block J-1, which used `nxt` */                                   \
+    lds_barrier();   /* everyone has finished block J-1, which used `nxt` */                                   \
     if ((J) + 1 < vis) {                                                                                       \
       if ((J) + 1 == (T1)) THRIFT_STAGE16((J) + 1, nxt);                                                       \
       else THRIFT_COMMIT4(nxt);                                                                                \
