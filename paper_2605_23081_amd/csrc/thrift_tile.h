@@ -115,14 +115,17 @@ __device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mas
   const float m_new = fmaxf(st.m, fmaxf(mloc, other_half(mloc)));
   const float m_safe = m_new == -INFINITY ? 0.f : m_new;       // a row that has seen nothing stays empty
   const float alpha = fast_exp2((st.m - m_safe) * c);
-  // (s - m) first: the row maximum then maps to exactly 2^0, which the power-of-two scale rule of the
-  // P quantiser depends on (a fused s*c - m*c leaves a rounding residue that moves it across the binade).
+  // Elements use one fused multiply-add, s*c - m*c; its rounding residue (a few 1e-7 relative on p) is
+  // harmless for the codes and the row sum.  The group maximum, which fixes the power-of-two scale of
+  // the P quantiser, is formed as (s - m)*c instead: the row maximum then maps to exactly 2^0 and can
+  // never slip under the binade boundary (where the floor scale rule would saturate it to 0.75).
+  const float mc = m_safe * c;
   float sum = 0.f;
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const float p = fast_exp2((s[t][i] - m_safe) * c);
+      const float p = fast_exp2(__builtin_fmaf(s[t][i], c, -mc));
       s[t][i] = p;
       sum += p;
     }
