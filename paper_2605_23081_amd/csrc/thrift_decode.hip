@@ -125,14 +125,14 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       const uint8_t* vt = v4base + (size_t)j * 4096 + vr;
       const uint8_t* vsr = vsbase + ((size_t)j * 2 + half) * kD + r;
       const uint32_t vsw = (uint32_t)vsr[0] | ((uint32_t)vsr[32] << 8) | ((uint32_t)vsr[64] << 16) | ((uint32_t)vsr[96] << 24);
-      pv_fp4_regs(p4, g4, vsw, *reinterpret_cast<const v4i*>(vt), *reinterpret_cast<const v4i*>(vt + 1024),
+      pv_fp4_regs<true>(p4, g4, vsw, 0u, 0u, 0u, *reinterpret_cast<const v4i*>(vt), *reinterpret_cast<const v4i*>(vt + 1024),
                   *reinterpret_cast<const v4i*>(vt + 2048), *reinterpret_cast<const v4i*>(vt + 3072), o);
     }
     if (any16) {
       v16f p16[2] = {s[0], s[1]};
       if (!mine16) { p16[0] = (v16f){0.f}; p16[1] = (v16f){0.f}; }
       __builtin_amdgcn_wave_barrier();
-      pv_16<T>(lds, lane, p16, o);
+      pv_16<T, false>(lds, lane, p16, o);
       __builtin_amdgcn_wave_barrier();
     }
   }

@@ -1,33 +1,61 @@
 // Fused mixed-precision flash attention for prefill (Algorithm 1 steps 4-23; Sec. 3.3).
 //
 // One workgroup = one (batch, query head, query block); wavefront w owns query rows 32w .. 32w+31 of
-// the block and keeps Q (4-bit and 16-bit fragments), the online-softmax state and the O^T accumulators
-// in registers.  Key blocks are visited in ascending order (the order of Alg. 1); each block is staged
-// once into LDS for all wavefronts — MXFP4 codes + scales for ordinary blocks, the 16-bit K/V tile for
-// blocks listed in the row's TopK set — and dispatched per tile to the scaled-FP4 or the 16-bit MFMA
-// path.  4-bit tiles are prefetched into registers two blocks ahead and written to the other of two LDS
-// buffers one block ahead, so their global latency hides behind arithmetic and one barrier per block
-// suffices.
+// the block and keeps Q, the online-softmax state and the O^T accumulators in registers.  Key blocks are
+// visited in ascending order (the order of Alg. 1) and dispatched per tile to the scaled-FP4 or the
+// 16-bit MFMA path.  Every block is staged once into LDS for all wavefronts by LDS DMA (global loads
+// that write LDS directly: no staging registers, no LDS write instructions):
+//   * MXFP4 codes + scales of an ordinary block go into a ring of three 8.5 KiB slots, two blocks ahead
+//     of the arithmetic, so their latency is hidden behind two key blocks of work;
+//   * the 16-bit K and V tiles of a block listed in the row's TopK set go into a K buffer and one of
+//     two V buffers, one block ahead.
+// One workgroup barrier per key block orders the traffic (plus one more between the score phase of a
+// promoted block and the arrival of the next K tile when two promoted blocks follow each other).
 //
 // Differences from the kernel the paper sketches for Blackwell (Sec. 3.3): no two-phase split (4-bit
-// tiles first, 16-bit helper afterwards) — on gfx950 both Q fragment sets fit in the 512-entry register
-// file at two wavefronts per SIMD, and ascending order keeps the result independent of the schedule;
-// LDS aliasing of the two tile formats is kept.
+// tiles first, 16-bit helper afterwards) — on gfx950 both paths fit in the 512-entry register file at
+// two wavefronts per SIMD, and ascending order keeps the result independent of the schedule.
 #include "thrift_launch.h"
 #include "thrift_tile.h"
 
 namespace thrift {
 
+// LDS map of the prefill kernel (bytes)
+constexpr int kRing = 3;
+constexpr int kLdsRing = 0;                                  // kRing slots of kLdsBytes4
+constexpr int kLdsV16 = kRing * kLdsBytes4;                  // two swizzled 16-bit V tiles
+constexpr int kLdsK16 = kLdsV16 + 2 * kTile16;               // one swizzled 16-bit K tile
+constexpr int kLdsPrefill = kLdsK16 + kTile16;               // 75264: two workgroups per CU
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
-// load (a full fence), which would wait for the 4-bit tile prefetched two blocks ahead at every key
-// block; here only this wavefront's LDS reads and writes must have completed before the rendezvous.
+// load (a full fence), which would wait for the tiles in flight at every key block; here only this
+// wavefront's LDS reads must have completed before the rendezvous.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Wait until at most N of this wavefront's global loads (LDS DMA included) are still in flight.
+template <int N>
+__device__ __forceinline__ void vm_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+__device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)(p); }
+
+// LDS DMA: the 64 lanes fetch 16 (4) bytes each from base + off and the hardware writes them to the
+// 1 KiB (256 B) of consecutive LDS that starts at lds_base, lane l at lds_base + 16 l (4 l).  base and
+// lds_base are wavefront-uniform.  The instruction takes its LDS base from M0; the compiler has no
+// other use for M0 in this kernel.  Completion is counted by vmcnt like any global load.
+__device__ __forceinline__ void dma_b128(const void* base, uint32_t off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void dma_b32(const void* base, uint32_t off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+}
 
 template <typename T, int NW>
 __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
-  constexpr int NT = NW * 64;
-  constexpr int CH = 256 / NT;                         // 16-byte chunks of a 4 KiB tile per thread
-  __shared__ __align__(16) unsigned char lds[2 * kLdsBytes16];
+  constexpr int KF = 4 / NW;                 // 1 KiB fragments of a 4-bit K (and of a V) tile per wavefront
+  constexpr int C4 = 2 * KF + 1;             // DMA instructions per wavefront for one 4-bit block
+  constexpr int C16 = 16 / NW;               // ... for one 16-bit K or V tile
+  __shared__ __align__(1024) unsigned char lds[kLdsPrefill];
 
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
@@ -70,53 +98,53 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   const uint8_t* v4base = a.v4 + kh * (size_t)(N / 64) * 4096;
   const uint8_t* ksbase = a.ks + kh * N * 4;
   const uint8_t* vsbase = a.vs + kh * (size_t)(N / 32) * kD;
-  const uint16_t* k16base = a.k + kh * N * kD;
-  const uint16_t* v16base = a.v + kh * N * kD;
+  const uint8_t* k16base = reinterpret_cast<const uint8_t*>(a.k + kh * N * kD);
+  const uint8_t* v16base = reinterpret_cast<const uint8_t*>(a.v + kh * N * kD);
 
-  // ---- staging.  A 4-bit tile travels global -> registers (one block ahead) -> LDS; each thread carries
-  // CH 16-byte chunks of K and of V and (threads 0-127) one dword of scale bytes.  A 16-bit tile is copied
-  // global -> LDS in place.  Two LDS buffers alternate, so one barrier per key block is enough. ----
-  uint4 pk0 = make_uint4(0, 0, 0, 0), pk1 = pk0, pv0 = pk0, pv1 = pk0;
-  uint32_t psc = 0;
-#define THRIFT_PREFETCH4(J)                                                                                    \
+  // ---- staging: per-lane source offsets of the DMA instructions this wavefront issues.  The LDS side of
+  // a DMA is linear in the lane index, so every layout change (MFMA fragment order of the 4-bit tiles,
+  // chunk swizzle of the 16-bit tiles) is expressed in the global offsets. ----
+  const uint32_t lds0 = lds_address(lds);
+  uint32_t k4off[KF], v4off[KF];
+#pragma unroll
+  for (int u = 0; u < KF; ++u) {
+    const int f = wave * KF + u;                         // K: fragment (t, kk) = (f>>1, f&1); V: channels 32f .. 32f+31
+    k4off[u] = (uint32_t)(key_of_row(r, f >> 1) * 64 + (2 * (f & 1) + half) * 16);
+    v4off[u] = (uint32_t)((32 * f + r) * 32 + half * 16);
+  }
+  const uint32_t scoff = (uint32_t)lane * 4;
+  // 16-bit tiles: one instruction covers 4 rows; lane l writes chunk position l&15 of row l>>4
+  const uint32_t v16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ v16_swizzle(lane >> 4)) * 16);
+  const uint32_t k16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ (lane >> 4)) * 16);   // rows 32..63: chunk ^ 4 more
+
+#define THRIFT_ISSUE4(J, S)                                                                                    \
   do {                                                                                                         \
-    const uint8_t* kt_ = k4base + (size_t)(J) * 4096 + tid * 16;                                               \
-    const uint8_t* vt_ = v4base + (size_t)(J) * 4096 + tid * 16;                                               \
-    pk0 = *reinterpret_cast<const uint4*>(kt_);                                                                \
-    pv0 = *reinterpret_cast<const uint4*>(vt_);                                                                \
-    if (CH == 2) {                                                                                             \
-      pk1 = *reinterpret_cast<const uint4*>(kt_ + NT * 16);                                                    \
-      pv1 = *reinterpret_cast<const uint4*>(vt_ + NT * 16);                                                    \
+    const uint8_t* kt_ = k4base + (size_t)(J) * 4096;                                                          \
+    const uint8_t* vt_ = v4base + (size_t)(J) * 4096;                                                          \
+    const uint32_t sl_ = lds0 + kLdsRing + (S) * kLdsBytes4;                                                   \
+    _Pragma("unroll") for (int u = 0; u < KF; ++u) {                                                           \
+      dma_b128(kt_, k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024);                                          \
+      dma_b128(vt_, v4off[u], sl_ + kLdsV4 + (wave * KF + u) * 1024);                                          \
     }                                                                                                          \
-    if (tid < 64) psc = *reinterpret_cast<const uint32_t*>(ksbase + (size_t)(J) * 256 + tid * 4);              \
-    else if (tid < 128) psc = *reinterpret_cast<const uint32_t*>(vsbase + (size_t)(J) * 256 + (tid - 64) * 4); \
+    /* scale bytes: even wavefronts fetch K's 256, odd ones V's (duplicates write the same bytes) */           \
+    if (wave & 1) dma_b32(vsbase + (size_t)(J) * 256, scoff, sl_ + kLdsVS);                                    \
+    else dma_b32(ksbase + (size_t)(J) * 256, scoff, sl_ + kLdsKS);                                             \
   } while (0)
-#define THRIFT_COMMIT4(BUF)                                                                                    \
+#define THRIFT_ISSUE_V16(J, BUF)                                                                               \
   do {                                                                                                         \
-    unsigned char* b_ = (BUF);                                                                                 \
-    *reinterpret_cast<uint4*>(b_ + kLdsK4 + k4_fragment_offset(tid >> 2, tid & 3)) = pk0;                      \
-    *reinterpret_cast<uint4*>(b_ + kLdsV4 + tid * 16) = pv0;                                                   \
-    if (CH == 2) {                                                                                             \
-      *reinterpret_cast<uint4*>(b_ + kLdsK4 + k4_fragment_offset((tid + NT) >> 2, (tid + NT) & 3)) = pk1;      \
-      *reinterpret_cast<uint4*>(b_ + kLdsV4 + (tid + NT) * 16) = pv1;                                          \
-    }                                                                                                          \
-    if (tid < 64) {                                                                                            \
-      *reinterpret_cast<uint32_t*>(b_ + kLdsKS + tid * 4) = psc;                                               \
-    } else if (tid < 128) {                                                                                    \
-      /* bytes 4w..4w+3 of the [2 groups][128 channels] scale rows -> [group][r][n], channel = 32n + r */      \
-      const int w_ = tid - 64, grp_ = w_ >> 5, ch_ = (4 * w_) & 127, n_ = ch_ >> 5, rr_ = ch_ & 31;            \
-      for (int bb = 0; bb < 4; ++bb) b_[kLdsVS + (grp_ * 32 + rr_ + bb) * 4 + n_] = (unsigned char)(psc >> (8 * bb)); \
+    const uint8_t* vt_ = v16base + (size_t)(J) * kTile16;                                                      \
+    const uint32_t vb_ = lds0 + kLdsV16 + (BUF) * kTile16;                                                     \
+    _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                          \
+      const int q_ = u * NW + wave;                                                                            \
+      dma_b128(vt_ + q_ * 1024, v16off, vb_ + q_ * 1024);                                                      \
     }                                                                                                          \
   } while (0)
-#define THRIFT_STAGE16(J, BUF)                                                                                 \
+#define THRIFT_ISSUE_K16(J)                                                                                    \
   do {                                                                                                         \
-    unsigned char* b_ = (BUF);                                                                                 \
-    _Pragma("unroll") for (int u = 0; u < 1024 / NT; ++u) {                                                    \
-      const int chunk = tid + NT * u, row = chunk >> 4, col = chunk & 15;                                      \
-      const uint4 kk = *reinterpret_cast<const uint4*>(k16base + ((size_t)(J) * kBk + row) * kD + col * 8);    \
-      const uint4 vv = *reinterpret_cast<const uint4*>(v16base + ((size_t)(J) * kBk + row) * kD + col * 8);    \
-      *reinterpret_cast<uint4*>(b_ + kLdsK16 + row * kRow16 + col * 16) = kk;                                  \
-      *reinterpret_cast<uint4*>(b_ + kLdsV16 + row * kRow16 + col * 16) = vv;                                  \
+    const uint8_t* kt_ = k16base + (size_t)(J) * kTile16;                                                      \
+    _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                          \
+      const int q_ = u * NW + wave;                                                                            \
+      dma_b128(kt_ + q_ * 1024, u * NW >= 8 ? k16off ^ 64u : k16off, lds0 + kLdsK16 + q_ * 1024);              \
     }                                                                                                          \
   } while (0)
 
@@ -126,36 +154,43 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   for (int n = 0; n < 4; ++n) o[n] = (v16f){0.f};
   const float c = a.scale * 1.4426950408889634f;
 
-  // prologue: block 0 into buffer 0, block 1 (if 4-bit) into the prefetch registers
+  // prologue: block 0 (either format) and block 1 (if 4-bit) on their way
   if (vis > 0) {
     if (n0 == 0) {
-      THRIFT_STAGE16(0, lds);
+      THRIFT_ISSUE_V16(0, 0);
+      THRIFT_ISSUE_K16(0);
     } else {
-      THRIFT_PREFETCH4(0);
-      THRIFT_COMMIT4(lds);
+      THRIFT_ISSUE4(0, 0);
     }
-    const int t1 = n0 == 0 ? n1 : n0;
-    if (vis > 1 && t1 != 1) THRIFT_PREFETCH4(1);
+    if (vis > 1 && (n0 == 0 ? n1 : n0) != 1) THRIFT_ISSUE4(1, 1);
   }
   // Blocks this wavefront computes: those with at least one key at or before its last query row.  The
   // later blocks of the workgroup (visible only to wavefronts with later rows) are still staged and
   // synchronised on, in a final loop without arithmetic.
   const int vis_wave = a.causal ? min(vis, (q0 + 31) / kBk + 1) : vis;
 
-  // One step of the staging pipeline at block J: wait until block J is complete in `cur`, then move block
-  // J+1 into the other buffer and start the global loads of block J+2.  T1 / T2: the first promoted ids at
-  // or after J+1 / J+2.
-#define THRIFT_STEP(J, T1, T2)                                                                                 \
-  unsigned char* cur = lds + ((J) & 1) * kLdsBytes16;                                                          \
-  {                                                                                                            \
-    unsigned char* nxt = lds + (((J) + 1) & 1) * kLdsBytes16;                                                  \
-    lds_barrier();   /* everyone has finished block J-1, which used `nxt` */                                   \
-    if ((J) + 1 < vis) {                                                                                       \
-      if ((J) + 1 == (T1)) THRIFT_STAGE16((J) + 1, nxt);                                                       \
-      else THRIFT_COMMIT4(nxt);                                                                                \
-      if ((J) + 2 < vis && (J) + 2 != (T2)) THRIFT_PREFETCH4((J) + 2);                                         \
-    }                                                                                                          \
-  }
+  // One step of the staging pipeline at block J, with P0 / P1 / P2 = "block J / J+1 / J+2 is promoted".
+  //  SYNC:  wait for this wavefront's share of block J, then meet the others: block J is complete in LDS
+  //         and everyone has finished block J-1.  Loads issued after block J's stay in flight: those of
+  //         the 4-bit block J+1 (issued one step ago) — unless block J's K tile had to be issued last,
+  //         after the score phase of a promoted block J-1.
+  //  ISSUE: block J+1's 16-bit tiles (its K tile only if the K buffer is not in use by block J), then the
+  //         4-bit block J+2 into the ring slot block J-1 has just left.
+  bool pm1 = false;                                     // block J-1 was promoted
+  int s0 = 0, s2 = 2;                                   // ring slots of blocks J and J+2 (J mod 3, (J+2) mod 3)
+#define THRIFT_SYNC(J, P0, P1)                                                                                 \
+  if ((pm1 && (P0)) || (J) + 1 >= vis || (P1)) vm_wait<0>();                                                   \
+  else vm_wait<C4>();                                                                                          \
+  lds_barrier();
+#define THRIFT_ISSUE(J, P0, P1, P2)                                                                            \
+  if ((J) + 1 < vis && (P1)) {                                                                                 \
+    THRIFT_ISSUE_V16((J) + 1, (ps + ((P0) ? 1 : 0)) & 1);                                                      \
+    if (!(P0)) THRIFT_ISSUE_K16((J) + 1);                                                                      \
+  }                                                                                                            \
+  if ((J) + 2 < vis && !(P2)) THRIFT_ISSUE4((J) + 2, s2);
+#define THRIFT_ADVANCE()                                                                                       \
+  s2 = s0;                                                                                                     \
+  s0 = s0 == 2 ? 0 : s0 + 1;
 #define THRIFT_MASK(J)                                                                                         \
   const bool mask = a.causal && (J) * kBk + kBk - 1 > q0;                                                      \
   const int n_valid = q0 + r - (J) * kBk + 1; /* keys of the block at positions <= the query's */
@@ -166,41 +201,70 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   while (j < vis_wave) {
     const int run_end = min(vis_wave, n0);
     for (; j < run_end; ++j) {
-      THRIFT_STEP(j, n0, (j + 1 == n0 ? n1 : n0))
+      const bool p1 = j + 1 == n0, p2 = j + 2 == n0 || j + 2 == n1;
+      THRIFT_SYNC(j, false, p1)
+      THRIFT_ISSUE(j, false, p1, p2)
       THRIFT_MASK(j)
+      const unsigned char* slot = lds + kLdsRing + s0 * kLdsBytes4;
       v16f s[2];
       float gmax;
-      scores_fp4(cur, lane, qf4, qsc, s);
+      scores_fp4(slot, lane, qf4, qsc, s);
       const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
       rescale(o, alpha);
-      pv_fp4(cur, lane, s, gmax, o);
+      pv_fp4(slot, lane, s, gmax, o);
+      pm1 = false;
+      THRIFT_ADVANCE()
     }
     if (j < vis_wave) {                                 // j == n0: a promoted block
-      THRIFT_STEP(j, n1, (j + 1 == n1 ? n2 : n1))
+      const bool p1 = j + 1 == n1, p2 = j + 2 == n1 || j + 2 == n2;
+      THRIFT_SYNC(j, true, p1)
+      THRIFT_ISSUE(j, true, p1, p2)
       THRIFT_MASK(j)
+      v8s qf[8];
+#pragma unroll
+      for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16row + 16 * s8 + 8 * half);
       v16f s[2];
       float gmax;
-      scores_16<T>(cur, lane, q16row, s);
+      scores_16<T>(lds + kLdsK16, lane, qf, s);
+      if (j + 1 < vis && p1) {                          // the K buffer is free once every wavefront has its scores
+        lds_barrier();
+        THRIFT_ISSUE_K16(j + 1);
+      }
       const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
       rescale(o, alpha);
-      pv_16<T>(cur + kLdsV16, lane, s, o);
+      pv_16<T, true>(lds + kLdsV16 + (ps & 1) * kTile16, lane, s, o);
       ++ps;
       n0 = n1; n1 = n2; n2 = ps + 2 < nsel ? sel[ps + 2] : 0x7fffffff;
+      pm1 = true;
+      THRIFT_ADVANCE()
       ++j;
     }
   }
   for (; j < vis; ++j) {                                // staging only
-    const bool is16 = j == n0;
-    const int t1 = is16 ? n1 : n0;
-    THRIFT_STEP(j, t1, (j + 1 == t1 ? (is16 ? n2 : n1) : t1))
-    (void)cur;
-    if (is16) {
+    const bool p0 = j == n0;
+    const bool p1 = p0 ? j + 1 == n1 : j + 1 == n0;
+    const bool p2 = j + 2 == n0 || j + 2 == n1 || j + 2 == n2;
+    THRIFT_SYNC(j, p0, p1)
+    THRIFT_ISSUE(j, p0, p1, p2)
+    if (p0) {
+      if (j + 1 < vis && p1) {
+        lds_barrier();
+        THRIFT_ISSUE_K16(j + 1);
+      }
       ++ps;
       n0 = n1; n1 = n2; n2 = ps + 2 < nsel ? sel[ps + 2] : 0x7fffffff;
     }
+    pm1 = p0;
+    THRIFT_ADVANCE()
   }
-#undef THRIFT_STEP
+  vm_wait<0>();
+#undef THRIFT_SYNC
+#undef THRIFT_ISSUE
+#undef THRIFT_ADVANCE
 #undef THRIFT_MASK
+#undef THRIFT_ISSUE4
+#undef THRIFT_ISSUE_V16
+#undef THRIFT_ISSUE_K16
 
   // ---- epilogue (Alg. 1 step 21): O / l; accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
   const float l = st.l + other_half(st.l);
@@ -228,10 +292,6 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
     }
   if (a.lse != nullptr && half == 0) a.lse[qrow] = st.m * a.scale + __logf(l);
 }
-
-#undef THRIFT_PREFETCH4
-#undef THRIFT_COMMIT4
-#undef THRIFT_STAGE16
 
 void launch_prefill(const PrefillArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((long)a.B * a.Hq * (a.N / a.Bq));

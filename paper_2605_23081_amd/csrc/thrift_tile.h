@@ -23,16 +23,21 @@
 
 namespace thrift {
 
-// LDS layout of one staged key block (bytes).  The 4-bit and 16-bit tiles alias the same region.
-constexpr int kRow16 = 2 * kD + 16;          // padded 16-bit row
-constexpr int kLdsK16 = 0;
-constexpr int kLdsV16 = kBk * kRow16;
-constexpr int kLdsBytes16 = 2 * kBk * kRow16;   // 34816
+// LDS layout of one staged 4-bit key block (bytes): a slot of the prefill kernel's ring.
 constexpr int kLdsK4 = 0;                    // 4096 B, stored in MFMA fragment order
-constexpr int kLdsV4 = 4096;                 // 4096 B, [channel][32 B]
+constexpr int kLdsV4 = 4096;                 // 4096 B, MFMA fragment order: chunk (n*64 + lane) = channel 32n + r, token half
 constexpr int kLdsKS = 8192;                 // 64 x 4 scale bytes of K, [key][d-group]
-constexpr int kLdsVS = 8448;                 // 256 scale bytes of V, [token group][r][n] for channel 32n + r
+constexpr int kLdsVS = 8448;                 // 2 x 128 scale bytes of V, [token group][channel]
 constexpr int kLdsBytes4 = 8704;
+// 16-bit tiles.  Padded rows (272 B) where a wavefront stages its own tile through registers (decode);
+// unpadded 256-byte rows with an XOR swizzle of the 16-byte chunks where the tile arrives by LDS DMA
+// (prefill), which can only write 1 KiB of consecutive LDS per instruction.
+constexpr int kRow16 = 2 * kD + 16;
+constexpr int kTile16 = kBk * 2 * kD;        // 16384
+// chunk c of row `row` lives at chunk position c ^ swz: K is read by rows (8 consecutive lanes take
+// rows {R..R+3, R+32..R+35} at one chunk index), V by 4-row x 64-byte patches (transposing reads).
+__device__ __forceinline__ int k16_swizzle(int row) { return (row & 3) | (((row >> 5) & 1) << 2); }
+__device__ __forceinline__ int v16_swizzle(int row) { return 4 * (row & 3); }
 
 __device__ __forceinline__ int key_of_row(int rho, int t) {
   return 32 * ((rho >> 2) & 1) + 16 * t + 4 * (rho >> 3) + (rho & 3);
@@ -70,22 +75,19 @@ __device__ __forceinline__ void scores_fp4(const unsigned char* lds, int lane, c
   }
 }
 
-// S^T for a 16-bit tile.  qrow: the lane's 16-bit query row in global memory; fragment s8 holds its
-// elements d = 16*s8 + 8*half + [0,8).  The fragments are fetched per promoted tile (a small share of
-// all tiles) instead of being pinned in 32 registers for the whole kernel.
+// S^T for a 16-bit tile.  ktile: the swizzled [64 keys][256 B] LDS tile; qf[s8]: the lane's query
+// elements d = 16*s8 + 8*half + [0,8).
 template <typename T>
-__device__ __forceinline__ void scores_16(const unsigned char* lds, int lane, const uint16_t* qrow, v16f (&s)[2]) {
+__device__ __forceinline__ void scores_16(const unsigned char* ktile, int lane, const v8s (&qf)[8], v16f (&s)[2]) {
   const int half = lane >> 5, r = lane & 31;
-  v8s qf[8];
-#pragma unroll
-  for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(qrow + 16 * s8 + 8 * half);
+  const int row0 = key_of_row(r, 0);                    // the row of sub-tile 1 is 16 further: same swizzle
+  const uint32_t base = (uint32_t)(row0 * 256 + 16 * (half ^ k16_swizzle(row0)));
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    const unsigned char* krow = lds + kLdsK16 + key_of_row(r, t) * kRow16 + 16 * half;
     v16f acc = {0.f};
 #pragma unroll
     for (int s8 = 0; s8 < 8; ++s8) {
-      const v8s a = *reinterpret_cast<const v8s*>(krow + 32 * s8);
+      const v8s a = *reinterpret_cast<const v8s*>(ktile + ((base ^ (32u * s8)) + 4096u * t));
       acc = T::mfma(a, qf[s8], acc);
     }
     s[t] = acc;
@@ -101,11 +103,13 @@ __device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mas
                                                 float& group_max) {
   const int half = lane >> 5;
   if (mask) {
+    int lim = n_valid - 32 * half;                      // the lane's keys 16t + i at or past lim are masked
+    asm volatile("" : "+v"(lim));                       // keep one register: no per-element thresholds hoisted out of the key loop
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int i = 0; i < 16; ++i)
-        if (32 * half + 16 * t + i >= n_valid) s[t][i] = -INFINITY;
+        if (16 * t + i >= lim) s[t][i] = -INFINITY;
   }
   float mloc = s[0][0];
 #pragma unroll
@@ -154,9 +158,11 @@ __device__ __forceinline__ void rescale(v16f (&o)[4], float alpha) {
 
 // 4-bit P.V (Alg. 1 steps 19-20 with the first-level scale equal to 1): quantise the lane's 32
 // probabilities as one MXFP4 group and accumulate O^T += V^T . P^T on the scaled MFMA.  v0..v3: the
-// lane's V^T fragments (channel 32n + r, tokens 32*half .. +31), vsw: their four scale bytes (byte n).
-__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], float group_max, uint32_t vsw, v4i v0, v4i v1, v4i v2, v4i v3,
-                                            v16f (&o)[4]) {
+// lane's V^T fragments (channel 32n + r, tokens 32*half .. +31).  Their scale bytes come either packed
+// in one register (PACKED: byte n of vs0) or one per register (byte 0 of vs0..vs3).
+template <bool PACKED>
+__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], float group_max, uint32_t vs0, uint32_t vs1, uint32_t vs2,
+                                            uint32_t vs3, v4i v0, v4i v1, v4i v2, v4i v3, v16f (&o)[4]) {
   uint32_t ef = __float_as_uint(group_max) >> 23;
   const uint32_t pb = ef >= 3u ? ef - 2u : 1u;                 // E8M0 byte, kept >= 1 so the scale is a normal float
   const float pscale = __uint_as_float(pb << 23);
@@ -172,27 +178,37 @@ __device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], float group_max,
     pq[w] = (int)o32;
   }
   const v8i pb8 = widen(pq);
-  o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v0), pb8, o[0], 4, 4, 0, vsw, 0, pb);
-  o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v1), pb8, o[1], 4, 4, 1, vsw, 0, pb);
-  o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v2), pb8, o[2], 4, 4, 2, vsw, 0, pb);
-  o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v3), pb8, o[3], 4, 4, 3, vsw, 0, pb);
+  if (PACKED) {
+    o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v0), pb8, o[0], 4, 4, 0, vs0, 0, pb);
+    o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v1), pb8, o[1], 4, 4, 1, vs0, 0, pb);
+    o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v2), pb8, o[2], 4, 4, 2, vs0, 0, pb);
+    o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v3), pb8, o[3], 4, 4, 3, vs0, 0, pb);
+  } else {
+    o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v0), pb8, o[0], 4, 4, 0, vs0, 0, pb);
+    o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v1), pb8, o[1], 4, 4, 0, vs1, 0, pb);
+    o[2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v2), pb8, o[2], 4, 4, 0, vs2, 0, pb);
+    o[3] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v3), pb8, o[3], 4, 4, 0, vs3, 0, pb);
+  }
 }
 
-// The same with V^T fragments and scales taken from the staged LDS tile.
-__device__ __forceinline__ void pv_fp4(const unsigned char* lds, int lane, const v16f (&p)[2], float group_max, v16f (&o)[4]) {
+// The same with V^T fragments and scales taken from a staged LDS slot.
+__device__ __forceinline__ void pv_fp4(const unsigned char* slot, int lane, const v16f (&p)[2], float group_max, v16f (&o)[4]) {
   const int half = lane >> 5, r = lane & 31;
-  const uint32_t vsw = *reinterpret_cast<const uint32_t*>(lds + kLdsVS + (half * 32 + r) * 4);
-  const unsigned char* vbase = lds + kLdsV4 + r * 32 + half * 16;
-  pv_fp4_regs(p, group_max, vsw, *reinterpret_cast<const v4i*>(vbase), *reinterpret_cast<const v4i*>(vbase + 1024),
-              *reinterpret_cast<const v4i*>(vbase + 2048), *reinterpret_cast<const v4i*>(vbase + 3072), o);
+  const unsigned char* vs = slot + kLdsVS + half * kD + r;
+  const unsigned char* vbase = slot + kLdsV4 + lane * 16;
+  pv_fp4_regs<false>(p, group_max, vs[0], vs[32], vs[64], vs[96], *reinterpret_cast<const v4i*>(vbase),
+                     *reinterpret_cast<const v4i*>(vbase + 1024), *reinterpret_cast<const v4i*>(vbase + 2048),
+                     *reinterpret_cast<const v4i*>(vbase + 3072), o);
 }
 
 // 16-bit P.V (Alg. 1 step 13): P rounded to the input dtype; V^T fragments come straight out of the
-// row-major LDS tile `vtile` ([64 keys][kRow16 bytes]) through the transposing 64-bit LDS read (each
-// 16-lane group turns a 4-key x 16-channel patch into 4 consecutive keys of one channel per lane).
-template <typename T>
+// row-major LDS tile `vtile` through the transposing 64-bit LDS read (each 16-lane group turns a
+// 4-key x 16-channel patch into 4 consecutive keys of one channel per lane).  SWZ: the tile has unpadded
+// 256-byte rows with swizzled chunks (v16_swizzle), otherwise rows of kRow16 bytes.
+template <typename T, bool SWZ>
 __device__ __forceinline__ void pv_16(const unsigned char* vtile, int lane, const v16f (&p)[2], v16f (&o)[4]) {
   const int half = lane >> 5, r = lane & 31, g = r >> 4, i16 = r & 15;
+  constexpr int kRow = SWZ ? 2 * kD : kRow16;
   v8s pf[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
@@ -201,14 +217,17 @@ __device__ __forceinline__ void pv_16(const unsigned char* vtile, int lane, cons
     for (int e = 0; e < 8; ++e) pf[s][e] = (short)T::from_float(p[t][i0 + e]);
   }
   typedef v4s __attribute__((address_space(3))) * lds_v4s_ptr;
+  // keys 32*half + 8*s + 4*u + (i16>>2), channels 32*n + 16*g + 4*(i16&3); the swizzle term of all these
+  // rows is 4*((i16>>2)&3), which turns the 64-byte step of n into an XOR
+  const uint32_t lane_off = (uint32_t)((32 * half + (i16 >> 2)) * kRow + (16 * g + 4 * (i16 & 3)) * 2);
+  const uint32_t sw = SWZ ? 64u * ((i16 >> 2) & 3) : 0u;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    // keys 32*half + 8*s + 4*u + (i16>>2), channels 32*n + 16*g + 4*(i16&3)
-    const unsigned char* base = vtile + (32 * half + 8 * s + (i16 >> 2)) * kRow16 + (16 * g + 4 * (i16 & 3)) * 2;
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
-      const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(base + n * 64));
-      const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(base + n * 64 + 4 * kRow16));
+      const unsigned char* base = vtile + ((SWZ ? ((lane_off + sw) ^ (64u * n)) : lane_off + 64u * n) + 8u * s * kRow);
+      const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(base));
+      const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(base + 4 * kRow));
       const v8s a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       o[n] = T::mfma(a, pf[s], o[n]);
     }
