@@ -3,29 +3,33 @@
 // One workgroup = one (batch, query head, query block); wavefront w owns query rows 32w .. 32w+31 of
 // the block and keeps Q, the online-softmax state and the O^T accumulators in registers.  Key blocks are
 // visited in ascending order (the order of Alg. 1) and dispatched per tile to the scaled-FP4 or the
-// 16-bit MFMA path.  Every block is staged once into LDS for all wavefronts by LDS DMA (global loads
-// that write LDS directly: no staging registers, no LDS write instructions):
-//   * MXFP4 codes + scales of an ordinary block go into a ring of three 8.5 KiB slots, two blocks ahead
-//     of the arithmetic, so their latency is hidden behind two key blocks of work;
-//   * the 16-bit K and V tiles of a block listed in the row's TopK set go into a K buffer and one of
-//     two V buffers, one block ahead.
-// One workgroup barrier per key block orders the traffic (plus one more between the score phase of a
-// promoted block and the arrival of the next K tile when two promoted blocks follow each other).
+// 16-bit MFMA path.
+//
+// The kernel is bound by the vector ALU work of the softmax and the P quantiser (exp and the FP4
+// converter run at a third of the plain rate), and one wavefront can issue vector instructions at only
+// about half the rate its SIMD can execute them.  Everything is therefore sized for THREE workgroups per
+// CU (three wavefronts per SIMD): at most 168 vector registers and a third of the LDS per workgroup.
+//   * Every block is staged once into LDS for all wavefronts by LDS DMA (global loads that write LDS
+//     directly: no staging registers, no LDS write instructions), one block ahead of the arithmetic:
+//     MXFP4 codes + scales into one of two 8.5 KiB slots, the 16-bit K and V tiles of a block listed in
+//     the row's TopK set into one K and one V buffer.
+//   * One workgroup barrier per key block orders the traffic.  Two promoted blocks in a row share the
+//     16-bit buffers: the second K tile is fetched after the score phase of the first, the second V tile
+//     at the start of its own step, each behind one more barrier.
 //
 // Differences from the kernel the paper sketches for Blackwell (Sec. 3.3): no two-phase split (4-bit
-// tiles first, 16-bit helper afterwards) — on gfx950 both paths fit in the 512-entry register file at
-// two wavefronts per SIMD, and ascending order keeps the result independent of the schedule.
+// tiles first, 16-bit helper afterwards): ascending order keeps the result independent of the schedule
+// and identical to Alg. 1 as written.
 #include "thrift_launch.h"
 #include "thrift_tile.h"
 
 namespace thrift {
 
 // LDS map of the prefill kernel (bytes)
-constexpr int kRing = 3;
-constexpr int kLdsRing = 0;                                  // kRing slots of kLdsBytes4
-constexpr int kLdsV16 = kRing * kLdsBytes4;                  // two swizzled 16-bit V tiles
-constexpr int kLdsK16 = kLdsV16 + 2 * kTile16;               // one swizzled 16-bit K tile
-constexpr int kLdsPrefill = kLdsK16 + kTile16;               // 75264: two workgroups per CU
+constexpr int kLdsRing = 0;                                  // two slots of kLdsBytes4 (block j -> slot j & 1)
+constexpr int kLdsV16 = 2 * kLdsBytes4;                      // one swizzled 16-bit V tile
+constexpr int kLdsK16 = kLdsV16 + kTile16;                   // one swizzled 16-bit K tile
+constexpr int kLdsPrefill = kLdsK16 + kTile16;               // 50176: three workgroups per CU
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
 // load (a full fence), which would wait for the tiles in flight at every key block; here only this
@@ -51,9 +55,8 @@ __device__ __forceinline__ void dma_b32(const void* base, uint32_t off, uint32_t
 }
 
 template <typename T, int NW>
-__global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
+__global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   constexpr int KF = 4 / NW;                 // 1 KiB fragments of a 4-bit K (and of a V) tile per wavefront
-  constexpr int C4 = 2 * KF + 1;             // DMA instructions per wavefront for one 4-bit block
   constexpr int C16 = 16 / NW;               // ... for one 16-bit K or V tile
   __shared__ __align__(1024) unsigned char lds[kLdsPrefill];
 
@@ -90,9 +93,9 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   const int vis = a.causal ? min(Tk, ((i + 1) * Bq - 1) / kBk + 1) : Tk;
   const int32_t* sel = a.idx + (qh * Tq + i) * a.kmax;
   const int nsel = a.cnt[qh * Tq + i];
-  // the next three promoted block ids at or after the current block (ascending list)
+  // the next two promoted block ids at or after the current block (ascending list)
   int ps = 0;
-  int n0 = nsel > 0 ? sel[0] : 0x7fffffff, n1 = nsel > 1 ? sel[1] : 0x7fffffff, n2 = nsel > 2 ? sel[2] : 0x7fffffff;
+  int n0 = nsel > 0 ? sel[0] : 0x7fffffff, n1 = nsel > 1 ? sel[1] : 0x7fffffff;
 
   const uint8_t* k4base = a.k4 + kh * N * 64;
   const uint8_t* v4base = a.v4 + kh * (size_t)(N / 64) * 4096;
@@ -117,11 +120,11 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   const uint32_t v16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ v16_swizzle(lane >> 4)) * 16);
   const uint32_t k16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ (lane >> 4)) * 16);   // rows 32..63: chunk ^ 4 more
 
-#define THRIFT_ISSUE4(J, S)                                                                                    \
+#define THRIFT_ISSUE4(J)                                                                                       \
   do {                                                                                                         \
     const uint8_t* kt_ = k4base + (size_t)(J) * 4096;                                                          \
     const uint8_t* vt_ = v4base + (size_t)(J) * 4096;                                                          \
-    const uint32_t sl_ = lds0 + kLdsRing + (S) * kLdsBytes4;                                                   \
+    const uint32_t sl_ = lds0 + kLdsRing + ((J) & 1) * kLdsBytes4;                                                   \
     _Pragma("unroll") for (int u = 0; u < KF; ++u) {                                                           \
       dma_b128(kt_, k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024);                                          \
       dma_b128(vt_, v4off[u], sl_ + kLdsV4 + (wave * KF + u) * 1024);                                          \
@@ -130,10 +133,10 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
     if (wave & 1) dma_b32(vsbase + (size_t)(J) * 256, scoff, sl_ + kLdsVS);                                    \
     else dma_b32(ksbase + (size_t)(J) * 256, scoff, sl_ + kLdsKS);                                             \
   } while (0)
-#define THRIFT_ISSUE_V16(J, BUF)                                                                               \
+#define THRIFT_ISSUE_V16(J)                                                                                    \
   do {                                                                                                         \
     const uint8_t* vt_ = v16base + (size_t)(J) * kTile16;                                                      \
-    const uint32_t vb_ = lds0 + kLdsV16 + (BUF) * kTile16;                                                     \
+    const uint32_t vb_ = lds0 + kLdsV16;                                                     \
     _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                          \
       const int q_ = u * NW + wave;                                                                            \
       dma_b128(vt_ + q_ * 1024, v16off, vb_ + q_ * 1024);                                                      \
@@ -154,46 +157,46 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   for (int n = 0; n < 4; ++n) o[n] = (v16f){0.f};
   const float c = a.scale * 1.4426950408889634f;
 
-  // prologue: block 0 (either format) and block 1 (if 4-bit) on their way
+  // prologue: block 0 on its way
   if (vis > 0) {
     if (n0 == 0) {
-      THRIFT_ISSUE_V16(0, 0);
       THRIFT_ISSUE_K16(0);
+      THRIFT_ISSUE_V16(0);
     } else {
-      THRIFT_ISSUE4(0, 0);
+      THRIFT_ISSUE4(0);
     }
-    if (vis > 1 && (n0 == 0 ? n1 : n0) != 1) THRIFT_ISSUE4(1, 1);
   }
   // Blocks this wavefront computes: those with at least one key at or before its last query row.  The
   // later blocks of the workgroup (visible only to wavefronts with later rows) are still staged and
   // synchronised on, in a final loop without arithmetic.
   const int vis_wave = a.causal ? min(vis, (q0 + 31) / kBk + 1) : vis;
 
-  // One step of the staging pipeline at block J, with P0 / P1 / P2 = "block J / J+1 / J+2 is promoted".
+  // One step of the staging pipeline at block J, with P0 / P1 = "block J / J+1 is promoted".
   //  SYNC:  wait for this wavefront's share of block J, then meet the others: block J is complete in LDS
-  //         and everyone has finished block J-1.  Loads issued after block J's stay in flight: those of
-  //         the 4-bit block J+1 (issued one step ago) — unless block J's K tile had to be issued last,
-  //         after the score phase of a promoted block J-1.
-  //  ISSUE: block J+1's 16-bit tiles (its K tile only if the K buffer is not in use by block J), then the
-  //         4-bit block J+2 into the ring slot block J-1 has just left.
-  bool pm1 = false;                                     // block J-1 was promoted
-  int s0 = 0, s2 = 2;                                   // ring slots of blocks J and J+2 (J mod 3, (J+2) mod 3)
-#define THRIFT_SYNC(J, P0, P1)                                                                                 \
-  if ((pm1 && (P0)) || (J) + 1 >= vis || (P1)) vm_wait<0>();                                                   \
-  else vm_wait<C4>();                                                                                          \
+  //         and everyone has finished block J-1 (whose buffers are free again).
+  //  ISSUE: block J+1 — a 4-bit block into the other slot; a promoted block into the 16-bit buffers,
+  //         unless block J is using them (then its K tile follows the score phase of block J and its V
+  //         tile the start of step J+1: late_v).
+  bool late_v = false;                                  // block J is promoted and its V tile is not issued yet
+#define THRIFT_SYNC()                                                                                          \
+  vm_wait<0>();                                                                                                \
   lds_barrier();
-#define THRIFT_ISSUE(J, P0, P1, P2)                                                                            \
-  if ((J) + 1 < vis && (P1)) {                                                                                 \
-    THRIFT_ISSUE_V16((J) + 1, (ps + ((P0) ? 1 : 0)) & 1);                                                      \
-    if (!(P0)) THRIFT_ISSUE_K16((J) + 1);                                                                      \
-  }                                                                                                            \
-  if ((J) + 2 < vis && !(P2)) THRIFT_ISSUE4((J) + 2, s2);
-#define THRIFT_ADVANCE()                                                                                       \
-  s2 = s0;                                                                                                     \
-  s0 = s0 == 2 ? 0 : s0 + 1;
+#define THRIFT_ISSUE(J, P0, P1)                                                                                \
+  if ((J) + 1 < vis) {                                                                                         \
+    if (!(P1)) {                                                                                               \
+      THRIFT_ISSUE4((J) + 1);                                                                                  \
+    } else if (!(P0)) {                                                                                        \
+      THRIFT_ISSUE_K16((J) + 1);                                                                               \
+      THRIFT_ISSUE_V16((J) + 1);                                                                               \
+    }                                                                                                          \
+  }
 #define THRIFT_MASK(J)                                                                                         \
   const bool mask = a.causal && (J) * kBk + kBk - 1 > q0;                                                      \
   const int n_valid = q0 + r - (J) * kBk + 1; /* keys of the block at positions <= the query's */
+#define THRIFT_NEXT_PROMOTED()                                                                                 \
+  ++ps;                                                                                                        \
+  n0 = n1;                                                                                                     \
+  n1 = ps + 1 < nsel ? sel[ps + 1] : 0x7fffffff;
 
   // The walk alternates between runs of 4-bit blocks (tight loop: only the scaled-FP4 path, accumulators
   // updated in place) and single promoted blocks.
@@ -201,67 +204,77 @@ __global__ void __launch_bounds__(NW * 64, 2) prefill_kernel(PrefillArgs a) {
   while (j < vis_wave) {
     const int run_end = min(vis_wave, n0);
     for (; j < run_end; ++j) {
-      const bool p1 = j + 1 == n0, p2 = j + 2 == n0 || j + 2 == n1;
-      THRIFT_SYNC(j, false, p1)
-      THRIFT_ISSUE(j, false, p1, p2)
+      THRIFT_SYNC()
+      THRIFT_ISSUE(j, false, j + 1 == n0)
       THRIFT_MASK(j)
-      const unsigned char* slot = lds + kLdsRing + s0 * kLdsBytes4;
+      const unsigned char* slot = lds + kLdsRing + (j & 1) * kLdsBytes4;
       v16f s[2];
       float gmax;
       scores_fp4(slot, lane, qf4, qsc, s);
       const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
       rescale(o, alpha);
       pv_fp4(slot, lane, s, gmax, o);
-      pm1 = false;
-      THRIFT_ADVANCE()
+      late_v = false;
     }
     if (j < vis_wave) {                                 // j == n0: a promoted block
-      const bool p1 = j + 1 == n1, p2 = j + 2 == n1 || j + 2 == n2;
-      THRIFT_SYNC(j, true, p1)
-      THRIFT_ISSUE(j, true, p1, p2)
+      const bool p1 = j + 1 == n1 && j + 1 < vis;
+      THRIFT_SYNC()
+      THRIFT_ISSUE(j, true, j + 1 == n1)
+      if (late_v) THRIFT_ISSUE_V16(j);
       THRIFT_MASK(j)
-      v8s qf[8];
-#pragma unroll
-      for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16row + 16 * s8 + 8 * half);
       v16f s[2];
       float gmax;
-      scores_16<T>(lds + kLdsK16, lane, qf, s);
-      if (j + 1 < vis && p1) {                          // the K buffer is free once every wavefront has its scores
+      {
+        v8s qf[8];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16row + 16 * s8 + 8 * half);
+        scores_16<T>(lds + kLdsK16, lane, qf, s);
+      }
+      if (p1) {                                         // the K buffer is free once every wavefront has its scores
         lds_barrier();
         THRIFT_ISSUE_K16(j + 1);
       }
       const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
       rescale(o, alpha);
-      pv_16<T, true>(lds + kLdsV16 + (ps & 1) * kTile16, lane, s, o);
-      ++ps;
-      n0 = n1; n1 = n2; n2 = ps + 2 < nsel ? sel[ps + 2] : 0x7fffffff;
-      pm1 = true;
-      THRIFT_ADVANCE()
+      if (late_v) {                                     // this block's V tile was issued in this step
+        if (p1) vm_wait<C16>();
+        else vm_wait<0>();
+        lds_barrier();
+      }
+      pv_16<T, true>(lds + kLdsV16, lane, s, o);
+      THRIFT_NEXT_PROMOTED()
+      late_v = p1;
       ++j;
     }
   }
   for (; j < vis; ++j) {                                // staging only
     const bool p0 = j == n0;
-    const bool p1 = p0 ? j + 1 == n1 : j + 1 == n0;
-    const bool p2 = j + 2 == n0 || j + 2 == n1 || j + 2 == n2;
-    THRIFT_SYNC(j, p0, p1)
-    THRIFT_ISSUE(j, p0, p1, p2)
+    const bool p1 = (p0 ? j + 1 == n1 : j + 1 == n0);
+    THRIFT_SYNC()
+    THRIFT_ISSUE(j, p0, p1)
     if (p0) {
-      if (j + 1 < vis && p1) {
+      const bool p1v = p1 && j + 1 < vis;
+      if (late_v) THRIFT_ISSUE_V16(j);
+      if (p1v) {
         lds_barrier();
         THRIFT_ISSUE_K16(j + 1);
       }
-      ++ps;
-      n0 = n1; n1 = n2; n2 = ps + 2 < nsel ? sel[ps + 2] : 0x7fffffff;
+      if (late_v) {
+        if (p1v) vm_wait<C16>();
+        else vm_wait<0>();
+        lds_barrier();
+      }
+      THRIFT_NEXT_PROMOTED()
+      late_v = p1v;
+    } else {
+      late_v = false;
     }
-    pm1 = p0;
-    THRIFT_ADVANCE()
   }
   vm_wait<0>();
 #undef THRIFT_SYNC
 #undef THRIFT_ISSUE
-#undef THRIFT_ADVANCE
 #undef THRIFT_MASK
+#undef THRIFT_NEXT_PROMOTED
 #undef THRIFT_ISSUE4
 #undef THRIFT_ISSUE_V16
 #undef THRIFT_ISSUE_K16
