@@ -96,8 +96,10 @@ __device__ __forceinline__ void scores_16(const unsigned char* ktile, int lane, 
 
 // Online-softmax update for the lane's 32 scores (Alg. 1 steps 10-12 / 16-17): masks, raises the
 // running maximum, turns s into the unnormalised probabilities exp(scale*(s - m_new)) in place, adds
-// them to the partial row sum and returns alpha = exp(scale*(m_old - m_new)).  group_max receives the
-// largest probability of the lane's 32-key group (the MXFP4 scale of P derives from it).
+// them to the partial row sum and returns alpha = exp(scale*(m_old - m_new)) — exactly 1 in every lane,
+// with no arithmetic spent on it, when no row of the wavefront raised its maximum (the common case
+// once the first blocks are behind).  group_max receives the largest probability of the lane's 32-key
+// group (the MXFP4 scale of P derives from it).
 //   c = softmax_scale * log2(e);  n_valid = number of leading keys of the block this query may see.
 __device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mask, int n_valid, float c, RowState& st,
                                                 float& group_max) {
@@ -118,7 +120,9 @@ __device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mas
   for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, s[1][i]);
   const float m_new = fmaxf(st.m, fmaxf(mloc, other_half(mloc)));
   const float m_safe = m_new == -INFINITY ? 0.f : m_new;       // a row that has seen nothing stays empty
-  const float alpha = fast_exp2((st.m - m_safe) * c);
+  float alpha = 1.0f;
+  const bool grew = __builtin_amdgcn_ballot_w64(m_new != st.m) != 0ULL;
+  if (grew) alpha = fast_exp2((st.m - m_safe) * c);
   // Elements use one fused multiply-add, s*c - m*c; its rounding residue (a few 1e-7 relative on p) is
   // harmless for the codes and the row sum.  The group maximum, which fixes the power-of-two scale of
   // the P quantiser, is formed as (s - m)*c instead: the row maximum then maps to exactly 2^0 and can
@@ -134,7 +138,7 @@ __device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mas
       sum += p;
     }
   group_max = fast_exp2((mloc - m_safe) * c);
-  st.l = st.l * alpha + sum;
+  st.l = grew ? st.l * alpha + sum : st.l + sum;
   st.m = m_new;
   return alpha;
 }
