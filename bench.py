@@ -28,12 +28,15 @@ if ROOT not in sys.path:
 PEAK_16 = 2500.0     # TFLOP/s, dense bf16 / fp16 MFMA, MI355X datasheet
 PEAK_FP4 = 10100.0   # TFLOP/s, dense MXFP4 MFMA
 PEAK_HBM = 8000.0    # GB/s
-# Vector-ALU ceiling of the fused kernel: each score of a 4-bit tile needs at least one subtract, one
-# multiply, one v_exp_f32 (2 issue slots), one add (row sum), half a v_max3 and one half-rate FP4 convert
-# slot = 6.5 issue slots; a wave-tile (32 queries x 64 keys, 1.05 MFLOP) holds 32 scores per lane; a SIMD
-# issues one wavefront instruction per 4 cycles; 1024 SIMDs at the 2.4 GHz nominal clock.
-ALU_SLOTS_PER_SCORE = 6.5
-ALU_PEAK = 1024 * 2.4e9 / (ALU_SLOTS_PER_SCORE * 32 * 4) * (2 * 2 * 32 * 64 * 128) / 1e12   # TFLOP/s
+# Vector-ALU ceiling of the fused kernel.  Per score of a 4-bit tile the softmax and the P quantiser need at
+# least one fused multiply-add, one v_exp_f32, one add (row sum), half a v_max3 and half a
+# v_cvt_scalef32_pk_fp4_f32.  Cycles a SIMD spends per wavefront instruction (64 scores): 2 for fp32
+# FMA / ADD (the rate behind the 157.3 TFLOP/s vector figure), 4 for other plain VALU work, 8 for the
+# exponential and the FP4 converter (measured: 1.17 / 1.74 / 3.55 / 3.40 ns under load; the two do not
+# overlap with other VALU work of the SIMD).  1024 SIMDs at the 2.4 GHz nominal clock; 4*D flop per score.
+ALU_CYCLES_PER_SCORE_INSTR = {"fma": 2, "exp": 8, "add": 2, "half_max3": 2, "half_cvt_fp4": 4}
+ALU_CYCLES = sum(ALU_CYCLES_PER_SCORE_INSTR.values())          # 18 cycles per 64 scores
+ALU_PEAK = 1024 * 64 * 2.4e9 / ALU_CYCLES * (4 * 128) / 1e12   # TFLOP/s
 PAPER_CONTEXT = {"gap_recovery_pct_at_5_10_25": [89.1, 91.8, 92.4], "e2e_speedup_at_131k": 2.0,
                  "hardware": "RTX PRO 6000 Blackwell, NVFP4+FP16 (context only, not a target)"}
 
@@ -132,7 +135,7 @@ def main() -> int:
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
                      "note": "the kernel is limited by softmax / quantisation VALU work, not by the MFMA rate",
                      "alu": {"peak": round(ALU_PEAK, 1), "unit": "TFLOP/s", "frac": round(achieved / ALU_PEAK, 4),
-                             "slots_per_score": ALU_SLOTS_PER_SCORE}},
+                             "simd_cycles_per_64_scores": ALU_CYCLES}},
         "paper_context": PAPER_CONTEXT,
     }
 
