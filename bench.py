@@ -37,6 +37,12 @@ PEAK_HBM = 8000.0    # GB/s
 ALU_CYCLES_PER_SCORE_INSTR = {"fma": 2, "exp": 8, "add": 2, "half_max3": 2, "half_cvt_fp4": 4}
 ALU_CYCLES = sum(ALU_CYCLES_PER_SCORE_INSTR.values())          # 18 cycles per 64 scores
 ALU_PEAK = 1024 * 64 * 2.4e9 / ALU_CYCLES * (4 * 128) / 1e12   # TFLOP/s
+# HBM traffic per launch of the two dominant kernels on the default workloads, from separate rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE; scaled by what the same counters read for the 1 GiB calibration copy below: x2.0 and
+# x1.0).  The summary of those runs is profiles/prefill_decode_hbm_traffic_pmc.txt; counters cannot be read from
+# inside this process, so the figures are reported only for the configuration they were measured on.
+MEASURED_TRAFFIC_GB = {"prefill_131k_f0.05": {"fetched": 35.90, "written": 1.07},
+                       "decode_16x131k_f0.05": {"fetched": 3.86, "written": 0.002}}
 PAPER_CONTEXT = {"gap_recovery_pct_at_5_10_25": [89.1, 91.8, 92.4], "e2e_speedup_at_131k": 2.0,
                  "hardware": "RTX PRO 6000 Blackwell, NVFP4+FP16 (context only, not a target)"}
 
@@ -132,7 +138,8 @@ def main() -> int:
         "prefill": {"ms_prepass": round(ms_pre, 4), "ms_fused_kernel": round(ms_attn, 3),
                     "kernel_tflops": round(achieved, 2)},
         "roofline": {"bound": "mfma", "kernel": "prefill_kernel<BF16,4>", "achieved": round(achieved, 2), "peak": round(peak, 1),
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "traffic": (MEASURED_TRAFFIC_GB["prefill_131k_f0.05"] if (N == 131072 and args.budget == 0.05) else None),
                      "note": "the kernel is limited by softmax / quantisation VALU work, not by the MFMA rate",
                      "alu": {"peak": round(ALU_PEAK, 1), "unit": "TFLOP/s", "frac": round(achieved / ALU_PEAK, 4),
                              "simd_cycles_per_64_scores": ALU_CYCLES}},
@@ -235,7 +242,9 @@ def main() -> int:
                             "us": round(us, 1), "algorithmic_GB": round(alg_bytes / 1e9, 3), "GBps": round(gbs, 1),
                             "promoted_block_share_union": round(n_union / blocks, 4),
                             "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(gbs, 1), "peak": PEAK_HBM,
-                                         "unit": "GB/s", "frac": round(gbs / PEAK_HBM, 4), "traffic": None},
+                                         "unit": "GB/s", "frac": round(gbs / PEAK_HBM, 4),
+                                         "traffic": (MEASURED_TRAFFIC_GB["decode_16x131k_f0.05"]
+                                                     if (wd.N == 131072 and wd.B == 16 and args.budget == 0.05) else None)},
                             "fp16_cache_equivalent_GB": round(blocks * fp16_block / 1e9, 3)}
         log(f"decode {us:.1f} us, {alg_bytes / 1e9:.2f} GB algorithmic -> {gbs:.0f} GB/s = {100 * gbs / PEAK_HBM:.1f} % of 8 TB/s")
 
