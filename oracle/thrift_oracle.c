@@ -221,6 +221,69 @@ int oracle_select_topk(const float* qmean, const float* kmean, int B, int Hq, in
 }
 
 /* ------------------------------------------------------------------ */
+/* Ablation selectors  (App. A "Heuristic Ablation")                   */
+/* ------------------------------------------------------------------ */
+
+/* The appendix compares the mean-score heuristic with "randomly promoted blocks" and with
+ * "diagonal-only selection" at the same budget and gives no further definition.  Reading taken:
+ * per row, the same number k_i of visible blocks as the heuristic would promote;
+ *   random:   a uniformly random k_i-subset of the visible blocks, drawn by ranking the blocks by
+ *             independent 64-bit keys and keeping the k_i largest (equal keys: smaller block id);
+ *   diagonal: the k_i visible blocks closest to the causal diagonal, i.e. the largest block ids.
+ * The random keys come from the SplitMix64 generator (Steele, Lea, Flood 2014): output number n+1 of
+ * the stream seeded with `seed`, n = rowid * 2^32 + j, which is mix(seed + (n+1) * golden). */
+uint64_t oracle_splitmix64_output(uint64_t seed, uint64_t n_plus_1) {
+  uint64_t z = seed + n_plus_1 * 0x9e3779b97f4a7c15ULL;
+  z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ULL;
+  z = (z ^ (z >> 27)) * 0x94d049bb133111ebULL;
+  return z ^ (z >> 31);
+}
+
+typedef struct { uint64_t key; int j; } keyed_t;
+
+static int cmp_keyed(const void* pa, const void* pb) {
+  const keyed_t* a = (const keyed_t*)pa;
+  const keyed_t* b = (const keyed_t*)pb;
+  if (a->key > b->key) return -1;
+  if (a->key < b->key) return 1;
+  return a->j - b->j;
+}
+
+/* selector: 1 = random, 2 = diagonal.  Output as oracle_select_topk.  Returns 0, -1 if kmax is too
+ * small, -2 for an unknown selector. */
+int oracle_select_ablation(int selector, uint64_t seed, int B, int Hq, int Tq, int Tk, int Bq, int Bk, int causal,
+                           double budget, int fixed_k, int q_block_offset, int32_t* idx, int32_t* cnt, int kmax) {
+  if (selector != 1 && selector != 2) return -2;
+  keyed_t* row = (keyed_t*)malloc(sizeof(keyed_t) * (size_t)(Tk > 0 ? Tk : 1));
+  int* sel = (int*)malloc(sizeof(int) * (size_t)(Tk > 0 ? Tk : 1));
+  int rc = 0;
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < Hq; ++h)
+      for (int i = 0; i < Tq; ++i) {
+        long rowid = ((long)b * Hq + h) * Tq + i;
+        int vis = oracle_visible_blocks(i, Tk, Bq, Bk, causal, q_block_offset);
+        int k = oracle_row_k(vis, budget, fixed_k);
+        if (k > kmax) { rc = -1; k = kmax; }
+        if (selector == 1) {
+          for (int j = 0; j < vis; ++j) {
+            row[j].key = oracle_splitmix64_output(seed, (((uint64_t)rowid << 32) | (uint64_t)j) + 1ULL);
+            row[j].j = j;
+          }
+          qsort(row, (size_t)vis, sizeof(keyed_t), cmp_keyed);
+          for (int t = 0; t < k; ++t) sel[t] = row[t].j;
+          qsort(sel, (size_t)k, sizeof(int), cmp_int);
+        } else {
+          for (int t = 0; t < k; ++t) sel[t] = vis - k + t;
+        }
+        for (int t = 0; t < kmax; ++t) idx[rowid * kmax + t] = t < k ? sel[t] : -1;
+        cnt[rowid] = k;
+      }
+  free(row);
+  free(sel);
+  return rc;
+}
+
+/* ------------------------------------------------------------------ */
 /* MXFP4 quantiser  (Sec. 3.2 "FP4 quantisation", MXFP4 reading)       */
 /* ------------------------------------------------------------------ */
 

@@ -126,6 +126,31 @@ def select_topk(qmean: np.ndarray, kmean: np.ndarray, Bq: int, Bk: int, causal: 
     return idx, cnt
 
 
+SELECT_RANDOM, SELECT_DIAGONAL = 1, 2
+
+
+def splitmix64_output(seed: int, n_plus_1: int) -> int:
+    f = lib().oracle_splitmix64_output
+    f.restype = C.c_uint64
+    return int(f(C.c_uint64(seed & (2 ** 64 - 1)), C.c_uint64(n_plus_1 & (2 ** 64 - 1))))
+
+
+def select_ablation(selector: int, seed: int, B: int, Hq: int, Tq: int, Tk: int, Bq: int, Bk: int, causal: bool,
+                    budget: float, fixed_k: int = -1, q_block_offset: int = 0, kmax: Optional[int] = None):
+    """App. A selectors (random / diagonal) at the heuristic's per-row budget; output as select_topk."""
+    if kmax is None:
+        kmax = max(1, max(row_k(visible_blocks(i, Tk, Bq, Bk, causal, q_block_offset), budget, fixed_k) for i in range(Tq)))
+    idx = np.empty((B, Hq, Tq, kmax), np.int32)
+    cnt = np.empty((B, Hq, Tq), np.int32)
+    rc = lib().oracle_select_ablation(int(selector), C.c_uint64(seed & (2 ** 64 - 1)), B, Hq, Tq, Tk, Bq, Bk, int(causal),
+                                      C.c_double(budget), int(fixed_k), int(q_block_offset), _p(idx), _p(cnt), kmax)
+    if rc == -2:
+        raise ValueError("unknown selector")
+    if rc != 0:
+        raise ValueError("kmax too small")
+    return idx, cnt
+
+
 def mx_quantize_group(x: Sequence[float]) -> Tuple[np.ndarray, int]:
     x = np.ascontiguousarray(x, np.float64)
     codes = np.empty(x.shape[0], np.uint8)

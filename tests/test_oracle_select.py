@@ -146,3 +146,61 @@ def test_recovery_definition_matches_paper_table():
     assert abs(metrics.recovery(0.01, 0.11, 0.02) - 0.9) < 1e-12
     # blended peak: 5 % at 2.5 PF and 95 % at 10 PF -> 8.70 PF; equal to the matched-compute 28.75 %
     assert abs(metrics.blended_peak(0.05, 2.5, 10.0) - 10.0 / (4 * 0.2875)) < 1e-12
+
+
+# ---------------------------------------------------------------- App. A ablation selectors
+
+def test_splitmix64_published_vector(oracle):
+    want = [int(l) for l in open(os.path.join(GOLDEN, "splitmix64_seed1234567.txt")) if l[0] != "#"]
+    assert [oracle.splitmix64_output(1234567, n + 1) for n in range(5)] == want
+
+
+def test_diagonal_selector_is_the_most_recent_blocks(oracle):
+    Tq, Tk, Bq, Bk = 16, 32, 128, 64
+    idx, cnt = oracle.select_ablation(oracle.SELECT_DIAGONAL, 0, 1, 2, Tq, Tk, Bq, Bk, True, 0.25)
+    for i in range(Tq):
+        vis = 2 * (i + 1)                                  # hand count: blocks 0 .. 2i+1 are visible
+        k = max(1, -(-vis // 4))
+        assert cnt[0, 1, i] == k
+        assert idx[0, 1, i, :k].tolist() == list(range(vis - k, vis))
+        assert (idx[0, 1, i, k:] == -1).all()
+    # non-causal: the tail of the whole key range; fixed k
+    idx, cnt = oracle.select_ablation(oracle.SELECT_DIAGONAL, 0, 1, 1, 4, 10, 64, 64, False, 0.0, fixed_k=3)
+    assert (cnt == 3).all() and (idx[0, 0, :, :3] == np.array([7, 8, 9])).all()
+
+
+def test_random_selector_properties(oracle):
+    B, Hq, Tq, Tk, Bq, Bk = 2, 3, 24, 24, 64, 64
+    idx, cnt = oracle.select_ablation(oracle.SELECT_RANDOM, 7, B, Hq, Tq, Tk, Bq, Bk, True, 0.25)
+    idx2, cnt2 = oracle.select_ablation(oracle.SELECT_RANDOM, 7, B, Hq, Tq, Tk, Bq, Bk, True, 0.25)
+    idx3, _ = oracle.select_ablation(oracle.SELECT_RANDOM, 8, B, Hq, Tq, Tk, Bq, Bk, True, 0.25)
+    assert np.array_equal(idx, idx2) and np.array_equal(cnt, cnt2)         # deterministic in the seed
+    assert not np.array_equal(idx, idx3)                                   # and depends on it
+    rows = set()
+    for b in range(B):
+        for h in range(Hq):
+            for i in range(Tq):
+                vis = i + 1
+                k = oracle.row_k(vis, 0.25)
+                assert cnt[b, h, i] == k
+                ids = idx[b, h, i, :k].tolist()
+                assert ids == sorted(set(ids)) and 0 <= ids[0] and ids[-1] < vis    # distinct, ascending, visible
+                # brute force: rank the visible blocks by their published-generator keys
+                rowid = (b * Hq + h) * Tq + i
+                keys = [oracle.splitmix64_output(7, ((rowid << 32) | j) + 1) for j in range(vis)]
+                want = sorted(sorted(range(vis), key=lambda j: (-keys[j], j))[:k])
+                assert ids == want
+                rows.add(tuple(ids))
+    assert len(rows) > B * Hq * Tq // 2                                    # rows differ from each other
+
+
+def test_random_selector_is_uniform(oracle):
+    """Every visible block is promoted with probability k/vis: chi-square over many rows (non-causal, one k)."""
+    B, Hq, Tq, Tk = 1, 8, 512, 16
+    idx, cnt = oracle.select_ablation(oracle.SELECT_RANDOM, 123, B, Hq, Tq, Tk, 64, 64, False, 0.0, fixed_k=4)
+    counts = np.bincount(idx[..., :4].ravel(), minlength=Tk).astype(np.float64)
+    n = B * Hq * Tq
+    expect = n * 4 / Tk
+    # a single cell of a uniform 4-of-16 draw has variance n*p*(1-p); 15 degrees of freedom after the sum constraint
+    chi2 = ((counts - expect) ** 2 / (expect * (1 - 4 / Tk))).sum()
+    assert counts.sum() == 4 * n and chi2 < 45.0, chi2                     # P(chi2_15 > 45) < 1e-4
