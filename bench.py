@@ -192,10 +192,19 @@ def main() -> int:
             o = p2.run(q[:, :wl.group].contiguous(), k[:, :1].contiguous(), v[:, :1].contiguous())
             errs[f] = metrics.rel_fro(sampled(o), exact)
             del p2
+        # App. A analogue: the same budget spent on random / most-recent blocks instead of the heuristic's choice
+        abl = {}
+        for name, selector in (("random", T.SELECT_RANDOM), ("diagonal", T.SELECT_DIAGONAL)):
+            p2 = T.PrefillPlan(B, wl.group, 1, N, D, Bq, Bk, True, 0.05, q.dtype, dev, selector=selector, seed=wl.seed)
+            o = p2.run(q[:, :wl.group].contiguous(), k[:, :1].contiguous(), v[:, :1].contiguous())
+            abl[name] = metrics.rel_fro(sampled(o), exact)
+            del p2
         result["recovery"] = {"definition": "(E_fp4 - E_f) / (E_fp4 - E_fp16), E = rel. Frobenius error vs fp64 exact attention on sampled rows",
                               "rel_err": {str(f): round(e, 5) for f, e in errs.items()},
-                              "recovery_pct": {str(f): round(100 * metrics.recovery(errs[1.0], errs[0.0], errs[f]), 1) for f in (0.05, 0.10, 0.25)}}
-        log(f"rel. errors {errs}; recovery {result['recovery']['recovery_pct']}")
+                              "recovery_pct": {str(f): round(100 * metrics.recovery(errs[1.0], errs[0.0], errs[f]), 1) for f in (0.05, 0.10, 0.25)},
+                              "selector_ablation_at_0.05": {n: {"rel_err": round(e, 5), "recovery_pct": round(100 * metrics.recovery(errs[1.0], errs[0.0], e), 1)}
+                                                            for n, e in abl.items()}}
+        log(f"rel. errors {errs}; recovery {result['recovery']['recovery_pct']}; ablation at 5 % {result['recovery']['selector_ablation_at_0.05']}")
 
     del plan, q, k, v
     torch.cuda.empty_cache()

@@ -2,10 +2,11 @@
  * thrift.h — C ABI of the MI355X (gfx950) library for block-selective mixed-precision attention
  * (ThriftAttention, arXiv 2605.23081).
  *
- * The five compute entry points are the steps of the paper's Algorithm 1:
+ * The compute entry points are the steps of the paper's Algorithm 1:
  *   thrift_block_means      Alg. 1 step 3   (Sec. 3.2 "Block-importance scoring")
  *   thrift_select_topk      Alg. 1 step 5   (Sec. 3.2, TopK of  Qbar_i . Kbar_j ; causal restriction
  *                                            of the last paragraph of Sec. 3.2)
+ *   thrift_select_ablation  App. A: random / diagonal selectors in place of the heuristic
  *   thrift_quantize_mxfp4   Alg. 1 step 2   (Sec. 3.2 "FP4 quantisation", in MXFP4: E2M1 elements with
  *                                            one E8M0 scale per 32 elements instead of NVFP4)
  *   thrift_attn_prefill     Alg. 1 steps 4-23 (Sec. 3.2 "Mixed-precision attention computation", Sec. 3.3)
@@ -98,6 +99,21 @@ thrift_status thrift_block_means(const void* x, thrift_dtype dt, int B, int H, i
 thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
                                  int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
                                  int32_t* idx, int32_t* cnt, int kmax, void* stream);
+
+/*
+ * Ablation selectors (App. A "Heuristic Ablation": randomly promoted blocks, diagonal-only selection).
+ * Same outputs, budget rule and visibility as thrift_select_topk, but the k_i blocks of a row are
+ *   THRIFT_SELECT_RANDOM    a uniformly random k_i-subset of the visible blocks: the blocks with the k_i
+ *                           largest 64-bit keys, key(row, j) = output number (row * 2^32 + j) + 1 of the
+ *                           SplitMix64 generator seeded with `seed`, row = (b*Hq + h)*Tq + i; equal keys
+ *                           go to the smaller block id;
+ *   THRIFT_SELECT_DIAGONAL  the k_i visible blocks closest to the causal diagonal (the largest ids).
+ * The result feeds thrift_attn_prefill like any other selection.  Unknown selector: THRIFT_ERR_SHAPE.
+ */
+typedef enum { THRIFT_SELECT_RANDOM = 1, THRIFT_SELECT_DIAGONAL = 2 } thrift_selector;
+thrift_status thrift_select_ablation(int selector, uint64_t seed, int B, int Hq, int Tq, int Tk, int Bq, int Bk,
+                                     int causal, double budget, int fixed_k, int q_block_offset,
+                                     int32_t* idx, int32_t* cnt, int kmax, void* stream);
 
 /*
  * MXFP4 quantisation (Sec. 3.2 "FP4 quantisation"; Alg. 1 step 2).

@@ -20,7 +20,7 @@ _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 
 EXPORTS = (
     "thrift_status_string", "thrift_row_budget", "thrift_visible_blocks", "thrift_budget_to_global_k",
-    "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_quantize_mxfp4",
+    "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_select_ablation", "thrift_quantize_mxfp4",
     "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_decode_workspace", "thrift_attn_decode",
 )
 
@@ -49,6 +49,7 @@ def lib() -> C.CDLL:
         L.thrift_select_kmax.argtypes = [i, i, i, i, i, d, i, i]
         L.thrift_block_means.argtypes = [p, i, i, i, i, i, i, p, p]
         L.thrift_select_topk.argtypes = [p, p, i, i, i, i, i, i, i, i, i, d, i, i, p, p, i, p]
+        L.thrift_select_ablation.argtypes = [i, C.c_uint64, i, i, i, i, i, i, i, d, i, i, p, p, i, p]
         L.thrift_quantize_mxfp4.argtypes = [p, i, i, i, i, i, i, p, p, p]
         L.thrift_attn_prefill_workspace.restype = sz
         L.thrift_attn_prefill_workspace.argtypes = [i] * 8
@@ -132,6 +133,25 @@ def thrift_select_topk(qmean: torch.Tensor, kmean: torch.Tensor, Bq: int, Bk: in
     return idx, cnt
 
 
+SELECT_RANDOM, SELECT_DIAGONAL = 1, 2
+
+
+def thrift_select_ablation(selector: int, seed: int, B: int, Hq: int, Tq: int, Tk: int, Bq: int, Bk: int, causal: bool,
+                           budget: float, fixed_k: int = -1, q_block_offset: int = 0, kmax: Optional[int] = None,
+                           device=None, idx: Optional[torch.Tensor] = None, cnt: Optional[torch.Tensor] = None
+                           ) -> Tuple[torch.Tensor, torch.Tensor]:
+    device = torch.device("cuda", torch.cuda.current_device()) if device is None else device
+    if kmax is None:
+        kmax = max(1, select_kmax(Tq, Tk, Bq, Bk, causal, budget, fixed_k, q_block_offset))
+    if idx is None:
+        idx = torch.empty(B, Hq, Tq, kmax, dtype=torch.int32, device=device)
+        cnt = torch.empty(B, Hq, Tq, dtype=torch.int32, device=device)
+    _check(lib().thrift_select_ablation(int(selector), int(seed) & (2 ** 64 - 1), B, Hq, Tq, Tk, Bq, Bk, int(causal), float(budget),
+                                        int(fixed_k), int(q_block_offset), _ptr(idx), _ptr(cnt), int(kmax), _stream()),
+           "thrift_select_ablation")
+    return idx, cnt
+
+
 def thrift_quantize_mxfp4(x: torch.Tensor, axis: int, codes: Optional[torch.Tensor] = None,
                           scales: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     _dev(x)
@@ -202,8 +222,10 @@ def thrift_attn_decode(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budget: floa
 class PrefillPlan:
     """Buffers of one prefill problem, allocated once so that repeated steps do not allocate."""
 
-    def __init__(self, B, Hq, Hkv, N, D, Bq, Bk, causal, budget, dtype, device, fixed_k=-1, out_dtype=None):
+    def __init__(self, B, Hq, Hkv, N, D, Bq, Bk, causal, budget, dtype, device, fixed_k=-1, out_dtype=None,
+                 selector: int = 0, seed: int = 0):
         self.args = (B, Hq, Hkv, N, D, Bq, Bk, causal, budget, fixed_k)
+        self.selector, self.seed = selector, seed           # 0: the paper's heuristic; else an App. A ablation selector
         dev = device
         u8, f32, i32 = torch.uint8, torch.float32, torch.int32
         self.qmean = torch.empty(B, Hq, N // Bq, D, dtype=f32, device=dev)
@@ -224,7 +246,11 @@ class PrefillPlan:
         if prepass:
             thrift_block_means(q, Bq, out=self.qmean)
             thrift_block_means(k, Bk, out=self.kmean)
-            thrift_select_topk(self.qmean, self.kmean, Bq, Bk, causal, budget, fixed_k, kmax=self.kmax, idx=self.idx, cnt=self.cnt)
+            if self.selector == 0:
+                thrift_select_topk(self.qmean, self.kmean, Bq, Bk, causal, budget, fixed_k, kmax=self.kmax, idx=self.idx, cnt=self.cnt)
+            else:
+                thrift_select_ablation(self.selector, self.seed, B, Hq, N // Bq, N // Bk, Bq, Bk, causal, budget, fixed_k,
+                                       kmax=self.kmax, idx=self.idx, cnt=self.cnt)
             thrift_quantize_mxfp4(q, 0, self.q4, self.qs)
             thrift_quantize_mxfp4(k, 0, self.k4, self.ks)
             thrift_quantize_mxfp4(v, 1, self.v4, self.vs)

@@ -145,6 +145,28 @@ thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, 
   a.qmean = qmean; a.kmean = kmean; a.idx = idx; a.cnt = cnt;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Tq = Tq; a.Tk = Tk; a.Bq = Bq; a.Bk = Bk; a.causal = causal ? 1 : 0;
   a.fixed_k = fixed_k; a.q_block_offset = q_block_offset; a.kmax = kmax; a.ppm = fixed_k >= 0 ? 0 : budget_ppm(budget);
+  a.selector = 0; a.seed = 0;
+  launch_select_topk(a, (hipStream_t)stream);
+  return after_launch();
+}
+
+thrift_status thrift_select_ablation(int selector, uint64_t seed, int B, int Hq, int Tq, int Tk, int Bq, int Bk,
+                                     int causal, double budget, int fixed_k, int q_block_offset,
+                                     int32_t* idx, int32_t* cnt, int kmax, void* stream) {
+  if (!idx || !cnt) return THRIFT_ERR_NULL;
+  if (selector != THRIFT_SELECT_RANDOM && selector != THRIFT_SELECT_DIAGONAL) return THRIFT_ERR_SHAPE;
+  if (B <= 0 || Hq <= 0 || Tq <= 0 || Tk <= 0 || Tk > kMaxKeyBlocks || Bq <= 0 || Bk <= 0 || q_block_offset < 0 || kmax <= 0)
+    return THRIFT_ERR_SHAPE;
+  if ((long)B * Hq * Tq > 0x7fffffffL) return THRIFT_ERR_SHAPE;    // the row index is the high word of the random counter
+  if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
+  if (kmax < thrift_select_kmax(Tq, Tk, Bq, Bk, causal, budget, fixed_k, q_block_offset)) return THRIFT_ERR_BUDGET;
+  if ((long)B * Hq * (((long)Tq + 3) / 4) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (thrift_status s = check_arch()) return s;
+  SelectArgs a;
+  a.qmean = nullptr; a.kmean = nullptr; a.idx = idx; a.cnt = cnt;
+  a.B = B; a.Hq = Hq; a.Hkv = Hq; a.Tq = Tq; a.Tk = Tk; a.Bq = Bq; a.Bk = Bk; a.causal = causal ? 1 : 0;   // no KV heads involved: one row group per head
+  a.fixed_k = fixed_k; a.q_block_offset = q_block_offset; a.kmax = kmax; a.ppm = fixed_k >= 0 ? 0 : budget_ppm(budget);
+  a.selector = selector; a.seed = seed;
   launch_select_topk(a, (hipStream_t)stream);
   return after_launch();
 }

@@ -18,6 +18,8 @@ struct SelectArgs {
   int32_t* cnt;
   int B, Hq, Hkv, Tq, Tk, Bq, Bk, causal, fixed_k, q_block_offset, kmax;
   long long ppm;                // budget in millionths
+  int selector;                 // 0: TopK of the mean scores; 1: random keys; 2: largest block ids
+  unsigned long long seed;      // random selector only
 };
 void launch_select_topk(const SelectArgs& a, hipStream_t st);
 

@@ -189,6 +189,14 @@ __device__ __forceinline__ uint64_t order_key(double s) {
   return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);   // larger double <=> larger key
 }
 
+// Output number n of the SplitMix64 generator seeded with `seed` (Steele, Lea, Flood 2014).
+__device__ __forceinline__ uint64_t splitmix64_output(uint64_t seed, uint64_t n) {
+  uint64_t z = seed + n * 0x9e3779b97f4a7c15ULL;
+  z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ULL;
+  z = (z ^ (z >> 27)) * 0x94d049bb133111ebULL;
+  return z ^ (z >> 31);
+}
+
 template <int MAXC>
 __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
   constexpr int kStride = kD + 4;                       // padded fp32 row of a staged key mean
@@ -212,7 +220,7 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
   const int vis_max = min(cap, visible_blocks_dev(last_row / G, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset));
   const size_t rowid = ((size_t)b * p.Hq + hq) * p.Tq + i;
 
-  if (active) {
+  if (active && p.selector == 0) {
     const float* qm = p.qmean + rowid * kD;
     qst[wave][lane] = qm[lane];
     qst[wave][lane + 64] = qm[lane + 64];
@@ -223,7 +231,12 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
 #pragma unroll
   for (int c = 0; c < MAXC; ++c) {
     key[c] = 0;
-    if (c * 64 < vis_max) {                              // uniform over the workgroup
+    if (p.selector != 0) {
+      // Ablation selectors (App. A): the same k-th-largest search over other keys.  Random: output
+      // number n+1 of the SplitMix64 stream of `seed`, n = rowid * 2^32 + j; diagonal: the block id.
+      const int j = c * 64 + lane;
+      if (j < vis) key[c] = p.selector == 1 ? splitmix64_output(p.seed, (((uint64_t)rowid << 32) | (uint64_t)j) + 1ULL) : (uint64_t)j + 1ULL;
+    } else if (c * 64 < vis_max) {                       // uniform over the workgroup
       __syncthreads();
       // stage 64 key means (rows beyond Tk are not read)
 #pragma unroll

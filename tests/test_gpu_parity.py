@@ -350,3 +350,51 @@ def test_decode_is_deterministic_and_keeps_guards(T, oracle):
     torch.cuda.synchronize()
     assert torch.equal(a, b)
     assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + n:] == 777.0)
+
+
+# ------------------------------------------------------------------ App. A ablation selectors
+@pytest.mark.parametrize("selector", [1, 2])
+def test_select_ablation_bit_exact(T, oracle, selector):
+    cases = [  # B, Hq, Tq, Tk, Bq, Bk, causal, budget, fixed_k, offset
+        (1, 1, 32, 32, 64, 64, True, 0.05, -1, 0),
+        (2, 3, 16, 32, 128, 64, True, 0.25, -1, 0),
+        (1, 2, 9, 80, 64, 64, False, 0.1, -1, 0),          # two 64-block chunks, ragged
+        (1, 2, 5, 40, 64, 64, True, 0.0, 7, 3),            # fixed k, shifted causal frontier
+        (1, 1, 4, 12, 64, 64, True, 0.0, -1, 0),           # empty budget
+        (1, 1, 1, 2048, 1, 64, True, 0.05, -1, 131071),    # decode-shaped row over 2048 blocks
+    ]
+    for (B, Hq, Tq, Tk, Bq, Bk, causal, budget, fixed_k, off) in cases:
+        _say(f"ablation selector {selector}: B={B} Hq={Hq} Tq={Tq} Tk={Tk} Bq={Bq} causal={causal} f={budget} k={fixed_k} off={off}")
+        for seed in (0, 0x9e3779b97f4a7c15, 2 ** 64 - 1):
+            idx_r, cnt_r = oracle.select_ablation(selector, seed, B, Hq, Tq, Tk, Bq, Bk, causal, budget, fixed_k, off)
+            idx_g, cnt_g = T.thrift_select_ablation(selector, seed, B, Hq, Tq, Tk, Bq, Bk, causal, budget, fixed_k, off)
+            torch.cuda.synchronize()
+            assert np.array_equal(to_np(cnt_g), cnt_r)
+            assert np.array_equal(to_np(idx_g)[..., :idx_r.shape[-1]], idx_r) and np.all(to_np(idx_g)[..., idx_r.shape[-1]:] == -1)
+            if selector == 2:
+                break                                       # the seed plays no part
+
+
+def test_select_ablation_guards_and_prefill(T, oracle):
+    _say("ablation selector guards; random selection through the fused kernel")
+    with pytest.raises(T.ThriftError) as e:
+        T.thrift_select_ablation(3, 0, 1, 1, 4, 4, 64, 64, True, 0.5)
+    assert e.value.code == 2
+    with pytest.raises(T.ThriftError) as e:
+        T.thrift_select_ablation(1, 0, 1, 1, 4, 4, 64, 64, True, 1.5)
+    assert e.value.code == 4
+    wl = _small_bf16(N=1024)
+    Tq, Tk = wl.N // wl.Bq, wl.N // wl.Bk
+    sel = oracle.select_ablation(1, 11, wl.B, wl.Hq, Tq, Tk, wl.Bq, wl.Bk, True, 0.25)
+    got, want, _, _ = _prefill_both(T, oracle, wl, 0.25, force_sel=sel)
+    err = np.abs(got - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert err <= TOLMIX
+    # the plan object with the selector switched on reproduces the same selection on the GPU
+    q, k, v, _, _ = W.make_prefill(wl)
+    plan = T.PrefillPlan(wl.B, wl.Hq, wl.Hkv, wl.N, wl.D, wl.Bq, wl.Bk, True, 0.25, q.dtype, torch.device("cuda"),
+                         out_dtype=torch.float32, selector=1, seed=11)
+    out = plan.run(q.cuda(), k.cuda(), v.cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(plan.idx)[..., :sel[0].shape[-1]], sel[0]) and np.array_equal(to_np(plan.cnt), sel[1])
+    assert np.abs(to_np(out) - want).max() <= TOLMIX
