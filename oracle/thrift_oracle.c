@@ -504,14 +504,18 @@ static void head_quant_dequant(const uint16_t* x, int dtype, int N, int D, int a
  * (the kernel order Sec. 3.3 describes).  quantize_p 0 disables step 19's P quantisation (test aid).
  * force_path: -1 use idx; 0 all tiles on the 4-bit path; 1 all tiles on the 16-bit path.
  */
-int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
-                               const int32_t* idx, const int32_t* cnt, int kmax,
-                               int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, double scale,
-                               int tile_order, int quantize_p, int force_path,
-                               const int32_t* units, int n_units, double* out, double* lse) {
+/* General form (chunked prefill): q holds Nq query tokens per head, [B,Hq,Nq,D]; k, v hold N key
+ * tokens.  Query block i stands at block position i + q_block_offset of the sequence (its first
+ * token at position (i + q_block_offset)*Bq), which matters only for the causal mask and the
+ * visible range; idx / cnt / units are indexed by the chunk's own block number i < Nq/Bq. */
+int oracle_attn_thrift_prefill_chunk(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
+                                     const int32_t* idx, const int32_t* cnt, int kmax,
+                                     int B, int Hq, int Hkv, int Nq, int q_block_offset, int N, int D, int Bq, int Bk,
+                                     int causal, double scale, int tile_order, int quantize_p, int force_path,
+                                     const int32_t* units, int n_units, double* out, double* lse) {
   (void)B;
   if (Bk > 256 || Bk % 32 || D % 32) return -1;
-  int grp = Hq / Hkv, Tq = N / Bq, Tk = N / Bk;
+  int grp = Hq / Hkv, Tq = Nq / Bq, Tk = N / Bk;
   /* group the work by kv head so that each head's K/V is converted once */
   for (int b0 = 0; b0 < B; ++b0)
     for (int g = 0; g < Hkv; ++g) {
@@ -534,7 +538,7 @@ int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint1
       for (int u = 0; u < n_units; ++u) {
         int b = units[3 * u], h = units[3 * u + 1], i = units[3 * u + 2];
         if (b != b0 || h / grp != g) continue;
-        const uint16_t* qb = q + (((long)b * Hq + h) * N + (long)i * Bq) * D;
+        const uint16_t* qb = q + (((long)b * Hq + h) * Nq + (long)i * Bq) * D;
         double* qh = (double*)malloc(sizeof(double) * (size_t)Bq * D);
         double* qq = (double*)malloc(sizeof(double) * (size_t)Bq * D);
         head_to_double(qb, dtype, (long)Bq * D, qh);
@@ -542,7 +546,7 @@ int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint1
         long rowid = ((long)b * Hq + h) * Tq + i;
         const int32_t* sel = idx ? idx + rowid * kmax : NULL;
         int nsel = cnt ? cnt[rowid] : 0;
-        int vis = oracle_visible_blocks(i, Tk, Bq, Bk, causal, 0);
+        int vis = oracle_visible_blocks(i, Tk, Bq, Bk, causal, q_block_offset);
         int* order = (int*)malloc(sizeof(int) * (size_t)(vis > 0 ? vis : 1));
         int* path = (int*)malloc(sizeof(int) * (size_t)(vis > 0 ? vis : 1));
         int no = 0;
@@ -556,7 +560,7 @@ int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint1
           double m = -INFINITY, l = 0.0;
           double* O = out + ((long)u * Bq + r) * D;
           for (int x = 0; x < D; ++x) O[x] = 0.0;
-          long qpos = (long)i * Bq + r;
+          long qpos = ((long)i + q_block_offset) * Bq + r;
           for (int t = 0; t < no; ++t) {
             int j = order[t];
             int n_valid = Bk;
@@ -574,6 +578,15 @@ int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint1
       free(kh); free(vh); free(kq); free(vq);
     }
   return 0;
+}
+
+int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
+                               const int32_t* idx, const int32_t* cnt, int kmax,
+                               int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, double scale,
+                               int tile_order, int quantize_p, int force_path,
+                               const int32_t* units, int n_units, double* out, double* lse) {
+  return oracle_attn_thrift_prefill_chunk(q, k, v, dtype, idx, cnt, kmax, B, Hq, Hkv, N, 0, N, D, Bq, Bk, causal, scale,
+                                          tile_order, quantize_p, force_path, units, n_units, out, lse);
 }
 
 /*

@@ -193,11 +193,14 @@ def attn_exact(q, k, v, dtype: int, causal: bool, scale: float, rows: np.ndarray
 
 def attn_thrift_prefill(q, k, v, dtype: int, idx, cnt, Bq: int, Bk: int, causal: bool, scale: float,
                         units: np.ndarray, tile_order: int = 0, quantize_p: bool = True, force_path: int = -1,
-                        want_lse: bool = False):
-    """units: [n,3] int32 (b, h, i).  -> out [n, Bq, D] fp64 (and lse [n, Bq])."""
+                        want_lse: bool = False, q_block_offset: int = 0):
+    """units: [n,3] int32 (b, h, i).  -> out [n, Bq, D] fp64 (and lse [n, Bq]).
+
+    q may hold fewer tokens than k, v (chunked prefill): query block i then stands at block position
+    i + q_block_offset of the sequence."""
     q, k, v = _u16(q), _u16(k), _u16(v)
-    B, Hq, N, D = q.shape
-    Hkv = k.shape[1]
+    B, Hq, Nq, D = q.shape
+    Hkv, N = k.shape[1], k.shape[2]
     units = np.ascontiguousarray(units, np.int32).reshape(-1, 3)
     kmax = 0
     if idx is not None:
@@ -206,9 +209,10 @@ def attn_thrift_prefill(q, k, v, dtype: int, idx, cnt, Bq: int, Bk: int, causal:
         kmax = idx.shape[-1]
     out = np.empty((units.shape[0], Bq, D), np.float64)
     lse = np.empty((units.shape[0], Bq), np.float64) if want_lse else None
-    rc = lib().oracle_attn_thrift_prefill(_p(q), _p(k), _p(v), dtype, _p(idx), _p(cnt), kmax, B, Hq, Hkv, N, D, Bq, Bk,
-                                          int(causal), C.c_double(scale), int(tile_order), int(quantize_p),
-                                          int(force_path), _p(units), units.shape[0], _p(out), _p(lse))
+    rc = lib().oracle_attn_thrift_prefill_chunk(_p(q), _p(k), _p(v), dtype, _p(idx), _p(cnt), kmax, B, Hq, Hkv, Nq,
+                                                int(q_block_offset), N, D, Bq, Bk,
+                                                int(causal), C.c_double(scale), int(tile_order), int(quantize_p),
+                                                int(force_path), _p(units), units.shape[0], _p(out), _p(lse))
     if rc != 0:
         raise ValueError("unsupported shape")
     return (out, lse) if want_lse else out

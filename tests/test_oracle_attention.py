@@ -317,3 +317,44 @@ def test_error_bound_diagnostic_bookkeeping(oracle):
     assert total > 0 and np.all(per >= 0)
     assert abs(per.sum() - total) < 1e-12 * max(1, total)
     assert np.all(per[21:] == 0) and per[20] > 0
+
+
+@pytest.mark.parametrize("dtype,Bq,nq_blocks", [("f16", 64, 3), ("bf16", 128, 1)])
+def test_chunked_prefill_pins(oracle, dtype, Bq, nq_blocks):
+    """Chunked prefill (the last Nq queries of a longer sequence):
+    (a) at 100 % budget it is exact attention with the queries at their shifted positions (the textbook routine,
+        up to the rounding of P); with P quantisation off and all tiles on the 4-bit path it is exact attention
+        on the dequantised tensors at those positions (numpy brute force);
+    (b) rows of a chunk equal the same rows of the full prefill given the same selected sets."""
+    w, q, k, v = _small(dtype, N=512, Bq=Bq)
+    Nq = nq_blocks * Bq
+    off = (w.N - Nq) // Bq
+    scale = 1 / math.sqrt(w.D)
+    qc = q[:, :, w.N - Nq:, :].contiguous()
+    qb, dt = oracle.bits_of(q); qcb, _ = oracle.bits_of(qc); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    units_c = _all_units(1, w.Hq, nq_blocks)
+    # (a) 100 %: against exact attention at shifted positions
+    exact = oracle.attn_exact(qcb, kb, vb, dt, True, scale, _all_rows(1, w.Hq, Nq), q_pos0=w.N - Nq).reshape(w.Hq, Nq, w.D)
+    full16 = oracle.attn_thrift_prefill(qcb, kb, vb, dt, None, None, Bq, 64, True, scale, units_c, force_path=1,
+                                        q_block_offset=off).reshape(w.Hq, Nq, w.D)
+    assert np.abs(full16 - exact).max() < (2e-3 if dtype == "f16" else 8e-3)
+    # (a') 4-bit path, P not quantised: numpy attention on the dequantised tensors
+    c, s = oracle.quantize_mxfp4(qcb, dt, 0); qd = oracle.dequantize_mxfp4(c, s, 0)
+    c, s = oracle.quantize_mxfp4(kb, dt, 0); kd = oracle.dequantize_mxfp4(c, s, 0)
+    c, s = oracle.quantize_mxfp4(vb, dt, 1); vd = oracle.dequantize_mxfp4(c, s, 1)
+    got = oracle.attn_thrift_prefill(qcb, kb, vb, dt, None, None, Bq, 64, True, scale, units_c, force_path=0, quantize_p=False,
+                                     q_block_offset=off).reshape(w.Hq, Nq, w.D)
+    for h in range(w.Hq):
+        want = _softmax_attention_np(qd[0, h], kd[0, 0], vd[0, 0], True, scale, q_pos0=w.N - Nq)
+        assert np.abs(got[h] - want).max() < 1e-10
+    # (b) mixed: chunk rows == full-prefill rows for the same sets
+    qm = oracle.block_means(qb, dt, Bq); km = oracle.block_means(kb, dt, 64)
+    idx, cnt = oracle.select_topk(qm, km, Bq, 64, True, 0.25)
+    Tq = w.N // Bq
+    full = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, Bq, 64, True, scale, _all_units(1, w.Hq, Tq)).reshape(w.Hq, Tq, Bq, w.D)
+    chunk = oracle.attn_thrift_prefill(qcb, kb, vb, dt, idx[:, :, off:], cnt[:, :, off:], Bq, 64, True, scale, units_c,
+                                       q_block_offset=off).reshape(w.Hq, nq_blocks, Bq, w.D)
+    assert np.array_equal(chunk, full[:, off:])
+    # selection with the same offset reproduces the tail rows of the full selection
+    idx_c, cnt_c = oracle.select_topk(qm[:, :, off:], km, Bq, 64, True, 0.25, q_block_offset=off, kmax=idx.shape[-1])
+    assert np.array_equal(idx_c, idx[:, :, off:]) and np.array_equal(cnt_c, cnt[:, :, off:])
