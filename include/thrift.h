@@ -10,6 +10,7 @@
  *   thrift_quantize_mxfp4   Alg. 1 step 2   (Sec. 3.2 "FP4 quantisation", in MXFP4: E2M1 elements with
  *                                            one E8M0 scale per 32 elements instead of NVFP4)
  *   thrift_attn_prefill     Alg. 1 steps 4-23 (Sec. 3.2 "Mixed-precision attention computation", Sec. 3.3)
+ *   thrift_attn_prefill_chunk  the same kernel for a chunk of queries against a longer key range
  *   thrift_attn_decode      the same algorithm for one query token over a dual 4-bit / 16-bit KV
  *                           cache (Sec. 4.1, last sentences; Sec. 5), evaluated split-K
  *
@@ -152,6 +153,26 @@ thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, t
                                   int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, float softmax_scale,
                                   void* out, thrift_dtype out_dt, float* lse,
                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Chunked prefill: the same kernel for Nq query tokens per head against Nkv >= Nq key tokens, as needed
+ * when a prompt is processed in pieces or extends a cached prefix (Alg. 1 is stated for Q and K, V of any
+ * lengths; the causal restriction is the last paragraph of Sec. 3.2).  Query block i of the chunk stands
+ * at block position i + q_block_offset of the sequence: its first token is token (i + q_block_offset)*Bq,
+ * which fixes its causal mask and visible key range; with causal == 0 the offset is ignored.
+ *   q, q4, qs, out, lse   hold Nq tokens per head ([B,Hq,Nq,...]);  k, v, k4, ks, v4, vs hold Nkv
+ *   idx [B,Hq,Nq/Bq,kmax], cnt [B,Hq,Nq/Bq]: from thrift_select_topk with the same q_block_offset
+ *   Nq % Bq == 0, Nkv % Bk == 0; causal: (q_block_offset*Bq + Nq) <= Nkv, else THRIFT_ERR_SHAPE
+ * thrift_attn_prefill is this call with Nq = Nkv = N and q_block_offset = 0.
+ */
+thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void* v, thrift_dtype dt,
+                                        const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
+                                        const uint8_t* v4, const uint8_t* vs,
+                                        const int32_t* idx, const int32_t* cnt, int kmax,
+                                        int B, int Hq, int Hkv, int Nq, int q_block_offset, int Nkv, int D, int Bq, int Bk,
+                                        int causal, float softmax_scale,
+                                        void* out, thrift_dtype out_dt, float* lse,
+                                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* Host: bytes of workspace thrift_attn_decode needs. */
 size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int Bk, int split_blocks);

@@ -187,6 +187,35 @@ thrift_status thrift_quantize_mxfp4(const void* x, thrift_dtype dt, int B, int H
 
 size_t thrift_attn_prefill_workspace(int, int, int, int, int, int, int, int) { return 0; }
 
+thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void* v, thrift_dtype dt,
+                                        const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
+                                        const uint8_t* v4, const uint8_t* vs,
+                                        const int32_t* idx, const int32_t* cnt, int kmax,
+                                        int B, int Hq, int Hkv, int Nq, int q_block_offset, int Nkv, int D, int Bq, int Bk,
+                                        int causal, float softmax_scale,
+                                        void* out, thrift_dtype out_dt, float* lse,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (!q || !k || !v || !q4 || !qs || !k4 || !ks || !v4 || !vs || !idx || !cnt || !out) return THRIFT_ERR_NULL;
+  if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Nq <= 0 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock ||
+      (Bq != 64 && Bq != 128) || Nq % Bq != 0 || Nkv % Bk != 0 || kmax <= 0 || Nkv / Bk > kMaxKeyBlocks || q_block_offset < 0)
+    return THRIFT_ERR_SHAPE;
+  // causal: the chunk must lie inside the sequence (its last query at or before the last key)
+  if (causal && ((long)q_block_offset * Bq + Nq > (long)Nkv)) return THRIFT_ERR_SHAPE;
+  if ((long)B * Hq * (Nq / Bq) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (thrift_status s = check_arch()) return s;
+  PrefillArgs a;
+  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
+  a.q4 = q4; a.qs = qs; a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.idx = idx; a.cnt = cnt;
+  a.out = out; a.lse = lse; a.kmax = kmax; a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.N = Nkv; a.Bq = Bq; a.causal = causal ? 1 : 0;
+  a.Nq = Nq; a.q_off = causal ? q_block_offset : 0;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
+  a.dt = dt; a.out_dt = out_dt;
+  launch_prefill(a, (hipStream_t)stream);
+  return after_launch();
+}
+
 thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, thrift_dtype dt,
                                   const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
                                   const uint8_t* v4, const uint8_t* vs,
@@ -194,22 +223,9 @@ thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, t
                                   int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, float softmax_scale,
                                   void* out, thrift_dtype out_dt, float* lse,
                                   void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace; (void)workspace_bytes;
-  if (!q || !k || !v || !q4 || !qs || !k4 || !ks || !v4 || !vs || !idx || !cnt || !out) return THRIFT_ERR_NULL;
-  if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
-  if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || N <= 0 || D != kHeadDim || Bk != kKeyBlock ||
-      (Bq != 64 && Bq != 128) || N % Bq != 0 || N % Bk != 0 || kmax <= 0 || N / Bk > kMaxKeyBlocks)
-    return THRIFT_ERR_SHAPE;
-  if ((long)B * Hq * (N / Bq) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
-  if (thrift_status s = check_arch()) return s;
-  PrefillArgs a;
-  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
-  a.q4 = q4; a.qs = qs; a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.idx = idx; a.cnt = cnt;
-  a.out = out; a.lse = lse; a.kmax = kmax; a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.N = N; a.Bq = Bq; a.causal = causal ? 1 : 0;
-  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
-  a.dt = dt; a.out_dt = out_dt;
-  launch_prefill(a, (hipStream_t)stream);
-  return after_launch();
+  if (N > 0 && Bq > 0 && N % Bq != 0) return THRIFT_ERR_SHAPE;
+  return thrift_attn_prefill_chunk(q, k, v, dt, q4, qs, k4, ks, v4, vs, idx, cnt, kmax, B, Hq, Hkv, N, 0, N, D, Bq, Bk, causal,
+                                   softmax_scale, out, out_dt, lse, workspace, workspace_bytes, stream);
 }
 
 size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int Bk, int split_blocks) {

@@ -37,7 +37,8 @@ struct PrefillArgs {
   const int32_t* cnt;
   void* out;
   float* lse;
-  int kmax, B, Hq, Hkv, N, Bq, causal;
+  int kmax, B, Hq, Hkv, N, Bq, causal;   // N: key tokens per head
+  int Nq, q_off;                          // query tokens per head; block position of query block 0 in the sequence
   float scale;            // softmax scale (already defaulted)
   thrift_dtype dt, out_dt;
 };

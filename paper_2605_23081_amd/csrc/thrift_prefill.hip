@@ -62,7 +62,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
-  const int N = a.N, Bq = NW * 32, Tq = N / Bq, Tk = N / kBk, G = a.Hq / a.Hkv;
+  const int N = a.N, Nq = a.Nq, Bq = NW * 32, Tq = Nq / Bq, Tk = N / kBk, G = a.Hq / a.Hkv;
 
   // ---- work item: heavy (late) query blocks first; KV heads spread over the 8 XCDs so that the query
   // heads and neighbouring query blocks that share a KV head also share an L2 ----
@@ -80,8 +80,8 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   const int i = Tq - 1 - within / G;
   const int hq = kvh * G + within % G;
   const size_t qh = (size_t)b * a.Hq + hq, kh = (size_t)b * a.Hkv + kvh;
-  const int q0 = i * Bq + wave * 32;                    // first query row of this wavefront
-  const size_t qrow = qh * N + q0 + r;
+  const int q0 = (i + a.q_off) * Bq + wave * 32;        // sequence position of this wavefront's first query row
+  const size_t qrow = qh * Nq + i * Bq + wave * 32 + r;
 
   // ---- Q fragments ----
   v4i qf4[2];
@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   const uint32_t qsc = *reinterpret_cast<const uint32_t*>(a.qs + qrow * 4) >> (8 * half);
   const uint16_t* q16row = a.q + qrow * kD;
 
-  const int vis = a.causal ? min(Tk, ((i + 1) * Bq - 1) / kBk + 1) : Tk;
+  const int vis = a.causal ? min(Tk, ((i + a.q_off + 1) * Bq - 1) / kBk + 1) : Tk;
   const int32_t* sel = a.idx + (qh * Tq + i) * a.kmax;
   const int nsel = a.cnt[qh * Tq + i];
   // the next two promoted block ids at or after the current block (ascending list)
@@ -307,7 +307,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
 }
 
 void launch_prefill(const PrefillArgs& a, hipStream_t st) {
-  const unsigned grid = (unsigned)((long)a.B * a.Hq * (a.N / a.Bq));
+  const unsigned grid = (unsigned)((long)a.B * a.Hq * (a.Nq / a.Bq));
   if (a.Bq == 128) {
     if (a.dt == THRIFT_F16) prefill_kernel<F16, 4><<<dim3(grid), dim3(256), 0, st>>>(a);
     else prefill_kernel<BF16, 4><<<dim3(grid), dim3(256), 0, st>>>(a);

@@ -398,3 +398,66 @@ def test_select_ablation_guards_and_prefill(T, oracle):
     torch.cuda.synchronize()
     assert np.array_equal(to_np(plan.idx)[..., :sel[0].shape[-1]], sel[0]) and np.array_equal(to_np(plan.cnt), sel[1])
     assert np.abs(to_np(out) - want).max() <= TOLMIX
+
+
+# ------------------------------------------------------------------ chunked prefill
+@pytest.mark.parametrize("wl,nq_blocks,budget,causal", [
+    (_small_bf16(N=2048), 3, 0.1, True),                       # three 128-row blocks at the end of 2048 keys
+    (_small_bf16(N=1024, Hq=2, Hkv=1, Bq=64), 5, 0.25, True),  # Bq = 64
+    (_small_bf16(N=1024), 1, 1.0, True),                       # one block, every tile on the 16-bit path
+    (_small_bf16(N=1024), 2, 0.0, True),                       # every tile on the 4-bit path
+    (W.TINY, 4, 0.05, False),                                  # non-causal: the offset plays no part
+])
+def test_prefill_chunk(T, oracle, wl, nq_blocks, budget, causal):
+    _say(f"chunked prefill {wl.name} N={wl.N} Bq={wl.Bq} chunk={nq_blocks} blocks f={budget} causal={causal}")
+    q, k, v, _, _ = W.make_prefill(wl)
+    Nq = nq_blocks * wl.Bq
+    off = (wl.N - Nq) // wl.Bq
+    qc = q[:, :, wl.N - Nq:, :].contiguous()
+    qcb, dt = oracle.bits_of(qc); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(wl.D)
+    qm = oracle.block_means(qcb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    idx, cnt = oracle.select_topk(qm, km, wl.Bq, wl.Bk, causal, budget, q_block_offset=off)
+    want = oracle.attn_thrift_prefill(qcb, kb, vb, dt, idx, cnt, wl.Bq, wl.Bk, causal, scale, _units(wl.B, wl.Hq, nq_blocks),
+                                      q_block_offset=off).reshape(wl.B, wl.Hq, Nq, wl.D)
+    qg, kg, vg = qc.cuda(), k.cuda(), v.cuda()
+    # the whole pre-pass on the GPU with the same offset
+    qm_g = T.thrift_block_means(qg, wl.Bq); km_g = T.thrift_block_means(kg, wl.Bk)
+    idx_g, cnt_g = T.thrift_select_topk(qm_g, km_g, wl.Bq, wl.Bk, causal, budget, q_block_offset=off)
+    assert np.array_equal(to_np(cnt_g), cnt) and np.array_equal(to_np(idx_g)[..., :idx.shape[-1]], idx)
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    got = T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, idx_g, cnt_g, wl.Bq, wl.Bk, causal, off,
+                                      out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    err = np.abs(to_np(got) - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert err <= (TOL16 if budget == 1.0 else TOLMIX)
+    if causal:
+        # the chunk's rows are the same rows of the full prefill, bit for bit, given the same sets
+        qf = q.cuda()
+        q4f, qsf = T.thrift_quantize_mxfp4(qf, 0)
+        Tq = wl.N // wl.Bq
+        idx_f = torch.full((wl.B, wl.Hq, Tq, idx_g.shape[-1]), -1, dtype=torch.int32, device="cuda")
+        cnt_f = torch.zeros((wl.B, wl.Hq, Tq), dtype=torch.int32, device="cuda")
+        idx_f[:, :, off:] = idx_g; cnt_f[:, :, off:] = cnt_g
+        full = T.thrift_attn_prefill(qf, kg, vg, q4f, qsf, k4, ks, v4, vs, idx_f, cnt_f, wl.Bq, wl.Bk, True, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(full[:, :, wl.N - Nq:], got)
+
+
+def test_prefill_chunk_guards(T):
+    _say("chunked prefill guards")
+    wl = _small_bf16(N=1024)
+    q, k, v, _, _ = W.make_prefill(wl)
+    qg, kg, vg = q[:, :, :256].contiguous().cuda(), k.cuda(), v.cuda()
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    idx = torch.full((wl.B, wl.Hq, 2, 1), -1, dtype=torch.int32, device="cuda"); cnt = torch.zeros((wl.B, wl.Hq, 2), dtype=torch.int32, device="cuda")
+    with pytest.raises(T.ThriftError) as e:     # the chunk would end after the last key
+        T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, idx, cnt, 128, 64, True, 7)
+    assert e.value.code == 2
+    with pytest.raises(T.ThriftError) as e:
+        T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, idx, cnt, 128, 64, True, -1)
+    assert e.value.code == 2
+    out = T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, idx, cnt, 128, 64, True, 6)   # the last two blocks: fine
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
