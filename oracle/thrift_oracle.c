@@ -220,6 +220,50 @@ int oracle_select_topk(const float* qmean, const float* kmean, int B, int Hq, in
   return rc;
 }
 
+/* Group-shared selection for grouped-query attention (an extension: the paper selects per head and
+ * does not discuss GQA).  One set T_i per (batch, KV head, query block), shared by the G = Hq/Hkv query
+ * heads of the group: the blocks with the largest summed score  sum_h Qbar_{h,i} . Kbar_j  (each head's
+ * score as in oracle_block_scores, added in ascending head order).  Same budget rule, visibility and
+ * tie rule; the set is written to every head of the group, so idx / cnt keep the per-head shape. */
+int oracle_select_topk_shared(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                              int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
+                              int32_t* idx, int32_t* cnt, int kmax) {
+  int grp = Hq / Hkv;
+  scored_t* row = (scored_t*)malloc(sizeof(scored_t) * (size_t)(Tk > 0 ? Tk : 1));
+  int* sel = (int*)malloc(sizeof(int) * (size_t)(Tk > 0 ? Tk : 1));
+  int rc = 0;
+  for (int b = 0; b < B; ++b)
+    for (int g = 0; g < Hkv; ++g)
+      for (int i = 0; i < Tq; ++i) {
+        int vis = oracle_visible_blocks(i, Tk, Bq, Bk, causal, q_block_offset);
+        int k = oracle_row_k(vis, budget, fixed_k);
+        for (int j = 0; j < vis; ++j) {
+          const float* km = kmean + (((long)b * Hkv + g) * Tk + j) * D;
+          double total = 0.0;
+          for (int hh = 0; hh < grp; ++hh) {
+            const float* qm = qmean + ((((long)b * Hq + g * grp + hh) * Tq) + i) * D;
+            double s = 0.0;
+            for (int c = 0; c < D; ++c) s += (double)qm[c] * (double)km[c];
+            total += s;
+          }
+          row[j].s = total;
+          row[j].j = j;
+        }
+        qsort(row, (size_t)vis, sizeof(scored_t), cmp_scored);
+        if (k > kmax) { rc = -1; k = kmax; }
+        for (int t = 0; t < k; ++t) sel[t] = row[t].j;
+        qsort(sel, (size_t)k, sizeof(int), cmp_int);
+        for (int hh = 0; hh < grp; ++hh) {
+          long rowid = ((long)b * Hq + g * grp + hh) * Tq + i;
+          for (int t = 0; t < kmax; ++t) idx[rowid * kmax + t] = t < k ? sel[t] : -1;
+          cnt[rowid] = k;
+        }
+      }
+  free(row);
+  free(sel);
+  return rc;
+}
+
 /* ------------------------------------------------------------------ */
 /* Ablation selectors  (App. A "Heuristic Ablation")                   */
 /* ------------------------------------------------------------------ */

@@ -110,7 +110,8 @@ def block_scores(qmean: np.ndarray, kmean: np.ndarray) -> np.ndarray:
 
 
 def select_topk(qmean: np.ndarray, kmean: np.ndarray, Bq: int, Bk: int, causal: bool, budget: float,
-                fixed_k: int = -1, q_block_offset: int = 0, kmax: Optional[int] = None):
+                fixed_k: int = -1, q_block_offset: int = 0, kmax: Optional[int] = None, group_shared: bool = False):
+    """group_shared: one set per (batch, KV head, query block) from the scores summed over the group's query heads."""
     qmean = np.ascontiguousarray(qmean, np.float32)
     kmean = np.ascontiguousarray(kmean, np.float32)
     B, Hq, Tq, D = qmean.shape
@@ -119,8 +120,9 @@ def select_topk(qmean: np.ndarray, kmean: np.ndarray, Bq: int, Bk: int, causal: 
         kmax = max(1, max(row_k(visible_blocks(i, Tk, Bq, Bk, causal, q_block_offset), budget, fixed_k) for i in range(Tq)))
     idx = np.empty((B, Hq, Tq, kmax), np.int32)
     cnt = np.empty((B, Hq, Tq), np.int32)
-    rc = lib().oracle_select_topk(_p(qmean), _p(kmean), B, Hq, Hkv, Tq, Tk, D, Bq, Bk, int(causal),
-                                  C.c_double(budget), int(fixed_k), int(q_block_offset), _p(idx), _p(cnt), kmax)
+    fn = lib().oracle_select_topk_shared if group_shared else lib().oracle_select_topk
+    rc = fn(_p(qmean), _p(kmean), B, Hq, Hkv, Tq, Tk, D, Bq, Bk, int(causal),
+            C.c_double(budget), int(fixed_k), int(q_block_offset), _p(idx), _p(cnt), kmax)
     if rc != 0:
         raise ValueError("kmax too small")
     return idx, cnt

@@ -204,3 +204,36 @@ def test_random_selector_is_uniform(oracle):
     # a single cell of a uniform 4-of-16 draw has variance n*p*(1-p); 15 degrees of freedom after the sum constraint
     chi2 = ((counts - expect) ** 2 / (expect * (1 - 4 / Tk))).sum()
     assert counts.sum() == 4 * n and chi2 < 45.0, chi2                     # P(chi2_15 > 45) < 1e-4
+
+
+# ---------------------------------------------------------------- group-shared selection (GQA extension)
+
+def test_group_shared_selection(oracle):
+    rng = np.random.default_rng(11)
+    B, Hq, Hkv, Tq, Tk, D = 2, 6, 2, 10, 20, 128
+    qm = rng.standard_normal((B, Hq, Tq, D)).astype(np.float32)
+    km = rng.standard_normal((B, Hkv, Tk, D)).astype(np.float32)
+    qm[0, 0, 3] = 0; qm[0, 1, 3] = 0; qm[0, 2, 3] = 0            # a row of all-equal (zero) group scores: ties by id
+    G = Hq // Hkv
+    idx, cnt = oracle.select_topk(qm, km, 128, 64, True, 0.3, group_shared=True)
+    per_head = oracle.block_scores(qm, km)                        # [B,Hq,Tq,Tk] fp64, pinned to numpy elsewhere
+    for b in range(B):
+        for g in range(Hkv):
+            total = per_head[b, g * G:(g + 1) * G].sum(axis=0)    # exact here: few terms, fp64
+            for i in range(Tq):
+                vis = min(Tk, 2 * (i + 1))
+                k = oracle.row_k(vis, 0.3)
+                order = np.lexsort((np.arange(vis), -total[i, :vis]))     # descending score, ascending id
+                want = sorted(order[:k].tolist())
+                for h in range(g * G, (g + 1) * G):
+                    assert cnt[b, h, i] == k and idx[b, h, i, :k].tolist() == want and (idx[b, h, i, k:] == -1).all()
+    assert idx[0, 0, 3, :cnt[0, 0, 3]].tolist() == list(range(cnt[0, 0, 3]))       # the tie row takes the smallest ids
+    # one head per group: identical to the per-head rule
+    a = oracle.select_topk(qm[:, :2], km, 128, 64, True, 0.3, group_shared=True)
+    b_ = oracle.select_topk(qm[:, :2], km, 128, 64, True, 0.3)
+    assert np.array_equal(a[0], b_[0]) and np.array_equal(a[1], b_[1])
+    # a summed score is the score of the summed query (linearity): same sets when the means are small integers (exact sums)
+    qi = rng.integers(-3, 4, (1, 4, 5, D)).astype(np.float32); ki = rng.integers(-3, 4, (1, 1, 12, D)).astype(np.float32)
+    s1 = oracle.select_topk(qi, ki, 64, 64, False, 0.0, fixed_k=4, group_shared=True)
+    s2 = oracle.select_topk(qi.sum(axis=1, keepdims=True), ki, 64, 64, False, 0.0, fixed_k=4)
+    assert all(np.array_equal(s1[0][0, h], s2[0][0, 0]) for h in range(4))
