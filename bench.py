@@ -220,41 +220,51 @@ def main() -> int:
         kmean = T.thrift_block_means(kd, wd.Bk)
         ws = torch.empty(T.decode_workspace_bytes(wd.B, wd.Hq, wd.Hkv, wd.N, wd.D, wd.Bk, wd.split_blocks), dtype=torch.uint8, device=dev)
         out = torch.empty(wd.B, wd.Hq, wd.D, dtype=qd.dtype, device=dev)
-        run = lambda: T.thrift_attn_decode(qd, kd, vd, k4, ks, v4, vs, kmean, wd.Bk, args.budget, split_blocks=wd.split_blocks,
-                                           out=out, workspace=ws)
-        for _ in range(3):
-            run()
-        torch.cuda.synchronize()
-        reps = 20
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            run()
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
-        _, idx_d, cnt_d = T.thrift_attn_decode(qd, kd, vd, k4, ks, v4, vs, kmean, wd.Bk, args.budget, split_blocks=wd.split_blocks,
-                                               out=out, workspace=ws, return_selection=True)
-        # algorithmic bytes: every byte the method must read once per (sequence, KV head)
-        Tk, G = wd.N // wd.Bk, wd.group
-        sel = torch.zeros(wd.B, wd.Hq, Tk + 1, dtype=torch.int32, device=dev)
-        sel.scatter_(2, torch.where(idx_d >= 0, idx_d, Tk).long(), 1)
-        votes = sel[:, :, :Tk].reshape(wd.B, wd.Hkv, G, Tk).sum(2)
-        n_union = int((votes > 0).sum().item())
-        n_all = int((votes == G).sum().item())
-        blocks = wd.B * wd.Hkv * Tk
-        fp4_block = 2 * (wd.Bk * wd.D // 2 + wd.Bk * wd.D // 32)          # K and V codes + scales
-        fp16_block = 2 * wd.Bk * wd.D * 2
-        alg_bytes = (blocks - n_all) * fp4_block + n_union * fp16_block + kmean.numel() * 4 + qd.numel() * 2 + out.numel() * 2
+        def timed_decode(group_shared):
+            run = lambda: T.thrift_attn_decode(qd, kd, vd, k4, ks, v4, vs, kmean, wd.Bk, args.budget, split_blocks=wd.split_blocks,
+                                               out=out, workspace=ws, group_shared=group_shared)
+            for _ in range(3):
+                run()
+            torch.cuda.synchronize()
+            reps = 20
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            _, idx_d, cnt_d = T.thrift_attn_decode(qd, kd, vd, k4, ks, v4, vs, kmean, wd.Bk, args.budget, split_blocks=wd.split_blocks,
+                                                   out=out, workspace=ws, return_selection=True, group_shared=group_shared)
+            # algorithmic bytes: every byte the method must read once per (sequence, KV head)
+            Tk, G = wd.N // wd.Bk, wd.group
+            sel = torch.zeros(wd.B, wd.Hq, Tk + 1, dtype=torch.int32, device=dev)
+            sel.scatter_(2, torch.where(idx_d >= 0, idx_d, Tk).long(), 1)
+            votes = sel[:, :, :Tk].reshape(wd.B, wd.Hkv, G, Tk).sum(2)
+            n_union = int((votes > 0).sum().item())
+            n_all = int((votes == G).sum().item())
+            blocks = wd.B * wd.Hkv * Tk
+            fp4_block = 2 * (wd.Bk * wd.D // 2 + wd.Bk * wd.D // 32)          # K and V codes + scales
+            fp16_block = 2 * wd.Bk * wd.D * 2
+            alg_bytes = (blocks - n_all) * fp4_block + n_union * fp16_block + kmean.numel() * 4 + qd.numel() * 2 + out.numel() * 2
+            return us, alg_bytes, n_union / blocks, blocks * fp16_block
+
+        us, alg_bytes, union_share, fp16_bytes = timed_decode(False)
         gbs = alg_bytes / (us * 1e-6) / 1e9
         result["decode"] = {"workload": wd.name, "batch": wd.B, "cache_tokens": wd.N, "split_blocks": wd.split_blocks,
                             "us": round(us, 1), "algorithmic_GB": round(alg_bytes / 1e9, 3), "GBps": round(gbs, 1),
-                            "promoted_block_share_union": round(n_union / blocks, 4),
+                            "promoted_block_share_union": round(union_share, 4),
                             "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(gbs, 1), "peak": PEAK_HBM,
                                          "unit": "GB/s", "frac": round(gbs / PEAK_HBM, 4),
                                          "traffic": (MEASURED_TRAFFIC_GB["decode_16x131k_f0.05"]
                                                      if (wd.N == 131072 and wd.B == 16 and args.budget == 0.05) else None)},
-                            "fp16_cache_equivalent_GB": round(blocks * fp16_block / 1e9, 3)}
+                            "fp16_cache_equivalent_GB": round(fp16_bytes / 1e9, 3)}
+        # extension: one promoted set per KV head (group-shared selection) instead of one per query head
+        us_s, bytes_s, union_s, _ = timed_decode(True)
+        result["decode"]["group_shared_selection"] = {"us": round(us_s, 1), "algorithmic_GB": round(bytes_s / 1e9, 3),
+                                                      "GBps": round(bytes_s / (us_s * 1e-6) / 1e9, 1),
+                                                      "promoted_block_share_union": round(union_s, 4)}
+        log(f"decode with group-shared selection {us_s:.1f} us, {bytes_s / 1e9:.2f} GB algorithmic")
         log(f"decode {us:.1f} us, {alg_bytes / 1e9:.2f} GB algorithmic -> {gbs:.0f} GB/s = {100 * gbs / PEAK_HBM:.1f} % of 8 TB/s")
 
     print(json.dumps(result), flush=True)

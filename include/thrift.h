@@ -102,6 +102,20 @@ thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, 
                                  int32_t* idx, int32_t* cnt, int kmax, void* stream);
 
 /*
+ * Group-shared selection for grouped-query attention — an extension; the paper selects per head and
+ * does not discuss GQA.  One set per (batch, KV head, query block), shared by the G = Hq/Hkv query
+ * heads of the group: the heuristic of Sec. 3.2 applied to the group's summed query mean,
+ * score_j = (sum_h Qbar_{h,i}) . Kbar_j  (per channel the fp64 sum over the heads in ascending order,
+ * then an fp64 fused-multiply-add chain over the channels in ascending order).  Arguments, budget
+ * rule, visibility and tie rule as thrift_select_topk; the set is written to the idx / cnt rows of
+ * every head of the group, so the attention entry points take it unchanged.  In decode it cuts the
+ * 16-bit cache traffic of a KV head from the union of G per-head sets to one set.
+ */
+thrift_status thrift_select_topk_shared(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                                        int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
+                                        int32_t* idx, int32_t* cnt, int kmax, void* stream);
+
+/*
  * Ablation selectors (App. A "Heuristic Ablation": randomly promoted blocks, diagonal-only selection).
  * Same outputs, budget rule and visibility as thrift_select_topk, but the k_i blocks of a row are
  *   THRIFT_SELECT_RANDOM    a uniformly random k_i-subset of the visible blocks: the blocks with the k_i
@@ -201,6 +215,15 @@ thrift_status thrift_attn_decode(const void* q, thrift_dtype dt, const void* k16
                                  double budget, int fixed_k, int split_blocks, float softmax_scale,
                                  void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* thrift_attn_decode with the group-shared selection of thrift_select_topk_shared in step (i). */
+thrift_status thrift_attn_decode_shared(const void* q, thrift_dtype dt, const void* k16, const void* v16,
+                                        const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
+                                        const float* kmean, const int32_t* seqlens,
+                                        int B, int Hq, int Hkv, int Nkv, int D, int Bk,
+                                        double budget, int fixed_k, int split_blocks, float softmax_scale,
+                                        void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                                        void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -222,9 +222,13 @@ int oracle_select_topk(const float* qmean, const float* kmean, int B, int Hq, in
 
 /* Group-shared selection for grouped-query attention (an extension: the paper selects per head and
  * does not discuss GQA).  One set T_i per (batch, KV head, query block), shared by the G = Hq/Hkv query
- * heads of the group: the blocks with the largest summed score  sum_h Qbar_{h,i} . Kbar_j  (each head's
- * score as in oracle_block_scores, added in ascending head order).  Same budget rule, visibility and
- * tie rule; the set is written to every head of the group, so idx / cnt keep the per-head shape. */
+ * heads of the group: the blocks with the largest score of the group's summed query mean,
+ *   ( sum_h Qbar_{h,i} ) . Kbar_j   =   sum_h ( Qbar_{h,i} . Kbar_j )   by linearity,
+ * evaluated as: per channel the fp64 sum of the heads' means in ascending head order, then the fp64
+ * dot product over the channels in ascending order with one fused multiply-add per term (the summed
+ * mean no longer fits 24 bits, so the rounding of each product is part of the definition).  Same
+ * budget rule, visibility and tie rule; the set is written to every head of the group, so idx / cnt
+ * keep the per-head shape. */
 int oracle_select_topk_shared(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
                               int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
                               int32_t* idx, int32_t* cnt, int kmax) {
@@ -240,11 +244,10 @@ int oracle_select_topk_shared(const float* qmean, const float* kmean, int B, int
         for (int j = 0; j < vis; ++j) {
           const float* km = kmean + (((long)b * Hkv + g) * Tk + j) * D;
           double total = 0.0;
-          for (int hh = 0; hh < grp; ++hh) {
-            const float* qm = qmean + ((((long)b * Hq + g * grp + hh) * Tq) + i) * D;
-            double s = 0.0;
-            for (int c = 0; c < D; ++c) s += (double)qm[c] * (double)km[c];
-            total += s;
+          for (int c = 0; c < D; ++c) {
+            double qsum = 0.0;
+            for (int hh = 0; hh < grp; ++hh) qsum += (double)qmean[((((long)b * Hq + g * grp + hh) * Tq) + i) * D + c];
+            total = fma(qsum, (double)km[c], total);
           }
           row[j].s = total;
           row[j].j = j;

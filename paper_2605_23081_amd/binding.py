@@ -20,9 +20,9 @@ _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 
 EXPORTS = (
     "thrift_status_string", "thrift_row_budget", "thrift_visible_blocks", "thrift_budget_to_global_k",
-    "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_select_ablation", "thrift_quantize_mxfp4",
+    "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_select_topk_shared", "thrift_select_ablation", "thrift_quantize_mxfp4",
     "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_prefill_chunk",
-    "thrift_attn_decode_workspace", "thrift_attn_decode",
+    "thrift_attn_decode_workspace", "thrift_attn_decode", "thrift_attn_decode_shared",
 )
 
 _lib = None
@@ -50,6 +50,7 @@ def lib() -> C.CDLL:
         L.thrift_select_kmax.argtypes = [i, i, i, i, i, d, i, i]
         L.thrift_block_means.argtypes = [p, i, i, i, i, i, i, p, p]
         L.thrift_select_topk.argtypes = [p, p, i, i, i, i, i, i, i, i, i, d, i, i, p, p, i, p]
+        L.thrift_select_topk_shared.argtypes = L.thrift_select_topk.argtypes
         L.thrift_select_ablation.argtypes = [i, C.c_uint64, i, i, i, i, i, i, i, d, i, i, p, p, i, p]
         L.thrift_quantize_mxfp4.argtypes = [p, i, i, i, i, i, i, p, p, p]
         L.thrift_attn_prefill_workspace.restype = sz
@@ -59,6 +60,7 @@ def lib() -> C.CDLL:
         L.thrift_attn_decode_workspace.restype = sz
         L.thrift_attn_decode_workspace.argtypes = [i] * 7
         L.thrift_attn_decode.argtypes = [p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, d, i, i, f, p, i, p, p, i, p, sz, p]
+        L.thrift_attn_decode_shared.argtypes = L.thrift_attn_decode.argtypes
         _lib = L
     return _lib
 
@@ -119,8 +121,8 @@ def thrift_block_means(x: torch.Tensor, block: int, out: Optional[torch.Tensor] 
 
 def thrift_select_topk(qmean: torch.Tensor, kmean: torch.Tensor, Bq: int, Bk: int, causal: bool, budget: float,
                        fixed_k: int = -1, q_block_offset: int = 0, kmax: Optional[int] = None,
-                       idx: Optional[torch.Tensor] = None, cnt: Optional[torch.Tensor] = None
-                       ) -> Tuple[torch.Tensor, torch.Tensor]:
+                       idx: Optional[torch.Tensor] = None, cnt: Optional[torch.Tensor] = None,
+                       group_shared: bool = False) -> Tuple[torch.Tensor, torch.Tensor]:
     _dev(qmean, torch.float32), _dev(kmean, torch.float32)
     B, Hq, Tq, D = qmean.shape
     _, Hkv, Tk, _ = kmean.shape
@@ -129,9 +131,10 @@ def thrift_select_topk(qmean: torch.Tensor, kmean: torch.Tensor, Bq: int, Bk: in
     if idx is None:
         idx = torch.empty(B, Hq, Tq, kmax, dtype=torch.int32, device=qmean.device)
         cnt = torch.empty(B, Hq, Tq, dtype=torch.int32, device=qmean.device)
-    _check(lib().thrift_select_topk(_ptr(qmean), _ptr(kmean), B, Hq, Hkv, Tq, Tk, D, Bq, Bk, int(causal), float(budget),
-                                    int(fixed_k), int(q_block_offset), _ptr(idx), _ptr(cnt), int(kmax), _stream()),
-           "thrift_select_topk")
+    fn = lib().thrift_select_topk_shared if group_shared else lib().thrift_select_topk
+    _check(fn(_ptr(qmean), _ptr(kmean), B, Hq, Hkv, Tq, Tk, D, Bq, Bk, int(causal), float(budget),
+              int(fixed_k), int(q_block_offset), _ptr(idx), _ptr(cnt), int(kmax), _stream()),
+           "thrift_select_topk_shared" if group_shared else "thrift_select_topk")
     return idx, cnt
 
 
@@ -214,7 +217,8 @@ def decode_workspace_bytes(B: int, Hq: int, Hkv: int, Nkv: int, D: int, Bk: int,
 def thrift_attn_decode(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budget: float, fixed_k: int = -1,
                        split_blocks: int = 256, softmax_scale: float = 0.0, seqlens: Optional[torch.Tensor] = None,
                        out: Optional[torch.Tensor] = None, out_dtype: Optional[torch.dtype] = None,
-                       workspace: Optional[torch.Tensor] = None, return_selection: bool = False):
+                       workspace: Optional[torch.Tensor] = None, return_selection: bool = False,
+                       group_shared: bool = False):
     for t in (q, k16, v16, k4, ks, v4, vs, kmean):
         _dev(t)
     B, Hq, D = q.shape
@@ -230,10 +234,12 @@ def thrift_attn_decode(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budget: floa
         kmax = max(1, row_budget(Nkv // Bk, budget, fixed_k))
         idx = torch.empty(B, Hq, kmax, dtype=torch.int32, device=q.device)
         cnt = torch.empty(B, Hq, dtype=torch.int32, device=q.device)
-    _check(lib().thrift_attn_decode(_ptr(q), _DT[q.dtype], _ptr(k16), _ptr(v16), _ptr(k4), _ptr(ks), _ptr(v4), _ptr(vs),
-                                    _ptr(kmean), _ptr(seqlens), B, Hq, Hkv, Nkv, D, Bk, float(budget), int(fixed_k),
-                                    int(split_blocks), float(softmax_scale), _ptr(out), _DT[out.dtype], _ptr(idx), _ptr(cnt),
-                                    kmax, _ptr(workspace), workspace.numel(), _stream()), "thrift_attn_decode")
+    fn = lib().thrift_attn_decode_shared if group_shared else lib().thrift_attn_decode
+    _check(fn(_ptr(q), _DT[q.dtype], _ptr(k16), _ptr(v16), _ptr(k4), _ptr(ks), _ptr(v4), _ptr(vs),
+              _ptr(kmean), _ptr(seqlens), B, Hq, Hkv, Nkv, D, Bk, float(budget), int(fixed_k),
+              int(split_blocks), float(softmax_scale), _ptr(out), _DT[out.dtype], _ptr(idx), _ptr(cnt),
+              kmax, _ptr(workspace), workspace.numel(), _stream()),
+           "thrift_attn_decode_shared" if group_shared else "thrift_attn_decode")
     return (out, idx, cnt) if return_selection else out
 
 

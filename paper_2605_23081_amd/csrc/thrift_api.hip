@@ -130,9 +130,9 @@ thrift_status thrift_block_means(const void* x, thrift_dtype dt, int B, int H, i
   return after_launch();
 }
 
-thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
-                                 int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
-                                 int32_t* idx, int32_t* cnt, int kmax, void* stream) {
+static thrift_status select_topk_impl(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                                      int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
+                                      int32_t* idx, int32_t* cnt, int kmax, int shared, void* stream) {
   if (!qmean || !kmean || !idx || !cnt) return THRIFT_ERR_NULL;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Tq <= 0 || Tk <= 0 || Tk > kMaxKeyBlocks || D != kHeadDim ||
       Bq <= 0 || Bk <= 0 || q_block_offset < 0 || kmax <= 0)
@@ -142,12 +142,25 @@ thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, 
   if ((long)B * Hkv * (((long)Tq * (Hq / Hkv) + 3) / 4) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   SelectArgs a;
+  a.shared = shared;
   a.qmean = qmean; a.kmean = kmean; a.idx = idx; a.cnt = cnt;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Tq = Tq; a.Tk = Tk; a.Bq = Bq; a.Bk = Bk; a.causal = causal ? 1 : 0;
   a.fixed_k = fixed_k; a.q_block_offset = q_block_offset; a.kmax = kmax; a.ppm = fixed_k >= 0 ? 0 : budget_ppm(budget);
   a.selector = 0; a.seed = 0;
   launch_select_topk(a, (hipStream_t)stream);
   return after_launch();
+}
+
+thrift_status thrift_select_topk(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                                 int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
+                                 int32_t* idx, int32_t* cnt, int kmax, void* stream) {
+  return select_topk_impl(qmean, kmean, B, Hq, Hkv, Tq, Tk, D, Bq, Bk, causal, budget, fixed_k, q_block_offset, idx, cnt, kmax, 0, stream);
+}
+
+thrift_status thrift_select_topk_shared(const float* qmean, const float* kmean, int B, int Hq, int Hkv, int Tq, int Tk, int D,
+                                        int Bq, int Bk, int causal, double budget, int fixed_k, int q_block_offset,
+                                        int32_t* idx, int32_t* cnt, int kmax, void* stream) {
+  return select_topk_impl(qmean, kmean, B, Hq, Hkv, Tq, Tk, D, Bq, Bk, causal, budget, fixed_k, q_block_offset, idx, cnt, kmax, 1, stream);
 }
 
 thrift_status thrift_select_ablation(int selector, uint64_t seed, int B, int Hq, int Tq, int Tk, int Bq, int Bk,
@@ -166,7 +179,7 @@ thrift_status thrift_select_ablation(int selector, uint64_t seed, int B, int Hq,
   a.qmean = nullptr; a.kmean = nullptr; a.idx = idx; a.cnt = cnt;
   a.B = B; a.Hq = Hq; a.Hkv = Hq; a.Tq = Tq; a.Tk = Tk; a.Bq = Bq; a.Bk = Bk; a.causal = causal ? 1 : 0;   // no KV heads involved: one row group per head
   a.fixed_k = fixed_k; a.q_block_offset = q_block_offset; a.kmax = kmax; a.ppm = fixed_k >= 0 ? 0 : budget_ppm(budget);
-  a.selector = selector; a.seed = seed;
+  a.selector = selector; a.seed = seed; a.shared = 0;
   launch_select_topk(a, (hipStream_t)stream);
   return after_launch();
 }
@@ -234,13 +247,13 @@ size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int 
   return decode_layout(B, Hq, Nkv, Bk, split_blocks).total;
 }
 
-thrift_status thrift_attn_decode(const void* q, thrift_dtype dt, const void* k16, const void* v16,
-                                 const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
-                                 const float* kmean, const int32_t* seqlens,
-                                 int B, int Hq, int Hkv, int Nkv, int D, int Bk,
-                                 double budget, int fixed_k, int split_blocks, float softmax_scale,
-                                 void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
+static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void* k16, const void* v16,
+                                      const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
+                                      const float* kmean, const int32_t* seqlens,
+                                      int B, int Hq, int Hkv, int Nkv, int D, int Bk,
+                                      double budget, int fixed_k, int split_blocks, float softmax_scale,
+                                      void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                                      void* workspace, size_t workspace_bytes, int shared, void* stream) {
   if (!q || !k16 || !v16 || !k4 || !ks || !v4 || !vs || !kmean || !out) return THRIFT_ERR_NULL;
   if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Hq / Hkv > 32 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock ||
@@ -265,7 +278,7 @@ thrift_status thrift_attn_decode(const void* q, thrift_dtype dt, const void* k16
   launch_block_means(q, dt, (long)B * Hq, 1, qf32, st);
   launch_quantize(q, dt, (long)B * Hq, 1, 0, (uint8_t*)(ws + L.q4), (uint8_t*)(ws + L.qs), st);
   launch_decode_select(qf32, kmean, seqlens, (uint64_t*)(ws + L.keys), bitmap, L.words, idx_out, cnt_out, kmax_out,
-                       B, Hq, Hkv, Tk, fixed_k, fixed_k >= 0 ? 0 : budget_ppm(budget), st);
+                       B, Hq, Hkv, Tk, fixed_k, fixed_k >= 0 ? 0 : budget_ppm(budget), shared, st);
 
   // (ii) split-K partial attention, (iii) log-sum-exp merge
   DecodeArgs a;
@@ -278,6 +291,28 @@ thrift_status thrift_attn_decode(const void* q, thrift_dtype dt, const void* k16
   a.dt = dt; a.out_dt = out_dt;
   launch_decode(a, st);
   return after_launch();
+}
+
+thrift_status thrift_attn_decode(const void* q, thrift_dtype dt, const void* k16, const void* v16,
+                                 const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
+                                 const float* kmean, const int32_t* seqlens,
+                                 int B, int Hq, int Hkv, int Nkv, int D, int Bk,
+                                 double budget, int fixed_k, int split_blocks, float softmax_scale,
+                                 void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  return attn_decode_impl(q, dt, k16, v16, k4, ks, v4, vs, kmean, seqlens, B, Hq, Hkv, Nkv, D, Bk, budget, fixed_k, split_blocks,
+                          softmax_scale, out, out_dt, idx_out, cnt_out, kmax_out, workspace, workspace_bytes, 0, stream);
+}
+
+thrift_status thrift_attn_decode_shared(const void* q, thrift_dtype dt, const void* k16, const void* v16,
+                                        const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
+                                        const float* kmean, const int32_t* seqlens,
+                                        int B, int Hq, int Hkv, int Nkv, int D, int Bk,
+                                        double budget, int fixed_k, int split_blocks, float softmax_scale,
+                                        void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  return attn_decode_impl(q, dt, k16, v16, k4, ks, v4, vs, kmean, seqlens, B, Hq, Hkv, Nkv, D, Bk, budget, fixed_k, split_blocks,
+                          softmax_scale, out, out_dt, idx_out, cnt_out, kmax_out, workspace, workspace_bytes, 1, stream);
 }
 
 }  // extern "C"

@@ -172,10 +172,11 @@ __device__ __forceinline__ uint64_t order_key64(double s) {
 
 __global__ void __launch_bounds__(256) decode_scores_kernel(const float* __restrict__ qf32, const float* __restrict__ kmean,
                                                             const int32_t* __restrict__ seqlens, uint64_t* __restrict__ keys,
-                                                            int Hq, int Hkv, int Tk) {
+                                                            int Hq, int Hkv, int Tk, int shared) {
   constexpr int kStride = kD + 4;
   __shared__ __align__(16) float kst[64 * kStride];
   __shared__ __align__(16) float qst[32 * kD];
+  __shared__ __align__(16) double qsum[kD];            // shared mode: the group's query vectors added up (fp64, head order)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int G = Hq / Hkv, chunks = (Tk + 63) / 64;
   const int chunk = blockIdx.x % chunks, unit = blockIdx.x / chunks;
@@ -191,9 +192,31 @@ __global__ void __launch_bounds__(256) decode_scores_kernel(const float* __restr
   }
   const float* qbase = qf32 + ((size_t)b * Hq + (size_t)kvh * G) * kD;
   for (int e = tid; e < G * kD; e += 256) qst[e] = qbase[e];
+  if (shared && tid < kD) {
+    double t = 0.0;
+    for (int g = 0; g < G; ++g) t += (double)qbase[g * kD + tid];
+    qsum[tid] = t;
+  }
   __syncthreads();
   const int j = chunk * 64 + lane;
   if (j >= cap) return;
+  if (shared) {
+    // one score per block for the whole group; every head's key row receives it
+    double s = 0.0;
+    if (wave == 0) {
+#pragma unroll 8
+      for (int d = 0; d < kD; d += 4) {
+        const float4 kv = *reinterpret_cast<const float4*>(&kst[lane * kStride + d]);
+        s = fma(qsum[d], (double)kv.x, s);
+        s = fma(qsum[d + 1], (double)kv.y, s);
+        s = fma(qsum[d + 2], (double)kv.z, s);
+        s = fma(qsum[d + 3], (double)kv.w, s);
+      }
+      const uint64_t key = order_key64(s);
+      for (int g = 0; g < G; ++g) keys[((size_t)b * Hq + kvh * G + g) * Tk + j] = key;
+    }
+    return;
+  }
   for (int g = wave; g < G; g += 4) {
     double s = 0.0;
 #pragma unroll 8
@@ -297,9 +320,9 @@ __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, 
 
 void launch_decode_select(const float* qf32, const float* kmean, const int32_t* seqlens, uint64_t* keys,
                           unsigned long long* bitmap, int words, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
-                          int B, int Hq, int Hkv, int Tk, int fixed_k, long long ppm, hipStream_t st) {
+                          int B, int Hq, int Hkv, int Tk, int fixed_k, long long ppm, int shared, hipStream_t st) {
   const int chunks = (Tk + 63) / 64;
-  decode_scores_kernel<<<dim3((unsigned)((long)B * Hkv * chunks)), dim3(256), 0, st>>>(qf32, kmean, seqlens, keys, Hq, Hkv, Tk);
+  decode_scores_kernel<<<dim3((unsigned)((long)B * Hkv * chunks)), dim3(256), 0, st>>>(qf32, kmean, seqlens, keys, Hq, Hkv, Tk, shared);
   DecodeSelectArgs p;
   p.keys = keys; p.seqlens = seqlens; p.bitmap = bitmap; p.idx_out = idx_out; p.cnt_out = cnt_out;
   p.Hq = Hq; p.Tk = Tk; p.words = words; p.kmax_out = kmax_out; p.fixed_k = fixed_k; p.ppm = ppm;

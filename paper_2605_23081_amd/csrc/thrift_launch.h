@@ -20,6 +20,7 @@ struct SelectArgs {
   long long ppm;                // budget in millionths
   int selector;                 // 0: TopK of the mean scores; 1: random keys; 2: largest block ids
   unsigned long long seed;      // random selector only
+  int shared;                   // selector 0 only: one set per KV head from the query means summed over its group
 };
 void launch_select_topk(const SelectArgs& a, hipStream_t st);
 
@@ -68,6 +69,6 @@ void launch_decode(const DecodeArgs& a, hipStream_t st);
 // as a bitmap ([B*Hq][words], bit j%64 of word j/64) and optionally as ascending id lists
 void launch_decode_select(const float* qf32, const float* kmean, const int32_t* seqlens, uint64_t* keys,
                           unsigned long long* bitmap, int words, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
-                          int B, int Hq, int Hkv, int Tk, int fixed_k, long long ppm, hipStream_t st);
+                          int B, int Hq, int Hkv, int Tk, int fixed_k, long long ppm, int shared, hipStream_t st);
 
 }  // namespace thrift

@@ -201,29 +201,37 @@ template <int MAXC>
 __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
   constexpr int kStride = kD + 4;                       // padded fp32 row of a staged key mean
   __shared__ __align__(16) float kst[64 * kStride];
-  __shared__ __align__(16) float qst[4][kD];
+  __shared__ __align__(16) double qsd[4][kD];           // the row's query mean (shared mode: summed over the group's heads)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int G = p.Hq / p.Hkv;
-  const int rows_per_unit = p.Tq * G;                   // rows of one (b, kv head), ordered (i, head in group)
+  const int GR = p.shared ? 1 : G;                      // selection rows per query block and KV head
+  const int nheads = p.shared ? G : 1;                  // heads that receive a row's result
+  const int rows_per_unit = p.Tq * GR;                  // rows of one (b, kv head), ordered (i, head in group)
   const int wgs_per_unit = (rows_per_unit + 3) / 4;
   const int unit = blockIdx.x / wgs_per_unit;
   const int row0 = (blockIdx.x % wgs_per_unit) * 4;
   const int b = unit / p.Hkv, kvh = unit % p.Hkv;
   const int row = row0 + wave;
   const bool active = row < rows_per_unit;
-  const int i = active ? row / G : 0;
-  const int hq = kvh * G + (active ? row % G : 0);
+  const int i = active ? row / GR : 0;
+  const int hq = kvh * G + (active ? row % GR : 0);     // first (or only) head of the row
   const int cap = p.Tk;
   const int vis = active ? min(cap, visible_blocks_dev(i, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset)) : 0;
   const int k = row_budget_dev(vis, p.ppm, p.fixed_k);
   const int last_row = min(row0 + 3, rows_per_unit - 1);
-  const int vis_max = min(cap, visible_blocks_dev(last_row / G, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset));
+  const int vis_max = min(cap, visible_blocks_dev(last_row / GR, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset));
   const size_t rowid = ((size_t)b * p.Hq + hq) * p.Tq + i;
 
   if (active && p.selector == 0) {
-    const float* qm = p.qmean + rowid * kD;
-    qst[wave][lane] = qm[lane];
-    qst[wave][lane + 64] = qm[lane + 64];
+    // fp64 sum over the heads in ascending order (one head: the value itself)
+    double q0 = 0.0, q1 = 0.0;
+    for (int hh = 0; hh < nheads; ++hh) {
+      const float* qm = p.qmean + (rowid + (size_t)hh * p.Tq) * kD;
+      q0 += (double)qm[lane];
+      q1 += (double)qm[lane + 64];
+    }
+    qsd[wave][lane] = q0;
+    qsd[wave][lane + 64] = q1;
   }
   const float* kbase = p.kmean + ((size_t)b * p.Hkv + kvh) * p.Tk * kD;
 
@@ -254,11 +262,12 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
 #pragma unroll 8
         for (int d = 0; d < kD; d += 4) {
           float4 kv = *reinterpret_cast<const float4*>(&kst[lane * kStride + d]);
-          float4 qv = *reinterpret_cast<const float4*>(&qst[wave][d]);
-          s = fma((double)qv.x, (double)kv.x, s);
-          s = fma((double)qv.y, (double)kv.y, s);
-          s = fma((double)qv.z, (double)kv.z, s);
-          s = fma((double)qv.w, (double)kv.w, s);
+          const double2 qa = *reinterpret_cast<const double2*>(&qsd[wave][d]);
+          const double2 qb = *reinterpret_cast<const double2*>(&qsd[wave][d + 2]);
+          s = fma(qa.x, (double)kv.x, s);
+          s = fma(qa.y, (double)kv.y, s);
+          s = fma(qb.x, (double)kv.z, s);
+          s = fma(qb.y, (double)kv.w, s);
         }
         key[c] = order_key(s);
       }
@@ -266,10 +275,11 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
   }
   if (!active) return;
 
-  int32_t* out = p.idx + rowid * p.kmax;
-  if (lane == 0) p.cnt[rowid] = k;
+  if (lane == 0)
+    for (int hh = 0; hh < nheads; ++hh) p.cnt[rowid + (size_t)hh * p.Tq] = k;
   if (k <= 0) {
-    for (int t = lane; t < p.kmax; t += 64) out[t] = -1;
+    for (int hh = 0; hh < nheads; ++hh)
+      for (int t = lane; t < p.kmax; t += 64) p.idx[(rowid + (size_t)hh * p.Tq) * p.kmax + t] = -1;
     return;
   }
   // k-th largest key: greatest T with |{key >= T}| >= k, built bit by bit from the top
@@ -297,16 +307,19 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
       const uint64_t tie_b = __ballot(tie);
       const bool sel = valid && (key[c] > T || (tie && ties_seen + __popcll(tie_b & lt_mask) < need_ties));
       const uint64_t sel_b = __ballot(sel);
-      if (sel) out[written + __popcll(sel_b & lt_mask)] = c * 64 + lane;
+      if (sel)
+        for (int hh = 0; hh < nheads; ++hh)
+          p.idx[(rowid + (size_t)hh * p.Tq) * p.kmax + written + __popcll(sel_b & lt_mask)] = c * 64 + lane;
       written += __popcll(sel_b);
       ties_seen += __popcll(tie_b);
     }
   }
-  for (int t = k + lane; t < p.kmax; t += 64) out[t] = -1;
+  for (int hh = 0; hh < nheads; ++hh)
+    for (int t = k + lane; t < p.kmax; t += 64) p.idx[(rowid + (size_t)hh * p.Tq) * p.kmax + t] = -1;
 }
 
 void launch_select_topk(const SelectArgs& p, hipStream_t st) {
-  const int G = p.Hq / p.Hkv;
+  const int G = p.shared ? 1 : p.Hq / p.Hkv;
   const int wgs_per_unit = (p.Tq * G + 3) / 4;
   const unsigned grid = (unsigned)((long)p.B * p.Hkv * wgs_per_unit);
   const int chunks = (p.Tk + 63) / 64;

@@ -461,3 +461,48 @@ def test_prefill_chunk_guards(T):
     out = T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, idx, cnt, 128, 64, True, 6)   # the last two blocks: fine
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
+
+
+# ------------------------------------------------------------------ group-shared selection (GQA extension)
+def test_select_topk_shared_bit_exact(T, oracle):
+    for wl, budget, causal, fixed_k in [(_small_bf16(N=4096, Hq=8, Hkv=2), 0.05, True, -1),
+                                        (_small_bf16(N=2048, Hq=6, Hkv=2, Bq=64), 0.25, False, -1),
+                                        (_small_bf16(N=5120, Hq=3, Hkv=1, Bq=64), 0.0, True, 9),     # two chunks of key blocks
+                                        (_small_bf16(N=1024, Hq=4, Hkv=4), 0.1, True, -1)]:         # groups of one head
+        _say(f"shared selection N={wl.N} Hq={wl.Hq} Hkv={wl.Hkv} Bq={wl.Bq} f={budget} causal={causal} k={fixed_k}")
+        q, k, v, _, _ = W.make_prefill(wl)
+        qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k)
+        qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+        idx_r, cnt_r = oracle.select_topk(qm, km, wl.Bq, wl.Bk, causal, budget, fixed_k, group_shared=True)
+        qm_g = T.thrift_block_means(q.cuda(), wl.Bq); km_g = T.thrift_block_means(k.cuda(), wl.Bk)
+        idx_g, cnt_g = T.thrift_select_topk(qm_g, km_g, wl.Bq, wl.Bk, causal, budget, fixed_k, group_shared=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(cnt_g), cnt_r)
+        assert np.array_equal(to_np(idx_g)[..., :idx_r.shape[-1]], idx_r) and np.all(to_np(idx_g)[..., idx_r.shape[-1]:] == -1)
+        G = wl.Hq // wl.Hkv
+        ig = to_np(idx_g).reshape(wl.B, wl.Hkv, G, *idx_g.shape[2:])
+        assert all(np.array_equal(ig[:, :, 0], ig[:, :, g]) for g in range(G))        # one set per group
+
+
+@pytest.mark.parametrize("budget", [0.05, 0.25])
+def test_decode_shared_selection(T, oracle, budget):
+    wl = W.scaled(W.DECODE_131K, B=2, N=4096, Hq=8, Hkv=2)
+    _say(f"decode with group-shared selection B=2 N=4096 budget={budget}")
+    q, k, v = W.make_decode(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    B, Hq, Tk = wl.B, wl.Hq, wl.N // wl.Bk
+    km = oracle.block_means(kb, dt, wl.Bk)
+    qm = q.float().numpy().reshape(B, Hq, 1, wl.D)
+    idx_r, cnt_r = oracle.select_topk(qm, km, 1, wl.Bk, False, budget, group_shared=True)
+    idx_r, cnt_r = idx_r[:, :, 0], cnt_r[:, :, 0]
+    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, 1 / math.sqrt(wl.D), 16 // 4)
+    kg, vg = k.cuda(), v.cuda()
+    k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    kmean = T.thrift_block_means(kg, wl.Bk)
+    got, idx_g, cnt_g = T.thrift_attn_decode(q.cuda(), kg, vg, k4, ks, v4, vs, kmean, wl.Bk, budget, -1, 16,
+                                             out_dtype=torch.float32, return_selection=True, group_shared=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(cnt_g), cnt_r) and np.array_equal(to_np(idx_g)[..., :idx_r.shape[-1]], idx_r)
+    err = np.abs(to_np(got) - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert err <= TOLMIX
