@@ -271,13 +271,10 @@ static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void
   if (thrift_status s = check_arch()) return s;
   hipStream_t st = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  float* qf32 = (float*)(ws + L.qf32);
   unsigned long long* bitmap = (unsigned long long*)(ws + L.bitmap);
 
   // (i) the query token is its own block mean; score it against the cached key-block means and select
-  launch_block_means(q, dt, (long)B * Hq, 1, qf32, st);
-  launch_quantize(q, dt, (long)B * Hq, 1, 0, (uint8_t*)(ws + L.q4), (uint8_t*)(ws + L.qs), st);
-  launch_decode_select(qf32, kmean, seqlens, (uint64_t*)(ws + L.keys), bitmap, L.words, idx_out, cnt_out, kmax_out,
+  launch_decode_select((const uint16_t*)q, dt == THRIFT_BF16 ? 1 : 0, kmean, seqlens, (uint64_t*)(ws + L.keys), bitmap, L.words, idx_out, cnt_out, kmax_out,
                        B, Hq, Hkv, Tk, fixed_k, fixed_k >= 0 ? 0 : budget_ppm(budget), shared, st);
 
   // (ii) split-K partial attention, (iii) log-sum-exp merge

@@ -39,13 +39,25 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   const int j_begin = part * a.split_blocks + wave * quarter;
   const int j_end = min(Tk, j_begin + quarter);
 
-  // ---- Q fragments (zeros for padding columns) ----
+  // ---- Q fragments (zeros for padding columns): the lane quantises its own two MXFP4 groups of the query,
+  // channels 64*kk + 32*half .. +31 for fragment kk (Alg. 1 step 2 for the one-token query block) ----
   v4i qf4[2] = {(v4i){0, 0, 0, 0}, (v4i){0, 0, 0, 0}};
   uint32_t qsc = 0x7f7f7f7fu;
   if (real) {
-    qf4[0] = *reinterpret_cast<const v4i*>(a.q4 + qh * 64 + half * 16);
-    qf4[1] = *reinterpret_cast<const v4i*>(a.q4 + qh * 64 + 32 + half * 16);
-    qsc = *reinterpret_cast<const uint32_t*>(a.qs + qh * 4) >> (8 * half);
+    uint32_t sb[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const uint4* src = reinterpret_cast<const uint4*>(a.q + qh * kD + 64 * kk + 32 * half);
+      uint32_t pair[16], codes[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint4 w = src[t];
+        pair[4 * t] = w.x; pair[4 * t + 1] = w.y; pair[4 * t + 2] = w.z; pair[4 * t + 3] = w.w;
+      }
+      sb[kk] = quantize_group32<T>(pair, codes);
+      qf4[kk] = (v4i){(int)codes[0], (int)codes[1], (int)codes[2], (int)codes[3]};
+    }
+    qsc = sb[0] | (sb[1] << 16);                             // byte 2*kk: the scale of fragment kk
   }
 
   const uint8_t* k4base = a.k4 + kh * a.Nkv * 64;
@@ -158,8 +170,8 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
 // ------------------------------------------------------------------------------------------------
 // Decode-time block selection (Alg. 1 step 5 for one-token query blocks).  Two kernels, so that the
 // whole chip works on the B*Hq short rows:
-//   decode_scores_kernel  one workgroup per (sequence, KV head, 64 key blocks): stages the 64 cached
-//                         key-block means once and scores them against the G query heads of the group
+//   decode_scores_kernel  one workgroup per (sequence, KV head, 256 key blocks): stages the cached
+//                         key-block means 64 at a time and scores them against the G query heads of the group
 //                         (fp64, channels in ascending order), storing order-preserving 64-bit keys;
 //   decode_select_kernel  one wavefront per (sequence, query head): finds the k-th largest key by a
 //                         bitwise search with ballot counting and writes the selection as a bitmap
@@ -170,7 +182,9 @@ __device__ __forceinline__ uint64_t order_key64(double s) {
   return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);   // larger double <=> larger key
 }
 
-__global__ void __launch_bounds__(256) decode_scores_kernel(const float* __restrict__ qf32, const float* __restrict__ kmean,
+constexpr int kScoreChunksPerWg = 4;     // 64-block chunks one workgroup of decode_scores_kernel walks
+
+__global__ void __launch_bounds__(256) decode_scores_kernel(const uint16_t* __restrict__ q16, int q_is_bf16, const float* __restrict__ kmean,
                                                             const int32_t* __restrict__ seqlens, uint64_t* __restrict__ keys,
                                                             int Hq, int Hkv, int Tk, int shared) {
   constexpr int kStride = kD + 4;
@@ -179,57 +193,73 @@ __global__ void __launch_bounds__(256) decode_scores_kernel(const float* __restr
   __shared__ __align__(16) double qsum[kD];            // shared mode: the group's query vectors added up (fp64, head order)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int G = Hq / Hkv, chunks = (Tk + 63) / 64;
-  const int chunk = blockIdx.x % chunks, unit = blockIdx.x / chunks;
+  const int groups = (chunks + kScoreChunksPerWg - 1) / kScoreChunksPerWg;
+  const int chunk0 = (blockIdx.x % groups) * kScoreChunksPerWg, unit = blockIdx.x / groups;
   const int b = unit / Hkv, kvh = unit % Hkv;
   const int cap = seqlens ? min(Tk, max(0, seqlens[b]) / kBk) : Tk;
-  if (chunk * 64 >= cap) return;                            // uniform: nothing of this chunk is valid
-  const float* kbase = kmean + ((size_t)unit * Tk + (size_t)chunk * 64) * kD;
-#pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    const int c4 = tid + 256 * u, row = c4 >> 5, col = (c4 & 31) * 4;
-    if (chunk * 64 + row < Tk)
-      *reinterpret_cast<float4*>(&kst[row * kStride + col]) = *reinterpret_cast<const float4*>(kbase + (size_t)row * kD + col);
+  if (chunk0 * 64 >= cap) return;                           // uniform: nothing of these chunks is valid
+  const int chunk_end = min(chunk0 + kScoreChunksPerWg, (cap + 63) / 64);
+  const float* kunit = kmean + (size_t)unit * Tk * kD;
+  // the chunk after the one being scored travels through registers, so its latency hides behind the arithmetic
+  float4 pre[8];
+#define THRIFT_LOAD_CHUNK(C)                                                                                     \
+  _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                                \
+    const int c4 = tid + 256 * u, row = c4 >> 5, col = (c4 & 31) * 4;                                            \
+    pre[u] = (C) * 64 + row < Tk ? *reinterpret_cast<const float4*>(kunit + ((size_t)(C) * 64 + row) * kD + col) \
+                                 : make_float4(0.f, 0.f, 0.f, 0.f);                                              \
   }
-  const float* qbase = qf32 + ((size_t)b * Hq + (size_t)kvh * G) * kD;
-  for (int e = tid; e < G * kD; e += 256) qst[e] = qbase[e];
+  THRIFT_LOAD_CHUNK(chunk0)
+  // the query token is its own block mean (one-token block): the 16-bit value widened exactly
+  const uint16_t* qbase = q16 + ((size_t)b * Hq + (size_t)kvh * G) * kD;
+  for (int e = tid; e < G * kD; e += 256) qst[e] = q_is_bf16 ? BF16::to_float(qbase[e]) : F16::to_float(qbase[e]);
   if (shared && tid < kD) {
     double t = 0.0;
-    for (int g = 0; g < G; ++g) t += (double)qbase[g * kD + tid];
+    for (int g = 0; g < G; ++g) t += (double)(q_is_bf16 ? BF16::to_float(qbase[g * kD + tid]) : F16::to_float(qbase[g * kD + tid]));
     qsum[tid] = t;
   }
-  __syncthreads();
-  const int j = chunk * 64 + lane;
-  if (j >= cap) return;
-  if (shared) {
-    // one score per block for the whole group; every head's key row receives it
-    double s = 0.0;
-    if (wave == 0) {
+  for (int chunk = chunk0; chunk < chunk_end; ++chunk) {
+    __syncthreads();                                        // everyone has finished the previous chunk
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int c4 = tid + 256 * u, row = c4 >> 5, col = (c4 & 31) * 4;
+      *reinterpret_cast<float4*>(&kst[row * kStride + col]) = pre[u];
+    }
+    if (chunk + 1 < chunk_end) { THRIFT_LOAD_CHUNK(chunk + 1) }
+    __syncthreads();
+    const int j = chunk * 64 + lane;
+    if (j >= cap) continue;
+    if (shared) {
+      // one score per block for the whole group; every head's key row receives it
+      if (wave == 0) {
+        double s = 0.0;
+#pragma unroll 8
+        for (int d = 0; d < kD; d += 4) {
+          const float4 kv = *reinterpret_cast<const float4*>(&kst[lane * kStride + d]);
+          s = fma(qsum[d], (double)kv.x, s);
+          s = fma(qsum[d + 1], (double)kv.y, s);
+          s = fma(qsum[d + 2], (double)kv.z, s);
+          s = fma(qsum[d + 3], (double)kv.w, s);
+        }
+        const uint64_t key = order_key64(s);
+        for (int g = 0; g < G; ++g) keys[((size_t)b * Hq + kvh * G + g) * Tk + j] = key;
+      }
+      continue;
+    }
+    for (int g = wave; g < G; g += 4) {
+      double s = 0.0;
 #pragma unroll 8
       for (int d = 0; d < kD; d += 4) {
         const float4 kv = *reinterpret_cast<const float4*>(&kst[lane * kStride + d]);
-        s = fma(qsum[d], (double)kv.x, s);
-        s = fma(qsum[d + 1], (double)kv.y, s);
-        s = fma(qsum[d + 2], (double)kv.z, s);
-        s = fma(qsum[d + 3], (double)kv.w, s);
+        const float4 qv = *reinterpret_cast<const float4*>(&qst[g * kD + d]);
+        s = fma((double)qv.x, (double)kv.x, s);
+        s = fma((double)qv.y, (double)kv.y, s);
+        s = fma((double)qv.z, (double)kv.z, s);
+        s = fma((double)qv.w, (double)kv.w, s);
       }
-      const uint64_t key = order_key64(s);
-      for (int g = 0; g < G; ++g) keys[((size_t)b * Hq + kvh * G + g) * Tk + j] = key;
+      keys[((size_t)b * Hq + kvh * G + g) * Tk + j] = order_key64(s);
     }
-    return;
   }
-  for (int g = wave; g < G; g += 4) {
-    double s = 0.0;
-#pragma unroll 8
-    for (int d = 0; d < kD; d += 4) {
-      const float4 kv = *reinterpret_cast<const float4*>(&kst[lane * kStride + d]);
-      const float4 qv = *reinterpret_cast<const float4*>(&qst[g * kD + d]);
-      s = fma((double)qv.x, (double)kv.x, s);
-      s = fma((double)qv.y, (double)kv.y, s);
-      s = fma((double)qv.z, (double)kv.z, s);
-      s = fma((double)qv.w, (double)kv.w, s);
-    }
-    keys[((size_t)b * Hq + kvh * G + g) * Tk + j] = order_key64(s);
-  }
+#undef THRIFT_LOAD_CHUNK
 }
 
 struct DecodeSelectArgs {
@@ -287,7 +317,9 @@ __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, 
     int n_lane = 0;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) n_lane += key[c] >= cand ? 1 : 0;
-    if (wave_total(n_lane) >= k) T = cand;
+    const int n = wave_total(n_lane);
+    if (n >= k) T = cand;
+    if (n == k) break;                                       // exactly the k largest lie at or above cand: done
   }
   int n_gt;
   {
@@ -296,7 +328,7 @@ __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, 
     for (int c = 0; c < MAXC; ++c) n_lane += key[c] > T ? 1 : 0;
     n_gt = wave_total(n_lane);
   }
-  const int need_ties = k - n_gt;                            // >= 1: keys equal to T, taken from the smallest id up
+  const int need_ties = k - n_gt;                            // keys equal to T, taken from the smallest id up (0 after an early exit above a gap)
   const uint64_t lt_mask = (1ULL << lane) - 1ULL;
   int written = 0, ties_seen = 0;
 #pragma unroll
@@ -318,11 +350,12 @@ __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, 
   if (out) for (int t = k + lane; t < p.kmax_out; t += 64) out[t] = -1;
 }
 
-void launch_decode_select(const float* qf32, const float* kmean, const int32_t* seqlens, uint64_t* keys,
+void launch_decode_select(const uint16_t* q16, int q_is_bf16, const float* kmean, const int32_t* seqlens, uint64_t* keys,
                           unsigned long long* bitmap, int words, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
                           int B, int Hq, int Hkv, int Tk, int fixed_k, long long ppm, int shared, hipStream_t st) {
   const int chunks = (Tk + 63) / 64;
-  decode_scores_kernel<<<dim3((unsigned)((long)B * Hkv * chunks)), dim3(256), 0, st>>>(qf32, kmean, seqlens, keys, Hq, Hkv, Tk, shared);
+  const int score_groups = (chunks + kScoreChunksPerWg - 1) / kScoreChunksPerWg;
+  decode_scores_kernel<<<dim3((unsigned)((long)B * Hkv * score_groups)), dim3(256), 0, st>>>(q16, q_is_bf16, kmean, seqlens, keys, Hq, Hkv, Tk, shared);
   DecodeSelectArgs p;
   p.keys = keys; p.seqlens = seqlens; p.bitmap = bitmap; p.idx_out = idx_out; p.cnt_out = cnt_out;
   p.Hq = Hq; p.Tk = Tk; p.words = words; p.kmax_out = kmax_out; p.fixed_k = fixed_k; p.ppm = ppm;

@@ -67,7 +67,7 @@ struct DecodeArgs {
 void launch_decode(const DecodeArgs& a, hipStream_t st);
 // decode-time selection: scores of the cached key-block means against the query heads, then per-row TopK
 // as a bitmap ([B*Hq][words], bit j%64 of word j/64) and optionally as ascending id lists
-void launch_decode_select(const float* qf32, const float* kmean, const int32_t* seqlens, uint64_t* keys,
+void launch_decode_select(const uint16_t* q16, int q_is_bf16, const float* kmean, const int32_t* seqlens, uint64_t* keys,
                           unsigned long long* bitmap, int words, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
                           int B, int Hq, int Hkv, int Tk, int fixed_k, long long ppm, int shared, hipStream_t st);
 

@@ -57,47 +57,6 @@ void launch_block_means(const void* x, thrift_dtype dt, long n_blocks, int block
     block_means_kernel<BF16><<<dim3((unsigned)n_blocks), dim3(256), 0, st>>>((const uint16_t*)x, means, block);
 }
 
-// ------------------------------------------------------------------------------------------------
-// MXFP4 quantisation of one 32-element group held as 16 packed pairs (pair u = elements 2u, 2u+1).
-// Returns the 16 code bytes in out[0..3] and the E8M0 byte.
-// ------------------------------------------------------------------------------------------------
-template <typename T>
-__device__ __forceinline__ uint32_t quantize_group32(const uint32_t (&pair)[16], uint32_t (&out)[4]) {
-  // magnitudes of 16-bit floats order like their bit patterns without the sign
-  uint32_t amax16 = 0;
-#pragma unroll
-  for (int u = 0; u < 16; ++u) {
-    uint32_t lo = pair[u] & 0x7fffu, hi = (pair[u] >> 16) & 0x7fffu;
-    amax16 = max(amax16, max(lo, hi));
-  }
-  const uint32_t abits = __float_as_uint(T::to_float((uint16_t)amax16));
-  const uint32_t sb = e8m0_from_amax_bits(abits);
-  out[0] = out[1] = out[2] = out[3] = 0u;
-  if (sb >= 1u || abits == 0u) {
-    // the hardware converter divides by a power-of-two scale given as a normal float
-    const float scale = __uint_as_float(sb << 23);
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      uint32_t& o = out[u >> 2];
-      switch (u & 3) {
-        case 0: o = T::template cvt_pk_fp4<0>(o, pair[u], scale); break;
-        case 1: o = T::template cvt_pk_fp4<1>(o, pair[u], scale); break;
-        case 2: o = T::template cvt_pk_fp4<2>(o, pair[u], scale); break;
-        default: o = T::template cvt_pk_fp4<3>(o, pair[u], scale); break;
-      }
-    }
-  } else {
-    // scale 2^-127 is a subnormal float: encode x * 2^127 in software (bf16 groups below 2^-124 only)
-#pragma unroll
-    for (int u = 0; u < 16; ++u) {
-      float lo = T::to_float((uint16_t)(pair[u] & 0xffffu)) * 0x1p64f * 0x1p63f;
-      float hi = T::to_float((uint16_t)(pair[u] >> 16)) * 0x1p64f * 0x1p63f;
-      out[u >> 2] |= (e2m1_encode_sw(lo) | (e2m1_encode_sw(hi) << 4)) << (8 * (u & 3));
-    }
-  }
-  return sb;
-}
-
 // axis 0: one thread per group of 32 consecutive channels (64 bytes in, 16 code bytes + 1 scale out).
 template <typename T>
 __global__ void __launch_bounds__(256) quantize_axis0_kernel(const uint16_t* __restrict__ x, uint8_t* __restrict__ codes,
@@ -291,12 +250,13 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
     for (int c = 0; c < MAXC; ++c)
       if (c * 64 < vis) n += __popcll(__ballot((c * 64 + lane < vis) && key[c] >= cand));
     if (n >= k) T = cand;
+    if (n == k) break;                                   // exactly the k largest lie at or above cand: done
   }
   int n_gt = 0;
 #pragma unroll
   for (int c = 0; c < MAXC; ++c)
     if (c * 64 < vis) n_gt += __popcll(__ballot((c * 64 + lane < vis) && key[c] > T));
-  const int need_ties = k - n_gt;                        // >= 1: ties at T, taken from the smallest id up
+  const int need_ties = k - n_gt;                        // ties at T, taken from the smallest id up (0 after an early exit above a gap)
   const uint64_t lt_mask = (1ULL << lane) - 1ULL;
   int written = 0, ties_seen = 0;
 #pragma unroll
