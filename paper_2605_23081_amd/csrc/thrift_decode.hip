@@ -182,7 +182,7 @@ __device__ __forceinline__ uint64_t order_key64(double s) {
   return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);   // larger double <=> larger key
 }
 
-constexpr int kScoreChunksPerWg = 4;     // 64-block chunks one workgroup of decode_scores_kernel walks
+constexpr int kScoreChunksPerWg = 8;     // 64-block chunks one workgroup of decode_scores_kernel walks
 
 __global__ void __launch_bounds__(256) decode_scores_kernel(const uint16_t* __restrict__ q16, int q_is_bf16, const float* __restrict__ kmean,
                                                             const int32_t* __restrict__ seqlens, uint64_t* __restrict__ keys,
