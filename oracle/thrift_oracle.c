@@ -420,6 +420,36 @@ void oracle_dequantize_mxfp4(const uint8_t* codes, const uint8_t* scales, int B,
 }
 
 /* ------------------------------------------------------------------ */
+/* NVFP4 variant (Sec. 3.2 as printed) — study aid, not the build's format */
+/* ------------------------------------------------------------------ */
+
+/* The paper quantises to NVFP4: E2M1 elements with one E4M3 scale per 16 elements, and for P the
+ * two-level scheme of Alg. 1 step 19.  The GPU path uses MXFP4 instead (what gfx950's matrix units
+ * take), so this variant exists only to measure, in the oracle, what that substitution costs.  The
+ * paper gives no scale rule; reading taken: scale = the group's max |x| / 6 rounded to the nearest
+ * E4M3 value (ties to even, at most 448, subnormals down to 2^-9); elements = x / scale rounded to
+ * E2M1 as in the MXFP4 rule (saturating); a group whose scale rounds to 0 is all zeros. */
+double oracle_e4m3_round(double x) {
+  double y = round_to_format(x, 3, -6, 8);
+  if (fabs(y) > 448.0) y = x < 0 ? -448.0 : 448.0;   /* the top mantissa code of the top binade is NaN: 448 is the largest */
+  return y;
+}
+
+/* Quantise-dequantise one group of n (16) values x[0], x[stride], ... into out[0], out[ostride], ... */
+static void nvfp4_qdq_group(const double* x, int n, int stride, double* out, int ostride) {
+  double amax = 0.0;
+  for (int t = 0; t < n; ++t) { double a = fabs(x[(long)t * stride]); if (a > amax) amax = a; }
+  double scale = oracle_e4m3_round(amax / 6.0);
+  for (int t = 0; t < n; ++t)
+    out[(long)t * ostride] = scale == 0.0 ? 0.0 : oracle_e2m1_decode(e2m1_encode(x[(long)t * stride] / scale)) * scale;
+}
+
+/* x: n doubles (n a multiple of 16) -> NVFP4 quantise-dequantise, groups of 16 consecutive values. */
+void oracle_nvfp4_qdq(const double* x, long n, double* out) {
+  for (long g = 0; g < n / 16; ++g) nvfp4_qdq_group(x + g * 16, 16, 1, out + g * 16, 1);
+}
+
+/* ------------------------------------------------------------------ */
 /* Exact attention  (Sec. 3.1, Eq. (1)) — the error reference          */
 /* ------------------------------------------------------------------ */
 
@@ -470,6 +500,7 @@ typedef struct {
   const double* vh;   /* [Nk,D] high-precision values */
   const double* kq;   /* [Nk,D] dequantised MXFP4 keys   */
   const double* vq;   /* [Nk,D] dequantised MXFP4 values */
+  int fmt;            /* 0: MXFP4 (the build's format); 1: NVFP4 (the paper's), see oracle_nvfp4_qdq */
 } kv_view_t;
 
 /* One (query row, key block) step of Alg. 1: scores on the chosen path, running max / sum update,
@@ -507,7 +538,15 @@ static void row_tile_step(const kv_view_t* kv, const double* qh, const double* q
     }
   } else {
     double Pd[256];
-    if (kv->quantize_p) {
+    if (kv->quantize_p && kv->fmt == 1) {
+      /* Alg. 1 step 19 as printed: first-level scale s1 = rowmax(P)/(448*6), then NVFP4 on P/s1 */
+      double pmax = 0.0, Y[256];
+      for (int c = 0; c < Bk; ++c) if (P[c] > pmax) pmax = P[c];
+      double s1 = pmax / (448.0 * 6.0);
+      for (int c = 0; c < Bk; ++c) Y[c] = s1 > 0.0 ? P[c] / s1 : 0.0;
+      for (int g = 0; g < Bk / 16; ++g) nvfp4_qdq_group(Y + g * 16, 16, 1, Pd + g * 16, 1);
+      for (int c = 0; c < Bk; ++c) Pd[c] *= s1;
+    } else if (kv->quantize_p) {
       uint8_t codes[32];
       for (int g = 0; g < Bk / 32; ++g) {
         uint8_t sb = mx_quantize_group(P + g * 32, 32, 1, codes, 1);
@@ -534,6 +573,7 @@ static int in_sorted(const int32_t* a, int n, int j) {
 static void head_to_double(const uint16_t* x, int dtype, long n, double* out) {
   for (long e = 0; e < n; ++e) out[e] = bits_to_double(x[e], dtype);
 }
+static void head_quant_dequant_fmt(const uint16_t* x, int dtype, int N, int D, int axis, int fmt, double* out);
 static void head_quant_dequant(const uint16_t* x, int dtype, int N, int D, int axis, double* out) {
   uint8_t* codes = (uint8_t*)malloc((size_t)N * D);
   uint8_t* scales = (uint8_t*)malloc((size_t)N * D / 32);
@@ -541,6 +581,19 @@ static void head_quant_dequant(const uint16_t* x, int dtype, int N, int D, int a
   oracle_dequantize_mxfp4(codes, scales, 1, 1, N, D, axis, out);
   free(codes);
   free(scales);
+}
+/* fmt 1: NVFP4 groups of 16 along D (axis 0) or along the tokens (axis 1, the contraction axis of P.V). */
+static void head_quant_dequant_fmt(const uint16_t* x, int dtype, int N, int D, int axis, int fmt, double* out) {
+  if (fmt == 0) { head_quant_dequant(x, dtype, N, D, axis, out); return; }
+  double* xd = (double*)malloc(sizeof(double) * (size_t)N * D);
+  head_to_double(x, dtype, (long)N * D, xd);
+  if (axis == 0) {
+    oracle_nvfp4_qdq(xd, (long)N * D, out);
+  } else {
+    for (int g = 0; g < N / 16; ++g)
+      for (int c = 0; c < D; ++c) nvfp4_qdq_group(xd + (long)g * 16 * D + c, 16, D, out + (long)g * 16 * D + c, D);
+  }
+  free(xd);
 }
 
 /*
@@ -558,7 +611,7 @@ static void head_quant_dequant(const uint16_t* x, int dtype, int N, int D, int a
 int oracle_attn_thrift_prefill_chunk(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
                                      const int32_t* idx, const int32_t* cnt, int kmax,
                                      int B, int Hq, int Hkv, int Nq, int q_block_offset, int N, int D, int Bq, int Bk,
-                                     int causal, double scale, int tile_order, int quantize_p, int force_path,
+                                     int causal, double scale, int tile_order, int quantize_p, int force_path, int fmt,
                                      const int32_t* units, int n_units, double* out, double* lse) {
   (void)B;
   if (Bk > 256 || Bk % 32 || D % 32) return -1;
@@ -578,9 +631,9 @@ int oracle_attn_thrift_prefill_chunk(const uint16_t* q, const uint16_t* k, const
       double* vq = (double*)malloc(sizeof(double) * hd);
       head_to_double(kb, dtype, hd, kh);
       head_to_double(vb, dtype, hd, vh);
-      head_quant_dequant(kb, dtype, N, D, 0, kq);
-      head_quant_dequant(vb, dtype, N, D, 1, vq);
-      kv_view_t kv = {D, Bk, dtype, quantize_p, scale, kh, vh, kq, vq};
+      head_quant_dequant_fmt(kb, dtype, N, D, 0, fmt, kq);
+      head_quant_dequant_fmt(vb, dtype, N, D, 1, fmt, vq);
+      kv_view_t kv = {D, Bk, dtype, quantize_p, scale, kh, vh, kq, vq, fmt};
 #pragma omp parallel for schedule(dynamic, 1)
       for (int u = 0; u < n_units; ++u) {
         int b = units[3 * u], h = units[3 * u + 1], i = units[3 * u + 2];
@@ -589,7 +642,7 @@ int oracle_attn_thrift_prefill_chunk(const uint16_t* q, const uint16_t* k, const
         double* qh = (double*)malloc(sizeof(double) * (size_t)Bq * D);
         double* qq = (double*)malloc(sizeof(double) * (size_t)Bq * D);
         head_to_double(qb, dtype, (long)Bq * D, qh);
-        head_quant_dequant(qb, dtype, Bq, D, 0, qq);
+        head_quant_dequant_fmt(qb, dtype, Bq, D, 0, fmt, qq);
         long rowid = ((long)b * Hq + h) * Tq + i;
         const int32_t* sel = idx ? idx + rowid * kmax : NULL;
         int nsel = cnt ? cnt[rowid] : 0;
@@ -633,7 +686,7 @@ int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint1
                                int tile_order, int quantize_p, int force_path,
                                const int32_t* units, int n_units, double* out, double* lse) {
   return oracle_attn_thrift_prefill_chunk(q, k, v, dtype, idx, cnt, kmax, B, Hq, Hkv, N, 0, N, D, Bq, Bk, causal, scale,
-                                          tile_order, quantize_p, force_path, units, n_units, out, lse);
+                                          tile_order, quantize_p, force_path, 0, units, n_units, out, lse);
 }
 
 /*
@@ -667,7 +720,7 @@ int oracle_attn_thrift_decode(const uint16_t* q, const uint16_t* k, const uint16
       head_to_double(vb, dtype, used, vh);
       head_quant_dequant(kb, dtype, Tk * Bk, D, 0, kq);
       head_quant_dequant(vb, dtype, Tk * Bk, D, 1, vq);
-      kv_view_t kv = {D, Bk, dtype, quantize_p, scale, kh, vh, kq, vq};
+      kv_view_t kv = {D, Bk, dtype, quantize_p, scale, kh, vh, kq, vq, 0};
       int sb = split_blocks > 0 ? split_blocks : (Tk > 0 ? Tk : 1);
       for (int h = g * grp; h < (g + 1) * grp; ++h) {
         double qh[1024], qq[1024];

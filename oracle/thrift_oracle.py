@@ -153,6 +153,20 @@ def select_ablation(selector: int, seed: int, B: int, Hq: int, Tq: int, Tk: int,
     return idx, cnt
 
 
+def e4m3_round(x: float) -> float:
+    f = lib().oracle_e4m3_round
+    f.restype = C.c_double
+    return float(f(C.c_double(x)))
+
+
+def nvfp4_qdq(x: np.ndarray) -> np.ndarray:
+    """NVFP4 quantise-dequantise of consecutive groups of 16 (the paper's format; study aid)."""
+    x = np.ascontiguousarray(x, np.float64)
+    out = np.empty_like(x)
+    lib().oracle_nvfp4_qdq(_p(x), C.c_long(x.size), _p(out))
+    return out
+
+
 def mx_quantize_group(x: Sequence[float]) -> Tuple[np.ndarray, int]:
     x = np.ascontiguousarray(x, np.float64)
     codes = np.empty(x.shape[0], np.uint8)
@@ -195,11 +209,11 @@ def attn_exact(q, k, v, dtype: int, causal: bool, scale: float, rows: np.ndarray
 
 def attn_thrift_prefill(q, k, v, dtype: int, idx, cnt, Bq: int, Bk: int, causal: bool, scale: float,
                         units: np.ndarray, tile_order: int = 0, quantize_p: bool = True, force_path: int = -1,
-                        want_lse: bool = False, q_block_offset: int = 0):
+                        want_lse: bool = False, q_block_offset: int = 0, fmt: int = 0):
     """units: [n,3] int32 (b, h, i).  -> out [n, Bq, D] fp64 (and lse [n, Bq]).
 
     q may hold fewer tokens than k, v (chunked prefill): query block i then stands at block position
-    i + q_block_offset of the sequence."""
+    i + q_block_offset of the sequence.  fmt 1: the paper's NVFP4 numerics instead of MXFP4 (study aid)."""
     q, k, v = _u16(q), _u16(k), _u16(v)
     B, Hq, Nq, D = q.shape
     Hkv, N = k.shape[1], k.shape[2]
@@ -214,7 +228,7 @@ def attn_thrift_prefill(q, k, v, dtype: int, idx, cnt, Bq: int, Bk: int, causal:
     rc = lib().oracle_attn_thrift_prefill_chunk(_p(q), _p(k), _p(v), dtype, _p(idx), _p(cnt), kmax, B, Hq, Hkv, Nq,
                                                 int(q_block_offset), N, D, Bq, Bk,
                                                 int(causal), C.c_double(scale), int(tile_order), int(quantize_p),
-                                                int(force_path), _p(units), units.shape[0], _p(out), _p(lse))
+                                                int(force_path), int(fmt), _p(units), units.shape[0], _p(out), _p(lse))
     if rc != 0:
         raise ValueError("unsupported shape")
     return (out, lse) if want_lse else out

@@ -358,3 +358,29 @@ def test_chunked_prefill_pins(oracle, dtype, Bq, nq_blocks):
     # selection with the same offset reproduces the tail rows of the full selection
     idx_c, cnt_c = oracle.select_topk(qm[:, :, off:], km, Bq, 64, True, 0.25, q_block_offset=off, kmax=idx.shape[-1])
     assert np.array_equal(idx_c, idx[:, :, off:]) and np.array_equal(cnt_c, cnt[:, :, off:])
+
+
+def test_nvfp4_variant_invariants(oracle):
+    """The paper-format study variant: the 16-bit path is untouched; the 4-bit path without P quantisation is exact
+    attention on the NVFP4-dequantised tensors; the two-level P quantisation stays within the format's error."""
+    w, q, k, v = _small("f16", N=256, Bq=64)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    units = _all_units(1, w.Hq, w.N // 64)
+    a = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, units, force_path=1, fmt=1)
+    b = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, units, force_path=1, fmt=0)
+    assert np.array_equal(a, b)
+    qd = oracle.nvfp4_qdq(q.double().numpy()).reshape(w.Hq, w.N, w.D)
+    kd = oracle.nvfp4_qdq(k.double().numpy()).reshape(w.N, w.D)
+    vt = np.ascontiguousarray(v.double().numpy().reshape(w.N, w.D).T)            # groups of 16 along the tokens
+    vd = oracle.nvfp4_qdq(vt).T
+    got = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, units, force_path=0, quantize_p=False,
+                                     fmt=1).reshape(w.Hq, w.N, w.D)
+    for h in range(w.Hq):
+        assert np.abs(got[h] - _softmax_attention_np(qd[h], kd, vd, True, scale)).max() < 1e-10
+    withp = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, units, force_path=0, fmt=1).reshape(w.Hq, w.N, w.D)
+    assert 0 < np.abs(withp - got).max() < 0.5
+    # NVFP4 (E4M3 scales per 16) is the finer format: closer to exact attention than MXFP4 on the same inputs
+    exact = oracle.attn_exact(qb, kb, vb, dt, True, scale, _all_rows(1, w.Hq, w.N)).reshape(w.Hq, w.N, w.D)
+    mx = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, units, force_path=0, fmt=0).reshape(w.Hq, w.N, w.D)
+    assert metrics.rel_fro(withp, exact) < metrics.rel_fro(mx, exact)

@@ -200,3 +200,38 @@ def test_cache_footprint_closed_form():
     assert abs((4 + 8 / 16) / 16 - 0.28125) < 1e-12
     # matched-compute identity of Sec. 4.4: 5 % of tiles at full cost + 95 % at a quarter = 28.75 %
     assert abs(0.05 + 0.95 / 4 - 0.2875) < 1e-12
+
+
+# ---------------------------------------------------------------- NVFP4 study variant (the paper's printed format)
+
+def test_e4m3_rounding_against_torch(oracle):
+    import torch
+    rng = np.random.default_rng(21)
+    xs = np.concatenate([rng.uniform(0, 460, 4000), np.exp(rng.uniform(np.log(2.0 ** -12), np.log(448.0), 4000)),
+                         [0.0, 2.0 ** -9, 2.0 ** -10, 3 * 2.0 ** -10, 448.0, 447.9, 464.0, 1.0, 1.0625, 1.1875]])
+    got = np.array([oracle.e4m3_round(float(x)) for x in xs])
+    ref = torch.tensor(np.minimum(xs, 448.0)).to(torch.float8_e4m3fn).to(torch.float64).numpy()   # torch does not saturate: clamp first
+    assert np.array_equal(got, ref)
+    assert oracle.e4m3_round(1e6) == 448.0 and oracle.e4m3_round(-3.0) == -3.0
+
+
+def test_nvfp4_group_against_brute_force(oracle):
+    import torch
+    rng = np.random.default_rng(22)
+    grid = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+    for trial in range(300):
+        x = rng.standard_normal(16) * np.exp(rng.uniform(-6, 6))
+        if trial % 7 == 0:
+            x[rng.integers(0, 16)] *= 30.0
+        got = oracle.nvfp4_qdq(x)
+        scale = float(torch.tensor(min(np.abs(x).max() / 6.0, 448.0)).to(torch.float8_e4m3fn).to(torch.float64))
+        y = np.abs(x) / scale
+        want = np.array([grid[np.argmin(np.abs(grid - min(v, 6.0)))] for v in y]) * scale * np.sign(x)
+        ties = np.isin(np.minimum(y, 6.0), [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+        assert np.array_equal(got[~ties], want[~ties])
+        if 2.0 ** -6 <= scale < 448.0:                        # normal E4M3 range: the scale is within 1/16 of max/6
+            assert np.abs(x).max() <= 6.0 * scale * (1 + 1 / 16)
+    assert np.array_equal(oracle.nvfp4_qdq(np.zeros(32)), np.zeros(32))
+    # two groups are independent
+    a, b = rng.standard_normal(16), 100 * rng.standard_normal(16)
+    assert np.array_equal(oracle.nvfp4_qdq(np.concatenate([a, b])), np.concatenate([oracle.nvfp4_qdq(a), oracle.nvfp4_qdq(b)]))
