@@ -188,6 +188,23 @@ thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void
                                         void* out, thrift_dtype out_dt, float* lse,
                                         void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * thrift_attn_prefill_chunk with a choice of tile order.
+ *   tile_order 0: key blocks in ascending order, as Alg. 1 is written (what the other entry points use);
+ *   tile_order 1: the order of the kernel in Sec. 3.3 — every 4-bit block in ascending order first, then
+ *                 the promoted blocks in ascending order.
+ * In exact arithmetic the two agree; the 4-bit rounding of P depends on the running maximum, so the
+ * results differ at the level of the quantisation noise.  Other values: THRIFT_ERR_SHAPE.
+ */
+thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const void* v, thrift_dtype dt,
+                                          const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
+                                          const uint8_t* v4, const uint8_t* vs,
+                                          const int32_t* idx, const int32_t* cnt, int kmax,
+                                          int B, int Hq, int Hkv, int Nq, int q_block_offset, int Nkv, int D, int Bq, int Bk,
+                                          int causal, int tile_order, float softmax_scale,
+                                          void* out, thrift_dtype out_dt, float* lse,
+                                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* Host: bytes of workspace thrift_attn_decode needs. */
 size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int Bk, int split_blocks);
 

@@ -21,7 +21,7 @@ _DT = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 EXPORTS = (
     "thrift_status_string", "thrift_row_budget", "thrift_visible_blocks", "thrift_budget_to_global_k",
     "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_select_topk_shared", "thrift_select_ablation", "thrift_quantize_mxfp4",
-    "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_prefill_chunk",
+    "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_prefill_chunk", "thrift_attn_prefill_ordered",
     "thrift_attn_decode_workspace", "thrift_attn_decode", "thrift_attn_decode_shared",
 )
 
@@ -57,6 +57,7 @@ def lib() -> C.CDLL:
         L.thrift_attn_prefill_workspace.argtypes = [i] * 8
         L.thrift_attn_prefill.argtypes = [p, p, p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, i, i, i, f, p, i, p, p, sz, p]
         L.thrift_attn_prefill_chunk.argtypes = [p, p, p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, i, i, i, i, i, f, p, i, p, p, sz, p]
+        L.thrift_attn_prefill_ordered.argtypes = [p, p, p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, i, i, i, i, i, i, f, p, i, p, p, sz, p]
         L.thrift_attn_decode_workspace.restype = sz
         L.thrift_attn_decode_workspace.argtypes = [i] * 7
         L.thrift_attn_decode.argtypes = [p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, d, i, i, f, p, i, p, p, i, p, sz, p]
@@ -194,8 +195,9 @@ def thrift_attn_prefill(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq: int, Bk: 
 
 def thrift_attn_prefill_chunk(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq: int, Bk: int, causal: bool, q_block_offset: int,
                               softmax_scale: float = 0.0, out: Optional[torch.Tensor] = None,
-                              out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """q, q4, qs: the chunk's Nq tokens; k, v and their codes: the whole key range."""
+                              out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None,
+                              tile_order: int = 0) -> torch.Tensor:
+    """q, q4, qs: the chunk's Nq tokens; k, v and their codes: the whole key range.  tile_order 1: Sec. 3.3's order."""
     for t in (q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt):
         _dev(t)
     B, Hq, Nq, D = q.shape
@@ -203,10 +205,10 @@ def thrift_attn_prefill_chunk(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq: int
     if out is None:
         out = torch.empty(B, Hq, Nq, D, dtype=out_dtype or q.dtype, device=q.device)
     kmax = idx.shape[-1]
-    _check(lib().thrift_attn_prefill_chunk(_ptr(q), _ptr(k), _ptr(v), _DT[q.dtype], _ptr(q4), _ptr(qs), _ptr(k4), _ptr(ks),
-                                           _ptr(v4), _ptr(vs), _ptr(idx), _ptr(cnt), kmax, B, Hq, Hkv, Nq, int(q_block_offset),
-                                           Nkv, D, Bq, Bk, int(causal), float(softmax_scale), _ptr(out), _DT[out.dtype],
-                                           _ptr(lse), None, 0, _stream()), "thrift_attn_prefill_chunk")
+    _check(lib().thrift_attn_prefill_ordered(_ptr(q), _ptr(k), _ptr(v), _DT[q.dtype], _ptr(q4), _ptr(qs), _ptr(k4), _ptr(ks),
+                                             _ptr(v4), _ptr(vs), _ptr(idx), _ptr(cnt), kmax, B, Hq, Hkv, Nq, int(q_block_offset),
+                                             Nkv, D, Bq, Bk, int(causal), int(tile_order), float(softmax_scale), _ptr(out),
+                                             _DT[out.dtype], _ptr(lse), None, 0, _stream()), "thrift_attn_prefill_ordered")
     return out
 
 

@@ -200,15 +200,16 @@ thrift_status thrift_quantize_mxfp4(const void* x, thrift_dtype dt, int B, int H
 
 size_t thrift_attn_prefill_workspace(int, int, int, int, int, int, int, int) { return 0; }
 
-thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void* v, thrift_dtype dt,
-                                        const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
-                                        const uint8_t* v4, const uint8_t* vs,
-                                        const int32_t* idx, const int32_t* cnt, int kmax,
-                                        int B, int Hq, int Hkv, int Nq, int q_block_offset, int Nkv, int D, int Bq, int Bk,
-                                        int causal, float softmax_scale,
-                                        void* out, thrift_dtype out_dt, float* lse,
-                                        void* workspace, size_t workspace_bytes, void* stream) {
+thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const void* v, thrift_dtype dt,
+                                          const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
+                                          const uint8_t* v4, const uint8_t* vs,
+                                          const int32_t* idx, const int32_t* cnt, int kmax,
+                                          int B, int Hq, int Hkv, int Nq, int q_block_offset, int Nkv, int D, int Bq, int Bk,
+                                          int causal, int tile_order, float softmax_scale,
+                                          void* out, thrift_dtype out_dt, float* lse,
+                                          void* workspace, size_t workspace_bytes, void* stream) {
   (void)workspace; (void)workspace_bytes;
+  if (tile_order != 0 && tile_order != 1) return THRIFT_ERR_SHAPE;
   if (!q || !k || !v || !q4 || !qs || !k4 || !ks || !v4 || !vs || !idx || !cnt || !out) return THRIFT_ERR_NULL;
   if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Nq <= 0 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock ||
@@ -222,11 +223,23 @@ thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.q4 = q4; a.qs = qs; a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.idx = idx; a.cnt = cnt;
   a.out = out; a.lse = lse; a.kmax = kmax; a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.N = Nkv; a.Bq = Bq; a.causal = causal ? 1 : 0;
-  a.Nq = Nq; a.q_off = causal ? q_block_offset : 0;
+  a.Nq = Nq; a.q_off = causal ? q_block_offset : 0; a.tile_order = tile_order;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
   a.dt = dt; a.out_dt = out_dt;
   launch_prefill(a, (hipStream_t)stream);
   return after_launch();
+}
+
+thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void* v, thrift_dtype dt,
+                                        const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,
+                                        const uint8_t* v4, const uint8_t* vs,
+                                        const int32_t* idx, const int32_t* cnt, int kmax,
+                                        int B, int Hq, int Hkv, int Nq, int q_block_offset, int Nkv, int D, int Bq, int Bk,
+                                        int causal, float softmax_scale,
+                                        void* out, thrift_dtype out_dt, float* lse,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  return thrift_attn_prefill_ordered(q, k, v, dt, q4, qs, k4, ks, v4, vs, idx, cnt, kmax, B, Hq, Hkv, Nq, q_block_offset, Nkv, D,
+                                     Bq, Bk, causal, 0, softmax_scale, out, out_dt, lse, workspace, workspace_bytes, stream);
 }
 
 thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, thrift_dtype dt,

@@ -39,6 +39,7 @@ struct PrefillArgs {
   void* out;
   float* lse;
   int kmax, B, Hq, Hkv, N, Bq, causal;   // N: key tokens per head
+  int tile_order;                         // 0: key blocks ascending (Alg. 1); 1: 4-bit blocks first, then promoted (Sec. 3.3)
   int Nq, q_off;                          // query tokens per head; block position of query block 0 in the sequence
   float scale;            // softmax scale (already defaulted)
   thrift_dtype dt, out_dt;

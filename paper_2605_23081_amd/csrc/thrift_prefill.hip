@@ -54,7 +54,7 @@ __device__ __forceinline__ void dma_b32(const void* base, uint32_t off, uint32_t
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
 }
 
-template <typename T, int NW>
+template <typename T, int NW, int ORDER>
 __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   constexpr int KF = 4 / NW;                 // 1 KiB fragments of a 4-bit K (and of a V) tile per wavefront
   constexpr int C16 = 16 / NW;               // ... for one 16-bit K or V tile
@@ -120,22 +120,24 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   const uint32_t v16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ v16_swizzle(lane >> 4)) * 16);
   const uint32_t k16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ (lane >> 4)) * 16);   // rows 32..63: chunk ^ 4 more
 
-#define THRIFT_ISSUE4(J)                                                                                       \
+#define THRIFT_ISSUE4(J) THRIFT_ISSUE4_SLOT(J, (J) & 1)
+#define THRIFT_ISSUE4_SLOT(J, S)                                                                               \
   do {                                                                                                         \
-    const uint8_t* kt_ = k4base + (size_t)(J) * 4096;                                                          \
-    const uint8_t* vt_ = v4base + (size_t)(J) * 4096;                                                          \
-    const uint32_t sl_ = lds0 + kLdsRing + ((J) & 1) * kLdsBytes4;                                                   \
+    const int j_ = __builtin_amdgcn_readfirstlane(J), s_ = __builtin_amdgcn_readfirstlane(S); /* scalar operands */ \
+    const uint8_t* kt_ = k4base + (size_t)j_ * 4096;                                                           \
+    const uint8_t* vt_ = v4base + (size_t)j_ * 4096;                                                           \
+    const uint32_t sl_ = lds0 + kLdsRing + s_ * kLdsBytes4;                                                   \
     _Pragma("unroll") for (int u = 0; u < KF; ++u) {                                                           \
       dma_b128(kt_, k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024);                                          \
       dma_b128(vt_, v4off[u], sl_ + kLdsV4 + (wave * KF + u) * 1024);                                          \
     }                                                                                                          \
     /* scale bytes: even wavefronts fetch K's 256, odd ones V's (duplicates write the same bytes) */           \
-    if (wave & 1) dma_b32(vsbase + (size_t)(J) * 256, scoff, sl_ + kLdsVS);                                    \
-    else dma_b32(ksbase + (size_t)(J) * 256, scoff, sl_ + kLdsKS);                                             \
+    if (wave & 1) dma_b32(vsbase + (size_t)j_ * 256, scoff, sl_ + kLdsVS);                                     \
+    else dma_b32(ksbase + (size_t)j_ * 256, scoff, sl_ + kLdsKS);                                             \
   } while (0)
 #define THRIFT_ISSUE_V16(J)                                                                                    \
   do {                                                                                                         \
-    const uint8_t* vt_ = v16base + (size_t)(J) * kTile16;                                                      \
+    const uint8_t* vt_ = v16base + (size_t)__builtin_amdgcn_readfirstlane(J) * kTile16;                        \
     const uint32_t vb_ = lds0 + kLdsV16;                                                     \
     _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                          \
       const int q_ = u * NW + wave;                                                                            \
@@ -144,7 +146,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   } while (0)
 #define THRIFT_ISSUE_K16(J)                                                                                    \
   do {                                                                                                         \
-    const uint8_t* kt_ = k16base + (size_t)(J) * kTile16;                                                      \
+    const uint8_t* kt_ = k16base + (size_t)__builtin_amdgcn_readfirstlane(J) * kTile16;                        \
     _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                          \
       const int q_ = u * NW + wave;                                                                            \
       dma_b128(kt_ + q_ * 1024, u * NW >= 8 ? k16off ^ 64u : k16off, lds0 + kLdsK16 + q_ * 1024);              \
@@ -157,15 +159,6 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   for (int n = 0; n < 4; ++n) o[n] = (v16f){0.f};
   const float c = a.scale * 1.4426950408889634f;
 
-  // prologue: block 0 on its way
-  if (vis > 0) {
-    if (n0 == 0) {
-      THRIFT_ISSUE_K16(0);
-      THRIFT_ISSUE_V16(0);
-    } else {
-      THRIFT_ISSUE4(0);
-    }
-  }
   // Blocks this wavefront computes: those with at least one key at or before its last query row.  The
   // later blocks of the workgroup (visible only to wavefronts with later rows) are still staged and
   // synchronised on, in a final loop without arithmetic.
@@ -198,6 +191,89 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   n0 = n1;                                                                                                     \
   n1 = ps + 1 < nsel ? sel[ps + 1] : 0x7fffffff;
 
+  if constexpr (ORDER == 1) {
+    // ---- the order of Sec. 3.3: every 4-bit block in ascending order, then the promoted blocks in ascending
+    // order.  Same staging rules; the ring slot follows the step number because block ids now skip. ----
+    int nselv = nsel;                                   // promoted ids inside the visible range (the list is ascending)
+    if (nsel > 0 && sel[nsel - 1] >= vis) {
+      nselv = 0;
+      while (nselv < nsel && sel[nselv] < vis) ++nselv;
+    }
+    int pa = 0;                                         // promoted ids the 4-bit walk has passed
+    int nx = nselv > 0 ? sel[0] : 0x7fffffff;           // the next promoted id at or after the 4-bit walk's position
+    int j = 0;
+    while (j == nx) { ++j; ++pa; nx = pa < nselv ? sel[pa] : 0x7fffffff; }
+    if (j < vis) {
+      THRIFT_ISSUE4_SLOT(j, 0);
+    } else if (nselv > 0) {
+      THRIFT_ISSUE_K16(sel[0]);
+      THRIFT_ISSUE_V16(sel[0]);
+    }
+    int t = 0;
+    while (j < vis) {                                   // phase A
+      int jn = j + 1;
+      while (jn == nx) { ++jn; ++pa; nx = pa < nselv ? sel[pa] : 0x7fffffff; }
+      THRIFT_SYNC()
+      if (jn < vis) {
+        THRIFT_ISSUE4_SLOT(jn, (t + 1) & 1);
+      } else if (nselv > 0) {
+        THRIFT_ISSUE_K16(sel[0]);
+        THRIFT_ISSUE_V16(sel[0]);
+      }
+      if (j < vis_wave) {
+        THRIFT_MASK(j)
+        const unsigned char* slot = lds + kLdsRing + (t & 1) * kLdsBytes4;
+        v16f s[2];
+        float gmax;
+        scores_fp4(slot, lane, qf4, qsc, s);
+        const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+        rescale(o, alpha);
+        pv_fp4(slot, lane, s, gmax, o);
+      }
+      j = jn;
+      ++t;
+    }
+    for (int sidx = 0; sidx < nselv; ++sidx) {          // phase B: promoted blocks follow each other
+      const int jb = sel[sidx];
+      const bool p1 = sidx + 1 < nselv;
+      const bool mine = jb < vis_wave;
+      THRIFT_SYNC()
+      if (late_v) THRIFT_ISSUE_V16(jb);
+      THRIFT_MASK(jb)
+      v16f s[2];
+      float gmax, alpha = 1.0f;
+      if (mine) {
+        v8s qf[8];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16row + 16 * s8 + 8 * half);
+        scores_16<T>(lds + kLdsK16, lane, qf, s);
+      }
+      if (p1) {
+        lds_barrier();
+        THRIFT_ISSUE_K16(sel[sidx + 1]);
+      }
+      if (mine) {
+        alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+        rescale(o, alpha);
+      }
+      if (late_v) {
+        if (p1) vm_wait<C16>();
+        else vm_wait<0>();
+        lds_barrier();
+      }
+      if (mine) pv_16<T, true>(lds + kLdsV16, lane, s, o);
+      late_v = p1;
+    }
+  } else {
+  // prologue: block 0 on its way
+  if (vis > 0) {
+    if (n0 == 0) {
+      THRIFT_ISSUE_K16(0);
+      THRIFT_ISSUE_V16(0);
+    } else {
+      THRIFT_ISSUE4(0);
+    }
+  }
   // The walk alternates between runs of 4-bit blocks (tight loop: only the scaled-FP4 path, accumulators
   // updated in place) and single promoted blocks.
   int j = 0;
@@ -270,12 +346,14 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
       late_v = false;
     }
   }
+  }
   vm_wait<0>();
 #undef THRIFT_SYNC
 #undef THRIFT_ISSUE
 #undef THRIFT_MASK
 #undef THRIFT_NEXT_PROMOTED
 #undef THRIFT_ISSUE4
+#undef THRIFT_ISSUE4_SLOT
 #undef THRIFT_ISSUE_V16
 #undef THRIFT_ISSUE_K16
 
@@ -308,13 +386,19 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
 
 void launch_prefill(const PrefillArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((long)a.B * a.Hq * (a.Nq / a.Bq));
+#define THRIFT_LAUNCH(T, NW)                                                                                   \
+  do {                                                                                                         \
+    if (a.tile_order == 1) prefill_kernel<T, NW, 1><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);                  \
+    else prefill_kernel<T, NW, 0><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);                                    \
+  } while (0)
   if (a.Bq == 128) {
-    if (a.dt == THRIFT_F16) prefill_kernel<F16, 4><<<dim3(grid), dim3(256), 0, st>>>(a);
-    else prefill_kernel<BF16, 4><<<dim3(grid), dim3(256), 0, st>>>(a);
+    if (a.dt == THRIFT_F16) THRIFT_LAUNCH(F16, 4);
+    else THRIFT_LAUNCH(BF16, 4);
   } else {
-    if (a.dt == THRIFT_F16) prefill_kernel<F16, 2><<<dim3(grid), dim3(128), 0, st>>>(a);
-    else prefill_kernel<BF16, 2><<<dim3(grid), dim3(128), 0, st>>>(a);
+    if (a.dt == THRIFT_F16) THRIFT_LAUNCH(F16, 2);
+    else THRIFT_LAUNCH(BF16, 2);
   }
+#undef THRIFT_LAUNCH
 }
 
 }  // namespace thrift

@@ -506,3 +506,40 @@ def test_decode_shared_selection(T, oracle, budget):
     err = np.abs(to_np(got) - want).max()
     _say(f"  max abs err {err:.3e}")
     assert err <= TOLMIX
+
+
+# ------------------------------------------------------------------ tile order of Sec. 3.3 (4-bit blocks first)
+@pytest.mark.parametrize("wl,budget,causal", [
+    (W.TINY, 0.05, True),
+    (_small_bf16(N=2048), 0.25, True),
+    (_small_bf16(N=1024, Hq=2, Hkv=1, Bq=64), 0.5, True),
+    (_small_bf16(N=1024), 1.0, True),                       # no 4-bit block at all
+    (_small_bf16(N=1024), 0.0, True),                       # no promoted block at all
+    (_small_bf16(N=1024), 0.1, False),
+])
+def test_prefill_two_phase_order(T, oracle, wl, budget, causal):
+    _say(f"two-phase tile order {wl.name} N={wl.N} Bq={wl.Bq} f={budget} causal={causal}")
+    q, k, v, _, _ = W.make_prefill(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(wl.D)
+    Tq = wl.N // wl.Bq
+    qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    idx, cnt = oracle.select_topk(qm, km, wl.Bq, wl.Bk, causal, budget)
+    want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, wl.Bq, wl.Bk, causal, scale, _units(wl.B, wl.Hq, Tq),
+                                      tile_order=1).reshape(wl.B, wl.Hq, wl.N, wl.D)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    ig, cg = torch.from_numpy(idx).cuda(), torch.from_numpy(cnt).cuda()
+    got = T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0,
+                                      out_dtype=torch.float32, tile_order=1)
+    torch.cuda.synchronize()
+    err = np.abs(to_np(got) - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert err <= (TOL16 if budget == 1.0 else TOLMIX)
+    if budget in (0.0, 1.0):                                # a single phase: the same arithmetic as the ascending walk
+        asc = T.thrift_attn_prefill(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(asc, got)
+    with pytest.raises(T.ThriftError) as e:
+        T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0, tile_order=2)
+    assert e.value.code == 2
