@@ -92,7 +92,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
 
   const int vis = a.causal ? min(Tk, ((i + a.q_off + 1) * Bq - 1) / kBk + 1) : Tk;
   const int32_t* sel = a.idx + (qh * Tq + i) * a.kmax;
-  const int nsel = a.cnt[qh * Tq + i];
+  const int nsel = min(a.cnt[qh * Tq + i], a.kmax);      // a count beyond the list length is cut, never followed
   // the next two promoted block ids at or after the current block (ascending list)
   int ps = 0;
   int n0 = nsel > 0 ? sel[0] : 0x7fffffff, n1 = nsel > 1 ? sel[1] : 0x7fffffff;
