@@ -98,17 +98,20 @@ double oracle_round_to_dtype(double x, int dtype) {
 /* Block means  (Sec. 3.2, Alg. 1 step 3)                              */
 /* ------------------------------------------------------------------ */
 
-/* x: [B,H,N,D] raw 16-bit values; means: [B,H,N/block,D] fp32 (the arithmetic mean, computed in
- * fp64 and rounded once to fp32). */
+/* x: [B,H,N,D] raw 16-bit values; means: [B,H,ceil(N/block),D] fp32 (the arithmetic mean, computed in
+ * fp64 and rounded once to fp32).  A last block with fewer than `block` tokens (N not a multiple of
+ * the block: the paper's n = floor(L/64) leaves the tail unspecified) is the mean of the tokens it has. */
 void oracle_block_means(const uint16_t* x, int dtype, int B, int H, int N, int D, int block, float* means) {
-  int T = N / block;
+  int T = (N + block - 1) / block;
   for (long bh = 0; bh < (long)B * H; ++bh)
-    for (int t = 0; t < T; ++t)
+    for (int t = 0; t < T; ++t) {
+      int cnt = N - t * block < block ? N - t * block : block;
       for (int c = 0; c < D; ++c) {
         double s = 0.0;
-        for (int r = 0; r < block; ++r) s += bits_to_double(x[((bh * N) + (long)t * block + r) * D + c], dtype);
-        means[(bh * T + t) * D + c] = (float)(s / (double)block);
+        for (int r = 0; r < cnt; ++r) s += bits_to_double(x[((bh * N) + (long)t * block + r) * D + c], dtype);
+        means[(bh * T + t) * D + c] = (float)(s / (double)cnt);
       }
+    }
 }
 
 /* ------------------------------------------------------------------ */
@@ -383,7 +386,8 @@ uint8_t oracle_mx_quantize_group(const double* x, int n, uint8_t* codes) {
 
 /* x: [B,H,N,D] raw 16-bit.  codes: [B,H,N,D], ONE code (0..15) per byte, unpacked.
  * axis 0: groups of 32 along D, scales [B,H,N,D/32].
- * axis 1: groups of 32 along N, scales [B,H,N/32,D]. */
+ * axis 1: groups of 32 along N, scales [B,H,ceil(N/32),D]; a last group with fewer than 32 tokens is
+ *         quantised from the tokens it has. */
 void oracle_quantize_mxfp4(const uint16_t* x, int dtype, int B, int H, int N, int D, int axis,
                            uint8_t* codes, uint8_t* scales) {
   double grp[32];
@@ -398,11 +402,14 @@ void oracle_quantize_mxfp4(const uint16_t* x, int dtype, int B, int H, int N, in
           scales[(bh * N + n) * (D / 32) + g] = mx_quantize_group(grp, 32, 1, cb + (long)n * D + g * 32, 1);
         }
     } else {
-      for (int g = 0; g < N / 32; ++g)
+      int NG = (N + 31) / 32;
+      for (int g = 0; g < NG; ++g) {
+        int cntg = N - g * 32 < 32 ? N - g * 32 : 32;
         for (int c = 0; c < D; ++c) {
-          for (int t = 0; t < 32; ++t) grp[t] = bits_to_double(xb[((long)g * 32 + t) * D + c], dtype);
-          scales[(bh * (N / 32) + g) * D + c] = mx_quantize_group(grp, 32, 1, cb + (long)g * 32 * D + c, D);
+          for (int t = 0; t < cntg; ++t) grp[t] = bits_to_double(xb[((long)g * 32 + t) * D + c], dtype);
+          scales[(bh * NG + g) * D + c] = mx_quantize_group(grp, cntg, 1, cb + (long)g * 32 * D + c, D);
         }
+      }
     }
   }
 }
@@ -414,7 +421,7 @@ void oracle_dequantize_mxfp4(const uint8_t* codes, const uint8_t* scales, int B,
     for (int n = 0; n < N; ++n)
       for (int c = 0; c < D; ++c) {
         long e = bh * (long)N * D + (long)n * D + c;
-        int sb = axis == 0 ? scales[(bh * N + n) * (D / 32) + c / 32] : scales[(bh * (N / 32) + n / 32) * D + c];
+        int sb = axis == 0 ? scales[(bh * N + n) * (D / 32) + c / 32] : scales[(bh * ((N + 31) / 32) + n / 32) * D + c];
         out[e] = ldexp(oracle_e2m1_decode(codes[e]), sb - 127);
       }
 }
@@ -576,7 +583,7 @@ static void head_to_double(const uint16_t* x, int dtype, long n, double* out) {
 static void head_quant_dequant_fmt(const uint16_t* x, int dtype, int N, int D, int axis, int fmt, double* out);
 static void head_quant_dequant(const uint16_t* x, int dtype, int N, int D, int axis, double* out) {
   uint8_t* codes = (uint8_t*)malloc((size_t)N * D);
-  uint8_t* scales = (uint8_t*)malloc((size_t)N * D / 32);
+  uint8_t* scales = (uint8_t*)malloc((size_t)((N + 31) / 32) * D + (size_t)N * (D / 32));
   oracle_quantize_mxfp4(x, dtype, 1, 1, N, D, axis, codes, scales);
   oracle_dequantize_mxfp4(codes, scales, 1, 1, N, D, axis, out);
   free(codes);
@@ -615,7 +622,7 @@ int oracle_attn_thrift_prefill_chunk(const uint16_t* q, const uint16_t* k, const
                                      const int32_t* units, int n_units, double* out, double* lse) {
   (void)B;
   if (Bk > 256 || Bk % 32 || D % 32) return -1;
-  int grp = Hq / Hkv, Tq = Nq / Bq, Tk = N / Bk;
+  int grp = Hq / Hkv, Tq = (Nq + Bq - 1) / Bq, Tk = (N + Bk - 1) / Bk;   /* last blocks may be short */
   /* group the work by kv head so that each head's K/V is converted once */
   for (int b0 = 0; b0 < B; ++b0)
     for (int g = 0; g < Hkv; ++g) {
@@ -641,8 +648,9 @@ int oracle_attn_thrift_prefill_chunk(const uint16_t* q, const uint16_t* k, const
         const uint16_t* qb = q + (((long)b * Hq + h) * Nq + (long)i * Bq) * D;
         double* qh = (double*)malloc(sizeof(double) * (size_t)Bq * D);
         double* qq = (double*)malloc(sizeof(double) * (size_t)Bq * D);
-        head_to_double(qb, dtype, (long)Bq * D, qh);
-        head_quant_dequant_fmt(qb, dtype, Bq, D, 0, fmt, qq);
+        int rq = Nq - i * Bq < Bq ? Nq - i * Bq : Bq;        /* rows this query block really has */
+        head_to_double(qb, dtype, (long)rq * D, qh);
+        head_quant_dequant_fmt(qb, dtype, rq, D, 0, fmt, qq);
         long rowid = ((long)b * Hq + h) * Tq + i;
         const int32_t* sel = idx ? idx + rowid * kmax : NULL;
         int nsel = cnt ? cnt[rowid] : 0;
@@ -660,13 +668,14 @@ int oracle_attn_thrift_prefill_chunk(const uint16_t* q, const uint16_t* k, const
           double m = -INFINITY, l = 0.0;
           double* O = out + ((long)u * Bq + r) * D;
           for (int x = 0; x < D; ++x) O[x] = 0.0;
+          if (r >= rq) { if (lse) lse[(long)u * Bq + r] = 0.0; continue; }   /* past the last query: left zero */
           long qpos = ((long)i + q_block_offset) * Bq + r;
           for (int t = 0; t < no; ++t) {
             int j = order[t];
-            int n_valid = Bk;
+            int n_valid = N - j * Bk < Bk ? N - j * Bk : Bk;   /* a short last key block */
             if (causal) {
               long nv = qpos - (long)j * Bk + 1;
-              n_valid = nv < 0 ? 0 : (nv > Bk ? Bk : (int)nv);
+              if (nv < n_valid) n_valid = nv < 0 ? 0 : (int)nv;
             }
             row_tile_step(&kv, qh + (long)r * D, qq + (long)r * D, j, path[t], n_valid, &m, &l, O);
           }
@@ -694,8 +703,8 @@ int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint1
  * paper's algorithm with a one-row query block, evaluated split-K: the key blocks are cut into
  * partitions of split_blocks blocks, each partition runs Alg. 1's recurrence from a fresh
  * (m,l,O), and the partitions are merged by their log-sum-exp.  split_blocks <= 0: one partition.
- * q:[B,Hq,D]; k,v:[B,Hkv,Nkv,D]; idx:[B,Hq,kmax], cnt:[B,Hq]; seqlens nullable [B] (multiples
- * of Bk).  out: [B,Hq,D] fp64.
+ * q:[B,Hq,D]; k,v:[B,Hkv,Nkv,D]; idx:[B,Hq,kmax], cnt:[B,Hq]; seqlens nullable [B] (any length up
+ * to Nkv: the last key block may be short).  out: [B,Hq,D] fp64.
  */
 int oracle_attn_thrift_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
                               const int32_t* idx, const int32_t* cnt, int kmax, const int32_t* seqlens,
@@ -707,19 +716,19 @@ int oracle_attn_thrift_decode(const uint16_t* q, const uint16_t* k, const uint16
   for (int b = 0; b < B; ++b)
     for (int g = 0; g < Hkv; ++g) {
       int len = seqlens ? seqlens[b] : Nkv;
-      int Tk = len / Bk;
+      int Tk = (len + Bk - 1) / Bk;                         /* the last block may hold fewer than Bk tokens */
       long hd = (long)Nkv * D;
       const uint16_t* kb = k + ((long)b * Hkv + g) * hd;
       const uint16_t* vb = v + ((long)b * Hkv + g) * hd;
-      long used = (long)Tk * Bk * D;
+      long used = (long)len * D;
       double* kh = (double*)malloc(sizeof(double) * (size_t)(used > 0 ? used : 1));
       double* vh = (double*)malloc(sizeof(double) * (size_t)(used > 0 ? used : 1));
       double* kq = (double*)malloc(sizeof(double) * (size_t)(used > 0 ? used : 1));
       double* vq = (double*)malloc(sizeof(double) * (size_t)(used > 0 ? used : 1));
       head_to_double(kb, dtype, used, kh);
       head_to_double(vb, dtype, used, vh);
-      head_quant_dequant(kb, dtype, Tk * Bk, D, 0, kq);
-      head_quant_dequant(vb, dtype, Tk * Bk, D, 1, vq);
+      head_quant_dequant(kb, dtype, len, D, 0, kq);
+      head_quant_dequant(vb, dtype, len, D, 1, vq);
       kv_view_t kv = {D, Bk, dtype, quantize_p, scale, kh, vh, kq, vq, 0};
       int sb = split_blocks > 0 ? split_blocks : (Tk > 0 ? Tk : 1);
       for (int h = g * grp; h < (g + 1) * grp; ++h) {
@@ -736,7 +745,7 @@ int oracle_attn_thrift_decode(const uint16_t* q, const uint16_t* k, const uint16
           for (int x = 0; x < D; ++x) O[x] = 0.0;
           for (int j = p0; j < p0 + sb && j < Tk; ++j) {
             int is16 = force_path >= 0 ? force_path : in_sorted(sel, nsel, j);
-            row_tile_step(&kv, qh, qq, j, is16, Bk, &m, &l, O);
+            row_tile_step(&kv, qh, qq, j, is16, len - j * Bk < Bk ? len - j * Bk : Bk, &m, &l, O);
           }
           /* log-sum-exp merge of the partition into the running total */
           double Mn = M > m ? M : m;

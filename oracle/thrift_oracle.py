@@ -82,7 +82,7 @@ def round_to_dtype(x: float, dtype: int) -> float:
 def block_means(x: np.ndarray, dtype: int, block: int) -> np.ndarray:
     x = _u16(x)
     B, H, N, D = x.shape
-    out = np.empty((B, H, N // block, D), np.float32)
+    out = np.empty((B, H, -(-N // block), D), np.float32)      # a short last block is the mean of its own tokens
     lib().oracle_block_means(_p(x), dtype, B, H, N, D, block, _p(out))
     return out
 
@@ -175,11 +175,11 @@ def mx_quantize_group(x: Sequence[float]) -> Tuple[np.ndarray, int]:
 
 
 def quantize_mxfp4(x: np.ndarray, dtype: int, axis: int):
-    """-> (codes [B,H,N,D] one code per byte, scales [B,H,N,D/32] or [B,H,N/32,D])."""
+    """-> (codes [B,H,N,D] one code per byte, scales [B,H,N,D/32] or [B,H,ceil(N/32),D])."""
     x = _u16(x)
     B, H, N, D = x.shape
     codes = np.empty((B, H, N, D), np.uint8)
-    scales = np.empty((B, H, N, D // 32) if axis == 0 else (B, H, N // 32, D), np.uint8)
+    scales = np.empty((B, H, N, D // 32) if axis == 0 else (B, H, -(-N // 32), D), np.uint8)
     lib().oracle_quantize_mxfp4(_p(x), dtype, B, H, N, D, axis, _p(codes), _p(scales))
     return codes, scales
 

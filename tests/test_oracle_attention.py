@@ -384,3 +384,61 @@ def test_nvfp4_variant_invariants(oracle):
     exact = oracle.attn_exact(qb, kb, vb, dt, True, scale, _all_rows(1, w.Hq, w.N)).reshape(w.Hq, w.N, w.D)
     mx = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, True, scale, units, force_path=0, fmt=0).reshape(w.Hq, w.N, w.D)
     assert metrics.rel_fro(withp, exact) < metrics.rel_fro(mx, exact)
+
+
+@pytest.mark.parametrize("N,Bq,causal", [(200, 64, True), (333, 128, True), (97, 64, False), (64 + 31, 64, True)])
+def test_ragged_lengths_pins(oracle, N, Bq, causal):
+    """Sequence lengths that are not multiples of the blocks (short last query / key block, short last V group):
+    means of a short block over its own tokens (numpy); 100 % budget == exact attention (separate routine);
+    4-bit path without P quantisation == numpy attention on the dequantised tensors, whose last V group is
+    quantised from the tokens it has (checked against the stand-alone group quantiser)."""
+    w = W.scaled(W.TINY, N=512, Hq=2, Hkv=1, Bq=64, Bk=64, seed=5, planted_blocks=1, sink_tokens=0)
+    q, k, v, _, _ = W.make_prefill(w)
+    q, k, v = q[:, :, :N].contiguous(), k[:, :, :N].contiguous(), v[:, :, :N].contiguous()
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    # means
+    km = oracle.block_means(kb, dt, 64)
+    Tk = -(-N // 64)
+    assert km.shape == (1, 1, Tk, w.D)
+    kd64 = k.double().numpy()[0, 0]
+    for j in range(Tk):
+        assert np.array_equal(km[0, 0, j], kd64[j * 64:min(N, (j + 1) * 64)].mean(axis=0).astype(np.float32))
+    # V quantiser: last group from its own tokens
+    codes, scales = oracle.quantize_mxfp4(vb, dt, 1)
+    assert scales.shape == (1, 1, -(-N // 32), w.D)
+    g_last = (N - 1) // 32
+    vd64 = v.double().numpy()[0, 0]
+    for c in (0, 17, 127):
+        grp = vd64[g_last * 32:N, c]
+        cg, sb = oracle.mx_quantize_group(grp)
+        assert sb == scales[0, 0, g_last, c] and np.array_equal(cg, codes[0, 0, g_last * 32:N, c])
+    vdq = oracle.dequantize_mxfp4(codes, scales, 1)[0, 0]
+    c0, s0 = oracle.quantize_mxfp4(kb, dt, 0); kdq = oracle.dequantize_mxfp4(c0, s0, 0)[0, 0]
+    c0, s0 = oracle.quantize_mxfp4(qb, dt, 0); qdq = oracle.dequantize_mxfp4(c0, s0, 0)[0]
+    Tq = -(-N // Bq)
+    units = _all_units(1, w.Hq, Tq)
+    exact = oracle.attn_exact(qb, kb, vb, dt, causal, scale, _all_rows(1, w.Hq, N)).reshape(w.Hq, N, w.D)
+    full16 = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, Bq, 64, causal, scale, units, force_path=1)
+    full16 = full16.reshape(w.Hq, Tq * Bq, w.D)
+    assert np.abs(full16[:, :N] - exact).max() < 2e-3 and np.all(full16[:, N:] == 0)
+    got = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, Bq, 64, causal, scale, units, force_path=0,
+                                     quantize_p=False).reshape(w.Hq, Tq * Bq, w.D)
+    for h in range(w.Hq):
+        assert np.abs(got[h, :N] - _softmax_attention_np(qdq[h], kdq, vdq, causal, scale)).max() < 1e-10
+    # mixed with a real selection: shapes follow the ragged block counts, rows past the end stay zero
+    qm = oracle.block_means(qb, dt, Bq)
+    idx, cnt = oracle.select_topk(qm, km, Bq, 64, causal, 0.3)
+    assert idx.shape[2] == Tq and cnt.max() <= Tk
+    mixed = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, Bq, 64, causal, scale, units).reshape(w.Hq, Tq * Bq, w.D)
+    assert np.all(mixed[:, N:] == 0) and np.isfinite(mixed).all()
+    assert metrics.rel_fro(mixed[:, :N], exact) < metrics.rel_fro(got[:, :N], exact) + 0.05
+    # decode over a cache whose length is not a multiple of the block: == the last row of the prefill
+    if causal:
+        ql = q[:, :, N - 1].contiguous()
+        qlb, _ = oracle.bits_of(ql)
+        d16 = oracle.attn_thrift_decode(qlb, kb, vb, dt, None, None, 64, scale, 0, seqlens=np.array([N], np.int32), force_path=1)
+        assert np.abs(d16[0] - exact[:, N - 1]).max() < 2e-3
+        d4 = oracle.attn_thrift_decode(qlb, kb, vb, dt, None, None, 64, scale, 0, seqlens=np.array([N], np.int32), force_path=0,
+                                       quantize_p=False)
+        assert np.abs(d4[0] - got[:, N - 1]).max() < 1e-10
