@@ -81,8 +81,10 @@ int thrift_select_kmax(int Tq, int Tk, int Bq, int Bk, int causal, double budget
 /*
  * Block token means (Sec. 3.2; Alg. 1 step 3).
  *   x      [B,H,N,D] 16-bit (dt)
- *   means  [B,H,N/block,D] fp32: arithmetic mean over the block's tokens, accumulated in fp64 and
- *          rounded once.  block must divide N (any block >= 1).
+ *   means  [B,H,ceil(N/block),D] fp32: arithmetic mean over the block's tokens, accumulated in fp64 and
+ *          rounded once (any block >= 1).  N need not be a multiple of the block — the paper leaves the
+ *          tail open (App. B counts n = floor(L/64) blocks); here a short last block is the mean of the
+ *          tokens it has.
  */
 thrift_status thrift_block_means(const void* x, thrift_dtype dt, int B, int H, int N, int D, int block,
                                  float* means, void* stream);
@@ -136,9 +138,11 @@ thrift_status thrift_select_ablation(int selector, uint64_t seed, int B, int Hq,
  *   axis 0 (Q and K: groups of 32 along D):
  *       codes  [B,H,N,D/2]   byte t of a row holds elements 2t (low nibble) and 2t+1
  *       scales [B,H,N,D/32]
- *   axis 1 (V: groups of 32 along the token axis, the contraction axis of P.V; N % 64 == 0):
- *       codes  [B,H,N/64,D,32]  per 64-token block and channel, byte t holds tokens 2t (low) and 2t+1
- *       scales [B,H,N/32,D]
+ *   axis 1 (V: groups of 32 along the token axis, the contraction axis of P.V):
+ *       codes  [B,H,ceil(N/64),D,32]  per 64-token block and channel, byte t holds tokens 2t (low) and 2t+1
+ *       scales [B,H,2*ceil(N/64),D]   (= [B,H,N/32,D] when 64 divides N)
+ *     Tokens past N in the last block count as +0: a short last group is quantised from the tokens it
+ *     has, padded positions hold code 0, a group with no token at all gets scale byte 127.
  */
 thrift_status thrift_quantize_mxfp4(const void* x, thrift_dtype dt, int B, int H, int N, int D, int axis,
                                     uint8_t* codes, uint8_t* scales, void* stream);

@@ -115,7 +115,7 @@ def thrift_block_means(x: torch.Tensor, block: int, out: Optional[torch.Tensor] 
     _dev(x)
     B, H, N, D = x.shape
     if out is None:
-        out = torch.empty(B, H, N // max(block, 1), D, dtype=torch.float32, device=x.device)
+        out = torch.empty(B, H, -(-N // max(block, 1)), D, dtype=torch.float32, device=x.device)
     _check(lib().thrift_block_means(_ptr(x), _DT[x.dtype], B, H, N, D, block, _ptr(out), _stream()), "thrift_block_means")
     return out
 
@@ -167,8 +167,8 @@ def thrift_quantize_mxfp4(x: torch.Tensor, axis: int, codes: Optional[torch.Tens
             codes = torch.empty(B, H, N, D // 2, dtype=torch.uint8, device=x.device)
             scales = torch.empty(B, H, N, D // 32, dtype=torch.uint8, device=x.device)
         else:
-            codes = torch.empty(B, H, max(N // 64, 0), D, 32, dtype=torch.uint8, device=x.device)
-            scales = torch.empty(B, H, max(N // 32, 0), D, dtype=torch.uint8, device=x.device)
+            codes = torch.empty(B, H, -(-N // 64), D, 32, dtype=torch.uint8, device=x.device)
+            scales = torch.empty(B, H, 2 * -(-N // 64), D, dtype=torch.uint8, device=x.device)
     _check(lib().thrift_quantize_mxfp4(_ptr(x), _DT[x.dtype], B, H, N, D, int(axis), _ptr(codes), _ptr(scales), _stream()),
            "thrift_quantize_mxfp4")
     return codes, scales

@@ -122,11 +122,11 @@ thrift_status thrift_block_means(const void* x, thrift_dtype dt, int B, int H, i
                                  float* means, void* stream) {
   if (!x || !means) return THRIFT_ERR_NULL;
   if (!is16(dt)) return THRIFT_ERR_DTYPE;
-  if (B <= 0 || H <= 0 || N <= 0 || D != kHeadDim || block <= 0 || N % block != 0) return THRIFT_ERR_SHAPE;
-  const long n_blocks = (long)B * H * (N / block);
+  if (B <= 0 || H <= 0 || N <= 0 || D != kHeadDim || block <= 0) return THRIFT_ERR_SHAPE;
+  const long n_blocks = (long)B * H * (((long)N + block - 1) / block);
   if (n_blocks > 0x7fffffffL) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
-  launch_block_means(x, dt, n_blocks, block, means, (hipStream_t)stream);
+  launch_block_means(x, dt, (long)B * H, N, block, means, (hipStream_t)stream);
   return after_launch();
 }
 
@@ -189,9 +189,8 @@ thrift_status thrift_quantize_mxfp4(const void* x, thrift_dtype dt, int B, int H
   if (!x || !codes || !scales) return THRIFT_ERR_NULL;
   if (!is16(dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || H <= 0 || N <= 0 || D != kHeadDim || (axis != 0 && axis != 1)) return THRIFT_ERR_SHAPE;
-  if (axis == 1 && N % 64 != 0) return THRIFT_ERR_SHAPE;
   const long bh = (long)B * H;
-  if (axis == 1 && bh * (N / 64) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (axis == 1 && bh * (((long)N + 63) / 64) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
   if (axis == 0 && ((size_t)bh * N * (kHeadDim / 32) + 255) / 256 > 0x7fffffffUL) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   launch_quantize(x, dt, bh, N, axis, codes, scales, (hipStream_t)stream);

@@ -8,7 +8,7 @@
 
 namespace thrift {
 
-void launch_block_means(const void* x, thrift_dtype dt, long n_blocks, int block, float* means, hipStream_t st);
+void launch_block_means(const void* x, thrift_dtype dt, long heads, int N, int block, float* means, hipStream_t st);
 void launch_quantize(const void* x, thrift_dtype dt, long bh, int N, int axis, uint8_t* codes, uint8_t* scales, hipStream_t st);
 
 struct SelectArgs {

@@ -12,16 +12,20 @@ namespace thrift {
 // in fp64 (the sum of a block of 16-bit values is then exact, so the result does not depend on the
 // order of the additions and matches a serial fp64 mean bit for bit).
 // ------------------------------------------------------------------------------------------------
+// N need not be a multiple of the block: a head has ceil(N/block) blocks and the last one is the mean
+// of the tokens it has.
 template <typename T>
 __global__ void __launch_bounds__(256) block_means_kernel(const uint16_t* __restrict__ x, float* __restrict__ means,
-                                                          int block) {
+                                                          int block, int N, int blocks_per_head) {
   const int tid = threadIdx.x;
   const int cg = tid & 15, rs = tid >> 4;
-  const uint16_t* base = x + (size_t)blockIdx.x * block * kD + cg * 8;
+  const int head = blockIdx.x / blocks_per_head, t = blockIdx.x % blocks_per_head;
+  const int count = min(block, N - t * block);            // tokens of this block
+  const uint16_t* base = x + ((size_t)head * N + (size_t)t * block) * kD + cg * 8;
   double acc[8];
 #pragma unroll
   for (int c = 0; c < 8; ++c) acc[c] = 0.0;
-  for (int r = rs; r < block; r += 16) {
+  for (int r = rs; r < count; r += 16) {
     uint4 w = *reinterpret_cast<const uint4*>(base + (size_t)r * kD);
     uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
@@ -46,15 +50,17 @@ __global__ void __launch_bounds__(256) block_means_kernel(const uint16_t* __rest
   if (tid < kD) {
     const int g = tid >> 3, c = tid & 7;
     double s = part[0][g][c] + part[1][g][c] + part[2][g][c] + part[3][g][c];
-    means[(size_t)blockIdx.x * kD + tid] = (float)(s / (double)block);
+    means[(size_t)blockIdx.x * kD + tid] = (float)(s / (double)count);
   }
 }
 
-void launch_block_means(const void* x, thrift_dtype dt, long n_blocks, int block, float* means, hipStream_t st) {
+void launch_block_means(const void* x, thrift_dtype dt, long heads, int N, int block, float* means, hipStream_t st) {
+  const int per_head = (N + block - 1) / block;
+  const unsigned grid = (unsigned)(heads * per_head);
   if (dt == THRIFT_F16)
-    block_means_kernel<F16><<<dim3((unsigned)n_blocks), dim3(256), 0, st>>>((const uint16_t*)x, means, block);
+    block_means_kernel<F16><<<dim3(grid), dim3(256), 0, st>>>((const uint16_t*)x, means, block, N, per_head);
   else
-    block_means_kernel<BF16><<<dim3((unsigned)n_blocks), dim3(256), 0, st>>>((const uint16_t*)x, means, block);
+    block_means_kernel<BF16><<<dim3(grid), dim3(256), 0, st>>>((const uint16_t*)x, means, block, N, per_head);
 }
 
 // axis 0: one thread per group of 32 consecutive channels (64 bytes in, 16 code bytes + 1 scale out).
@@ -79,18 +85,24 @@ __global__ void __launch_bounds__(256) quantize_axis0_kernel(const uint16_t* __r
 // axis 1: one workgroup per (b, h, 64-token block).  The 64 x 128 tile is staged through LDS with
 // coalesced 16-byte loads; thread (token group g, channel c) then walks its 32 tokens down a column.
 // Output tile: [channel][32 bytes] (tokens 2t, 2t+1 in byte t), scales [2 groups][128 channels].
+// N need not be a multiple of 64: a head has ceil(N/64) blocks; tokens past the end count as +0 (they
+// do not change a group's largest magnitude and encode as code 0), so a short last group is quantised
+// from the tokens it has and the padded codes are zeros.
 template <typename T>
 __global__ void __launch_bounds__(256) quantize_axis1_kernel(const uint16_t* __restrict__ x, uint8_t* __restrict__ codes,
-                                                             uint8_t* __restrict__ scales) {
+                                                             uint8_t* __restrict__ scales, int N, int blocks_per_head) {
   constexpr int kRow = kD + 8;  // padded row (in 16-bit elements): keeps 16-byte alignment, spreads banks
   __shared__ __align__(16) uint16_t tile[64 * kRow];
   const int tid = threadIdx.x;
-  const uint16_t* src = x + (size_t)blockIdx.x * 64 * kD;
+  const int head = blockIdx.x / blocks_per_head, t = blockIdx.x % blocks_per_head;
+  const int count = min(64, N - t * 64);
+  const uint16_t* src = x + ((size_t)head * N + (size_t)t * 64) * kD;
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const int chunk = tid + 256 * u;           // 1024 chunks of 8 elements
     const int row = chunk >> 4, col = (chunk & 15) * 8;
-    *reinterpret_cast<uint4*>(&tile[row * kRow + col]) = *reinterpret_cast<const uint4*>(src + row * kD + col);
+    *reinterpret_cast<uint4*>(&tile[row * kRow + col]) =
+        row < count ? *reinterpret_cast<const uint4*>(src + row * kD + col) : make_uint4(0, 0, 0, 0);
   }
   __syncthreads();
   const int g = tid >> 7, c = tid & 127;
@@ -114,9 +126,10 @@ void launch_quantize(const void* x, thrift_dtype dt, long bh, int N, int axis, u
     if (dt == THRIFT_F16) quantize_axis0_kernel<F16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales, n_groups);
     else quantize_axis0_kernel<BF16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales, n_groups);
   } else {
-    unsigned grid = (unsigned)(bh * (N / 64));
-    if (dt == THRIFT_F16) quantize_axis1_kernel<F16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales);
-    else quantize_axis1_kernel<BF16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales);
+    const int per_head = (N + 63) / 64;
+    unsigned grid = (unsigned)(bh * per_head);
+    if (dt == THRIFT_F16) quantize_axis1_kernel<F16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales, N, per_head);
+    else quantize_axis1_kernel<BF16><<<dim3(grid), dim3(256), 0, st>>>(xs, codes, scales, N, per_head);
   }
 }
 

@@ -42,10 +42,11 @@ def test_validation_errors_come_before_any_launch():
     NULL, SHAPE, DTYPE, BUDGET, WORKSPACE = 1, 2, 3, 4, 5
     assert L.thrift_block_means(None, 0, 1, 1, 64, 128, 64, fake, None) == NULL
     assert L.thrift_block_means(fake, 0, 1, 1, 64, 64, 64, fake, None) == SHAPE      # D != 128
-    assert L.thrift_block_means(fake, 0, 1, 1, 100, 128, 64, fake, None) == SHAPE    # N % block
+    assert L.thrift_block_means(fake, 0, 1, 1, 100, 128, 0, fake, None) == SHAPE     # block < 1
+    assert L.thrift_block_means(fake, 0, 1, 1, 0, 128, 64, fake, None) == SHAPE      # empty sequence
     assert L.thrift_block_means(fake, 7, 1, 1, 64, 128, 64, fake, None) == DTYPE
     assert L.thrift_block_means(fake, 2, 1, 1, 64, 128, 64, fake, None) == DTYPE     # fp32 is output-only
-    assert L.thrift_quantize_mxfp4(fake, 0, 1, 1, 96, 128, 1, fake, fake, None) == SHAPE   # axis 1 needs N % 64
+    assert L.thrift_quantize_mxfp4(fake, 0, 1, 1, 0, 128, 1, fake, fake, None) == SHAPE    # empty sequence
     assert L.thrift_quantize_mxfp4(fake, 0, 1, 1, 64, 128, 2, fake, fake, None) == SHAPE
     sel = lambda **kw: L.thrift_select_topk(fake, fake, 1, kw.get("Hq", 4), kw.get("Hkv", 2), 8, kw.get("Tk", 8), 128, 64, 64, 1,
                                             C.c_double(kw.get("budget", 0.05)), kw.get("fixed_k", -1), 0, fake, fake,

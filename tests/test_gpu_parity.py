@@ -543,3 +543,26 @@ def test_prefill_two_phase_order(T, oracle, wl, budget, causal):
     with pytest.raises(T.ThriftError) as e:
         T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0, tile_order=2)
     assert e.value.code == 2
+
+
+# ------------------------------------------------------------------ lengths that are not multiples of the blocks
+@pytest.mark.parametrize("N", [200, 333, 95, 33, 1])
+def test_ragged_means_and_quantiser(T, oracle, N):
+    _say(f"ragged pre-pass N={N}")
+    wl = _small_bf16(N=512, Hq=2, Hkv=2)
+    q, k, v, _, _ = W.make_prefill(wl)
+    for t in (q[:, :, :N].contiguous(), v[:, :, :N].contiguous()):
+        bits, dt = oracle.bits_of(t)
+        for block in (64, 128, 96):
+            got = to_np(T.thrift_block_means(t.cuda(), block))
+            want = oracle.block_means(bits, dt, block)
+            assert got.shape == want.shape and np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        want_c, want_s = oracle.quantize_mxfp4(bits, dt, 0)
+        codes, scales = T.thrift_quantize_mxfp4(t.cuda(), 0)
+        assert np.array_equal(unpack_axis0(to_np(codes)), want_c) and np.array_equal(to_np(scales), want_s)
+        want_c, want_s = oracle.quantize_mxfp4(bits, dt, 1)
+        codes, scales = T.thrift_quantize_mxfp4(t.cuda(), 1)
+        got_c = unpack_axis1(to_np(codes))                       # [B,H,64*ceil(N/64),D]
+        assert np.array_equal(got_c[:, :, :N], want_c) and np.all(got_c[:, :, N:] == 0)
+        ng = want_s.shape[2]
+        assert np.array_equal(to_np(scales)[:, :, :ng], want_s) and np.all(to_np(scales)[:, :, ng:] == 127)
