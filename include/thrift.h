@@ -159,7 +159,9 @@ size_t thrift_attn_prefill_workspace(int B, int Hq, int Hkv, int N, int D, int B
  * 16-bit path P is rounded to dt.
  *   q [B,Hq,N,D], k,v [B,Hkv,N,D]                 16-bit (dt), read only for the selected tiles
  *   q4,qs / k4,ks : thrift_quantize_mxfp4(axis 0) of q / k;   v4,vs : axis 1 of v
- *   idx [B,Hq,N/Bq,kmax], cnt [B,Hq,N/Bq]         from thrift_select_topk (ascending, padded -1)
+ *   idx [B,Hq,ceil(N/Bq),kmax], cnt [B,Hq,ceil(N/Bq)]   from thrift_select_topk (ascending, padded -1)
+ *   N need not be a multiple of Bq or Bk: the last query block then has fewer rows and the keys past N
+ *   in the last key block are masked out (block means, V codes: see thrift_block_means, thrift_quantize_mxfp4)
  *   softmax_scale <= 0 selects 1/sqrt(D)
  *   out [B,Hq,N,D] in out_dt (THRIFT_F16, THRIFT_BF16 or THRIFT_F32)
  *   lse (nullable) [B,Hq,N] fp32: log-sum-exp of the scaled scores of each row
@@ -180,7 +182,7 @@ thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, t
  * which fixes its causal mask and visible key range; with causal == 0 the offset is ignored.
  *   q, q4, qs, out, lse   hold Nq tokens per head ([B,Hq,Nq,...]);  k, v, k4, ks, v4, vs hold Nkv
  *   idx [B,Hq,Nq/Bq,kmax], cnt [B,Hq,Nq/Bq]: from thrift_select_topk with the same q_block_offset
- *   Nq % Bq == 0, Nkv % Bk == 0; causal: (q_block_offset*Bq + Nq) <= Nkv, else THRIFT_ERR_SHAPE
+ *   causal: (q_block_offset*Bq + Nq) <= Nkv, else THRIFT_ERR_SHAPE; Nq and Nkv need not be multiples of the blocks
  * thrift_attn_prefill is this call with Nq = Nkv = N and q_block_offset = 0.
  */
 thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void* v, thrift_dtype dt,

@@ -256,17 +256,19 @@ class PrefillPlan:
         self.selector, self.seed = selector, seed           # 0: the paper's heuristic; else an App. A ablation selector
         dev = device
         u8, f32, i32 = torch.uint8, torch.float32, torch.int32
-        self.qmean = torch.empty(B, Hq, N // Bq, D, dtype=f32, device=dev)
-        self.kmean = torch.empty(B, Hkv, N // Bk, D, dtype=f32, device=dev)
-        self.kmax = max(1, select_kmax(N // Bq, N // Bk, Bq, Bk, causal, budget, fixed_k))
-        self.idx = torch.empty(B, Hq, N // Bq, self.kmax, dtype=i32, device=dev)
-        self.cnt = torch.empty(B, Hq, N // Bq, dtype=i32, device=dev)
+        Tq, Tk = -(-N // Bq), -(-N // Bk)                   # N need not be a multiple of the blocks
+        self.Tq, self.Tk = Tq, Tk
+        self.qmean = torch.empty(B, Hq, Tq, D, dtype=f32, device=dev)
+        self.kmean = torch.empty(B, Hkv, Tk, D, dtype=f32, device=dev)
+        self.kmax = max(1, select_kmax(Tq, Tk, Bq, Bk, causal, budget, fixed_k))
+        self.idx = torch.empty(B, Hq, Tq, self.kmax, dtype=i32, device=dev)
+        self.cnt = torch.empty(B, Hq, Tq, dtype=i32, device=dev)
         self.q4 = torch.empty(B, Hq, N, D // 2, dtype=u8, device=dev)
         self.qs = torch.empty(B, Hq, N, D // 32, dtype=u8, device=dev)
         self.k4 = torch.empty(B, Hkv, N, D // 2, dtype=u8, device=dev)
         self.ks = torch.empty(B, Hkv, N, D // 32, dtype=u8, device=dev)
-        self.v4 = torch.empty(B, Hkv, N // 64, D, 32, dtype=u8, device=dev)
-        self.vs = torch.empty(B, Hkv, N // 32, D, dtype=u8, device=dev)
+        self.v4 = torch.empty(B, Hkv, -(-N // 64), D, 32, dtype=u8, device=dev)
+        self.vs = torch.empty(B, Hkv, 2 * -(-N // 64), D, dtype=u8, device=dev)
         self.out = torch.empty(B, Hq, N, D, dtype=out_dtype or dtype, device=dev)
 
     def run(self, q, k, v, softmax_scale: float = 0.0, prepass: bool = True, attention: bool = True) -> torch.Tensor:
@@ -277,7 +279,7 @@ class PrefillPlan:
             if self.selector == 0:
                 thrift_select_topk(self.qmean, self.kmean, Bq, Bk, causal, budget, fixed_k, kmax=self.kmax, idx=self.idx, cnt=self.cnt)
             else:
-                thrift_select_ablation(self.selector, self.seed, B, Hq, N // Bq, N // Bk, Bq, Bk, causal, budget, fixed_k,
+                thrift_select_ablation(self.selector, self.seed, B, Hq, self.Tq, self.Tk, Bq, Bk, causal, budget, fixed_k,
                                        kmax=self.kmax, idx=self.idx, cnt=self.cnt)
             thrift_quantize_mxfp4(q, 0, self.q4, self.qs)
             thrift_quantize_mxfp4(k, 0, self.k4, self.ks)

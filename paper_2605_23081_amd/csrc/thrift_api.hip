@@ -212,11 +212,11 @@ thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const vo
   if (!q || !k || !v || !q4 || !qs || !k4 || !ks || !v4 || !vs || !idx || !cnt || !out) return THRIFT_ERR_NULL;
   if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Nq <= 0 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock ||
-      (Bq != 64 && Bq != 128) || Nq % Bq != 0 || Nkv % Bk != 0 || kmax <= 0 || Nkv / Bk > kMaxKeyBlocks || q_block_offset < 0)
+      (Bq != 64 && Bq != 128) || kmax <= 0 || (Nkv + Bk - 1) / Bk > kMaxKeyBlocks || q_block_offset < 0)
     return THRIFT_ERR_SHAPE;
   // causal: the chunk must lie inside the sequence (its last query at or before the last key)
   if (causal && ((long)q_block_offset * Bq + Nq > (long)Nkv)) return THRIFT_ERR_SHAPE;
-  if ((long)B * Hq * (Nq / Bq) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if ((long)B * Hq * ((Nq + Bq - 1) / Bq) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   PrefillArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
@@ -248,7 +248,6 @@ thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, t
                                   int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, float softmax_scale,
                                   void* out, thrift_dtype out_dt, float* lse,
                                   void* workspace, size_t workspace_bytes, void* stream) {
-  if (N > 0 && Bq > 0 && N % Bq != 0) return THRIFT_ERR_SHAPE;
   return thrift_attn_prefill_chunk(q, k, v, dt, q4, qs, k4, ks, v4, vs, idx, cnt, kmax, B, Hq, Hkv, N, 0, N, D, Bq, Bk, causal,
                                    softmax_scale, out, out_dt, lse, workspace, workspace_bytes, stream);
 }

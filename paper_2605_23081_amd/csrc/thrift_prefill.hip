@@ -62,7 +62,8 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
-  const int N = a.N, Nq = a.Nq, Bq = NW * 32, Tq = Nq / Bq, Tk = N / kBk, G = a.Hq / a.Hkv;
+  const int N = a.N, Nq = a.Nq, Bq = NW * 32, G = a.Hq / a.Hkv;
+  const int Tq = (Nq + Bq - 1) / Bq, Tk = (N + kBk - 1) / kBk;   // the last query / key block may be short
 
   // ---- work item: heavy (late) query blocks first; KV heads spread over the 8 XCDs so that the query
   // heads and neighbouring query blocks that share a KV head also share an L2 ----
@@ -81,7 +82,8 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   const int hq = kvh * G + within % G;
   const size_t qh = (size_t)b * a.Hq + hq, kh = (size_t)b * a.Hkv + kvh;
   const int q0 = (i + a.q_off) * Bq + wave * 32;        // sequence position of this wavefront's first query row
-  const size_t qrow = qh * Nq + i * Bq + wave * 32 + r;
+  const bool row_ok = i * Bq + wave * 32 + r < Nq;      // rows past the last query repeat it and are never stored
+  const size_t qrow = qh * Nq + min(i * Bq + wave * 32 + r, Nq - 1);
 
   // ---- Q fragments ----
   v4i qf4[2];
@@ -98,9 +100,9 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   int n0 = nsel > 0 ? sel[0] : 0x7fffffff, n1 = nsel > 1 ? sel[1] : 0x7fffffff;
 
   const uint8_t* k4base = a.k4 + kh * N * 64;
-  const uint8_t* v4base = a.v4 + kh * (size_t)(N / 64) * 4096;
+  const uint8_t* v4base = a.v4 + kh * (size_t)Tk * 4096;
   const uint8_t* ksbase = a.ks + kh * N * 4;
-  const uint8_t* vsbase = a.vs + kh * (size_t)(N / 32) * kD;
+  const uint8_t* vsbase = a.vs + kh * (size_t)Tk * 2 * kD;
   const uint8_t* k16base = reinterpret_cast<const uint8_t*>(a.k + kh * N * kD);
   const uint8_t* v16base = reinterpret_cast<const uint8_t*>(a.v + kh * N * kD);
 
@@ -120,38 +122,41 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   const uint32_t v16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ v16_swizzle(lane >> 4)) * 16);
   const uint32_t k16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ (lane >> 4)) * 16);   // rows 32..63: chunk ^ 4 more
 
+  // A short last key block: the rows past the last key do not exist in the row-major arrays (K codes and
+  // scales, 16-bit K and V); their lanes re-read the last key's row instead, and the mask below keeps
+  // whatever lands there out of the arithmetic.  (V codes and scales are stored in whole, zero-padded blocks.)
+  const int last_key_row = (N - 1) & (kBk - 1);
+#define THRIFT_CLAMP_ROWS(OFF, SHIFT) ((min((uint32_t)(OFF) >> (SHIFT), (uint32_t)last_key_row) << (SHIFT)) | ((OFF) & ((1u << (SHIFT)) - 1u)))
 #define THRIFT_ISSUE4(J) THRIFT_ISSUE4_SLOT(J, (J) & 1)
 #define THRIFT_ISSUE4_SLOT(J, S)                                                                               \
   do {                                                                                                         \
     const int j_ = __builtin_amdgcn_readfirstlane(J), s_ = __builtin_amdgcn_readfirstlane(S); /* scalar operands */ \
+    const bool short_ = (j_ + 1) * kBk > N;                                                                    \
     const uint8_t* kt_ = k4base + (size_t)j_ * 4096;                                                           \
     const uint8_t* vt_ = v4base + (size_t)j_ * 4096;                                                           \
-    const uint32_t sl_ = lds0 + kLdsRing + s_ * kLdsBytes4;                                                   \
+    const uint32_t sl_ = lds0 + kLdsRing + s_ * kLdsBytes4;                                                    \
     _Pragma("unroll") for (int u = 0; u < KF; ++u) {                                                           \
-      dma_b128(kt_, k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024);                                          \
+      dma_b128(kt_, short_ ? THRIFT_CLAMP_ROWS(k4off[u], 6) : k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024); \
       dma_b128(vt_, v4off[u], sl_ + kLdsV4 + (wave * KF + u) * 1024);                                          \
     }                                                                                                          \
     /* scale bytes: even wavefronts fetch K's 256, odd ones V's (duplicates write the same bytes) */           \
     if (wave & 1) dma_b32(vsbase + (size_t)j_ * 256, scoff, sl_ + kLdsVS);                                     \
-    else dma_b32(ksbase + (size_t)j_ * 256, scoff, sl_ + kLdsKS);                                             \
+    else dma_b32(ksbase + (size_t)j_ * 256, short_ ? THRIFT_CLAMP_ROWS(scoff, 2) : scoff, sl_ + kLdsKS);       \
   } while (0)
-#define THRIFT_ISSUE_V16(J)                                                                                    \
+  // 16-bit tiles: instruction q_ covers rows 4 q_ .. 4 q_ + 3; the lane offset is taken from the tile start
+#define THRIFT_ISSUE_TILE16(BASE, J, OFFEXPR, LDSBASE)                                                         \
   do {                                                                                                         \
-    const uint8_t* vt_ = v16base + (size_t)__builtin_amdgcn_readfirstlane(J) * kTile16;                        \
-    const uint32_t vb_ = lds0 + kLdsV16;                                                     \
+    const int j_ = __builtin_amdgcn_readfirstlane(J);                                                          \
+    const bool short_ = (j_ + 1) * kBk > N;                                                                    \
+    const uint8_t* t_ = (BASE) + (size_t)j_ * kTile16;                                                         \
     _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                          \
       const int q_ = u * NW + wave;                                                                            \
-      dma_b128(vt_ + q_ * 1024, v16off, vb_ + q_ * 1024);                                                      \
+      const uint32_t o_ = (uint32_t)(q_ * 1024) + (OFFEXPR);                                                   \
+      dma_b128(t_, short_ ? THRIFT_CLAMP_ROWS(o_, 8) : o_, (LDSBASE) + q_ * 1024);                             \
     }                                                                                                          \
   } while (0)
-#define THRIFT_ISSUE_K16(J)                                                                                    \
-  do {                                                                                                         \
-    const uint8_t* kt_ = k16base + (size_t)__builtin_amdgcn_readfirstlane(J) * kTile16;                        \
-    _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                          \
-      const int q_ = u * NW + wave;                                                                            \
-      dma_b128(kt_ + q_ * 1024, u * NW >= 8 ? k16off ^ 64u : k16off, lds0 + kLdsK16 + q_ * 1024);              \
-    }                                                                                                          \
-  } while (0)
+#define THRIFT_ISSUE_V16(J) THRIFT_ISSUE_TILE16(v16base, J, v16off, lds0 + kLdsV16)
+#define THRIFT_ISSUE_K16(J) THRIFT_ISSUE_TILE16(k16base, J, (u * NW >= 8 ? k16off ^ 64u : k16off), lds0 + kLdsK16)
 
   RowState st = {-INFINITY, 0.f};
   v16f o[4];
@@ -184,8 +189,9 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
     }                                                                                                          \
   }
 #define THRIFT_MASK(J)                                                                                         \
-  const bool mask = a.causal && (J) * kBk + kBk - 1 > q0;                                                      \
-  const int n_valid = q0 + r - (J) * kBk + 1; /* keys of the block at positions <= the query's */
+  const bool mask = (a.causal && (J) * kBk + kBk - 1 > q0) || ((J) + 1) * kBk > N;                             \
+  /* keys of the block the query may see: those at positions <= its own (causal), and only keys that exist */  \
+  const int n_valid = min(a.causal ? q0 + r - (J) * kBk + 1 : kBk, N - (J) * kBk);
 #define THRIFT_NEXT_PROMOTED()                                                                                 \
   ++ps;                                                                                                        \
   n0 = n1;                                                                                                     \
@@ -356,6 +362,8 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
 #undef THRIFT_ISSUE4_SLOT
 #undef THRIFT_ISSUE_V16
 #undef THRIFT_ISSUE_K16
+#undef THRIFT_ISSUE_TILE16
+#undef THRIFT_CLAMP_ROWS
 
   // ---- epilogue (Alg. 1 step 21): O / l; accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
   const float l = st.l + other_half(st.l);
@@ -366,6 +374,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
 #pragma unroll
     for (int q4i = 0; q4i < 4; ++q4i) {
       const int ch = 32 * n + 8 * q4i + 4 * half;
+      if (!row_ok) continue;
       const float x0 = o[n][4 * q4i] * inv, x1 = o[n][4 * q4i + 1] * inv, x2 = o[n][4 * q4i + 2] * inv, x3 = o[n][4 * q4i + 3] * inv;
       if (a.out_dt == THRIFT_F32) {
         *reinterpret_cast<float4*>((float*)a.out + orow + ch) = make_float4(x0, x1, x2, x3);
@@ -381,11 +390,11 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
         *reinterpret_cast<uint2*>((uint16_t*)a.out + orow + ch) = w;
       }
     }
-  if (a.lse != nullptr && half == 0) a.lse[qrow] = st.m * a.scale + __logf(l);
+  if (a.lse != nullptr && half == 0 && row_ok) a.lse[qrow] = st.m * a.scale + __logf(l);
 }
 
 void launch_prefill(const PrefillArgs& a, hipStream_t st) {
-  const unsigned grid = (unsigned)((long)a.B * a.Hq * (a.Nq / a.Bq));
+  const unsigned grid = (unsigned)((long)a.B * a.Hq * ((a.Nq + a.Bq - 1) / a.Bq));
 #define THRIFT_LAUNCH(T, NW)                                                                                   \
   do {                                                                                                         \
     if (a.tile_order == 1) prefill_kernel<T, NW, 1><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);                  \

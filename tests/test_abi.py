@@ -60,7 +60,7 @@ def test_validation_errors_come_before_any_launch():
                                              1, 4, kw.get("Hkv", 2), kw.get("N", 256), kw.get("D", 128), kw.get("Bq", 64),
                                              kw.get("Bk", 64), 1, C.c_float(0.0), kw.get("out", fake), kw.get("odt", 0), None,
                                              None, 0, None)
-    assert pre(Bq=32) == SHAPE and pre(Bk=128) == SHAPE and pre(D=64) == SHAPE and pre(N=200) == SHAPE and pre(Hkv=3) == SHAPE
+    assert pre(Bq=32) == SHAPE and pre(Bk=128) == SHAPE and pre(D=64) == SHAPE and pre(N=0) == SHAPE and pre(Hkv=3) == SHAPE
     assert pre(out=None) == NULL
     assert pre(odt=5) == DTYPE and pre(dt=2) == DTYPE
     dec = lambda **kw: L.thrift_attn_decode(fake, 0, fake, fake, fake, fake, fake, fake, fake, None, 1, 4, 2, kw.get("N", 1024), 128, 64,

@@ -566,3 +566,39 @@ def test_ragged_means_and_quantiser(T, oracle, N):
         assert np.array_equal(got_c[:, :, :N], want_c) and np.all(got_c[:, :, N:] == 0)
         ng = want_s.shape[2]
         assert np.array_equal(to_np(scales)[:, :, :ng], want_s) and np.all(to_np(scales)[:, :, ng:] == 127)
+
+
+@pytest.mark.parametrize("N,Bq,budget,causal,order", [
+    (200, 64, 0.25, True, 0), (333, 128, 0.1, True, 0), (1000, 128, 0.05, True, 0), (97, 64, 0.5, False, 0),
+    (777, 128, 1.0, True, 0), (450, 128, 0.0, True, 0), (333, 128, 0.3, True, 1), (65, 128, 0.05, True, 0),
+])
+def test_prefill_ragged_lengths(T, oracle, N, Bq, budget, causal, order):
+    _say(f"prefill with N={N} (not a multiple of the blocks) Bq={Bq} f={budget} causal={causal} order={order}")
+    wl = _small_bf16(N=1024, Hq=4, Hkv=2, Bq=Bq)
+    q, k, v, _, _ = W.make_prefill(wl)
+    q, k, v = q[:, :, :N].contiguous(), k[:, :, :N].contiguous(), v[:, :, :N].contiguous()
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(wl.D)
+    Tq = -(-N // Bq)
+    qm = oracle.block_means(qb, dt, Bq); km = oracle.block_means(kb, dt, 64)
+    idx, cnt = oracle.select_topk(qm, km, Bq, 64, causal, budget)
+    want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, Bq, 64, causal, scale, _units(wl.B, wl.Hq, Tq),
+                                      tile_order=order).reshape(wl.B, wl.Hq, Tq * Bq, wl.D)[:, :, :N]
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    idx_g, cnt_g = T.thrift_select_topk(T.thrift_block_means(qg, Bq), T.thrift_block_means(kg, 64), Bq, 64, causal, budget)
+    assert np.array_equal(to_np(cnt_g), cnt) and np.array_equal(to_np(idx_g)[..., :idx.shape[-1]], idx)
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    lse = torch.full((wl.B, wl.Hq, N), 7.0, dtype=torch.float32, device="cuda")
+    res = torch.empty(wl.B, wl.Hq, N, wl.D, dtype=torch.float32, device="cuda")
+    T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, idx_g, cnt_g, Bq, 64, causal, 0, out=res, lse=lse,
+                                tile_order=order)
+    torch.cuda.synchronize()
+    err = np.abs(to_np(res) - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert err <= (TOL16 if budget == 1.0 else TOLMIX)
+    assert torch.isfinite(lse).all() and not (lse == 7.0).any()
+    # the one-call form allocates by the same rules
+    got2 = T.thrift_attention(qg, kg, vg, causal, Bq, 64, budget, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    if order == 0:
+        assert torch.equal(got2, res)
