@@ -82,15 +82,18 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   const int hq = kvh * G + within % G;
   const size_t qh = (size_t)b * a.Hq + hq, kh = (size_t)b * a.Hkv + kvh;
   const int q0 = (i + a.q_off) * Bq + wave * 32;        // sequence position of this wavefront's first query row
-  const bool row_ok = i * Bq + wave * 32 + r < Nq;      // rows past the last query repeat it and are never stored
-  const size_t qrow = qh * Nq + min(i * Bq + wave * 32 + r, Nq - 1);
+  // The lane's query row inside the head.  Rows past the last query repeat it and are never stored.  Only this
+  // 32-bit index is kept; addresses are rebuilt from it and scalar bases where they are needed (registers are
+  // what limits this kernel to three wavefronts per SIMD).
+  const int lrow = min(i * Bq + wave * 32 + r, Nq - 1);
+  const size_t qrow = qh * Nq + lrow;
 
   // ---- Q fragments ----
   v4i qf4[2];
   qf4[0] = *reinterpret_cast<const v4i*>(a.q4 + qrow * 64 + half * 16);
   qf4[1] = *reinterpret_cast<const v4i*>(a.q4 + qrow * 64 + 32 + half * 16);
   const uint32_t qsc = *reinterpret_cast<const uint32_t*>(a.qs + qrow * 4) >> (8 * half);
-  const uint16_t* q16row = a.q + qrow * kD;
+  const uint8_t* q16head = reinterpret_cast<const uint8_t*>(a.q + qh * Nq * kD);   // wavefront-uniform
 
   const int vis = a.causal ? min(Tk, ((i + a.q_off + 1) * Bq - 1) / kBk + 1) : Tk;
   const int32_t* sel = a.idx + (qh * Tq + i) * a.kmax;
@@ -119,44 +122,64 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   }
   const uint32_t scoff = (uint32_t)lane * 4;
   // 16-bit tiles: one instruction covers 4 rows; lane l writes chunk position l&15 of row l>>4
-  const uint32_t v16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ v16_swizzle(lane >> 4)) * 16);
-  const uint32_t k16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ (lane >> 4)) * 16);   // rows 32..63: chunk ^ 4 more
+  // (formed from the lane index where a 16-bit tile is issued, one block in twenty on the headline budget,
+  // rather than held in registers through every 4-bit block)
+#define THRIFT_V16OFF() ((uint32_t)((lane16 >> 4) * 256 + ((lane16 & 15) ^ v16_swizzle(lane16 >> 4)) * 16))
+#define THRIFT_K16OFF() ((uint32_t)((lane16 >> 4) * 256 + ((lane16 & 15) ^ (lane16 >> 4)) * 16))   /* rows 32..63: chunk ^ 4 more */
 
   // A short last key block: the rows past the last key do not exist in the row-major arrays (K codes and
   // scales, 16-bit K and V); their lanes re-read the last key's row instead, and the mask below keeps
   // whatever lands there out of the arithmetic.  (V codes and scales are stored in whole, zero-padded blocks.)
+  // The clamped offsets are formed inside the branch that handles the short block (the empty asm keeps the
+  // compiler from hoisting a second set of per-lane offsets out of the key loop, which would cost registers
+  // on the path every other block takes).
   const int last_key_row = (N - 1) & (kBk - 1);
-#define THRIFT_CLAMP_ROWS(OFF, SHIFT) ((min((uint32_t)(OFF) >> (SHIFT), (uint32_t)last_key_row) << (SHIFT)) | ((OFF) & ((1u << (SHIFT)) - 1u)))
+#define THRIFT_CLAMP_ROWS(OFF, SHIFT, LAST) ((min((uint32_t)(OFF) >> (SHIFT), (LAST)) << (SHIFT)) | ((OFF) & ((1u << (SHIFT)) - 1u)))
 #define THRIFT_ISSUE4(J) THRIFT_ISSUE4_SLOT(J, (J) & 1)
 #define THRIFT_ISSUE4_SLOT(J, S)                                                                               \
   do {                                                                                                         \
     const int j_ = __builtin_amdgcn_readfirstlane(J), s_ = __builtin_amdgcn_readfirstlane(S); /* scalar operands */ \
-    const bool short_ = (j_ + 1) * kBk > N;                                                                    \
     const uint8_t* kt_ = k4base + (size_t)j_ * 4096;                                                           \
     const uint8_t* vt_ = v4base + (size_t)j_ * 4096;                                                           \
     const uint32_t sl_ = lds0 + kLdsRing + s_ * kLdsBytes4;                                                    \
-    _Pragma("unroll") for (int u = 0; u < KF; ++u) {                                                           \
-      dma_b128(kt_, short_ ? THRIFT_CLAMP_ROWS(k4off[u], 6) : k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024); \
-      dma_b128(vt_, v4off[u], sl_ + kLdsV4 + (wave * KF + u) * 1024);                                          \
+    if ((j_ + 1) * kBk <= N) {                                                                                 \
+      _Pragma("unroll") for (int u = 0; u < KF; ++u) dma_b128(kt_, k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024); \
+      if (!(wave & 1)) dma_b32(ksbase + (size_t)j_ * 256, scoff, sl_ + kLdsKS);                                \
+    } else {                                                                                                   \
+      uint32_t last_ = (uint32_t)last_key_row;                                                                 \
+      asm volatile("" : "+s"(last_));                                                                          \
+      _Pragma("unroll") for (int u = 0; u < KF; ++u)                                                           \
+        dma_b128(kt_, THRIFT_CLAMP_ROWS(k4off[u], 6, last_), sl_ + kLdsK4 + (wave * KF + u) * 1024);           \
+      if (!(wave & 1)) dma_b32(ksbase + (size_t)j_ * 256, THRIFT_CLAMP_ROWS(scoff, 2, last_), sl_ + kLdsKS);   \
     }                                                                                                          \
-    /* scale bytes: even wavefronts fetch K's 256, odd ones V's (duplicates write the same bytes) */           \
+    /* V codes and scales: whole blocks; the scale bytes ride with the odd wavefronts, K's with the even ones */ \
+    _Pragma("unroll") for (int u = 0; u < KF; ++u) dma_b128(vt_, v4off[u], sl_ + kLdsV4 + (wave * KF + u) * 1024); \
     if (wave & 1) dma_b32(vsbase + (size_t)j_ * 256, scoff, sl_ + kLdsVS);                                     \
-    else dma_b32(ksbase + (size_t)j_ * 256, short_ ? THRIFT_CLAMP_ROWS(scoff, 2) : scoff, sl_ + kLdsKS);       \
   } while (0)
-  // 16-bit tiles: instruction q_ covers rows 4 q_ .. 4 q_ + 3; the lane offset is taken from the tile start
+  // 16-bit tiles: instruction q_ covers rows 4 q_ .. 4 q_ + 3
 #define THRIFT_ISSUE_TILE16(BASE, J, OFFEXPR, LDSBASE)                                                         \
   do {                                                                                                         \
     const int j_ = __builtin_amdgcn_readfirstlane(J);                                                          \
-    const bool short_ = (j_ + 1) * kBk > N;                                                                    \
     const uint8_t* t_ = (BASE) + (size_t)j_ * kTile16;                                                         \
-    _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                          \
-      const int q_ = u * NW + wave;                                                                            \
-      const uint32_t o_ = (uint32_t)(q_ * 1024) + (OFFEXPR);                                                   \
-      dma_b128(t_, short_ ? THRIFT_CLAMP_ROWS(o_, 8) : o_, (LDSBASE) + q_ * 1024);                             \
+    int lane16 = lane;                                                                                         \
+    asm volatile("" : "+v"(lane16));   /* offsets are computed here, not carried through the key loop */       \
+    if ((j_ + 1) * kBk <= N) {                                                                                 \
+      _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                        \
+        const int q_ = u * NW + wave;                                                                          \
+        dma_b128(t_ + q_ * 1024, (OFFEXPR), (LDSBASE) + q_ * 1024);                                            \
+      }                                                                                                        \
+    } else {                                                                                                   \
+      uint32_t last_ = (uint32_t)last_key_row;                                                                 \
+      asm volatile("" : "+s"(last_));                                                                          \
+      _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                        \
+        const int q_ = u * NW + wave;                                                                          \
+        const uint32_t o_ = (uint32_t)(q_ * 1024) + (OFFEXPR);   /* offset from the tile start */              \
+        dma_b128(t_, THRIFT_CLAMP_ROWS(o_, 8, last_), (LDSBASE) + q_ * 1024);                                  \
+      }                                                                                                        \
     }                                                                                                          \
   } while (0)
-#define THRIFT_ISSUE_V16(J) THRIFT_ISSUE_TILE16(v16base, J, v16off, lds0 + kLdsV16)
-#define THRIFT_ISSUE_K16(J) THRIFT_ISSUE_TILE16(k16base, J, (u * NW >= 8 ? k16off ^ 64u : k16off), lds0 + kLdsK16)
+#define THRIFT_ISSUE_V16(J) THRIFT_ISSUE_TILE16(v16base, J, THRIFT_V16OFF(), lds0 + kLdsV16)
+#define THRIFT_ISSUE_K16(J) THRIFT_ISSUE_TILE16(k16base, J, (u * NW >= 8 ? THRIFT_K16OFF() ^ 64u : THRIFT_K16OFF()), lds0 + kLdsK16)
 
   RowState st = {-INFINITY, 0.f};
   v16f o[4];
@@ -168,6 +191,9 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   // later blocks of the workgroup (visible only to wavefronts with later rows) are still staged and
   // synchronised on, in a final loop without arithmetic.
   const int vis_wave = a.causal ? min(vis, (q0 + 31) / kBk + 1) : vis;
+  // keys at positions below key_limit are visible to the lane's query: those at or before its own position
+  // (causal) and only keys that exist
+  const int key_limit = a.causal ? min(q0 + r + 1, N) : N;
 
   // One step of the staging pipeline at block J, with P0 / P1 = "block J / J+1 is promoted".
   //  SYNC:  wait for this wavefront's share of block J, then meet the others: block J is complete in LDS
@@ -190,8 +216,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   }
 #define THRIFT_MASK(J)                                                                                         \
   const bool mask = (a.causal && (J) * kBk + kBk - 1 > q0) || ((J) + 1) * kBk > N;                             \
-  /* keys of the block the query may see: those at positions <= its own (causal), and only keys that exist */  \
-  const int n_valid = min(a.causal ? q0 + r - (J) * kBk + 1 : kBk, N - (J) * kBk);
+  const int n_valid = key_limit - (J) * kBk;   /* leading keys of the block this query may see */
 #define THRIFT_NEXT_PROMOTED()                                                                                 \
   ++ps;                                                                                                        \
   n0 = n1;                                                                                                     \
@@ -251,7 +276,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
       if (mine) {
         v8s qf[8];
 #pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16row + 16 * s8 + 8 * half);
+        for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16head + (uint32_t)(lrow * (2 * kD) + 32 * s8 + 16 * half));
         scores_16<T>(lds + kLdsK16, lane, qf, s);
       }
       if (p1) {
@@ -309,7 +334,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
       {
         v8s qf[8];
 #pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16row + 16 * s8 + 8 * half);
+        for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16head + (uint32_t)(lrow * (2 * kD) + 32 * s8 + 16 * half));
         scores_16<T>(lds + kLdsK16, lane, qf, s);
       }
       if (p1) {                                         // the K buffer is free once every wavefront has its scores
@@ -363,12 +388,15 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
 #undef THRIFT_ISSUE_V16
 #undef THRIFT_ISSUE_K16
 #undef THRIFT_ISSUE_TILE16
+#undef THRIFT_V16OFF
+#undef THRIFT_K16OFF
 #undef THRIFT_CLAMP_ROWS
 
   // ---- epilogue (Alg. 1 step 21): O / l; accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
   const float l = st.l + other_half(st.l);
   const float inv = l > 0.f ? 1.0f / l : 0.f;
-  const size_t orow = qrow * kD;
+  const size_t orow = (qh * Nq + lrow) * kD;
+  const bool row_ok = i * Bq + wave * 32 + r < Nq;
 #pragma unroll
   for (int n = 0; n < 4; ++n)
 #pragma unroll
@@ -390,7 +418,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
         *reinterpret_cast<uint2*>((uint16_t*)a.out + orow + ch) = w;
       }
     }
-  if (a.lse != nullptr && half == 0 && row_ok) a.lse[qrow] = st.m * a.scale + __logf(l);
+  if (a.lse != nullptr && half == 0 && row_ok) a.lse[qh * Nq + lrow] = st.m * a.scale + __logf(l);
 }
 
 void launch_prefill(const PrefillArgs& a, hipStream_t st) {
