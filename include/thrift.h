@@ -224,7 +224,11 @@ size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int 
  *   q [B,Hq,D] 16-bit (dt)
  *   k16,v16 [B,Hkv,Nkv,D] 16-bit (dt)             read only for selected blocks
  *   k4,ks (axis 0) and v4,vs (axis 1) of the same cache; kmean [B,Hkv,Nkv/Bk,D] fp32
- *   seqlens (nullable, device) [B] int32: valid tokens per sequence, multiples of Bk, <= Nkv; NULL = Nkv
+ *   seqlens (nullable, device) [B] int32: cached tokens per sequence, 0 .. Nkv (values outside are clamped);
+ *     NULL = Nkv.  A length that is not a multiple of Bk leaves the last key block partly filled: its keys past
+ *     the length are masked, its kmean entry must be the mean of the tokens it has and its V groups must have
+ *     been quantised from those tokens alone (what thrift_kv_cache_append, or the pre-pass on a tensor of that
+ *     length, produces).  Cache contents past that block are never read.  A sequence of length 0 yields zeros.
  *   split_blocks: key blocks per partition (> 0)
  *   out [B,Hq,D] in out_dt
  *   idx_out (nullable) [B,Hq,kmax_out], cnt_out (nullable) [B,Hq]: the selection that was used
@@ -247,6 +251,29 @@ thrift_status thrift_attn_decode_shared(const void* q, thrift_dtype dt, const vo
                                         double budget, int fixed_k, int split_blocks, float softmax_scale,
                                         void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
                                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Append tokens to the dual cache that thrift_attn_decode reads (Sec. 4.1 and Sec. 5 describe the cache: 4-bit
+ * K and V for every block, the 16-bit copy for promoted blocks, and the key-block means).  After the call the
+ * cache holds, for every sequence, exactly what the pre-pass (thrift_block_means with block Bk on K,
+ * thrift_quantize_mxfp4 axis 0 on K and axis 1 on V) would produce from the sequence's first
+ * seqlens[b] + n tokens: new 4-bit K rows; the V groups of 32 tokens that received tokens quantised again from
+ * the tokens they now hold (a group's scale follows its largest magnitude so far); the mean of a block that is
+ * still filling up taken over the tokens it has.  Every key block that receives a token is written whole (V codes
+ * of absent tokens are 0), so a partly filled last block is always defined.
+ *   k_new, v_new [B,Hkv,n_new,D] 16-bit (dt), device; must not overlap the cache
+ *   seqlens (device) [B] int32: tokens cached before the call (clamped to 0 .. Nkv); NOT modified - the caller
+ *     adds the appended count afterwards
+ *   new_lens (nullable, device) [B] int32: tokens to take per sequence, clamped to 0 .. n_new; NULL = n_new for all.
+ *     Tokens that would pass the capacity Nkv are dropped.
+ *   k16,v16 [B,Hkv,Nkv,D]; k4 [B,Hkv,Nkv,D/2]; ks [B,Hkv,Nkv,D/32]; v4 [B,Hkv,Nkv/64,D,32]; vs [B,Hkv,Nkv/32,D];
+ *   kmean [B,Hkv,Nkv/Bk,D] fp32: the cache, device, updated in place.  Nkv % Bk == 0, D == 128, Bk == 64.
+ * Calls that touch the same sequence must be ordered (same stream); nothing is allocated.
+ */
+thrift_status thrift_kv_cache_append(const void* k_new, const void* v_new, thrift_dtype dt, int n_new,
+                                     const int32_t* seqlens, const int32_t* new_lens,
+                                     void* k16, void* v16, uint8_t* k4, uint8_t* ks, uint8_t* v4, uint8_t* vs, float* kmean,
+                                     int B, int Hkv, int Nkv, int D, int Bk, void* stream);
 
 #ifdef __cplusplus
 }

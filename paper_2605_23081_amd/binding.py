@@ -7,6 +7,7 @@ memory and for the current stream.  There is no CPU fallback: if the library has
 from __future__ import annotations
 
 import ctypes as C
+import math
 import os
 from typing import Optional, Tuple
 
@@ -22,7 +23,7 @@ EXPORTS = (
     "thrift_status_string", "thrift_row_budget", "thrift_visible_blocks", "thrift_budget_to_global_k",
     "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_select_topk_shared", "thrift_select_ablation", "thrift_quantize_mxfp4",
     "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_prefill_chunk", "thrift_attn_prefill_ordered",
-    "thrift_attn_decode_workspace", "thrift_attn_decode", "thrift_attn_decode_shared",
+    "thrift_attn_decode_workspace", "thrift_attn_decode", "thrift_attn_decode_shared", "thrift_kv_cache_append",
 )
 
 _lib = None
@@ -62,6 +63,7 @@ def lib() -> C.CDLL:
         L.thrift_attn_decode_workspace.argtypes = [i] * 7
         L.thrift_attn_decode.argtypes = [p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, d, i, i, f, p, i, p, p, i, p, sz, p]
         L.thrift_attn_decode_shared.argtypes = L.thrift_attn_decode.argtypes
+        L.thrift_kv_cache_append.argtypes = [p, p, i, i, p, p, p, p, p, p, p, p, p, i, i, i, i, i, p]
         _lib = L
     return _lib
 
@@ -243,6 +245,54 @@ def thrift_attn_decode(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budget: floa
               kmax, _ptr(workspace), workspace.numel(), _stream()),
            "thrift_attn_decode_shared" if group_shared else "thrift_attn_decode")
     return (out, idx, cnt) if return_selection else out
+
+
+class KVCache:
+    """Device buffers of the dual cache (Sec. 4.1, Sec. 5): 16-bit K/V, MXFP4 K/V and the key-block means."""
+
+    def __init__(self, B, Hkv, Nkv, D, Bk, dtype, device, fill: Optional[int] = None):
+        assert Nkv % Bk == 0
+        u8 = torch.uint8
+
+        def mk(*shape, dtype):
+            # fill: a byte pattern for every buffer (tests poison the cache to show that nothing unwritten is read)
+            if fill is None:
+                return torch.empty(shape, dtype=dtype, device=device)
+            nbytes = math.prod(shape) * torch.empty((), dtype=dtype).element_size()
+            return torch.full((nbytes,), fill, dtype=u8, device=device).view(dtype).view(shape)
+
+        self.B, self.Hkv, self.Nkv, self.D, self.Bk = B, Hkv, Nkv, D, Bk
+        self.k16 = mk(B, Hkv, Nkv, D, dtype=dtype)
+        self.v16 = mk(B, Hkv, Nkv, D, dtype=dtype)
+        self.k4 = mk(B, Hkv, Nkv, D // 2, dtype=u8)
+        self.ks = mk(B, Hkv, Nkv, D // 32, dtype=u8)
+        self.v4 = mk(B, Hkv, Nkv // 64, D, 32, dtype=u8)
+        self.vs = mk(B, Hkv, Nkv // 32, D, dtype=u8)
+        self.kmean = mk(B, Hkv, Nkv // Bk, D, dtype=torch.float32)
+        self.seqlens = torch.zeros(B, dtype=torch.int32, device=device)
+
+    def append(self, k_new, v_new, new_lens: Optional[torch.Tensor] = None):
+        """Append k_new, v_new [B,Hkv,n,D] (all n tokens, or new_lens[b] of them) and advance seqlens."""
+        thrift_kv_cache_append(k_new, v_new, self.seqlens, self.k16, self.v16, self.k4, self.ks, self.v4, self.vs,
+                               self.kmean, self.Bk, new_lens)
+        n = k_new.shape[2]
+        step = torch.full_like(self.seqlens, n) if new_lens is None else new_lens.clamp(0, n).to(torch.int32)
+        self.seqlens = torch.minimum(self.seqlens + step, torch.full_like(self.seqlens, self.Nkv))
+
+
+def thrift_kv_cache_append(k_new, v_new, seqlens, k16, v16, k4, ks, v4, vs, kmean, Bk: int,
+                           new_lens: Optional[torch.Tensor] = None) -> None:
+    for t in (k_new, v_new, k16, v16, k4, ks, v4, vs, kmean):
+        _dev(t)
+    _dev(seqlens, torch.int32)
+    if new_lens is not None:
+        _dev(new_lens, torch.int32)
+    assert k_new.shape == v_new.shape and k_new.dtype == k16.dtype == v16.dtype
+    B, Hkv, n_new, D = k_new.shape
+    _, _, Nkv, _ = k16.shape
+    _check(lib().thrift_kv_cache_append(_ptr(k_new), _ptr(v_new), _DT[k_new.dtype], n_new, _ptr(seqlens), _ptr(new_lens),
+                                        _ptr(k16), _ptr(v16), _ptr(k4), _ptr(ks), _ptr(v4), _ptr(vs), _ptr(kmean),
+                                        B, Hkv, Nkv, D, Bk, _stream()), "thrift_kv_cache_append")
 
 
 # ---- Alg. 1 end to end: the user-level form of the paper's signature ----

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libthrift_hip.so")
-SOURCES = ["thrift_api.hip", "thrift_prepass.hip", "thrift_prefill.hip", "thrift_decode.hip"]
+SOURCES = ["thrift_api.hip", "thrift_prepass.hip", "thrift_prefill.hip", "thrift_decode.hip", "thrift_cache.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-FP32 VALU forms are kept out of the generated code on the test machines
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -323,4 +323,24 @@ thrift_status thrift_attn_decode_shared(const void* q, thrift_dtype dt, const vo
                           softmax_scale, out, out_dt, idx_out, cnt_out, kmax_out, workspace, workspace_bytes, 1, stream);
 }
 
+thrift_status thrift_kv_cache_append(const void* k_new, const void* v_new, thrift_dtype dt, int n_new,
+                                     const int32_t* seqlens, const int32_t* new_lens,
+                                     void* k16, void* v16, uint8_t* k4, uint8_t* ks, uint8_t* v4, uint8_t* vs, float* kmean,
+                                     int B, int Hkv, int Nkv, int D, int Bk, void* stream) {
+  if (!k_new || !v_new || !seqlens || !k16 || !v16 || !k4 || !ks || !v4 || !vs || !kmean) return THRIFT_ERR_NULL;
+  if (!is16(dt)) return THRIFT_ERR_DTYPE;
+  if (B <= 0 || Hkv <= 0 || Nkv <= 0 || n_new <= 0 || n_new > Nkv || D != kHeadDim || Bk != kKeyBlock || Nkv % Bk != 0 ||
+      Nkv / Bk > kMaxKeyBlocks)
+    return THRIFT_ERR_SHAPE;
+  if (thrift_status s = check_arch()) return s;
+  CacheAppendArgs a;
+  a.k_new = (const uint16_t*)k_new; a.v_new = (const uint16_t*)v_new; a.seqlens = seqlens; a.new_lens = new_lens;
+  a.k16 = (uint16_t*)k16; a.v16 = (uint16_t*)v16; a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.kmean = kmean;
+  a.B = B; a.Hkv = Hkv; a.Nkv = Nkv; a.n_new = n_new;
+  // n tokens starting anywhere inside a block touch at most floor((63 + n - 1) / 64) + 1 blocks
+  a.blocks_per_unit = (n_new + Bk - 2) / Bk + 1;
+  launch_cache_append(a, dt, (hipStream_t)stream);
+  return after_launch();
+}
+
 }  // extern "C"

@@ -25,11 +25,13 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
   unsigned char* lds = lds_all + wave * kDecodeLdsPerWave;
-  const int G = a.Hq / a.Hkv, Tk_all = a.Nkv / kBk;
+  const int G = a.Hq / a.Hkv;
   const int part = blockIdx.x % a.nsplit;
   const int unit = blockIdx.x / a.nsplit;
   const int b = unit / a.Hkv, kvh = unit % a.Hkv;
-  const int Tk = a.seqlens ? min(Tk_all, max(0, a.seqlens[b]) / kBk) : Tk_all;
+  // cached tokens of this sequence; the last key block may still be filling up
+  const int len = a.seqlens ? min(a.Nkv, max(0, a.seqlens[b])) : a.Nkv;
+  const int Tk = (len + kBk - 1) / kBk;
   const bool real = r < G;                                   // this lane's column is a real query head
   const int hq = kvh * G + (real ? r : 0);
   const size_t qh = (size_t)b * a.Hq + hq, kh = (size_t)b * a.Hkv + kvh;
@@ -83,6 +85,8 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
     const unsigned long long votes = __builtin_amdgcn_ballot_w64(mine16) & group_mask;
     const bool any16 = votes != 0ULL;
     const bool all16 = votes == group_mask;
+    const int n_valid = len - j * kBk;                       // < kBk only in a last block that is not full
+    const bool tail = n_valid < kBk;
 
     v16f s[2];
     if (!all16) {
@@ -104,9 +108,11 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       // ---- 16-bit scores; the V tile goes through this wavefront's LDS slice for the transposing reads ----
 #pragma unroll
       for (int u = 0; u < 16; ++u) {
+        // rows past the cached tokens are never written by anyone: stage the last valid row in their place
+        // (their probabilities are zero, but zero times an arbitrary bit pattern need not be)
         const int chunk = lane + 64 * u, row = chunk >> 4, col = chunk & 15;
         *reinterpret_cast<uint4*>(lds + row * kRow16 + col * 16) =
-            *reinterpret_cast<const uint4*>(v16base + ((size_t)j * kBk + row) * kD + col * 8);
+            *reinterpret_cast<const uint4*>(v16base + ((size_t)j * kBk + min(row, n_valid - 1)) * kD + col * 8);
       }
       v8s qf16[8];
 #pragma unroll
@@ -125,7 +131,7 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       else if (mine16) { s[0] = s16[0]; s[1] = s16[1]; }
     }
     float gmax;
-    const float alpha = softmax_update(s, lane, false, kBk, c, st, gmax);
+    const float alpha = softmax_update(s, lane, tail, n_valid, c, st, gmax);
     rescale(o, alpha);
     if (!all16) {
       // heads that took the 16-bit scores contribute nothing on the 4-bit path
@@ -196,7 +202,7 @@ __global__ void __launch_bounds__(256) decode_scores_kernel(const uint16_t* __re
   const int groups = (chunks + kScoreChunksPerWg - 1) / kScoreChunksPerWg;
   const int chunk0 = (blockIdx.x % groups) * kScoreChunksPerWg, unit = blockIdx.x / groups;
   const int b = unit / Hkv, kvh = unit % Hkv;
-  const int cap = seqlens ? min(Tk, max(0, seqlens[b]) / kBk) : Tk;
+  const int cap = seqlens ? min(Tk, (max(0, seqlens[b]) + kBk - 1) / kBk) : Tk;
   if (chunk0 * 64 >= cap) return;                           // uniform: nothing of these chunks is valid
   const int chunk_end = min(chunk0 + kScoreChunksPerWg, (cap + 63) / 64);
   const float* kunit = kmean + (size_t)unit * Tk * kD;
@@ -280,7 +286,7 @@ __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, 
   const long row = (long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   if (row >= n_rows) return;
   const int b = (int)(row / p.Hq);
-  const int vis = p.seqlens ? min(p.Tk, max(0, p.seqlens[b]) / kBk) : p.Tk;
+  const int vis = p.seqlens ? min(p.Tk, (max(0, p.seqlens[b]) + kBk - 1) / kBk) : p.Tk;
   int k;
   if (p.fixed_k >= 0) k = min(p.fixed_k, vis);
   else if (p.ppm <= 0 || vis == 0) k = 0;

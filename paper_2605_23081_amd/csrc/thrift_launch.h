@@ -72,4 +72,21 @@ void launch_decode_select(const uint16_t* q16, int q_is_bf16, const float* kmean
                           unsigned long long* bitmap, int words, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
                           int B, int Hq, int Hkv, int Tk, int fixed_k, long long ppm, int shared, hipStream_t st);
 
+// Append to the dual cache: tokens seqlens[b] .. seqlens[b] + n - 1 of every (sequence, KV head)
+struct CacheAppendArgs {
+  const uint16_t* k_new;      // [B,Hkv,n_new,D]
+  const uint16_t* v_new;
+  const int32_t* seqlens;     // [B] tokens cached before the call
+  const int32_t* new_lens;    // nullable [B]: tokens to take from k_new / v_new (<= n_new)
+  uint16_t* k16;              // [B,Hkv,Nkv,D]
+  uint16_t* v16;
+  uint8_t* k4;
+  uint8_t* ks;
+  uint8_t* v4;
+  uint8_t* vs;
+  float* kmean;
+  int B, Hkv, Nkv, n_new, blocks_per_unit;
+};
+void launch_cache_append(const CacheAppendArgs& a, thrift_dtype dt, hipStream_t st);
+
 }  // namespace thrift

@@ -69,6 +69,12 @@ def test_validation_errors_come_before_any_launch():
     assert dec(split=0) == SHAPE and dec(split=6) == SHAPE and dec(N=1000) == SHAPE
     assert dec(budget=2.0) == BUDGET
     assert dec(ws=None) == WORKSPACE and dec(wsb=16) == WORKSPACE
+    app = lambda **kw: L.thrift_kv_cache_append(kw.get("k", fake), fake, kw.get("dt", 0), kw.get("n", 1), kw.get("sl", fake), None,
+                                                fake, fake, fake, fake, fake, fake, fake, 1, 2, kw.get("N", 1024), kw.get("D", 128),
+                                                kw.get("Bk", 64), None)
+    assert app(k=None) == NULL and app(sl=None) == NULL
+    assert app(n=0) == SHAPE and app(n=2000) == SHAPE and app(N=1000) == SHAPE and app(D=64) == SHAPE and app(Bk=32) == SHAPE
+    assert app(dt=2) == DTYPE
     need = T.decode_workspace_bytes(16, 32, 8, 131072, 128, 64, 256)
     assert 0 < need < (64 << 20)
     assert T.decode_workspace_bytes(16, 32, 8, 131072, 64, 64, 256) == 0

@@ -602,3 +602,113 @@ def test_prefill_ragged_lengths(T, oracle, N, Bq, budget, causal, order):
     torch.cuda.synchronize()
     if order == 0:
         assert torch.equal(got2, res)
+
+
+# ------------------------------------------------------------------ dual cache: append and decode at any length
+
+def _check_cache(T, oracle, cache, k_all, v_all, lens):
+    """The cache must equal the pre-pass applied to each sequence's prefix; nothing else may have been written."""
+    k16, v16 = to_np(cache.k16.view(torch.int16)), to_np(cache.v16.view(torch.int16))
+    k4, ks, v4, vs, km = (to_np(x) for x in (cache.k4, cache.ks, cache.v4, cache.vs, cache.kmean))
+    for b, n in enumerate(lens):
+        nb = -(-n // 64)
+        if n == 0:
+            continue
+        kb, dt = oracle.bits_of(k_all[b:b + 1, :, :n].contiguous()); vb, _ = oracle.bits_of(v_all[b:b + 1, :, :n].contiguous())
+        assert np.array_equal(k16[b, :, :n].view(np.uint16), kb[0]) and np.array_equal(v16[b, :, :n].view(np.uint16), vb[0])
+        want_c, want_s = oracle.quantize_mxfp4(kb, dt, 0)
+        assert np.array_equal(unpack_axis0(k4[b:b + 1, :, :n]), want_c) and np.array_equal(ks[b:b + 1, :, :n], want_s)
+        want_c, want_s = oracle.quantize_mxfp4(vb, dt, 1)
+        got_c = unpack_axis1(v4[b:b + 1, :, :nb])
+        assert np.array_equal(got_c[:, :, :n], want_c) and np.all(got_c[:, :, n:] == 0)
+        ng = want_s.shape[2]
+        assert np.array_equal(vs[b:b + 1, :, :ng], want_s) and np.all(vs[b:b + 1, :, ng:2 * nb] == 127)
+        want_m = oracle.block_means(kb, dt, 64)
+        assert np.array_equal(km[b:b + 1, :, :nb].view(np.uint32), want_m.view(np.uint32))
+    return k16, v16, k4, ks, v4, vs, km
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_cache_append_equals_prepass_of_prefix(T, oracle, dtype):
+    _say(f"cache append {dtype}")
+    B, Hkv, Nkv = 3, 2, 512
+    wl = W.scaled(W.DECODE_131K, B=B, N=Nkv, Hq=4, Hkv=Hkv, dtype=dtype)
+    _, k, v = W.make_decode(wl)
+    POISON = 0xFF
+    cache = T.KVCache(B, Hkv, Nkv, wl.D, 64, k.dtype, "cuda", fill=POISON)
+    lens = [0] * B
+    # chunks and single tokens; steps that stay inside a group, cross a group, cross blocks, fill to the capacity
+    steps = [(70, [70, 33, 0]), (1, None), (1, [1, 0, 1]), (96, [64, 31, 95]), (130, [130, 130, 7]), (1, None), (300, [300, 2, 1])]
+    for n_max, per in steps:
+        take = [n_max] * B if per is None else per
+        new_k = torch.zeros(B, Hkv, n_max, wl.D, dtype=k.dtype); new_v = torch.zeros_like(new_k)
+        for b in range(B):
+            t = min(take[b], Nkv - lens[b])
+            new_k[b, :, :t] = k[b, :, lens[b]:lens[b] + t]; new_v[b, :, :t] = v[b, :, lens[b]:lens[b] + t]
+        nl = None if per is None else torch.tensor(per, dtype=torch.int32).cuda()
+        cache.append(new_k.cuda(), new_v.cuda(), nl)
+        lens = [min(Nkv, lens[b] + take[b]) for b in range(B)]
+        assert to_np(cache.seqlens).tolist() == lens
+        arrays = _check_cache(T, oracle, cache, k, v, lens)
+    # what lies past each sequence's last touched block still holds the fill pattern
+    k16, v16, k4, ks, v4, vs, km = arrays
+    for b, n in enumerate(lens):
+        nb = -(-n // 64)
+        assert np.all(k16[b, :, n:].view(np.uint8) == POISON) and np.all(v16[b, :, n:].view(np.uint8) == POISON)
+        assert np.all(k4[b, :, n:] == POISON) and np.all(ks[b, :, n:] == POISON)
+        assert np.all(v4[b, :, nb:] == POISON) and np.all(vs[b, :, 2 * nb:] == POISON)
+        assert np.all(km[b, :, nb:].view(np.uint8) == POISON)
+    assert lens[0] == Nkv                                     # one sequence reached the capacity and dropped the rest
+
+
+@pytest.mark.parametrize("budget,shared", [(0.05, False), (0.25, False), (1.0, False), (0.0, False), (0.1, True)])
+def test_decode_at_any_length(T, oracle, budget, shared):
+    """Decode over caches built by appends, lengths that leave the last key block partly filled; everything the
+    appends did not write holds an all-ones byte pattern (NaN as a float of any width)."""
+    lens = [2047, 641, 65, 1, 1984]
+    B, Hq, Hkv, Nkv, split = len(lens), 8, 2, 2048, 16
+    _say(f"decode at lengths {lens} budget={budget} shared={shared}")
+    wl = W.scaled(W.DECODE_131K, B=B, N=Nkv, Hq=Hq, Hkv=Hkv)
+    q, k, v = W.make_decode(wl)
+    cache = T.KVCache(B, Hkv, Nkv, wl.D, 64, k.dtype, "cuda", fill=0xFF)
+    nl = torch.tensor(lens, dtype=torch.int32).cuda()
+    cache.append(k.cuda(), v.cuda(), nl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    qm = q.float().numpy().reshape(B, Hq, 1, wl.D)
+    Tk = Nkv // 64
+    kmax = max(1, oracle.row_k(Tk, budget, -1))
+    idx_r = np.full((B, Hq, kmax), -1, np.int32); cnt_r = np.zeros((B, Hq), np.int32)
+    scores = np.zeros((B, Hq, Tk))
+    for b, n in enumerate(lens):
+        km_b = oracle.block_means(np.ascontiguousarray(kb[b:b + 1, :, :n]), dt, 64)
+        i_b, c_b = oracle.select_topk(qm[b:b + 1], km_b, 1, 64, False, budget, -1, group_shared=shared)
+        idx_r[b, :, :i_b.shape[-1]] = i_b[0, :, 0]; cnt_r[b] = c_b[0, :, 0]
+        sc = oracle.block_scores(qm[b:b + 1], km_b)[0, :, 0]
+        if shared:
+            sc = np.repeat(sc.reshape(Hkv, Hq // Hkv, -1).sum(1), Hq // Hkv, axis=0)
+        scores[b, :, :sc.shape[-1]] = sc
+    sl = np.asarray(lens, np.int32)
+    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, 64, 1 / math.sqrt(wl.D), split // 4, seqlens=sl)
+    got, idx_g, cnt_g = T.thrift_attn_decode(q.cuda(), cache.k16, cache.v16, cache.k4, cache.ks, cache.v4, cache.vs, cache.kmean,
+                                             64, budget, -1, split, seqlens=cache.seqlens, out_dtype=torch.float32,
+                                             return_selection=True, group_shared=shared)
+    torch.cuda.synchronize()
+    swaps = check_selection(to_np(idx_g), to_np(cnt_g), idx_r, cnt_r, scores)
+    err = np.abs(to_np(got) - want).max()
+    _say(f"  max abs err {err:.3e} swaps {swaps}")
+    assert np.isfinite(to_np(got)).all() and swaps == 0
+    assert err <= (TOL16 if budget == 1.0 else TOLMIX)
+    # one more token: the appended token changes the last block's mean, its V group and the selection
+    cache.append(k[:, :, :1].contiguous().cuda(), v[:, :, :1].contiguous().cuda())
+    assert to_np(cache.seqlens).tolist() == [n + 1 for n in lens]
+
+
+def test_decode_empty_sequence_gives_zeros(T, oracle):
+    wl = W.scaled(W.DECODE_131K, B=2, N=256, Hq=4, Hkv=2)
+    q, k, v = W.make_decode(wl)
+    cache = T.KVCache(2, 2, 256, wl.D, 64, k.dtype, "cuda", fill=0xFF)
+    cache.append(k.cuda(), v.cuda(), torch.tensor([0, 100], dtype=torch.int32).cuda())
+    got = T.thrift_attn_decode(q.cuda(), cache.k16, cache.v16, cache.k4, cache.ks, cache.v4, cache.vs, cache.kmean, 64, 0.25, -1, 4,
+                               seqlens=cache.seqlens, out_dtype=torch.float32)
+    g = to_np(got)
+    assert np.all(g[0] == 0) and np.isfinite(g[1]).all() and np.abs(g[1]).max() > 0
