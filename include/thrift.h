@@ -200,7 +200,13 @@ thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void
  *   tile_order 1: the order of the kernel in Sec. 3.3 — every 4-bit block in ascending order first, then
  *                 the promoted blocks in ascending order.
  * In exact arithmetic the two agree; the 4-bit rounding of P depends on the running maximum, so the
- * results differ at the level of the quantisation noise.  Other values: THRIFT_ERR_SHAPE.
+ * results differ at the level of the quantisation noise.
+ *   tile_order 2, 3: ascending order like 0, with the staging schedule fixed instead of chosen by the library
+ *                 (2: three workgroups per CU, 16-bit tiles of a promoted block half a step ahead; 3: two
+ *                 workgroups per CU, every block a whole step ahead and the 16-bit query rows in registers,
+ *                 Bq = 128 only, else it falls back to 2).  0 picks 3 when kmax is at least 15 % of the key
+ *                 blocks, where the promoted blocks dominate the time.  The results of 0, 2 and 3 are bit-identical.
+ * Other values: THRIFT_ERR_SHAPE.
  */
 thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const void* v, thrift_dtype dt,
                                           const uint8_t* q4, const uint8_t* qs, const uint8_t* k4, const uint8_t* ks,

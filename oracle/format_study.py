@@ -1,7 +1,9 @@
-"""Oracle-only study: what does the MXFP4 substitution (the build's format) cost against the paper's NVFP4?
+"""Oracle-only study: what does the MXFP4 substitution (the build's format) cost against the paper's NVFP4,
+what would a scale rule that never saturates change, and how does the paper's single global k (App. B) compare
+with the per-row budget rule of the benchmark configurations?
 
-Runs the CPU oracle on sampled query blocks of the synthetic Qwen3-8B-shaped workload in both formats and prints
-the relative Frobenius error against fp64 exact attention and the error-gap recovery at 5 / 10 / 25 % budgets.
+Runs the CPU oracle on sampled query blocks of the synthetic Qwen3-8B-shaped workload and prints the relative
+Frobenius error against fp64 exact attention and the error-gap recovery at 5 / 10 / 25 % budgets.
 Test infrastructure: calls only oracle/ and the seeded input generators.
 
     python -m oracle.format_study [--seq 32768]
@@ -40,15 +42,18 @@ def main() -> int:
     exact = O.attn_exact(qb, kb, vb, dt, True, scale, rows)
     qm = O.block_means(qb, dt, wl.Bq); km = O.block_means(kb, dt, wl.Bk)
     print(f"workload {wl.name} N={wl.N}, head 0, query blocks {picks}; rel. Frobenius error vs fp64 exact attention")
-    print(f"{'format':8s} " + " ".join(f"{'f=' + str(f):>10s}" for f in (0.0, 0.05, 0.10, 0.25, 1.0)) + "   recovery % at 5/10/25")
-    for name, fmt in (("MXFP4", 0), ("NVFP4", 1)):
+    print(f"{'format':9s} " + " ".join(f"{'f=' + str(f):>10s}" for f in (0.0, 0.05, 0.10, 0.25, 1.0)) + "   recovery % at 5/10/25")
+    Tk = wl.N // wl.Bk
+    for name, fmt, global_k in (("MXFP4", 0, False), ("NVFP4", 1, False), ("MX-nosat", 2, False), ("MX-glob-k", 0, True)):
         errs = {}
         for f in (0.0, 0.05, 0.10, 0.25, 1.0):
-            idx, cnt = O.select_topk(qm, km, wl.Bq, wl.Bk, True, f)
+            # App. B: one k for every row, chosen so that the causal tile fraction is closest to f
+            fixed_k = O.paper_global_k(Tk, f) if global_k and 0.0 < f < 1.0 else -1
+            idx, cnt = O.select_topk(qm, km, wl.Bq, wl.Bk, True, f, fixed_k)
             out = O.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, wl.Bq, wl.Bk, True, scale, units, fmt=fmt)
             errs[f] = metrics.rel_fro(out.reshape(-1, wl.D), exact)
         rec = [100 * metrics.recovery(errs[1.0], errs[0.0], errs[f]) for f in (0.05, 0.10, 0.25)]
-        print(f"{name:8s} " + " ".join(f"{errs[f]:10.5f}" for f in (0.0, 0.05, 0.10, 0.25, 1.0)) + "   " + " / ".join(f"{r:.1f}" for r in rec))
+        print(f"{name:9s} " + " ".join(f"{errs[f]:10.5f}" for f in (0.0, 0.05, 0.10, 0.25, 1.0)) + "   " + " / ".join(f"{r:.1f}" for r in rec))
     return 0
 
 

@@ -457,6 +457,35 @@ void oracle_nvfp4_qdq(const double* x, long n, double* out) {
 }
 
 /* ------------------------------------------------------------------ */
+/* MXFP4 with a scale that never saturates — study aid                  */
+/* ------------------------------------------------------------------ */
+
+/* The OCP rule above lets a group maximum in (6,8) * 2^e saturate to 6 * 2^e.  The alternative picks the
+ * smallest power of two that brings every element of the group to at most 6 (one binade coarser for
+ * exactly those groups, identical otherwise), trading the saturation error of the maximum for a wider
+ * step on the rest of the group.  Quantise-dequantise of n values x[0], x[stride], ... */
+static void mx_nosat_qdq_group(const double* x, int n, int stride, double* out, int ostride) {
+  double amax = 0.0;
+  for (int t = 0; t < n; ++t) { double a = fabs(x[(long)t * stride]); if (a > amax) amax = a; }
+  int e = 0;
+  if (amax != 0.0) {
+    int ex;
+    frexp(amax, &ex);
+    e = (ex - 1) - 2;                                   /* the floor rule's exponent: amax * 2^-e in [4,8) */
+    if (ldexp(amax, -e) > 6.0) e += 1;
+    if (e < -127) e = -127;
+    if (e > 127) e = 127;
+  }
+  for (int t = 0; t < n; ++t)
+    out[(long)t * ostride] = ldexp(oracle_e2m1_decode(e2m1_encode(ldexp(x[(long)t * stride], -e))), e);
+}
+
+/* x: n doubles (n a multiple of 32) -> quantise-dequantise in groups of 32 consecutive values. */
+void oracle_mx_nosat_qdq(const double* x, long n, double* out) {
+  for (long g = 0; g < n / 32; ++g) mx_nosat_qdq_group(x + g * 32, 32, 1, out + g * 32, 1);
+}
+
+/* ------------------------------------------------------------------ */
 /* Exact attention  (Sec. 3.1, Eq. (1)) — the error reference          */
 /* ------------------------------------------------------------------ */
 
@@ -507,7 +536,8 @@ typedef struct {
   const double* vh;   /* [Nk,D] high-precision values */
   const double* kq;   /* [Nk,D] dequantised MXFP4 keys   */
   const double* vq;   /* [Nk,D] dequantised MXFP4 values */
-  int fmt;            /* 0: MXFP4 (the build's format); 1: NVFP4 (the paper's), see oracle_nvfp4_qdq */
+  int fmt;            /* 0: MXFP4 (the build's format); 1: NVFP4 (the paper's), see oracle_nvfp4_qdq;
+                         2: MXFP4 with the scale rule that never saturates, see oracle_mx_nosat_qdq */
 } kv_view_t;
 
 /* One (query row, key block) step of Alg. 1: scores on the chosen path, running max / sum update,
@@ -553,6 +583,8 @@ static void row_tile_step(const kv_view_t* kv, const double* qh, const double* q
       for (int c = 0; c < Bk; ++c) Y[c] = s1 > 0.0 ? P[c] / s1 : 0.0;
       for (int g = 0; g < Bk / 16; ++g) nvfp4_qdq_group(Y + g * 16, 16, 1, Pd + g * 16, 1);
       for (int c = 0; c < Bk; ++c) Pd[c] *= s1;
+    } else if (kv->quantize_p && kv->fmt == 2) {
+      for (int g = 0; g < Bk / 32; ++g) mx_nosat_qdq_group(P + g * 32, 32, 1, Pd + g * 32, 1);
     } else if (kv->quantize_p) {
       uint8_t codes[32];
       for (int g = 0; g < Bk / 32; ++g) {
@@ -589,12 +621,18 @@ static void head_quant_dequant(const uint16_t* x, int dtype, int N, int D, int a
   free(codes);
   free(scales);
 }
-/* fmt 1: NVFP4 groups of 16 along D (axis 0) or along the tokens (axis 1, the contraction axis of P.V). */
+/* fmt 1: NVFP4 groups of 16 along D (axis 0) or along the tokens (axis 1, the contraction axis of P.V);
+ * fmt 2: groups of 32 on the same axes with the scale rule that never saturates (N a multiple of 32). */
 static void head_quant_dequant_fmt(const uint16_t* x, int dtype, int N, int D, int axis, int fmt, double* out) {
   if (fmt == 0) { head_quant_dequant(x, dtype, N, D, axis, out); return; }
   double* xd = (double*)malloc(sizeof(double) * (size_t)N * D);
   head_to_double(x, dtype, (long)N * D, xd);
-  if (axis == 0) {
+  if (fmt == 2) {
+    if (axis == 0) oracle_mx_nosat_qdq(xd, (long)N * D, out);
+    else
+      for (int g = 0; g < N / 32; ++g)
+        for (int c = 0; c < D; ++c) mx_nosat_qdq_group(xd + (long)g * 32 * D + c, 32, D, out + (long)g * 32 * D + c, D);
+  } else if (axis == 0) {
     oracle_nvfp4_qdq(xd, (long)N * D, out);
   } else {
     for (int g = 0; g < N / 16; ++g)

@@ -167,6 +167,14 @@ def nvfp4_qdq(x: np.ndarray) -> np.ndarray:
     return out
 
 
+def mx_nosat_qdq(x: np.ndarray) -> np.ndarray:
+    """MXFP4 quantise-dequantise of consecutive groups of 32 with the scale rule that never saturates (study aid)."""
+    x = np.ascontiguousarray(x, np.float64)
+    out = np.empty_like(x)
+    lib().oracle_mx_nosat_qdq(_p(x), C.c_long(x.size), _p(out))
+    return out
+
+
 def mx_quantize_group(x: Sequence[float]) -> Tuple[np.ndarray, int]:
     x = np.ascontiguousarray(x, np.float64)
     codes = np.empty(x.shape[0], np.uint8)
@@ -213,7 +221,8 @@ def attn_thrift_prefill(q, k, v, dtype: int, idx, cnt, Bq: int, Bk: int, causal:
     """units: [n,3] int32 (b, h, i).  -> out [n, Bq, D] fp64 (and lse [n, Bq]).
 
     q may hold fewer tokens than k, v (chunked prefill): query block i then stands at block position
-    i + q_block_offset of the sequence.  fmt 1: the paper's NVFP4 numerics instead of MXFP4 (study aid)."""
+    i + q_block_offset of the sequence.  fmt 1: the paper's NVFP4 numerics instead of MXFP4; fmt 2: MXFP4 with the
+    scale rule that never saturates (study aids; fmt 2 needs N % 32 == 0)."""
     q, k, v = _u16(q), _u16(k), _u16(v)
     B, Hq, Nq, D = q.shape
     Hkv, N = k.shape[1], k.shape[2]

@@ -199,7 +199,8 @@ def thrift_attn_prefill_chunk(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq: int
                               softmax_scale: float = 0.0, out: Optional[torch.Tensor] = None,
                               out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None,
                               tile_order: int = 0) -> torch.Tensor:
-    """q, q4, qs: the chunk's Nq tokens; k, v and their codes: the whole key range.  tile_order 1: Sec. 3.3's order."""
+    """q, q4, qs: the chunk's Nq tokens; k, v and their codes: the whole key range.  tile_order 1: Sec. 3.3's order;
+    2 / 3: ascending order with the staging schedule fixed (see include/thrift.h)."""
     for t in (q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt):
         _dev(t)
     B, Hq, Nq, D = q.shape

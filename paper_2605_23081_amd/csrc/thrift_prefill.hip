@@ -30,6 +30,11 @@ constexpr int kLdsRing = 0;                                  // two slots of kLd
 constexpr int kLdsV16 = 2 * kLdsBytes4;                      // one swizzled 16-bit V tile
 constexpr int kLdsK16 = kLdsV16 + kTile16;                   // one swizzled 16-bit K tile
 constexpr int kLdsPrefill = kLdsK16 + kTile16;               // 50176: three workgroups per CU
+// LDS map of the wide schedule: two slots that hold one key block each, whatever its path
+// (a 4-bit block in the first kLdsBytes4 bytes; a promoted block as its K tile followed by its V tile)
+constexpr int kWideSlot = 2 * kTile16;                       // 32768
+constexpr int kLdsPrefillWide = 2 * kWideSlot;               // 65536: two workgroups per CU
+constexpr int kWidePercent = 15;                             // list length / key blocks (in %) from which the wide schedule is used
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
 // load (a full fence), which would wait for the tiles in flight at every key block; here only this
@@ -54,11 +59,12 @@ __device__ __forceinline__ void dma_b32(const void* base, uint32_t off, uint32_t
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
 }
 
-template <typename T, int NW, int ORDER>
-__global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
+template <typename T, int NW, int ORDER, int WIDE>
+__global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillArgs a) {
   constexpr int KF = 4 / NW;                 // 1 KiB fragments of a 4-bit K (and of a V) tile per wavefront
   constexpr int C16 = 16 / NW;               // ... for one 16-bit K or V tile
-  __shared__ __align__(1024) unsigned char lds[kLdsPrefill];
+  constexpr int kSlotStride = WIDE ? kWideSlot : kLdsBytes4;
+  __shared__ __align__(1024) unsigned char lds[WIDE ? kLdsPrefillWide : kLdsPrefill];
 
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
@@ -141,7 +147,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
     const int j_ = __builtin_amdgcn_readfirstlane(J), s_ = __builtin_amdgcn_readfirstlane(S); /* scalar operands */ \
     const uint8_t* kt_ = k4base + (size_t)j_ * 4096;                                                           \
     const uint8_t* vt_ = v4base + (size_t)j_ * 4096;                                                           \
-    const uint32_t sl_ = lds0 + kLdsRing + s_ * kLdsBytes4;                                                    \
+    const uint32_t sl_ = lds0 + kLdsRing + s_ * kSlotStride;                                                   \
     if ((j_ + 1) * kBk <= N) {                                                                                 \
       _Pragma("unroll") for (int u = 0; u < KF; ++u) dma_b128(kt_, k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024); \
       if (!(wave & 1)) dma_b32(ksbase + (size_t)j_ * 256, scoff, sl_ + kLdsKS);                                \
@@ -222,7 +228,68 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   n0 = n1;                                                                                                     \
   n1 = ps + 1 < nsel ? sel[ps + 1] : 0x7fffffff;
 
-  if constexpr (ORDER == 1) {
+  // 16-bit query fragments of the lane's row (the wide schedule keeps them in registers for the whole walk; the
+  // three-workgroup schedule has no registers to spare and fetches them again at every promoted block)
+#define THRIFT_LOAD_Q16(QF)                                                                                    \
+  _Pragma("unroll") for (int s8 = 0; s8 < 8; ++s8)                                                             \
+    QF[s8] = *reinterpret_cast<const v8s*>(q16head + (uint32_t)(lrow * (2 * kD) + 32 * s8 + 16 * half));       \
+  _Pragma("unroll") for (int s8 = 0; s8 < 8; ++s8) asm volatile("" : "+v"(QF[s8]));
+
+  if constexpr (WIDE) {
+    // ---- wide schedule: every block, 4-bit or promoted, is fetched one whole step ahead into the slot the
+    // block before last has left; one barrier per key block, no second rendezvous for promoted blocks ----
+#define THRIFT_ISSUE_WIDE(J1, P1)                                                                              \
+  if ((J1) < vis) {                                                                                            \
+    if (P1) {                                                                                                  \
+      THRIFT_ISSUE_TILE16(k16base, J1, (u * NW >= 8 ? THRIFT_K16OFF() ^ 64u : THRIFT_K16OFF()),                \
+                          lds0 + (uint32_t)(((J1) & 1) * kWideSlot));                                          \
+      THRIFT_ISSUE_TILE16(v16base, J1, THRIFT_V16OFF(), lds0 + (uint32_t)(((J1) & 1) * kWideSlot + kTile16));  \
+    } else {                                                                                                   \
+      THRIFT_ISSUE4(J1);                                                                                       \
+    }                                                                                                          \
+  }
+    // the 16-bit query fragments stay in registers (this schedule has 256 of them)
+    v8s qf[8];
+    THRIFT_LOAD_Q16(qf)
+    if (vis > 0) { THRIFT_ISSUE_WIDE(0, n0 == 0) }
+    int j = 0;
+    while (j < vis_wave) {
+      const int run_end = min(vis_wave, n0);
+      for (; j < run_end; ++j) {                          // a run of 4-bit blocks
+        THRIFT_SYNC()
+        THRIFT_ISSUE_WIDE(j + 1, j + 1 == n0)
+        THRIFT_MASK(j)
+        const unsigned char* slot = lds + (j & 1) * kWideSlot;
+        v16f s[2];
+        float gmax;
+        scores_fp4(slot, lane, qf4, qsc, s);
+        const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+        rescale(o, alpha);
+        pv_fp4(slot, lane, s, gmax, o);
+      }
+      if (j < vis_wave) {                                 // j == n0: a promoted block
+        THRIFT_SYNC()
+        THRIFT_ISSUE_WIDE(j + 1, j + 1 == n1)
+        THRIFT_MASK(j)
+        const unsigned char* slot = lds + (j & 1) * kWideSlot;
+        v16f s[2];
+        scores_16<T>(slot, lane, qf, s);
+        float gmax;
+        const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
+        rescale(o, alpha);
+        pv_16<T, true>(slot + kTile16, lane, s, o);
+        THRIFT_NEXT_PROMOTED()
+        ++j;
+      }
+    }
+    for (; j < vis; ++j) {                                // staging only: blocks that later wavefronts still need
+      const bool p0 = j == n0;
+      THRIFT_SYNC()
+      THRIFT_ISSUE_WIDE(j + 1, j + 1 == (p0 ? n1 : n0))
+      if (p0) { THRIFT_NEXT_PROMOTED() }
+    }
+#undef THRIFT_ISSUE_WIDE
+  } else if constexpr (ORDER == 1) {
     // ---- the order of Sec. 3.3: every 4-bit block in ascending order, then the promoted blocks in ascending
     // order.  Same staging rules; the ring slot follows the step number because block ids now skip. ----
     int nselv = nsel;                                   // promoted ids inside the visible range (the list is ascending)
@@ -275,8 +342,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
       float gmax, alpha = 1.0f;
       if (mine) {
         v8s qf[8];
-#pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16head + (uint32_t)(lrow * (2 * kD) + 32 * s8 + 16 * half));
+        THRIFT_LOAD_Q16(qf)
         scores_16<T>(lds + kLdsK16, lane, qf, s);
       }
       if (p1) {
@@ -325,16 +391,15 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
     }
     if (j < vis_wave) {                                 // j == n0: a promoted block
       const bool p1 = j + 1 == n1 && j + 1 < vis;
+      v16f s[2];
+      float gmax;
       THRIFT_SYNC()
       THRIFT_ISSUE(j, true, j + 1 == n1)
       if (late_v) THRIFT_ISSUE_V16(j);
       THRIFT_MASK(j)
-      v16f s[2];
-      float gmax;
       {
         v8s qf[8];
-#pragma unroll
-        for (int s8 = 0; s8 < 8; ++s8) qf[s8] = *reinterpret_cast<const v8s*>(q16head + (uint32_t)(lrow * (2 * kD) + 32 * s8 + 16 * half));
+        THRIFT_LOAD_Q16(qf)
         scores_16<T>(lds + kLdsK16, lane, qf, s);
       }
       if (p1) {                                         // the K buffer is free once every wavefront has its scores
@@ -380,6 +445,7 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   }
   vm_wait<0>();
 #undef THRIFT_SYNC
+#undef THRIFT_LOAD_Q16
 #undef THRIFT_ISSUE
 #undef THRIFT_MASK
 #undef THRIFT_NEXT_PROMOTED
@@ -396,7 +462,9 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   const float l = st.l + other_half(st.l);
   const float inv = l > 0.f ? 1.0f / l : 0.f;
   const size_t orow = (qh * Nq + lrow) * kD;
-  const bool row_ok = i * Bq + wave * 32 + r < Nq;
+  int r_again = (int)(threadIdx.x & 31);
+  asm volatile("" : "+v"(r_again));                    // recomputed here: the unclamped row index is not worth a register through the key loop
+  const bool row_ok = i * Bq + wave * 32 + r_again < Nq;
 #pragma unroll
   for (int n = 0; n < 4; ++n)
 #pragma unroll
@@ -421,14 +489,27 @@ __global__ void __launch_bounds__(NW * 64, 3) prefill_kernel(PrefillArgs a) {
   if (a.lse != nullptr && half == 0 && row_ok) a.lse[qh * Nq + lrow] = st.m * a.scale + __logf(l);
 }
 
+// The wide schedule pays for itself once promoted blocks are frequent: their 32 KiB of 16-bit tiles then
+// arrive a whole step ahead instead of half a step, at the price of two instead of three workgroups per CU
+// for the 4-bit blocks.  The per-row list length bounds the promoted share from above.
+static bool wide_schedule(const PrefillArgs& a) {
+  if (a.Bq != 128 || a.tile_order == 1 || a.tile_order == 2) return false;
+  if (a.tile_order == 3) return true;
+  const long Tk = (a.N + kBk - 1) / kBk;
+  return (long)a.kmax * 100L >= Tk * (long)kWidePercent;
+}
+
 void launch_prefill(const PrefillArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((long)a.B * a.Hq * ((a.Nq + a.Bq - 1) / a.Bq));
 #define THRIFT_LAUNCH(T, NW)                                                                                   \
   do {                                                                                                         \
-    if (a.tile_order == 1) prefill_kernel<T, NW, 1><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);                  \
-    else prefill_kernel<T, NW, 0><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);                                    \
+    if (a.tile_order == 1) prefill_kernel<T, NW, 1, 0><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);               \
+    else prefill_kernel<T, NW, 0, 0><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);                                 \
   } while (0)
-  if (a.Bq == 128) {
+  if (wide_schedule(a)) {
+    if (a.dt == THRIFT_F16) prefill_kernel<F16, 4, 0, 1><<<dim3(grid), dim3(256), 0, st>>>(a);
+    else prefill_kernel<BF16, 4, 0, 1><<<dim3(grid), dim3(256), 0, st>>>(a);
+  } else if (a.Bq == 128) {
     if (a.dt == THRIFT_F16) THRIFT_LAUNCH(F16, 4);
     else THRIFT_LAUNCH(BF16, 4);
   } else {

@@ -541,8 +541,45 @@ def test_prefill_two_phase_order(T, oracle, wl, budget, causal):
         torch.cuda.synchronize()
         assert torch.equal(asc, got)
     with pytest.raises(T.ThriftError) as e:
-        T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0, tile_order=2)
+        T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0, tile_order=4)
     assert e.value.code == 2
+
+
+# ------------------------------------------------------------------ the two schedules of the ascending walk
+@pytest.mark.parametrize("wl,N,budget,causal", [
+    (_small_bf16(N=2048), 2048, 0.25, True),
+    (_small_bf16(N=1024), 1024, 1.0, True),                  # promoted blocks only: both slots carry 16-bit tiles
+    (_small_bf16(N=1024), 1024, 0.0, True),
+    (_small_bf16(N=1024, Hq=6, Hkv=2), 1000, 0.3, True),    # short last blocks
+    (_small_bf16(N=1024), 1024, 0.5, False),
+    (W.scaled(W.TINY, N=1024, Hq=2, Hkv=1, Bq=128), 1024, 0.4, True),   # fp16
+    (_small_bf16(N=128, Hq=1, Hkv=1), 128, 0.5, True),       # one query block over two key blocks
+    (_small_bf16(N=128, Hq=1, Hkv=1), 65, 1.0, True),
+])
+def test_prefill_schedules_agree_bit_for_bit(T, oracle, wl, N, budget, causal):
+    """tile_order 2 (three workgroups per CU, promoted tiles half a step ahead) and 3 (two workgroups per CU, every
+    block a whole step ahead) run the same arithmetic in the same order: equal bits, and parity with the oracle."""
+    _say(f"schedules {wl.name} N={N} f={budget} causal={causal}")
+    q, k, v, _, _ = W.make_prefill(wl)
+    q, k, v = q[:, :, :N].contiguous(), k[:, :, :N].contiguous(), v[:, :, :N].contiguous()
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    Tq = -(-N // wl.Bq)
+    qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    idx, cnt = oracle.select_topk(qm, km, wl.Bq, wl.Bk, causal, budget)
+    want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, wl.Bq, wl.Bk, causal, 1 / math.sqrt(wl.D),
+                                      _units(wl.B, wl.Hq, Tq)).reshape(wl.B, wl.Hq, Tq * wl.Bq, wl.D)[:, :, :N]
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    if idx.shape[-1] == 0:
+        idx = np.full(idx.shape[:-1] + (1,), -1, np.int32)
+    ig, cg = torch.from_numpy(idx).cuda(), torch.from_numpy(cnt).cuda()
+    outs = [T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0,
+                                        out_dtype=torch.float32, tile_order=order) for order in (0, 2, 3)]
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[1], outs[2])
+    err = np.abs(to_np(outs[2]) - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert err <= (TOL16 if budget == 1.0 else TOLMIX)
 
 
 # ------------------------------------------------------------------ lengths that are not multiples of the blocks

@@ -235,3 +235,34 @@ def test_nvfp4_group_against_brute_force(oracle):
     # two groups are independent
     a, b = rng.standard_normal(16), 100 * rng.standard_normal(16)
     assert np.array_equal(oracle.nvfp4_qdq(np.concatenate([a, b])), np.concatenate([oracle.nvfp4_qdq(a), oracle.nvfp4_qdq(b)]))
+
+
+def test_mx_nosat_group_against_brute_force(oracle):
+    """The scale rule without saturation: the power-of-two scale is the smallest that keeps max|x|/scale <= 6
+    (found here by scanning exponents), elements go to the nearest grid value; it coincides with the floor rule
+    unless the group's maximum falls in (6,8) scale units, and then nothing saturates."""
+    rng = np.random.default_rng(23)
+    grid = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+    differed = 0
+    for trial in range(400):
+        x = rng.standard_normal(32) * np.exp(rng.uniform(-6, 6))
+        if trial % 5 == 0:
+            x[rng.integers(0, 32)] = 7.0 * 2.0 ** rng.integers(-5, 5)       # a maximum the floor rule saturates
+        got = oracle.mx_nosat_qdq(x)
+        amax = np.abs(x).max()
+        e = next(e for e in range(-140, 140) if amax / 2.0 ** e <= 6.0)
+        y = np.abs(x) / 2.0 ** e
+        assert y.max() <= 6.0 and (y.max() > 3.0)                           # smallest such exponent
+        want = np.array([grid[np.argmin(np.abs(grid - v))] for v in y]) * 2.0 ** e * np.sign(x)
+        ties = np.isin(y, [0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+        assert np.array_equal(got[~ties], want[~ties])
+        codes, sb = oracle.mx_quantize_group(x)
+        floor_dq = np.array([oracle.lib().oracle_e2m1_decode(int(c)) for c in codes]) * 2.0 ** (sb - 127)
+        if amax / 2.0 ** (sb - 127) <= 6.0:
+            assert np.array_equal(got, floor_dq)
+        else:
+            differed += 1
+            assert sb - 127 == e - 1 and np.abs(floor_dq).max() == 6.0 * 2.0 ** (e - 1) < amax
+            assert abs(np.abs(got).max() - amax) <= 0.5 * 2.0 ** e
+    assert differed >= 40
+    assert np.array_equal(oracle.mx_nosat_qdq(np.zeros(32)), np.zeros(32))
