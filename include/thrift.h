@@ -235,6 +235,7 @@ size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int 
  *     the length are masked, its kmean entry must be the mean of the tokens it has and its V groups must have
  *     been quantised from those tokens alone (what thrift_kv_cache_append, or the pre-pass on a tensor of that
  *     length, produces).  Cache contents past that block are never read.  A sequence of length 0 yields zeros.
+ *     Split-K: the full key blocks are cut into the partitions; a partly filled last block is a partition of its own.
  *   split_blocks: key blocks per partition (> 0)
  *   out [B,Hq,D] in out_dt
  *   idx_out (nullable) [B,Hq,kmax_out], cnt_out (nullable) [B,Hq]: the selection that was used

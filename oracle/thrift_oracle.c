@@ -743,6 +743,9 @@ int oracle_attn_thrift_prefill(const uint16_t* q, const uint16_t* k, const uint1
  * (m,l,O), and the partitions are merged by their log-sum-exp.  split_blocks <= 0: one partition.
  * q:[B,Hq,D]; k,v:[B,Hkv,Nkv,D]; idx:[B,Hq,kmax], cnt:[B,Hq]; seqlens nullable [B] (any length up
  * to Nkv: the last key block may be short).  out: [B,Hq,D] fp64.
+ * Where the partition boundaries fall is this build's choice (the paper reports decode results only):
+ * the full key blocks are cut into partitions of split_blocks, and a partly filled last block, the one a
+ * growing cache is still writing, forms a partition of its own.
  */
 int oracle_attn_thrift_decode(const uint16_t* q, const uint16_t* k, const uint16_t* v, int dtype,
                               const int32_t* idx, const int32_t* cnt, int kmax, const int32_t* seqlens,
@@ -778,10 +781,12 @@ int oracle_attn_thrift_decode(const uint16_t* q, const uint16_t* k, const uint16
         int nsel = cnt ? cnt[(long)b * Hq + h] : 0;
         double M = -INFINITY, L = 0.0, Oacc[1024];
         for (int x = 0; x < D; ++x) Oacc[x] = 0.0;
-        for (int p0 = 0; p0 < Tk; p0 += sb) {
+        int Tfull = split_blocks > 0 ? len / Bk : Tk;       /* without splitting the short block stays in the one partition */
+        for (int p0 = 0, pend; p0 < Tk; p0 = pend) {
           double m = -INFINITY, l = 0.0, O[1024];
           for (int x = 0; x < D; ++x) O[x] = 0.0;
-          for (int j = p0; j < p0 + sb && j < Tk; ++j) {
+          pend = p0 < Tfull ? (p0 + sb < Tfull ? p0 + sb : Tfull) : Tk;   /* past the full blocks: the short block alone */
+          for (int j = p0; j < pend; ++j) {
             int is16 = force_path >= 0 ? force_path : in_sorted(sel, nsel, j);
             row_tile_step(&kv, qh, qq, j, is16, len - j * Bk < Bk ? len - j * Bk : Bk, &m, &l, O);
           }

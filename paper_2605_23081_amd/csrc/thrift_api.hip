@@ -44,7 +44,7 @@ DecodeLayout decode_layout(int B, int Hq, int Nkv, int Bk, int split_blocks) {
   DecodeLayout L;
   const int Tk = Nkv / Bk;
   L.nsplit = (Tk + split_blocks - 1) / split_blocks;
-  L.nparts = L.nsplit * 4;                       // one partial per wavefront of a partition's workgroup
+  L.nparts = L.nsplit * 4 + 1;                   // one partial per wavefront of a partition's workgroup + one for a partly filled last block
   L.words = (Tk + 63) / 64;
   size_t off = 0;
   L.qf32 = off; off += align256((size_t)B * Hq * kHeadDim * sizeof(float));
@@ -294,7 +294,7 @@ static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void
   a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.seqlens = seqlens;
   a.bitmap = bitmap; a.bitmap_words = L.words;
   a.out = out; a.part_o = (float*)(ws + L.part_o); a.part_ml = (float*)(ws + L.part_ml);
-  a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Nkv = Nkv; a.split_blocks = split_blocks; a.nsplit = L.nsplit; a.nparts = L.nparts;
+  a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Nkv = Nkv; a.split_blocks = split_blocks; a.nsplit = L.nsplit; a.nparts = L.nparts; a.nmerge = seqlens ? L.nparts : L.nparts - 1;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
   a.dt = dt; a.out_dt = out_dt;
   launch_decode(a, st);

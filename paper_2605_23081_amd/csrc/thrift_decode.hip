@@ -19,27 +19,32 @@ namespace thrift {
 
 constexpr int kDecodeLdsPerWave = kBk * kRow16;   // one 16-bit V tile per wavefront (transposing reads)
 
-template <typename T>
+// TAIL_ONLY = false: the full key blocks of every sequence, the instantiation that carries the traffic.
+// TAIL_ONLY = true: one wavefront per (sequence, KV head) for the one key block a length that is not a multiple of
+// the block size leaves partly filled: its keys past the length are masked, the staging of its 16-bit V rows stops
+// at the last valid row, and the result is one more partial (the last slot) for the merge.  Kept out of the main
+// instantiation so that its hot loop carries none of the masking.
+template <typename T, bool TAIL_ONLY>
 __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   __shared__ __align__(16) unsigned char lds_all[4 * kDecodeLdsPerWave];
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
   unsigned char* lds = lds_all + wave * kDecodeLdsPerWave;
   const int G = a.Hq / a.Hkv;
-  const int part = blockIdx.x % a.nsplit;
-  const int unit = blockIdx.x / a.nsplit;
+  const int part = TAIL_ONLY ? 0 : blockIdx.x % a.nsplit;
+  const int unit = TAIL_ONLY ? blockIdx.x : blockIdx.x / a.nsplit;
   const int b = unit / a.Hkv, kvh = unit % a.Hkv;
   // cached tokens of this sequence; the last key block may still be filling up
   const int len = a.seqlens ? min(a.Nkv, max(0, a.seqlens[b])) : a.Nkv;
-  const int Tk = (len + kBk - 1) / kBk;
+  const int Tk = TAIL_ONLY ? (len + kBk - 1) / kBk : len / kBk;
   const bool real = r < G;                                   // this lane's column is a real query head
   const int hq = kvh * G + (real ? r : 0);
   const size_t qh = (size_t)b * a.Hq + hq, kh = (size_t)b * a.Hkv + kvh;
 
   // contiguous quarter of the partition for this wavefront
   const int quarter = a.split_blocks / 4;
-  const int j_begin = part * a.split_blocks + wave * quarter;
-  const int j_end = min(Tk, j_begin + quarter);
+  const int j_begin = TAIL_ONLY ? len / kBk : part * a.split_blocks + wave * quarter;
+  const int j_end = TAIL_ONLY ? Tk : min(Tk, j_begin + quarter);
 
   // ---- Q fragments (zeros for padding columns): the lane quantises its own two MXFP4 groups of the query,
   // channels 64*kk + 32*half .. +31 for fragment kk (Alg. 1 step 2 for the one-token query block) ----
@@ -80,13 +85,13 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   unsigned long long word = 0;
   int word_id = -1;
   for (int j = j_begin; j < j_end; ++j) {
+    constexpr bool TAIL = TAIL_ONLY;
     if ((j >> 6) != word_id) { word_id = j >> 6; word = real ? bm[word_id] : 0ULL; }
     const bool mine16 = (word >> (j & 63)) & 1ULL;           // promoted for this lane's head
     const unsigned long long votes = __builtin_amdgcn_ballot_w64(mine16) & group_mask;
     const bool any16 = votes != 0ULL;
     const bool all16 = votes == group_mask;
-    const int n_valid = len - j * kBk;                       // < kBk only in a last block that is not full
-    const bool tail = n_valid < kBk;
+    const int n_valid = TAIL ? len - j * kBk : kBk;
 
     v16f s[2];
     if (!all16) {
@@ -112,7 +117,7 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
         // (their probabilities are zero, but zero times an arbitrary bit pattern need not be)
         const int chunk = lane + 64 * u, row = chunk >> 4, col = chunk & 15;
         *reinterpret_cast<uint4*>(lds + row * kRow16 + col * 16) =
-            *reinterpret_cast<const uint4*>(v16base + ((size_t)j * kBk + min(row, n_valid - 1)) * kD + col * 8);
+            *reinterpret_cast<const uint4*>(v16base + ((size_t)j * kBk + (TAIL ? min(row, n_valid - 1) : row)) * kD + col * 8);
       }
       v8s qf16[8];
 #pragma unroll
@@ -131,7 +136,7 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       else if (mine16) { s[0] = s16[0]; s[1] = s16[1]; }
     }
     float gmax;
-    const float alpha = softmax_update(s, lane, tail, n_valid, c, st, gmax);
+    const float alpha = softmax_update(s, lane, TAIL, n_valid, c, st, gmax);
     rescale(o, alpha);
     if (!all16) {
       // heads that took the 16-bit scores contribute nothing on the 4-bit path
@@ -158,7 +163,7 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   // ---- partial (m, l, O) of this wavefront: accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
   const float l = st.l + other_half(st.l);
   if (real) {
-    const int pid = part * 4 + wave;
+    const int pid = TAIL_ONLY ? a.nparts - 1 : part * 4 + wave;
     float* po = a.part_o + (qh * a.nparts + pid) * kD;
 #pragma unroll
     for (int n = 0; n < 4; ++n)
@@ -380,13 +385,13 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
   const float c = a.scale * 1.4426950408889634f;
   const float* ml = a.part_ml + qh * a.nparts * 2;
   float M = -INFINITY;
-  for (int p = 0; p < a.nparts; ++p) M = fmaxf(M, ml[2 * p]);
+  for (int p = 0; p < a.nmerge; ++p) M = fmaxf(M, ml[2 * p]);
   float L = 0.f, O = 0.f;
   if (M > -INFINITY) {
     // an empty partial has m = -inf, l = 0, O = 0: its weight exp2(-inf) is 0, no branch needed, and the
     // loads of all partials can be in flight together
 #pragma unroll 8
-    for (int p = 0; p < a.nparts; ++p) {
+    for (int p = 0; p < a.nmerge; ++p) {
       const float w = fast_exp2((ml[2 * p] - M) * c);
       L += w * ml[2 * p + 1];
       O += w * a.part_o[(qh * a.nparts + p) * kD + ch];
@@ -400,8 +405,13 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
 
 void launch_decode(const DecodeArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((long)a.B * a.Hkv * a.nsplit);
-  if (a.dt == THRIFT_F16) decode_partial_kernel<F16><<<dim3(grid), dim3(256), 0, st>>>(a);
-  else decode_partial_kernel<BF16><<<dim3(grid), dim3(256), 0, st>>>(a);
+  if (a.dt == THRIFT_F16) decode_partial_kernel<F16, false><<<dim3(grid), dim3(256), 0, st>>>(a);
+  else decode_partial_kernel<BF16, false><<<dim3(grid), dim3(256), 0, st>>>(a);
+  if (a.seqlens != nullptr) {                          // without lengths every sequence fills the cache: no partly filled block
+    const unsigned tail_grid = (unsigned)((long)a.B * a.Hkv);
+    if (a.dt == THRIFT_F16) decode_partial_kernel<F16, true><<<dim3(tail_grid), dim3(64), 0, st>>>(a);
+    else decode_partial_kernel<BF16, true><<<dim3(tail_grid), dim3(64), 0, st>>>(a);
+  }
   decode_merge_kernel<<<dim3((unsigned)((long)a.B * a.Hq)), dim3(128), 0, st>>>(a);
 }
 

@@ -442,3 +442,8 @@ def test_ragged_lengths_pins(oracle, N, Bq, causal):
         d4 = oracle.attn_thrift_decode(qlb, kb, vb, dt, None, None, 64, scale, 0, seqlens=np.array([N], np.int32), force_path=0,
                                        quantize_p=False)
         assert np.abs(d4[0] - got[:, N - 1]).max() < 1e-10
+        # split-K (the short block is a partition of its own): without P quantisation the cut points do not matter
+        for sb in (1, 2):
+            d4s = oracle.attn_thrift_decode(qlb, kb, vb, dt, None, None, 64, scale, sb, seqlens=np.array([N], np.int32),
+                                            force_path=0, quantize_p=False)
+            assert np.abs(d4s - d4).max() < 1e-10
