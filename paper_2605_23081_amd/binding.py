@@ -24,6 +24,7 @@ EXPORTS = (
     "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_select_topk_shared", "thrift_select_ablation", "thrift_quantize_mxfp4",
     "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_prefill_chunk", "thrift_attn_prefill_ordered",
     "thrift_attn_decode_workspace", "thrift_attn_decode", "thrift_attn_decode_shared", "thrift_kv_cache_append",
+    "thrift_attention_forward_workspace", "thrift_attention_forward",
 )
 
 _lib = None
@@ -64,6 +65,9 @@ def lib() -> C.CDLL:
         L.thrift_attn_decode.argtypes = [p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, d, i, i, f, p, i, p, p, i, p, sz, p]
         L.thrift_attn_decode_shared.argtypes = L.thrift_attn_decode.argtypes
         L.thrift_kv_cache_append.argtypes = [p, p, i, i, p, p, p, p, p, p, p, p, p, i, i, i, i, i, p]
+        L.thrift_attention_forward_workspace.restype = sz
+        L.thrift_attention_forward_workspace.argtypes = [i, i, i, i, i, i, i, i, d, i]
+        L.thrift_attention_forward.argtypes = [p, p, p, i, i, i, i, i, i, i, i, i, d, i, f, p, i, p, p, sz, p]
         _lib = L
     return _lib
 
@@ -342,8 +346,20 @@ class PrefillPlan:
 
 
 def thrift_attention(q, k, v, causal: bool = True, Bq: int = 128, Bk: int = 64, budget: float = 0.05,
-                     fixed_k: int = -1, softmax_scale: float = 0.0, out_dtype=None) -> torch.Tensor:
-    """Alg. 1: Q, K, V, block sizes and FP16 budget in, attention output out (all stages on the GPU)."""
+                     fixed_k: int = -1, softmax_scale: float = 0.0, out_dtype=None,
+                     workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                     lse: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Alg. 1: Q, K, V, block sizes and FP16 budget in, attention output out (thrift_attention_forward: one C call)."""
+    for t in (q, k, v):
+        _dev(t)
     B, Hq, N, D = q.shape
-    plan = PrefillPlan(B, Hq, k.shape[1], N, D, Bq, Bk, causal, budget, q.dtype, q.device, fixed_k, out_dtype)
-    return plan.run(q, k, v, softmax_scale)
+    Hkv = k.shape[1]
+    need = int(lib().thrift_attention_forward_workspace(B, Hq, Hkv, N, D, Bq, Bk, int(causal), float(budget), int(fixed_k)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    if out is None:
+        out = torch.empty(B, Hq, N, D, dtype=out_dtype or q.dtype, device=q.device)
+    _check(lib().thrift_attention_forward(_ptr(q), _ptr(k), _ptr(v), _DT[q.dtype], B, Hq, Hkv, N, D, Bq, Bk, int(causal),
+                                          float(budget), int(fixed_k), float(softmax_scale), _ptr(out), _DT[out.dtype], _ptr(lse),
+                                          _ptr(workspace), workspace.numel(), _stream()), "thrift_attention_forward")
+    return out

@@ -58,6 +58,34 @@ DecodeLayout decode_layout(int B, int Hq, int Nkv, int Bk, int split_blocks) {
   return L;
 }
 
+// Workspace of the one-call form of Alg. 1: block means, selection, codes and scales of one problem.
+struct FusedLayout {
+  size_t qmean, kmean, idx, cnt, q4, qs, k4, ks, v4, vs, total;
+  int Tq, Tk, kmax;
+};
+
+FusedLayout fused_layout(int B, int Hq, int Hkv, int N, int Bq, int Bk, int causal, double budget, int fixed_k) {
+  FusedLayout L;
+  L.Tq = (N + Bq - 1) / Bq;
+  L.Tk = (N + Bk - 1) / Bk;
+  const int need = thrift_select_kmax(L.Tq, L.Tk, Bq, Bk, causal, budget, fixed_k, 0);
+  L.kmax = need > 0 ? need : 1;
+  const size_t bq = (size_t)B * Hq, bk = (size_t)B * Hkv, n = (size_t)N, tv = (size_t)((N + 63) / 64);
+  size_t off = 0;
+  L.qmean = off; off += align256(bq * L.Tq * kHeadDim * sizeof(float));
+  L.kmean = off; off += align256(bk * L.Tk * kHeadDim * sizeof(float));
+  L.idx = off; off += align256(bq * L.Tq * L.kmax * sizeof(int32_t));
+  L.cnt = off; off += align256(bq * L.Tq * sizeof(int32_t));
+  L.q4 = off; off += align256(bq * n * (kHeadDim / 2));
+  L.qs = off; off += align256(bq * n * (kHeadDim / 32));
+  L.k4 = off; off += align256(bk * n * (kHeadDim / 2));
+  L.ks = off; off += align256(bk * n * (kHeadDim / 32));
+  L.v4 = off; off += align256(bk * tv * kHeadDim * 32);
+  L.vs = off; off += align256(bk * tv * 2 * kHeadDim);
+  L.total = off;
+  return L;
+}
+
 }  // namespace
 
 extern "C" {
@@ -321,6 +349,48 @@ thrift_status thrift_attn_decode_shared(const void* q, thrift_dtype dt, const vo
                                         void* workspace, size_t workspace_bytes, void* stream) {
   return attn_decode_impl(q, dt, k16, v16, k4, ks, v4, vs, kmean, seqlens, B, Hq, Hkv, Nkv, D, Bk, budget, fixed_k, split_blocks,
                           softmax_scale, out, out_dt, idx_out, cnt_out, kmax_out, workspace, workspace_bytes, 1, stream);
+}
+
+static bool fused_shape_ok(int B, int Hq, int Hkv, int N, int D, int Bq, int Bk) {
+  return B > 0 && Hq > 0 && Hkv > 0 && Hq % Hkv == 0 && N > 0 && D == kHeadDim && Bk == kKeyBlock && (Bq == 64 || Bq == 128) &&
+         (N + Bk - 1) / Bk <= kMaxKeyBlocks;
+}
+
+size_t thrift_attention_forward_workspace(int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, double budget, int fixed_k) {
+  if (!fused_shape_ok(B, Hq, Hkv, N, D, Bq, Bk)) return 0;
+  if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return 0;
+  return fused_layout(B, Hq, Hkv, N, Bq, Bk, causal, budget, fixed_k).total;
+}
+
+thrift_status thrift_attention_forward(const void* q, const void* k, const void* v, thrift_dtype dt,
+                                       int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal,
+                                       double budget, int fixed_k, float softmax_scale,
+                                       void* out, thrift_dtype out_dt, float* lse,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!q || !k || !v || !out) return THRIFT_ERR_NULL;
+  if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
+  if (!fused_shape_ok(B, Hq, Hkv, N, D, Bq, Bk)) return THRIFT_ERR_SHAPE;
+  if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
+  const FusedLayout L = fused_layout(B, Hq, Hkv, N, Bq, Bk, causal, budget, fixed_k);
+  if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & 255) != 0) return THRIFT_ERR_WORKSPACE;
+  char* ws = (char*)workspace;
+  float* qmean = (float*)(ws + L.qmean);
+  float* kmean = (float*)(ws + L.kmean);
+  int32_t* idx = (int32_t*)(ws + L.idx);
+  int32_t* cnt = (int32_t*)(ws + L.cnt);
+  uint8_t *q4 = (uint8_t*)(ws + L.q4), *qs = (uint8_t*)(ws + L.qs), *k4 = (uint8_t*)(ws + L.k4), *ks = (uint8_t*)(ws + L.ks),
+          *v4 = (uint8_t*)(ws + L.v4), *vs = (uint8_t*)(ws + L.vs);
+  // every stage validates its own arguments before it launches; the first failure ends the chain
+  thrift_status s;
+  if ((s = thrift_block_means(q, dt, B, Hq, N, D, Bq, qmean, stream)) != THRIFT_OK) return s;                 // Alg. 1 step 3
+  if ((s = thrift_block_means(k, dt, B, Hkv, N, D, Bk, kmean, stream)) != THRIFT_OK) return s;
+  if ((s = thrift_select_topk(qmean, kmean, B, Hq, Hkv, L.Tq, L.Tk, D, Bq, Bk, causal, budget, fixed_k, 0, idx, cnt, L.kmax,
+                              stream)) != THRIFT_OK) return s;                                                // step 5
+  if ((s = thrift_quantize_mxfp4(q, dt, B, Hq, N, D, 0, q4, qs, stream)) != THRIFT_OK) return s;              // step 2
+  if ((s = thrift_quantize_mxfp4(k, dt, B, Hkv, N, D, 0, k4, ks, stream)) != THRIFT_OK) return s;
+  if ((s = thrift_quantize_mxfp4(v, dt, B, Hkv, N, D, 1, v4, vs, stream)) != THRIFT_OK) return s;
+  return thrift_attn_prefill(q, k, v, dt, q4, qs, k4, ks, v4, vs, idx, cnt, L.kmax, B, Hq, Hkv, N, D, Bq, Bk, causal,   // steps 4-23
+                             softmax_scale, out, out_dt, lse, nullptr, 0, stream);
 }
 
 thrift_status thrift_kv_cache_append(const void* k_new, const void* v_new, thrift_dtype dt, int n_new,

@@ -75,6 +75,14 @@ def test_validation_errors_come_before_any_launch():
     assert app(k=None) == NULL and app(sl=None) == NULL
     assert app(n=0) == SHAPE and app(n=2000) == SHAPE and app(N=1000) == SHAPE and app(D=64) == SHAPE and app(Bk=32) == SHAPE
     assert app(dt=2) == DTYPE
+    fwd = lambda **kw: L.thrift_attention_forward(kw.get("q", fake), fake, fake, kw.get("dt", 1), 1, 4, kw.get("Hkv", 2), kw.get("N", 300),
+                                                  kw.get("D", 128), kw.get("Bq", 128), 64, 1, C.c_double(kw.get("budget", 0.05)), -1,
+                                                  C.c_float(0.0), fake, 1, None, kw.get("ws", fake), kw.get("wsb", 16), None)
+    assert fwd(q=None) == NULL and fwd(dt=2) == DTYPE and fwd(Hkv=3) == SHAPE and fwd(N=0) == SHAPE and fwd(Bq=32) == SHAPE
+    assert fwd(budget=1.5) == BUDGET and fwd(ws=None) == WORKSPACE and fwd(wsb=16) == WORKSPACE
+    wsq = L.thrift_attention_forward_workspace
+    assert wsq(1, 4, 2, 300, 128, 128, 64, 1, C.c_double(0.05), -1) > 300 * 128 * 6 // 2
+    assert wsq(1, 4, 2, 300, 64, 128, 64, 1, C.c_double(0.05), -1) == 0 and wsq(1, 4, 2, 300, 128, 128, 64, 1, C.c_double(-1.0), -1) == 0
     need = T.decode_workspace_bytes(16, 32, 8, 131072, 128, 64, 256)
     assert 0 < need < (64 << 20)
     assert T.decode_workspace_bytes(16, 32, 8, 131072, 64, 64, 256) == 0

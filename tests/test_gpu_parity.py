@@ -749,3 +749,30 @@ def test_decode_empty_sequence_gives_zeros(T, oracle):
                                seqlens=cache.seqlens, out_dtype=torch.float32)
     g = to_np(got)
     assert np.all(g[0] == 0) and np.isfinite(g[1]).all() and np.abs(g[1]).max() > 0
+
+
+def test_one_call_forward_equals_the_staged_calls(T, oracle):
+    """thrift_attention_forward chains the same seven launches as the staged entry points: equal bits, also for a
+    length that is not a multiple of the blocks, with LSE, a reused workspace and a non-causal problem."""
+    for wl, N, causal, budget in ((_small_bf16(N=1024, Hq=4, Hkv=2), 1024, True, 0.1), (_small_bf16(N=512, Hq=2, Hkv=1), 333, True, 0.25),
+                                  (W.scaled(W.TINY, N=512), 512, False, 0.2)):
+        _say(f"one-call forward {wl.name} N={N} causal={causal}")
+        q, k, v, _, _ = W.make_prefill(wl)
+        qg, kg, vg = (t[:, :, :N].contiguous().cuda() for t in (q, k, v))
+        plan = T.PrefillPlan(wl.B, wl.Hq, wl.Hkv, N, wl.D, wl.Bq, wl.Bk, causal, budget, qg.dtype, "cuda", out_dtype=torch.float32)
+        want = plan.run(qg, kg, vg).clone()
+        lse = torch.empty(wl.B, wl.Hq, N, dtype=torch.float32, device="cuda")
+        ws = torch.full((T.lib().thrift_attention_forward_workspace(wl.B, wl.Hq, wl.Hkv, N, wl.D, wl.Bq, wl.Bk, int(causal), budget, -1),),
+                        0xFF, dtype=torch.uint8, device="cuda")
+        for _ in range(2):                                  # the second call reuses the workspace of the first
+            got = T.thrift_attention(qg, kg, vg, causal, wl.Bq, wl.Bk, budget, out_dtype=torch.float32, workspace=ws, lse=lse)
+            torch.cuda.synchronize()
+            assert torch.equal(got, want)
+        lse_staged = torch.empty_like(lse)
+        T.thrift_attn_prefill(qg, kg, vg, plan.q4, plan.qs, plan.k4, plan.ks, plan.v4, plan.vs, plan.idx, plan.cnt, wl.Bq, wl.Bk, causal,
+                              out_dtype=torch.float32, lse=lse_staged)
+        torch.cuda.synchronize()
+        assert torch.equal(lse, lse_staged) and torch.isfinite(lse).all()
+        with pytest.raises(T.ThriftError) as e:
+            T.thrift_attention(qg, kg, vg, causal, wl.Bq, wl.Bk, budget, workspace=ws[: ws.numel() // 2])
+        assert e.value.code == 5
