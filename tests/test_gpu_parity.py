@@ -776,3 +776,110 @@ def test_one_call_forward_equals_the_staged_calls(T, oracle):
         with pytest.raises(T.ThriftError) as e:
             T.thrift_attention(qg, kg, vg, causal, wl.Bq, wl.Bk, budget, workspace=ws[: ws.numel() // 2])
         assert e.value.code == 5
+
+
+# ------------------------------------------------------------------ seeded random shapes
+def _random_prefill_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for t in range(n):
+        Bq = int(rng.choice([64, 128]))
+        G = int(rng.choice([1, 2, 4]))
+        Hkv = int(rng.choice([1, 2]))
+        N = int(rng.integers(1, 1101))
+        causal = bool(rng.random() < 0.75)
+        budget = float(rng.choice([0.0, 0.03, 0.1, 0.3, 0.6, 1.0]))
+        fixed_k = int(rng.integers(0, 5)) if rng.random() < 0.2 else -1
+        order = int(rng.choice([0, 1, 2, 3]))
+        dtype = "bf16" if rng.random() < 0.6 else "f16"
+        cases.append((t, N, Bq, G * Hkv, Hkv, causal, budget, fixed_k, order, dtype))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_prefill_cases(28, 20260523), ids=lambda c: f"r{c[0]}-N{c[1]}-Bq{c[2]}-o{c[8]}")
+def test_prefill_random_shapes(T, oracle, case):
+    t, N, Bq, Hq, Hkv, causal, budget, fixed_k, order, dtype = case
+    _say(f"random prefill {case}")
+    wl = W.scaled(W.QWEN3_32K, N=1152, Hq=Hq, Hkv=Hkv, Bq=Bq, seed=100 + t, dtype=dtype)
+    q, k, v, _, _ = W.make_prefill(wl)
+    q, k, v = q[:, :, :N].contiguous(), k[:, :, :N].contiguous(), v[:, :, :N].contiguous()
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    Tq = -(-N // Bq)
+    qm = oracle.block_means(qb, dt, Bq); km = oracle.block_means(kb, dt, 64)
+    idx, cnt = oracle.select_topk(qm, km, Bq, 64, causal, budget, fixed_k)
+    want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, Bq, 64, causal, 1 / math.sqrt(wl.D), _units(1, Hq, Tq),
+                                      tile_order=1 if order == 1 else 0).reshape(1, Hq, Tq * Bq, wl.D)[:, :, :N]
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    qm_g = T.thrift_block_means(qg, Bq); km_g = T.thrift_block_means(kg, 64)
+    idx_g, cnt_g = T.thrift_select_topk(qm_g, km_g, Bq, 64, causal, budget, fixed_k)
+    swaps = check_selection(to_np(idx_g)[..., :idx.shape[-1]], to_np(cnt_g), idx, cnt, oracle.block_scores(qm, km))
+    got = T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, idx_g, cnt_g, Bq, 64, causal, 0,
+                                      out_dtype=torch.float32, tile_order=order)
+    torch.cuda.synchronize()
+    err = np.abs(to_np(got) - want).max()
+    _say(f"  max abs err {err:.3e} swaps {swaps}")
+    all16 = budget == 1.0 and fixed_k < 0
+    assert swaps == 0 and np.isfinite(to_np(got)).all()
+    assert err <= (TOL16 if all16 else TOLMIX)
+
+
+def _random_decode_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for t in range(n):
+        G = int(rng.choice([1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2]))
+        B = int(rng.integers(1, 4))
+        Nkv = int(rng.choice([512, 1024, 2048]))
+        lens = [int(rng.integers(1, Nkv + 1)) for _ in range(B)]
+        budget = float(rng.choice([0.0, 0.05, 0.2, 1.0]))
+        split = int(rng.choice([4, 8, 16]))
+        shared = bool(rng.random() < 0.3)
+        dtype = "bf16" if rng.random() < 0.5 else "f16"
+        cases.append((t, B, G * Hkv, Hkv, Nkv, tuple(lens), budget, split, shared, dtype))
+    return cases
+
+
+@pytest.mark.parametrize("case", _random_decode_cases(16, 8205), ids=lambda c: f"d{c[0]}-B{c[1]}-Hq{c[2]}-N{c[4]}")
+def test_decode_random_shapes(T, oracle, case):
+    t, B, Hq, Hkv, Nkv, lens, budget, split, shared, dtype = case
+    _say(f"random decode {case}")
+    wl = W.scaled(W.DECODE_131K, B=B, N=Nkv, Hq=Hq, Hkv=Hkv, seed=300 + t, dtype=dtype)
+    q, k, v = W.make_decode(wl)
+    cache = T.KVCache(B, Hkv, Nkv, wl.D, 64, k.dtype, "cuda", fill=0xFF)
+    # two appends: a prefix, then the rest
+    first = [n // 2 for n in lens]
+    kg, vg = k.cuda(), v.cuda()
+    cache.append(kg, vg, torch.tensor(first, dtype=torch.int32).cuda())
+    rest = max(n - f for n, f in zip(lens, first))
+    k2 = torch.zeros(B, Hkv, rest, wl.D, dtype=k.dtype); v2 = torch.zeros_like(k2)
+    for b in range(B):
+        m = lens[b] - first[b]
+        k2[b, :, :m] = k[b, :, first[b]:lens[b]]; v2[b, :, :m] = v[b, :, first[b]:lens[b]]
+    cache.append(k2.cuda(), v2.cuda(), torch.tensor([n - f for n, f in zip(lens, first)], dtype=torch.int32).cuda())
+    assert to_np(cache.seqlens).tolist() == list(lens)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    qm = q.float().numpy().reshape(B, Hq, 1, wl.D)
+    Tk = Nkv // 64
+    kmax = max(1, oracle.row_k(Tk, budget, -1))
+    idx_r = np.full((B, Hq, kmax), -1, np.int32); cnt_r = np.zeros((B, Hq), np.int32)
+    scores = np.zeros((B, Hq, Tk))
+    for b, n in enumerate(lens):
+        km_b = oracle.block_means(np.ascontiguousarray(kb[b:b + 1, :, :n]), dt, 64)
+        i_b, c_b = oracle.select_topk(qm[b:b + 1], km_b, 1, 64, False, budget, -1, group_shared=shared)
+        idx_r[b, :, :i_b.shape[-1]] = i_b[0, :, 0]; cnt_r[b] = c_b[0, :, 0]
+        sc = oracle.block_scores(qm[b:b + 1], km_b)[0, :, 0]
+        if shared:
+            sc = np.repeat(sc.reshape(Hkv, Hq // Hkv, -1).sum(1), Hq // Hkv, axis=0)
+        scores[b, :, :sc.shape[-1]] = sc
+    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, 64, 1 / math.sqrt(wl.D), split // 4, seqlens=np.asarray(lens, np.int32))
+    got, idx_g, cnt_g = T.thrift_attn_decode(q.cuda(), cache.k16, cache.v16, cache.k4, cache.ks, cache.v4, cache.vs, cache.kmean,
+                                             64, budget, -1, split, seqlens=cache.seqlens, out_dtype=torch.float32,
+                                             return_selection=True, group_shared=shared)
+    torch.cuda.synchronize()
+    swaps = check_selection(to_np(idx_g), to_np(cnt_g), idx_r, cnt_r, scores)
+    err = np.abs(to_np(got) - want).max()
+    _say(f"  max abs err {err:.3e} swaps {swaps}")
+    assert swaps == 0 and np.isfinite(to_np(got)).all()
+    assert err <= (TOL16 if budget == 1.0 else TOLMIX)
