@@ -265,6 +265,21 @@ def main() -> int:
                                                       "GBps": round(bytes_s / (us_s * 1e-6) / 1e9, 1),
                                                       "promoted_block_share_union": round(union_s, 4)}
         log(f"decode with group-shared selection {us_s:.1f} us, {bytes_s / 1e9:.2f} GB algorithmic")
+        # upkeep of the cache for one generated token per sequence: the last token written again at position N-1
+        # (same bits, so the cache the timed decode used stays as it was)
+        lens_before = torch.full((wd.B,), wd.N - 1, dtype=torch.int32, device=dev)
+        k_last, v_last = kd[:, :, -1:].contiguous(), vd[:, :, -1:].contiguous()
+        append = lambda: T.thrift_kv_cache_append(k_last, v_last, lens_before, kd, vd, k4, ks, v4, vs, kmean, wd.Bk)
+        for _ in range(3):
+            append()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            append()
+        e1.record()
+        torch.cuda.synchronize()
+        result["decode"]["cache_append_us"] = round(e0.elapsed_time(e1) * 1e3 / 20, 1)
         log(f"decode {us:.1f} us, {alg_bytes / 1e9:.2f} GB algorithmic -> {gbs:.0f} GB/s = {100 * gbs / PEAK_HBM:.1f} % of 8 TB/s")
 
     print(json.dumps(result), flush=True)
