@@ -94,7 +94,16 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
     const int n_valid = TAIL ? len - j * kBk : kBk;
 
     v16f s[2];
+    v4i vf4[4];
+    uint32_t vsw = 0;
     if (!all16) {
+      // the block's 4-bit V fragments and scales are requested together with its K rows: one memory round trip
+      // per block instead of two (they are used after the softmax)
+      const uint8_t* vt = v4base + (size_t)j * 4096 + r * 32 + half * 16;
+      const uint8_t* vsr = vsbase + ((size_t)j * 2 + half) * kD + r;
+#pragma unroll
+      for (int n = 0; n < 4; ++n) vf4[n] = *reinterpret_cast<const v4i*>(vt + 1024 * n);
+      vsw = (uint32_t)vsr[0] | ((uint32_t)vsr[32] << 8) | ((uint32_t)vsr[64] << 16) | ((uint32_t)vsr[96] << 24);
       // ---- 4-bit scores straight from global memory ----
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -143,13 +152,7 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       v16f p4[2] = {s[0], s[1]};
       float g4 = gmax;
       if (mine16) { p4[0] = (v16f){0.f}; p4[1] = (v16f){0.f}; g4 = 0.f; }
-      // V fragments and scales straight from global memory
-      const int vr = r * 32 + half * 16;
-      const uint8_t* vt = v4base + (size_t)j * 4096 + vr;
-      const uint8_t* vsr = vsbase + ((size_t)j * 2 + half) * kD + r;
-      const uint32_t vsw = (uint32_t)vsr[0] | ((uint32_t)vsr[32] << 8) | ((uint32_t)vsr[64] << 16) | ((uint32_t)vsr[96] << 24);
-      pv_fp4_regs<true>(p4, g4, vsw, 0u, 0u, 0u, *reinterpret_cast<const v4i*>(vt), *reinterpret_cast<const v4i*>(vt + 1024),
-                  *reinterpret_cast<const v4i*>(vt + 2048), *reinterpret_cast<const v4i*>(vt + 3072), o);
+      pv_fp4_regs<true>(p4, g4, vsw, 0u, 0u, 0u, vf4[0], vf4[1], vf4[2], vf4[3], o);
     }
     if (any16) {
       v16f p16[2] = {s[0], s[1]};
