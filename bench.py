@@ -47,6 +47,9 @@ PAPER_CONTEXT = {"gap_recovery_pct_at_5_10_25": [89.1, 91.8, 92.4], "e2e_speedup
                  "hardware": "RTX PRO 6000 Blackwell, NVFP4+FP16 (context only, not a target)"}
 
 
+ORDER_NAMES = {0: "key blocks ascending (Alg. 1 as written)", 1: "4-bit blocks first, then the promoted blocks (kernel of Sec. 3.3)"}
+
+
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -62,6 +65,9 @@ def main() -> int:
     ap.add_argument("--no-recovery", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--decode-batch", type=int, default=0)
+    ap.add_argument("--tile-order", type=int, default=1, choices=(0, 1),
+                    help="1: the order of the paper's kernel (Sec. 3.3: 4-bit blocks first, then the promoted ones); "
+                         "0: key blocks ascending as Alg. 1 is written")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -95,7 +101,7 @@ def main() -> int:
     del cal_src, cal_dst
 
     # ------------------------------------------------------------------ prefill: timed steps
-    plan = T.PrefillPlan(B, Hq, Hkv, N, D, Bq, Bk, True, args.budget, q.dtype, dev)
+    plan = T.PrefillPlan(B, Hq, Hkv, N, D, Bq, Bk, True, args.budget, q.dtype, dev, tile_order=args.tile_order)
     for _ in range(args.warmup):
         plan.run(q, k, v)
     torch.cuda.synchronize()
@@ -115,6 +121,20 @@ def main() -> int:
     ms_pre = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
     ms_attn = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
     flops = metrics.attention_flops(N, D, B * Hq, True)
+    # the fused kernel in the other tile order, for comparison (same selection, codes and scales)
+    other_order = 1 - args.tile_order
+    run_other = lambda: T.thrift_attn_prefill_chunk(q, k, v, plan.q4, plan.qs, plan.k4, plan.ks, plan.v4, plan.vs, plan.idx, plan.cnt,
+                                                    Bq, Bk, True, 0, out=plan.out, tile_order=other_order)
+    run_other()
+    eo = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    eo[0].record()
+    for _ in range(3):
+        run_other()
+    eo[1].record()
+    torch.cuda.synchronize()
+    ms_other = eo[0].elapsed_time(eo[1]) / 3
+    plan.run(q, k, v, prepass=False)                    # leave the headline order's output in plan.out for the parity sample
+    torch.cuda.synchronize()
     tiles16 = int(plan.cnt.sum().item())
     tiles_all = metrics.causal_tiles(N, Bq, Bk) * B * Hq
     frac16 = tiles16 / tiles_all
@@ -134,10 +154,13 @@ def main() -> int:
         "dtype": "bf16+mxfp4", "data": "synthetic",
         "config": {"workload": wl.name, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "seq_len": N, "head_dim": D,
                    "Bq": Bq, "Bk": Bk, "causal": True, "fp16_budget": args.budget, "fp16_tile_share": round(frac16, 5),
+                   "tile_order": ORDER_NAMES[args.tile_order],
                    "flop_convention": "4*D per unmasked (query,key) pair"},
         "prefill": {"ms_prepass": round(ms_pre, 4), "ms_fused_kernel": round(ms_attn, 3),
-                    "kernel_tflops": round(achieved, 2)},
-        "roofline": {"bound": "mfma", "kernel": "prefill_kernel<BF16,4>", "achieved": round(achieved, 2), "peak": round(peak, 1),
+                    "kernel_tflops": round(achieved, 2),
+                    "other_tile_order": {"order": ORDER_NAMES[other_order], "ms_fused_kernel": round(ms_other, 3),
+                                         "kernel_tflops": round(flops / (ms_other * 1e-3) / 1e12, 2)}},
+        "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<BF16,4,{args.tile_order},0>", "achieved": round(achieved, 2), "peak": round(peak, 1),
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                      "traffic": (MEASURED_TRAFFIC_GB["prefill_131k_f0.05"] if (N == 131072 and args.budget == 0.05) else None),
                      "note": "the kernel is limited by softmax / quantisation VALU work, not by the MFMA rate",
@@ -161,7 +184,7 @@ def main() -> int:
         c0 = time.perf_counter()
         qm = O.block_means(qb, dt, Bq); km = O.block_means(kb, dt, Bk)
         idx_o, cnt_o = O.select_topk(qm, km, Bq, Bk, True, args.budget)
-        want = O.attn_thrift_prefill(qb, kb, vb, dt, idx_o, cnt_o, Bq, Bk, True, scale, sample_units)
+        want = O.attn_thrift_prefill(qb, kb, vb, dt, idx_o, cnt_o, Bq, Bk, True, scale, sample_units, tile_order=args.tile_order)
         c1 = time.perf_counter()
         pairs = sum(Bq * (i * Bq) + Bq * (Bq + 1) / 2 for i in picks)
         sample_flops = 4.0 * D * pairs
@@ -188,14 +211,15 @@ def main() -> int:
 
         errs = {}
         for f in (0.0, 0.05, 0.10, 0.25, 1.0):
-            p2 = T.PrefillPlan(B, wl.group, 1, N, D, Bq, Bk, True, f, q.dtype, dev)
+            p2 = T.PrefillPlan(B, wl.group, 1, N, D, Bq, Bk, True, f, q.dtype, dev, tile_order=args.tile_order)
             o = p2.run(q[:, :wl.group].contiguous(), k[:, :1].contiguous(), v[:, :1].contiguous())
             errs[f] = metrics.rel_fro(sampled(o), exact)
             del p2
         # App. A analogue: the same budget spent on random / most-recent blocks instead of the heuristic's choice
         abl = {}
         for name, selector in (("random", T.SELECT_RANDOM), ("diagonal", T.SELECT_DIAGONAL)):
-            p2 = T.PrefillPlan(B, wl.group, 1, N, D, Bq, Bk, True, 0.05, q.dtype, dev, selector=selector, seed=wl.seed)
+            p2 = T.PrefillPlan(B, wl.group, 1, N, D, Bq, Bk, True, 0.05, q.dtype, dev, selector=selector, seed=wl.seed,
+                               tile_order=args.tile_order)
             o = p2.run(q[:, :wl.group].contiguous(), k[:, :1].contiguous(), v[:, :1].contiguous())
             abl[name] = metrics.rel_fro(sampled(o), exact)
             del p2

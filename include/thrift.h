@@ -223,13 +223,14 @@ thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const vo
  * seven launches on `stream` in that order.  The intermediate tensors live in `workspace`
  * (thrift_attention_forward_workspace(...) bytes, 256-byte aligned, device), which may be reused by the next call
  * on the same stream.  q [B,Hq,N,D], k, v [B,Hkv,N,D] 16-bit (dt); out [B,Hq,N,D] in out_dt; lse nullable [B,Hq,N].
- * budget / fixed_k as in thrift_select_topk; softmax_scale <= 0 means 1/sqrt(D).  A stage that rejects its arguments
+ * budget / fixed_k as in thrift_select_topk; tile_order as in thrift_attn_prefill_ordered (0: Alg. 1's order, 1: the
+ * order of the kernel in Sec. 3.3, the faster one); softmax_scale <= 0 means 1/sqrt(D).  A stage that rejects its arguments
  * ends the chain with that stage's status; the stages before it have then already been enqueued.
  */
 size_t thrift_attention_forward_workspace(int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, double budget, int fixed_k);
 thrift_status thrift_attention_forward(const void* q, const void* k, const void* v, thrift_dtype dt,
                                        int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal,
-                                       double budget, int fixed_k, float softmax_scale,
+                                       double budget, int fixed_k, int tile_order, float softmax_scale,
                                        void* out, thrift_dtype out_dt, float* lse,
                                        void* workspace, size_t workspace_bytes, void* stream);
 

@@ -67,7 +67,7 @@ def lib() -> C.CDLL:
         L.thrift_kv_cache_append.argtypes = [p, p, i, i, p, p, p, p, p, p, p, p, p, i, i, i, i, i, p]
         L.thrift_attention_forward_workspace.restype = sz
         L.thrift_attention_forward_workspace.argtypes = [i, i, i, i, i, i, i, i, d, i]
-        L.thrift_attention_forward.argtypes = [p, p, p, i, i, i, i, i, i, i, i, i, d, i, f, p, i, p, p, sz, p]
+        L.thrift_attention_forward.argtypes = [p, p, p, i, i, i, i, i, i, i, i, i, d, i, i, f, p, i, p, p, sz, p]
         _lib = L
     return _lib
 
@@ -306,8 +306,9 @@ class PrefillPlan:
     """Buffers of one prefill problem, allocated once so that repeated steps do not allocate."""
 
     def __init__(self, B, Hq, Hkv, N, D, Bq, Bk, causal, budget, dtype, device, fixed_k=-1, out_dtype=None,
-                 selector: int = 0, seed: int = 0):
+                 selector: int = 0, seed: int = 0, tile_order: int = 0):
         self.args = (B, Hq, Hkv, N, D, Bq, Bk, causal, budget, fixed_k)
+        self.tile_order = tile_order                        # 0: Alg. 1's ascending order; 1: the order of the kernel in Sec. 3.3
         self.selector, self.seed = selector, seed           # 0: the paper's heuristic; else an App. A ablation selector
         dev = device
         u8, f32, i32 = torch.uint8, torch.float32, torch.int32
@@ -340,15 +341,15 @@ class PrefillPlan:
             thrift_quantize_mxfp4(k, 0, self.k4, self.ks)
             thrift_quantize_mxfp4(v, 1, self.v4, self.vs)
         if attention:
-            thrift_attn_prefill(q, k, v, self.q4, self.qs, self.k4, self.ks, self.v4, self.vs, self.idx, self.cnt, Bq, Bk,
-                                causal, softmax_scale, out=self.out)
+            thrift_attn_prefill_chunk(q, k, v, self.q4, self.qs, self.k4, self.ks, self.v4, self.vs, self.idx, self.cnt, Bq, Bk,
+                                      causal, 0, softmax_scale, out=self.out, tile_order=self.tile_order)
         return self.out
 
 
 def thrift_attention(q, k, v, causal: bool = True, Bq: int = 128, Bk: int = 64, budget: float = 0.05,
                      fixed_k: int = -1, softmax_scale: float = 0.0, out_dtype=None,
                      workspace: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
-                     lse: Optional[torch.Tensor] = None) -> torch.Tensor:
+                     lse: Optional[torch.Tensor] = None, tile_order: int = 0) -> torch.Tensor:
     """Alg. 1: Q, K, V, block sizes and FP16 budget in, attention output out (thrift_attention_forward: one C call)."""
     for t in (q, k, v):
         _dev(t)
@@ -360,6 +361,6 @@ def thrift_attention(q, k, v, causal: bool = True, Bq: int = 128, Bk: int = 64, 
     if out is None:
         out = torch.empty(B, Hq, N, D, dtype=out_dtype or q.dtype, device=q.device)
     _check(lib().thrift_attention_forward(_ptr(q), _ptr(k), _ptr(v), _DT[q.dtype], B, Hq, Hkv, N, D, Bq, Bk, int(causal),
-                                          float(budget), int(fixed_k), float(softmax_scale), _ptr(out), _DT[out.dtype], _ptr(lse),
-                                          _ptr(workspace), workspace.numel(), _stream()), "thrift_attention_forward")
+                                          float(budget), int(fixed_k), int(tile_order), float(softmax_scale), _ptr(out), _DT[out.dtype],
+                                          _ptr(lse), _ptr(workspace), workspace.numel(), _stream()), "thrift_attention_forward")
     return out

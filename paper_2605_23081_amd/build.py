@@ -16,31 +16,54 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-I", INCLUDE, "-I", CSRC]
 
 
+def scratch_in_loops(asm_text: str):
+    """Kernel names whose generated code touches scratch memory (register spills) inside a loop.
+
+    The fused kernel keeps LDS DMA in flight across key blocks; a spill reload inside the walk would sit in the
+    same in-order memory queue and wait for those transfers at every block.  A spill that is stored before the
+    walk and reloaded after it costs nothing.  The compiler's listing marks every basic block that belongs to a
+    loop in the comment of its label line."""
+    bad, kernel, in_loop = set(), None, False
+    for line in asm_text.splitlines():
+        t = line.strip()
+        if t.startswith("_Z") and t.split(":")[0].isidentifier() and ":" in t:
+            kernel, in_loop = t.split(":")[0], False
+        elif t.startswith(".LBB") or t.startswith("; %bb."):
+            in_loop = "Loop" in t
+        elif t.startswith("scratch_") and in_loop and kernel:
+            bad.add(kernel)
+    return sorted(bad)
+
+
 def build(verbose: bool = False, extra=()):
     objs = []
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
         cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
-        if src == "thrift_prefill.hip":
-            cmd.insert(1, "-Rpass-analysis=kernel-resource-usage")
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
+    # the device listing of the fused kernel, for the spill check (runs beside the object builds)
+    listing = os.path.join(CSRC, "thrift_prefill.gfx950.s")
+    lcmd = ["hipcc", *FLAGS, *extra, "-S", "--cuda-device-only", os.path.join(CSRC, "thrift_prefill.hip"), "-o", listing]
+    lproc = subprocess.Popen(lcmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     for cmd, p in procs:
         out, _ = p.communicate()
         out = "\n".join(l for l in out.splitlines() if "not a recognized feature for this target" not in l)
-        if "-Rpass-analysis=kernel-resource-usage" in cmd:
-            # The fused kernel keeps LDS DMA in flight across key blocks; a register spill would put scratch
-            # loads into the same in-order memory queue and make every reload wait for those transfers.
-            spilled = [l for l in out.splitlines() if "VGPRs Spill:" in l and not l.rstrip().endswith("Spill: 0 [-Rpass-analysis=kernel-resource-usage]")]
-            out = "\n".join(l for l in out.splitlines() if "-Rpass-analysis=kernel-resource-usage" not in l)
-            if p.returncode == 0 and spilled:
-                raise RuntimeError("prefill kernel spills vector registers: " + "; ".join(x.strip() for x in spilled))
         if p.returncode != 0:
             sys.stderr.write(out + "\n")
             raise RuntimeError("hipcc failed: " + " ".join(cmd))
         if verbose and out.strip():
             print(out)
+    lout, _ = lproc.communicate()
+    if lproc.returncode != 0:
+        sys.stderr.write(lout + "\n")
+        raise RuntimeError("hipcc failed: " + " ".join(lcmd))
+    with open(listing) as f:
+        spilling = scratch_in_loops(f.read())
+    os.remove(listing)
+    if spilling:
+        raise RuntimeError("prefill kernel reloads spilled registers inside a loop: " + ", ".join(spilling))
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
     return LIB

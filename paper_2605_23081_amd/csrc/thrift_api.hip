@@ -364,7 +364,7 @@ size_t thrift_attention_forward_workspace(int B, int Hq, int Hkv, int N, int D, 
 
 thrift_status thrift_attention_forward(const void* q, const void* k, const void* v, thrift_dtype dt,
                                        int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal,
-                                       double budget, int fixed_k, float softmax_scale,
+                                       double budget, int fixed_k, int tile_order, float softmax_scale,
                                        void* out, thrift_dtype out_dt, float* lse,
                                        void* workspace, size_t workspace_bytes, void* stream) {
   if (!q || !k || !v || !out) return THRIFT_ERR_NULL;
@@ -389,8 +389,8 @@ thrift_status thrift_attention_forward(const void* q, const void* k, const void*
   if ((s = thrift_quantize_mxfp4(q, dt, B, Hq, N, D, 0, q4, qs, stream)) != THRIFT_OK) return s;              // step 2
   if ((s = thrift_quantize_mxfp4(k, dt, B, Hkv, N, D, 0, k4, ks, stream)) != THRIFT_OK) return s;
   if ((s = thrift_quantize_mxfp4(v, dt, B, Hkv, N, D, 1, v4, vs, stream)) != THRIFT_OK) return s;
-  return thrift_attn_prefill(q, k, v, dt, q4, qs, k4, ks, v4, vs, idx, cnt, L.kmax, B, Hq, Hkv, N, D, Bq, Bk, causal,   // steps 4-23
-                             softmax_scale, out, out_dt, lse, nullptr, 0, stream);
+  return thrift_attn_prefill_ordered(q, k, v, dt, q4, qs, k4, ks, v4, vs, idx, cnt, L.kmax, B, Hq, Hkv, N, 0, N, D, Bq, Bk,   // steps 4-23
+                                     causal, tile_order, softmax_scale, out, out_dt, lse, nullptr, 0, stream);
 }
 
 thrift_status thrift_kv_cache_append(const void* k_new, const void* v_new, thrift_dtype dt, int n_new,

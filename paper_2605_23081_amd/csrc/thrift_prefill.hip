@@ -230,10 +230,17 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
 
   // 16-bit query fragments of the lane's row (the wide schedule keeps them in registers for the whole walk; the
   // three-workgroup schedule has no registers to spare and fetches them again at every promoted block)
-#define THRIFT_LOAD_Q16(QF)                                                                                    \
+#define THRIFT_LOAD_Q16_ROW(QF, LROW)                                                                          \
   _Pragma("unroll") for (int s8 = 0; s8 < 8; ++s8)                                                             \
-    QF[s8] = *reinterpret_cast<const v8s*>(q16head + (uint32_t)(lrow * (2 * kD) + 32 * s8 + 16 * half));       \
+    QF[s8] = *reinterpret_cast<const v8s*>(q16head + (uint32_t)((LROW) * (2 * kD) + 32 * s8 + 16 * half));     \
   _Pragma("unroll") for (int s8 = 0; s8 < 8; ++s8) asm volatile("" : "+v"(QF[s8]));
+#define THRIFT_LOAD_Q16(QF) THRIFT_LOAD_Q16_ROW(QF, lrow)
+  // The lane's row index formed again from the thread id (the empty asm hides it from common-subexpression
+  // elimination): used where keeping the first copy alive through a long loop would cost a register there.
+#define THRIFT_ROW_AGAIN(UNCLAMPED)                                                                            \
+  int UNCLAMPED = (int)(threadIdx.x & 31);                                                                     \
+  asm volatile("" : "+v"(UNCLAMPED));                                                                          \
+  UNCLAMPED += i * Bq + wave * 32;
 
   if constexpr (WIDE) {
     // ---- wide schedule: every block, 4-bit or promoted, is fetched one whole step ahead into the slot the
@@ -331,36 +338,48 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
       j = jn;
       ++t;
     }
-    for (int sidx = 0; sidx < nselv; ++sidx) {          // phase B: promoted blocks follow each other
+    // phase B: the promoted blocks follow each other.  The lane's 16-bit query fragments are fetched once and stay
+    // in registers for the whole phase (the 4-bit phase, which has no registers to spare, is over: Sec. 3.3 scopes
+    // them the same way).  The 4-bit slots are idle now, so the 16-bit tiles rotate through THREE 16 KiB buffers in
+    // the order they are consumed, K(b), V(b), K(b+1), ...: tile t sits in buffer t mod 3 and may be fetched as
+    // soon as everyone has finished with tile t-3.  That puts K(b+1) in flight at the start of block b and V(b+1)
+    // right after the scores of block b, half a block earlier each than two fixed buffers allow.
+    v8s qf[8];
+    if (nselv > 0 && sel[0] < vis_wave) {
+      THRIFT_ROW_AGAIN(row_b)
+      THRIFT_LOAD_Q16_ROW(qf, min(row_b, Nq - 1))
+    }
+    // buffer 0: the K region (holds K of the first promoted block), 1: the V region (its V), 2: the 4-bit slots' region
+#define THRIFT_TILE_BUFFER(X) ((X) == 0 ? kLdsK16 : (X) == 1 ? kLdsV16 : kLdsRing)
+    int kbuf = 0;
+    for (int sidx = 0; sidx < nselv; ++sidx) {
       const int jb = sel[sidx];
       const bool p1 = sidx + 1 < nselv;
       const bool mine = jb < vis_wave;
-      THRIFT_SYNC()
-      if (late_v) THRIFT_ISSUE_V16(jb);
+      const int vbuf = kbuf == 2 ? 0 : kbuf + 1;
+      const int kbuf_next = vbuf == 2 ? 0 : vbuf + 1;
+      vm_wait<C16>();                                   // this wavefront's share of K(b); V(b) may still be on its way
+      lds_barrier();                                    // K(b) complete; everyone has finished the block before
+      if (p1) {
+        THRIFT_ISSUE_TILE16(k16base, sel[sidx + 1], (u * NW >= 8 ? THRIFT_K16OFF() ^ 64u : THRIFT_K16OFF()),
+                            lds0 + (uint32_t)THRIFT_TILE_BUFFER(kbuf_next));
+      }
       THRIFT_MASK(jb)
       v16f s[2];
       float gmax, alpha = 1.0f;
-      if (mine) {
-        v8s qf[8];
-        THRIFT_LOAD_Q16(qf)
-        scores_16<T>(lds + kLdsK16, lane, qf, s);
-      }
-      if (p1) {
-        lds_barrier();
-        THRIFT_ISSUE_K16(sel[sidx + 1]);
-      }
+      if (mine) scores_16<T>(lds + THRIFT_TILE_BUFFER(kbuf), lane, qf, s);
+      if (p1) vm_wait<C16>();                           // V(b); K(b+1) may still be on its way
+      else vm_wait<0>();
+      lds_barrier();                                    // V(b) complete; everyone has its scores, K(b)'s buffer is free
+      if (p1) { THRIFT_ISSUE_TILE16(v16base, sel[sidx + 1], THRIFT_V16OFF(), lds0 + (uint32_t)THRIFT_TILE_BUFFER(kbuf)); }
       if (mine) {
         alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
         rescale(o, alpha);
+        pv_16<T, true>(lds + THRIFT_TILE_BUFFER(vbuf), lane, s, o);
       }
-      if (late_v) {
-        if (p1) vm_wait<C16>();
-        else vm_wait<0>();
-        lds_barrier();
-      }
-      if (mine) pv_16<T, true>(lds + kLdsV16, lane, s, o);
-      late_v = p1;
+      kbuf = kbuf_next;
     }
+#undef THRIFT_TILE_BUFFER
   } else {
   // prologue: block 0 on its way
   if (vis > 0) {
@@ -446,6 +465,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
   vm_wait<0>();
 #undef THRIFT_SYNC
 #undef THRIFT_LOAD_Q16
+#undef THRIFT_LOAD_Q16_ROW
 #undef THRIFT_ISSUE
 #undef THRIFT_MASK
 #undef THRIFT_NEXT_PROMOTED
@@ -461,10 +481,10 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
   // ---- epilogue (Alg. 1 step 21): O / l; accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
   const float l = st.l + other_half(st.l);
   const float inv = l > 0.f ? 1.0f / l : 0.f;
-  const size_t orow = (qh * Nq + lrow) * kD;
-  int r_again = (int)(threadIdx.x & 31);
-  asm volatile("" : "+v"(r_again));                    // recomputed here: the unclamped row index is not worth a register through the key loop
-  const bool row_ok = i * Bq + wave * 32 + r_again < Nq;
+  THRIFT_ROW_AGAIN(row_e)
+  const bool row_ok = row_e < Nq;
+  const int lrow_again = min(row_e, Nq - 1);
+  const size_t orow = (qh * Nq + lrow_again) * kD;
 #pragma unroll
   for (int n = 0; n < 4; ++n)
 #pragma unroll
@@ -486,7 +506,8 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
         *reinterpret_cast<uint2*>((uint16_t*)a.out + orow + ch) = w;
       }
     }
-  if (a.lse != nullptr && half == 0 && row_ok) a.lse[qh * Nq + lrow] = st.m * a.scale + __logf(l);
+  if (a.lse != nullptr && half == 0 && row_ok) a.lse[qh * Nq + lrow_again] = st.m * a.scale + __logf(l);
+#undef THRIFT_ROW_AGAIN
 }
 
 // The wide schedule pays for itself once promoted blocks are frequent: their 32 KiB of 16-bit tiles then

@@ -76,7 +76,7 @@ def test_validation_errors_come_before_any_launch():
     assert app(n=0) == SHAPE and app(n=2000) == SHAPE and app(N=1000) == SHAPE and app(D=64) == SHAPE and app(Bk=32) == SHAPE
     assert app(dt=2) == DTYPE
     fwd = lambda **kw: L.thrift_attention_forward(kw.get("q", fake), fake, fake, kw.get("dt", 1), 1, 4, kw.get("Hkv", 2), kw.get("N", 300),
-                                                  kw.get("D", 128), kw.get("Bq", 128), 64, 1, C.c_double(kw.get("budget", 0.05)), -1,
+                                                  kw.get("D", 128), kw.get("Bq", 128), 64, 1, C.c_double(kw.get("budget", 0.05)), -1, 0,
                                                   C.c_float(0.0), fake, 1, None, kw.get("ws", fake), kw.get("wsb", 16), None)
     assert fwd(q=None) == NULL and fwd(dt=2) == DTYPE and fwd(Hkv=3) == SHAPE and fwd(N=0) == SHAPE and fwd(Bq=32) == SHAPE
     assert fwd(budget=1.5) == BUDGET and fwd(ws=None) == WORKSPACE and fwd(wsb=16) == WORKSPACE
@@ -95,3 +95,27 @@ def test_without_a_gpu_valid_calls_fail_loudly():
         pytest.skip("a GPU is present")
     fake = C.c_void_p(0x1000)
     assert T.lib().thrift_block_means(fake, 0, 1, 1, 64, 128, 64, fake, None) == 6   # THRIFT_ERR_ARCH, nothing launched
+
+
+def test_spill_check_reads_the_compiler_listing():
+    """The build refuses a fused kernel whose listing touches scratch memory inside a loop (and only then)."""
+    from paper_2605_23081_amd.build import scratch_in_loops
+    listing = "\n".join([
+        "_ZN6thrift4walkEv:",
+        "; %bb.0:",
+        "\tscratch_store_dword off, v1, off offset:16 ; 4-byte Folded Spill",          # before the loop: fine
+        ".LBB0_1:                                ; =>This Inner Loop Header: Depth=1",
+        "\tv_add_f32_e32 v0, v0, v1",
+        "; %bb.2:                                ;   in Loop: Header=BB0_1 Depth=1",
+        "\ts_cbranch_scc1 .LBB0_1",
+        ".LBB0_3:",
+        "\tscratch_load_dword v1, off, off offset:16 ; 4-byte Folded Reload",           # after it: fine
+        "\ts_endpgm",
+        "_ZN6thrift3badEv:",
+        ".LBB1_1:                                ; =>This Inner Loop Header: Depth=1",
+        "; %bb.2:                                ;   in Loop: Header=BB1_1 Depth=1",
+        "\tscratch_load_dword v1, off, off ; 4-byte Folded Reload",
+        "\ts_cbranch_scc1 .LBB1_1",
+        "\ts_endpgm",
+    ])
+    assert scratch_in_loops(listing) == ["_ZN6thrift3badEv"]

@@ -32,7 +32,7 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _prefill_sampled(T, oracle, wl, budgets, heads, blocks, tol_for):
+def _prefill_sampled(T, oracle, wl, budgets, heads, blocks, tol_for, tile_order=0):
     """Whole-problem GPU run per budget; oracle on (head, query block) samples."""
     _say(f"{wl.name}: drawing N={wl.N} Hq={wl.Hq} Hkv={wl.Hkv} on the CPU")
     q, k, v, _, _ = W.make_prefill(wl)
@@ -49,7 +49,8 @@ def _prefill_sampled(T, oracle, wl, budgets, heads, blocks, tol_for):
     units = np.array([(0, qh_ids.index(h), i) for h in heads for i in blocks], np.int32)
     for f in budgets:
         _say(f"  budget {f}: GPU run of the whole problem")
-        plan = T.PrefillPlan(wl.B, wl.Hq, wl.Hkv, wl.N, wl.D, wl.Bq, wl.Bk, True, f, q.dtype, qg.device, out_dtype=torch.float32)
+        plan = T.PrefillPlan(wl.B, wl.Hq, wl.Hkv, wl.N, wl.D, wl.Bq, wl.Bk, True, f, q.dtype, qg.device, out_dtype=torch.float32,
+                             tile_order=tile_order)
         out = plan.run(qg, kg, vg)
         torch.cuda.synchronize()
         idx_r, cnt_r = oracle.select_topk(qm, km, wl.Bq, wl.Bk, True, f)
@@ -66,7 +67,7 @@ def _prefill_sampled(T, oracle, wl, budgets, heads, blocks, tol_for):
             assert int(plan.cnt.sum().item()) == 0                      # 0 % == every tile on the 4-bit path
         if f == 1.0:
             assert int(plan.cnt.sum().item()) == wl.B * wl.Hq * sum(T.visible_blocks(i, wl.N // wl.Bk, wl.Bq, wl.Bk, True) for i in range(Tq))
-        want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx_r, cnt_r, wl.Bq, wl.Bk, True, scale, units)
+        want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx_r, cnt_r, wl.Bq, wl.Bk, True, scale, units, tile_order=tile_order)
         got = to_np(out)[0].reshape(wl.Hq, Tq, wl.Bq, wl.D)
         got = np.stack([got[h, i] for h in heads for i in blocks])
         err = np.abs(got - want)
@@ -78,6 +79,12 @@ def _prefill_sampled(T, oracle, wl, budgets, heads, blocks, tol_for):
 def test_qwen3_131k_budget_sweep(T, oracle):
     wl = W.QWEN3_131K
     _prefill_sampled(T, oracle, wl, wl.budgets, heads=[0, 21], blocks=[0, 517, 1023], tol_for=lambda f: TOLMIX)
+
+
+def test_qwen3_131k_kernel_order_of_the_paper(T, oracle):
+    """The configuration bench.py times: 4-bit blocks first, then the promoted ones (Sec. 3.3), against the oracle in that order."""
+    wl = W.QWEN3_131K
+    _prefill_sampled(T, oracle, wl, (0.05, 0.25), heads=[7, 30], blocks=[0, 640, 1023], tol_for=lambda f: TOLMIX, tile_order=1)
 
 
 def test_qwen3_32k(T, oracle):
