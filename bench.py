@@ -41,7 +41,8 @@ ALU_PEAK = 1024 * 64 * 2.4e9 / ALU_CYCLES * (4 * 128) / 1e12   # TFLOP/s
 # (FETCH_SIZE, WRITE_SIZE; scaled by what the same counters read for the 1 GiB calibration copy below: x2.0 and
 # x1.0).  The summary of those runs is profiles/prefill_decode_hbm_traffic_pmc.txt; counters cannot be read from
 # inside this process, so the figures are reported only for the configuration they were measured on.
-MEASURED_TRAFFIC_GB = {"prefill_131k_f0.05": {"fetched": 35.90, "written": 1.07},
+MEASURED_TRAFFIC_GB = {"prefill_131k_f0.05_order1": {"fetched": 20.81, "written": 1.11},
+                       "prefill_131k_f0.05_order0": {"fetched": 35.96, "written": 1.07},
                        "decode_16x131k_f0.05": {"fetched": 3.86, "written": 0.002}}
 PAPER_CONTEXT = {"gap_recovery_pct_at_5_10_25": [89.1, 91.8, 92.4], "e2e_speedup_at_131k": 2.0,
                  "hardware": "RTX PRO 6000 Blackwell, NVFP4+FP16 (context only, not a target)"}
@@ -162,7 +163,7 @@ def main() -> int:
                                          "kernel_tflops": round(flops / (ms_other * 1e-3) / 1e12, 2)}},
         "roofline": {"bound": "mfma", "kernel": f"prefill_kernel<BF16,4,{args.tile_order},0>", "achieved": round(achieved, 2), "peak": round(peak, 1),
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "traffic": (MEASURED_TRAFFIC_GB["prefill_131k_f0.05"] if (N == 131072 and args.budget == 0.05) else None),
+                     "traffic": (MEASURED_TRAFFIC_GB[f"prefill_131k_f0.05_order{args.tile_order}"] if (N == 131072 and args.budget == 0.05) else None),
                      "note": "the kernel is limited by softmax / quantisation VALU work, not by the MFMA rate",
                      "alu": {"peak": round(ALU_PEAK, 1), "unit": "TFLOP/s", "frac": round(achieved / ALU_PEAK, 4),
                              "simd_cycles_per_64_scores": ALU_CYCLES}},
