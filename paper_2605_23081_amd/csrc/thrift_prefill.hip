@@ -104,9 +104,18 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
   const int vis = a.causal ? min(Tk, ((i + a.q_off + 1) * Bq - 1) / kBk + 1) : Tk;
   const int32_t* sel = a.idx + (qh * Tq + i) * a.kmax;
   const int nsel = min(a.cnt[qh * Tq + i], a.kmax);      // a count beyond the list length is cut, never followed
+  // Entry t of the row's list, through the scalar data path.  The list index is wavefront-uniform, but the compiler
+  // cannot prove that (it depends on list entries read earlier) nor that the list is not written here, and turns a
+  // plain read into a vector load plus a wait for EVERY vector load in flight, the tile DMAs included.
+  auto sel_at = [&](int t) -> int {
+    const int32_t* p = sel + __builtin_amdgcn_readfirstlane(t);
+    int v;
+    asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+    return v;
+  };
   // the next two promoted block ids at or after the current block (ascending list)
   int ps = 0;
-  int n0 = nsel > 0 ? sel[0] : 0x7fffffff, n1 = nsel > 1 ? sel[1] : 0x7fffffff;
+  int n0 = nsel > 0 ? sel_at(0) : 0x7fffffff, n1 = nsel > 1 ? sel_at(1) : 0x7fffffff;
 
   const uint8_t* k4base = a.k4 + kh * N * 64;
   const uint8_t* v4base = a.v4 + kh * (size_t)Tk * 4096;
@@ -226,7 +235,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
 #define THRIFT_NEXT_PROMOTED()                                                                                 \
   ++ps;                                                                                                        \
   n0 = n1;                                                                                                     \
-  n1 = ps + 1 < nsel ? sel[ps + 1] : 0x7fffffff;
+  n1 = ps + 1 < nsel ? sel_at(ps + 1) : 0x7fffffff;
 
   // 16-bit query fragments of the lane's row (the wide schedule keeps them in registers for the whole walk; the
   // three-workgroup schedule has no registers to spare and fetches them again at every promoted block)
@@ -300,30 +309,31 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
     // ---- the order of Sec. 3.3: every 4-bit block in ascending order, then the promoted blocks in ascending
     // order.  Same staging rules; the ring slot follows the step number because block ids now skip. ----
     int nselv = nsel;                                   // promoted ids inside the visible range (the list is ascending)
-    if (nsel > 0 && sel[nsel - 1] >= vis) {
+    if (nsel > 0 && sel_at(nsel - 1) >= vis) {
       nselv = 0;
-      while (nselv < nsel && sel[nselv] < vis) ++nselv;
+      while (nselv < nsel && sel_at(nselv) < vis) ++nselv;
     }
     int pa = 0;                                         // promoted ids the 4-bit walk has passed
-    int nx = nselv > 0 ? sel[0] : 0x7fffffff;           // the next promoted id at or after the 4-bit walk's position
+    const int first_promoted = nselv > 0 ? sel_at(0) : 0x7fffffff;
+    int nx = first_promoted;                            // the next promoted id at or after the 4-bit walk's position
     int j = 0;
-    while (j == nx) { ++j; ++pa; nx = pa < nselv ? sel[pa] : 0x7fffffff; }
+    while (j == nx) { ++j; ++pa; nx = pa < nselv ? sel_at(pa) : 0x7fffffff; }
     if (j < vis) {
       THRIFT_ISSUE4_SLOT(j, 0);
     } else if (nselv > 0) {
-      THRIFT_ISSUE_K16(sel[0]);
-      THRIFT_ISSUE_V16(sel[0]);
+      THRIFT_ISSUE_K16(first_promoted);
+      THRIFT_ISSUE_V16(first_promoted);
     }
     int t = 0;
     while (j < vis) {                                   // phase A
       int jn = j + 1;
-      while (jn == nx) { ++jn; ++pa; nx = pa < nselv ? sel[pa] : 0x7fffffff; }
+      while (jn == nx) { ++jn; ++pa; nx = pa < nselv ? sel_at(pa) : 0x7fffffff; }
       THRIFT_SYNC()
       if (jn < vis) {
         THRIFT_ISSUE4_SLOT(jn, (t + 1) & 1);
       } else if (nselv > 0) {
-        THRIFT_ISSUE_K16(sel[0]);
-        THRIFT_ISSUE_V16(sel[0]);
+        THRIFT_ISSUE_K16(first_promoted);
+        THRIFT_ISSUE_V16(first_promoted);
       }
       if (j < vis_wave) {
         THRIFT_MASK(j)
@@ -345,23 +355,25 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
     // soon as everyone has finished with tile t-3.  That puts K(b+1) in flight at the start of block b and V(b+1)
     // right after the scores of block b, half a block earlier each than two fixed buffers allow.
     v8s qf[8];
-    if (nselv > 0 && sel[0] < vis_wave) {
+    if (nselv > 0 && first_promoted < vis_wave) {
       THRIFT_ROW_AGAIN(row_b)
       THRIFT_LOAD_Q16_ROW(qf, min(row_b, Nq - 1))
     }
     // buffer 0: the K region (holds K of the first promoted block), 1: the V region (its V), 2: the 4-bit slots' region
 #define THRIFT_TILE_BUFFER(X) ((X) == 0 ? kLdsK16 : (X) == 1 ? kLdsV16 : kLdsRing)
     int kbuf = 0;
+    int jb_next = first_promoted;
     for (int sidx = 0; sidx < nselv; ++sidx) {
-      const int jb = sel[sidx];
+      const int jb = jb_next;
       const bool p1 = sidx + 1 < nselv;
+      if (p1) jb_next = sel_at(sidx + 1);
       const bool mine = jb < vis_wave;
       const int vbuf = kbuf == 2 ? 0 : kbuf + 1;
       const int kbuf_next = vbuf == 2 ? 0 : vbuf + 1;
       vm_wait<C16>();                                   // this wavefront's share of K(b); V(b) may still be on its way
       lds_barrier();                                    // K(b) complete; everyone has finished the block before
       if (p1) {
-        THRIFT_ISSUE_TILE16(k16base, sel[sidx + 1], (u * NW >= 8 ? THRIFT_K16OFF() ^ 64u : THRIFT_K16OFF()),
+        THRIFT_ISSUE_TILE16(k16base, jb_next, (u * NW >= 8 ? THRIFT_K16OFF() ^ 64u : THRIFT_K16OFF()),
                             lds0 + (uint32_t)THRIFT_TILE_BUFFER(kbuf_next));
       }
       THRIFT_MASK(jb)
@@ -371,7 +383,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
       if (p1) vm_wait<C16>();                           // V(b); K(b+1) may still be on its way
       else vm_wait<0>();
       lds_barrier();                                    // V(b) complete; everyone has its scores, K(b)'s buffer is free
-      if (p1) { THRIFT_ISSUE_TILE16(v16base, sel[sidx + 1], THRIFT_V16OFF(), lds0 + (uint32_t)THRIFT_TILE_BUFFER(kbuf)); }
+      if (p1) { THRIFT_ISSUE_TILE16(v16base, jb_next, THRIFT_V16OFF(), lds0 + (uint32_t)THRIFT_TILE_BUFFER(kbuf)); }
       if (mine) {
         alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
         rescale(o, alpha);
