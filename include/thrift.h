@@ -198,7 +198,8 @@ thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void
  * thrift_attn_prefill_chunk with a choice of tile order.
  *   tile_order 0: key blocks in ascending order, as Alg. 1 is written (what the other entry points use);
  *   tile_order 1: the order of the kernel in Sec. 3.3 — every 4-bit block in ascending order first, then
- *                 the promoted blocks in ascending order.
+ *                 the promoted blocks in ascending order.  The faster one at every budget: the 16-bit query
+ *                 fragments are held in registers only during the promoted phase, as in the paper's kernel.
  * In exact arithmetic the two agree; the 4-bit rounding of P depends on the running maximum, so the
  * results differ at the level of the quantisation noise.
  *   tile_order 2, 3: ascending order like 0, with the staging schedule fixed instead of chosen by the library
