@@ -35,6 +35,24 @@ def scratch_in_loops(asm_text: str):
     return sorted(bad)
 
 
+def m0_outside_inline_asm(asm_text: str) -> int:
+    """Number of compiler-generated instructions that touch M0.
+
+    The LDS DMA instruction takes its LDS base from M0, which the inline assembly sets without the compiler knowing.
+    That is sound only while the compiler itself never keeps a value in M0 across those statements: the fused
+    kernel's listing must mention M0 nowhere but between the ASMSTART / ASMEND markers."""
+    inside, count = False, 0
+    for line in asm_text.splitlines():
+        t = line.strip()
+        if t.startswith(";;#ASMSTART"):
+            inside = True
+        elif t.startswith(";;#ASMEND"):
+            inside = False
+        elif not inside and not t.startswith(";") and "m0" in t.replace(",", " ").split():
+            count += 1
+    return count
+
+
 def build(verbose: bool = False, extra=()):
     objs = []
     procs = []
@@ -60,10 +78,13 @@ def build(verbose: bool = False, extra=()):
         sys.stderr.write(lout + "\n")
         raise RuntimeError("hipcc failed: " + " ".join(lcmd))
     with open(listing) as f:
-        spilling = scratch_in_loops(f.read())
+        text = f.read()
     os.remove(listing)
+    spilling = scratch_in_loops(text)
     if spilling:
         raise RuntimeError("prefill kernel reloads spilled registers inside a loop: " + ", ".join(spilling))
+    if m0_outside_inline_asm(text):
+        raise RuntimeError("the compiler uses M0 in the prefill kernel: the LDS DMA statements would clobber it")
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
     return LIB

@@ -119,3 +119,11 @@ def test_spill_check_reads_the_compiler_listing():
         "\ts_endpgm",
     ])
     assert scratch_in_loops(listing) == ["_ZN6thrift3badEv"]
+
+
+def test_m0_check_reads_the_compiler_listing():
+    from paper_2605_23081_amd.build import m0_outside_inline_asm
+    ok = "\n".join(["\t;;#ASMSTART", "\ts_mov_b32 m0, s10", "\ts_nop 0", "\tglobal_load_lds_dwordx4 v1, s[2:3]", "\t;;#ASMEND",
+                    "\tv_add_u32_e32 v0, v1, v2", "; a comment that mentions m0"])
+    assert m0_outside_inline_asm(ok) == 0
+    assert m0_outside_inline_asm(ok + "\n\ts_mov_b32 m0, -1\n\tds_gws_init v0 gds") == 1
