@@ -883,3 +883,38 @@ def test_decode_random_shapes(T, oracle, case):
     _say(f"  max abs err {err:.3e} swaps {swaps}")
     assert swaps == 0 and np.isfinite(to_np(got)).all()
     assert err <= (TOL16 if budget == 1.0 else TOLMIX)
+
+
+@pytest.mark.parametrize("order", [0, 1, 2, 3])
+def test_prefill_hand_set_lists_with_ids_out_of_view(T, oracle, order):
+    """Hand-set promoted lists (ascending) that also name blocks a causal row cannot see, an empty list and a list
+    that promotes everything: blocks out of view are ignored in every tile order, as in the oracle."""
+    wl = _small_bf16(N=1024, Hq=2, Hkv=1)
+    _say(f"hand-set lists, order {order}")
+    q, k, v, _, _ = W.make_prefill(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    Tq, Tk, kmax = wl.N // wl.Bq, wl.N // wl.Bk, 16
+    idx = np.full((1, wl.Hq, Tq, kmax), -1, np.int32); cnt = np.zeros((1, wl.Hq, Tq), np.int32)
+    for h in range(wl.Hq):
+        for i in range(Tq):
+            vis = min(Tk, 2 * (i + 1))
+            if i % 4 == 0:
+                ids = []                                                    # nothing promoted
+            elif i % 4 == 1:
+                ids = list(range(min(vis, kmax)))                          # the first blocks, consecutive
+            elif i % 4 == 2:
+                ids = sorted({0, vis - 1, vis, vis + 1, Tk - 1})           # two of them (three for the last rows) out of view
+            else:
+                ids = sorted({1, 2, vis - 2, vis - 1, Tk - 1} | ({5 + h} if vis > 6 else set()))
+            ids = [j for j in ids if 0 <= j < Tk][:kmax]
+            idx[0, h, i, :len(ids)] = ids; cnt[0, h, i] = len(ids)
+    want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, wl.Bq, wl.Bk, True, 1 / math.sqrt(wl.D), _units(1, wl.Hq, Tq),
+                                      tile_order=1 if order == 1 else 0).reshape(1, wl.Hq, wl.N, wl.D)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    got = T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, torch.from_numpy(idx).cuda(), torch.from_numpy(cnt).cuda(),
+                                      wl.Bq, wl.Bk, True, 0, out_dtype=torch.float32, tile_order=order)
+    torch.cuda.synchronize()
+    err = np.abs(to_np(got) - want).max()
+    _say(f"  max abs err {err:.3e}")
+    assert np.isfinite(to_np(got)).all() and err <= TOLMIX
