@@ -160,6 +160,9 @@ size_t thrift_attn_prefill_workspace(int B, int Hq, int Hkv, int N, int D, int B
  *   q [B,Hq,N,D], k,v [B,Hkv,N,D]                 16-bit (dt), read only for the selected tiles
  *   q4,qs / k4,ks : thrift_quantize_mxfp4(axis 0) of q / k;   v4,vs : axis 1 of v
  *   idx [B,Hq,ceil(N/Bq),kmax], cnt [B,Hq,ceil(N/Bq)]   from thrift_select_topk (ascending, padded -1)
+ *     A list that breaks this contract (entries out of order, negative, past the last block, a count beyond kmax)
+ *     gives unspecified numbers but is never followed outside the tensors: entries are clamped to existing
+ *     blocks, the count to kmax, and entries behind the walk's position are dropped.
  *   N need not be a multiple of Bq or Bk: the last query block then has fewer rows and the keys past N
  *   in the last key block are masked out (block means, V codes: see thrift_block_means, thrift_quantize_mxfp4)
  *   softmax_scale <= 0 selects 1/sqrt(D)

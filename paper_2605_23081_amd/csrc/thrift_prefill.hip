@@ -111,7 +111,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
     const int32_t* p = sel + __builtin_amdgcn_readfirstlane(t);
     int v;
     asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
-    return v;
+    return min(max(v, 0), Tk - 1);                      // whatever the list holds, only ids of existing key blocks become addresses
   };
   // the next two promoted block ids at or after the current block (ascending list)
   int ps = 0;
@@ -236,6 +236,11 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
   ++ps;                                                                                                        \
   n0 = n1;                                                                                                     \
   n1 = ps + 1 < nsel ? sel_at(ps + 1) : 0x7fffffff;
+  // List entries behind the walk's position (a list that is not strictly ascending breaks the contract) are
+  // dropped, at the same point of every wavefront's walk: the wavefronts of a workgroup must take identical
+  // staging and barrier decisions whatever the list holds.
+#define THRIFT_DROP_STALE(J)                                                                                   \
+  while (n0 < (J)) { THRIFT_NEXT_PROMOTED() }
 
   // 16-bit query fragments of the lane's row (the wide schedule keeps them in registers for the whole walk; the
   // three-workgroup schedule has no registers to spare and fetches them again at every promoted block)
@@ -270,6 +275,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
     if (vis > 0) { THRIFT_ISSUE_WIDE(0, n0 == 0) }
     int j = 0;
     while (j < vis_wave) {
+      THRIFT_DROP_STALE(j)
       const int run_end = min(vis_wave, n0);
       for (; j < run_end; ++j) {                          // a run of 4-bit blocks
         THRIFT_SYNC()
@@ -299,6 +305,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
       }
     }
     for (; j < vis; ++j) {                                // staging only: blocks that later wavefronts still need
+      THRIFT_DROP_STALE(j)
       const bool p0 = j == n0;
       THRIFT_SYNC()
       THRIFT_ISSUE_WIDE(j + 1, j + 1 == (p0 ? n1 : n0))
@@ -406,6 +413,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
   // updated in place) and single promoted blocks.
   int j = 0;
   while (j < vis_wave) {
+    THRIFT_DROP_STALE(j)
     const int run_end = min(vis_wave, n0);
     for (; j < run_end; ++j) {
       THRIFT_SYNC()
@@ -451,6 +459,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
     }
   }
   for (; j < vis; ++j) {                                // staging only
+    THRIFT_DROP_STALE(j)
     const bool p0 = j == n0;
     const bool p1 = (p0 ? j + 1 == n1 : j + 1 == n0);
     THRIFT_SYNC()
@@ -481,6 +490,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
 #undef THRIFT_ISSUE
 #undef THRIFT_MASK
 #undef THRIFT_NEXT_PROMOTED
+#undef THRIFT_DROP_STALE
 #undef THRIFT_ISSUE4
 #undef THRIFT_ISSUE4_SLOT
 #undef THRIFT_ISSUE_V16

@@ -918,3 +918,30 @@ def test_prefill_hand_set_lists_with_ids_out_of_view(T, oracle, order):
     err = np.abs(to_np(got) - want).max()
     _say(f"  max abs err {err:.3e}")
     assert np.isfinite(to_np(got)).all() and err <= TOLMIX
+
+
+@pytest.mark.parametrize("order", [0, 1, 2, 3])
+def test_prefill_malformed_list_entries_are_never_followed(T, oracle, order):
+    """A list that breaks the contract (negative ids inside the count, ids past the last block, entries out of order,
+    a count beyond the list length) yields unspecified numbers but must never turn into an address outside the
+    tensors: the call completes, and a correct call right after it gives the right answer."""
+    wl = _small_bf16(N=512, Hq=2, Hkv=1)
+    q, k, v, _, _ = W.make_prefill(wl)
+    Tq, kmax = wl.N // wl.Bq, 4
+    idx = np.tile(np.array([-1, -5, 10_000, 2], np.int32), (1, wl.Hq, Tq, 1))
+    cnt = np.full((1, wl.Hq, Tq), 9, np.int32)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    q4, qs = T.thrift_quantize_mxfp4(qg, 0); k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    _say(f"malformed lists, order {order}")
+    T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, torch.from_numpy(idx).cuda(), torch.from_numpy(cnt).cuda(),
+                                wl.Bq, wl.Bk, True, 0, out_dtype=torch.float32, tile_order=order)
+    torch.cuda.synchronize()
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    qm = oracle.block_means(qb, dt, wl.Bq); km = oracle.block_means(kb, dt, wl.Bk)
+    idx_r, cnt_r = oracle.select_topk(qm, km, wl.Bq, wl.Bk, True, 0.25)
+    want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx_r, cnt_r, wl.Bq, wl.Bk, True, 1 / math.sqrt(wl.D), _units(1, wl.Hq, Tq),
+                                      tile_order=1 if order == 1 else 0).reshape(1, wl.Hq, wl.N, wl.D)
+    got = T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, torch.from_numpy(idx_r).cuda(), torch.from_numpy(cnt_r).cuda(),
+                                      wl.Bq, wl.Bk, True, 0, out_dtype=torch.float32, tile_order=order)
+    torch.cuda.synchronize()
+    assert np.abs(to_np(got) - want).max() <= TOLMIX
