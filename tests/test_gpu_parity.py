@@ -945,3 +945,26 @@ def test_prefill_malformed_list_entries_are_never_followed(T, oracle, order):
                                       wl.Bq, wl.Bk, True, 0, out_dtype=torch.float32, tile_order=order)
     torch.cuda.synchronize()
     assert np.abs(to_np(got) - want).max() <= TOLMIX
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_prefill_degenerate_inputs(T, oracle, order):
+    """All-zero inputs (uniform attention over zeros), and zero Q, K with constant V: every probability is exactly 1,
+    its 4-bit code is exact, so the output is the constant on both paths: exactly in the oracle, up to the rounding of
+    the final multiplication by 1/l on the GPU."""
+    B, Hq, Hkv, N, D, Bq = 1, 2, 1, 512, 128, 128
+    z = torch.zeros(B, Hq, N, D, dtype=torch.bfloat16)
+    zk = torch.zeros(B, Hkv, N, D, dtype=torch.bfloat16)
+    for const in (0.0, 1.0, -3.0):
+        v = torch.full((B, Hkv, N, D), const, dtype=torch.bfloat16)
+        got = T.thrift_attention(z.cuda(), zk.cuda(), v.cuda(), True, Bq, 64, 0.25, out_dtype=torch.float32, tile_order=order)
+        torch.cuda.synchronize()
+        assert torch.all((got - const).abs() <= 2e-7 * abs(const)), (const, (got - const).abs().max())
+        qb, dt = oracle.bits_of(z); kb, _ = oracle.bits_of(zk); vb, _ = oracle.bits_of(v)
+        qm = oracle.block_means(qb, dt, Bq); km = oracle.block_means(kb, dt, 64)
+        idx, cnt = oracle.select_topk(qm, km, Bq, 64, True, 0.25)
+        want = oracle.attn_thrift_prefill(qb, kb, vb, dt, idx, cnt, Bq, 64, True, 1 / math.sqrt(D), _units(B, Hq, N // Bq), tile_order=order)
+        assert np.all(want == const)
+        # ties everywhere: the selection takes the smallest ids, on both sides
+        idx_g, cnt_g = T.thrift_select_topk(T.thrift_block_means(z.cuda(), Bq), T.thrift_block_means(zk.cuda(), 64), Bq, 64, True, 0.25)
+        assert np.array_equal(to_np(idx_g)[..., :idx.shape[-1]], idx) and np.array_equal(to_np(cnt_g), cnt)
