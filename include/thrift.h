@@ -281,6 +281,26 @@ thrift_status thrift_attn_decode_shared(const void* q, thrift_dtype dt, const vo
                                         void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * thrift_attn_decode for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * thrift_attn_decode, without the workspace: the score keys, the selection bitmap and the split-K partials live
+ * in a static device array of THRIFT_DECODE_STATIC_SCRATCH_BYTES that every GPU the library runs on holds until
+ * the process ends.  The call allocates and frees nothing.  A problem whose thrift_attn_decode_workspace(...)
+ * exceeds that size returns THRIFT_ERR_WORKSPACE (nothing launched).  All calls on one GPU share the array:
+ * calls that overlap on one GPU (different streams, different host threads) race on it; calls on one stream
+ * are ordered and safe.  Nothing in the array has to be cleared between calls: every byte a call reads it has
+ * written itself.
+ */
+#define THRIFT_DECODE_STATIC_SCRATCH_BYTES (32u << 20)
+thrift_status thrift_attn_decode_static(const void* q, thrift_dtype dt, const void* k16, const void* v16,
+                                        const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
+                                        const float* kmean, const int32_t* seqlens,
+                                        int B, int Hq, int Hkv, int Nkv, int D, int Bk,
+                                        double budget, int fixed_k, int split_blocks, float softmax_scale,
+                                        void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                                        void* stream);
+
+/*
  * Append tokens to the dual cache that thrift_attn_decode reads (Sec. 4.1 and Sec. 5 describe the cache: 4-bit
  * K and V for every block, the 16-bit copy for promoted blocks, and the key-block means).  After the call the
  * cache holds, for every sequence, exactly what the pre-pass (thrift_block_means with block Bk on K,

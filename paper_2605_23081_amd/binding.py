@@ -23,7 +23,8 @@ EXPORTS = (
     "thrift_status_string", "thrift_row_budget", "thrift_visible_blocks", "thrift_budget_to_global_k",
     "thrift_select_kmax", "thrift_block_means", "thrift_select_topk", "thrift_select_topk_shared", "thrift_select_ablation", "thrift_quantize_mxfp4",
     "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_prefill_chunk", "thrift_attn_prefill_ordered",
-    "thrift_attn_decode_workspace", "thrift_attn_decode", "thrift_attn_decode_shared", "thrift_kv_cache_append",
+    "thrift_attn_decode_workspace", "thrift_attn_decode", "thrift_attn_decode_shared", "thrift_attn_decode_static",
+    "thrift_kv_cache_append",
     "thrift_attention_forward_workspace", "thrift_attention_forward",
 )
 
@@ -64,6 +65,7 @@ def lib() -> C.CDLL:
         L.thrift_attn_decode_workspace.argtypes = [i] * 7
         L.thrift_attn_decode.argtypes = [p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, d, i, i, f, p, i, p, p, i, p, sz, p]
         L.thrift_attn_decode_shared.argtypes = L.thrift_attn_decode.argtypes
+        L.thrift_attn_decode_static.argtypes = [p, i, p, p, p, p, p, p, p, p, i, i, i, i, i, i, d, i, i, f, p, i, p, p, i, p]
         L.thrift_kv_cache_append.argtypes = [p, p, i, i, p, p, p, p, p, p, p, p, p, i, i, i, i, i, p]
         L.thrift_attention_forward_workspace.restype = sz
         L.thrift_attention_forward_workspace.argtypes = [i, i, i, i, i, i, i, i, d, i]
@@ -250,6 +252,27 @@ def thrift_attn_decode(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budget: floa
               kmax, _ptr(workspace), workspace.numel(), _stream()),
            "thrift_attn_decode_shared" if group_shared else "thrift_attn_decode")
     return (out, idx, cnt) if return_selection else out
+
+
+DECODE_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def thrift_attn_decode_static(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budget: float, out: torch.Tensor,
+                              fixed_k: int = -1, split_blocks: int = 256, softmax_scale: float = 0.0,
+                              seqlens: Optional[torch.Tensor] = None, idx: Optional[torch.Tensor] = None,
+                              cnt: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """thrift_attn_decode on the library's static scratch: the caller passes every buffer (out, and idx / cnt if it
+    wants the selection back); neither this wrapper nor the C call allocates."""
+    for t in (q, k16, v16, k4, ks, v4, vs, kmean, out):
+        _dev(t)
+    B, Hq, D = q.shape
+    _, Hkv, Nkv, _ = k16.shape
+    kmax = 0 if idx is None else idx.shape[-1]
+    _check(lib().thrift_attn_decode_static(_ptr(q), _DT[q.dtype], _ptr(k16), _ptr(v16), _ptr(k4), _ptr(ks), _ptr(v4), _ptr(vs),
+                                           _ptr(kmean), _ptr(seqlens), B, Hq, Hkv, Nkv, D, Bk, float(budget), int(fixed_k),
+                                           int(split_blocks), float(softmax_scale), _ptr(out), _DT[out.dtype], _ptr(idx), _ptr(cnt),
+                                           kmax, _stream()), "thrift_attn_decode_static")
+    return out
 
 
 class KVCache:

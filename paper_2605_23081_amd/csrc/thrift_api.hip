@@ -3,9 +3,17 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "thrift_launch.h"
 
 using namespace thrift;
+
+// Scratch of thrift_attn_decode_static: the decode workspace (score keys, selection bitmap, split-K partials) for
+// callers that may not allocate.  One copy per GPU, held until the process ends.  In host code the array's name
+// is only a handle; its device address on the current GPU comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticScratchBytes = (size_t)THRIFT_DECODE_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -35,8 +43,29 @@ thrift_status after_launch() { return hipGetLastError() == hipSuccess ? THRIFT_O
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void* scratch_address[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (looked up on the first call per device, then cached).
+thrift_status static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return THRIFT_ERR_ARCH;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (scratch_address[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return THRIFT_ERR_LAUNCH;
+    }
+    scratch_address[dev] = p;
+  }
+  *ptr = scratch_address[dev];
+  return THRIFT_OK;
+}
+
 struct DecodeLayout {
-  size_t qf32, q4, qs, keys, bitmap, part_o, part_ml, total;
+  size_t keys, bitmap, part_o, part_ml, total;
   int nsplit, nparts, words;
 };
 
@@ -47,9 +76,6 @@ DecodeLayout decode_layout(int B, int Hq, int Nkv, int Bk, int split_blocks) {
   L.nparts = L.nsplit * 4 + 1;                   // one partial per wavefront of a partition's workgroup + one for a partly filled last block
   L.words = (Tk + 63) / 64;
   size_t off = 0;
-  L.qf32 = off; off += align256((size_t)B * Hq * kHeadDim * sizeof(float));
-  L.q4 = off; off += align256((size_t)B * Hq * (kHeadDim / 2));
-  L.qs = off; off += align256((size_t)B * Hq * (kHeadDim / 32));
   L.keys = off; off += align256((size_t)B * Hq * Tk * sizeof(uint64_t));
   L.bitmap = off; off += align256((size_t)B * Hq * L.words * sizeof(unsigned long long));
   L.part_o = off; off += align256((size_t)B * Hq * L.nparts * kHeadDim * sizeof(float));
@@ -318,7 +344,7 @@ static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void
 
   // (ii) split-K partial attention, (iii) log-sum-exp merge
   DecodeArgs a;
-  a.q = (const uint16_t*)q; a.q4 = (const uint8_t*)(ws + L.q4); a.qs = (const uint8_t*)(ws + L.qs); a.k16 = (const uint16_t*)k16; a.v16 = (const uint16_t*)v16;
+  a.q = (const uint16_t*)q; a.k16 = (const uint16_t*)k16; a.v16 = (const uint16_t*)v16;
   a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.seqlens = seqlens;
   a.bitmap = bitmap; a.bitmap_words = L.words;
   a.out = out; a.part_o = (float*)(ws + L.part_o); a.part_ml = (float*)(ws + L.part_ml);
@@ -349,6 +375,25 @@ thrift_status thrift_attn_decode_shared(const void* q, thrift_dtype dt, const vo
                                         void* workspace, size_t workspace_bytes, void* stream) {
   return attn_decode_impl(q, dt, k16, v16, k4, ks, v4, vs, kmean, seqlens, B, Hq, Hkv, Nkv, D, Bk, budget, fixed_k, split_blocks,
                           softmax_scale, out, out_dt, idx_out, cnt_out, kmax_out, workspace, workspace_bytes, 1, stream);
+}
+
+thrift_status thrift_attn_decode_static(const void* q, thrift_dtype dt, const void* k16, const void* v16,
+                                        const uint8_t* k4, const uint8_t* ks, const uint8_t* v4, const uint8_t* vs,
+                                        const float* kmean, const int32_t* seqlens,
+                                        int B, int Hq, int Hkv, int Nkv, int D, int Bk,
+                                        double budget, int fixed_k, int split_blocks, float softmax_scale,
+                                        void* out, thrift_dtype out_dt, int32_t* idx_out, int32_t* cnt_out, int kmax_out,
+                                        void* stream) {
+  // sizes first: a problem whose workspace does not fit the static array is refused before anything else happens
+  const size_t need = thrift_attn_decode_workspace(B, Hq, Hkv, Nkv, D, Bk, split_blocks);
+  if (need == 0) return THRIFT_ERR_SHAPE;
+  if (need > kStaticScratchBytes) return THRIFT_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (thrift_status s = static_scratch(&ws)) return s;
+  // Every byte of the workspace that the kernels read is written earlier in the same call (score keys and bitmap
+  // words of the visible blocks, one partial per partition slot), so nothing has to be cleared between calls.
+  return attn_decode_impl(q, dt, k16, v16, k4, ks, v4, vs, kmean, seqlens, B, Hq, Hkv, Nkv, D, Bk, budget, fixed_k, split_blocks,
+                          softmax_scale, out, out_dt, idx_out, cnt_out, kmax_out, ws, kStaticScratchBytes, 0, stream);
 }
 
 static bool fused_shape_ok(int B, int Hq, int Hkv, int N, int D, int Bq, int Bk) {

@@ -48,8 +48,6 @@ void launch_prefill(const PrefillArgs& a, hipStream_t st);
 
 struct DecodeArgs {
   const uint16_t* q;
-  const uint8_t* q4;      // MXFP4 codes / scales of q (axis 0), [B,Hq,64] and [B,Hq,4]
-  const uint8_t* qs;
   const uint16_t* k16;
   const uint16_t* v16;
   const uint8_t* k4;
