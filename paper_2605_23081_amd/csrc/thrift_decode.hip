@@ -47,14 +47,15 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   const int j_end = TAIL_ONLY ? Tk : min(Tk, j_begin + quarter);
 
   // ---- Q fragments (zeros for padding columns): the lane quantises its own two MXFP4 groups of the query,
-  // channels 64*kk + 32*half .. +31 for fragment kk (Alg. 1 step 2 for the one-token query block) ----
+  // d-group 2*half + kk (channels 64*half + 32*kk .. +31) for fragment kk (Alg. 1 step 2 for the one-token
+  // query block) ----
   v4i qf4[2] = {(v4i){0, 0, 0, 0}, (v4i){0, 0, 0, 0}};
   uint32_t qsc = 0x7f7f7f7fu;
   if (real) {
     uint32_t sb[2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
-      const uint4* src = reinterpret_cast<const uint4*>(a.q + qh * kD + 64 * kk + 32 * half);
+      const uint4* src = reinterpret_cast<const uint4*>(a.q + qh * kD + 64 * half + 32 * kk);
       uint32_t pair[16], codes[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -64,7 +65,7 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       sb[kk] = quantize_group32<T>(pair, codes);
       qf4[kk] = (v4i){(int)codes[0], (int)codes[1], (int)codes[2], (int)codes[3]};
     }
-    qsc = sb[0] | (sb[1] << 16);                             // byte 2*kk: the scale of fragment kk
+    qsc = sb[0] | (sb[1] << 8);                              // byte kk: the scale of fragment kk
   }
 
   const uint8_t* k4base = a.k4 + kh * a.Nkv * 64;
@@ -75,7 +76,7 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   const uint16_t* v16base = a.v16 + kh * a.Nkv * kD;
   const unsigned long long* bm = a.bitmap + qh * a.bitmap_words;
 
-  RowState st = {-INFINITY, 0.f};
+  RowState st = {kEmptyMax, 0.f};
   v16f o[4];
 #pragma unroll
   for (int n = 0; n < 4; ++n) o[n] = (v16f){0.f};
@@ -108,13 +109,13 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int key = key_of_row(r, t);
-        const uint8_t* krow = k4base + ((size_t)j * kBk + key) * 64 + 16 * half;
+        const uint8_t* krow = k4base + ((size_t)j * kBk + key) * 64 + 32 * half;
         const v4i a0 = *reinterpret_cast<const v4i*>(krow);
-        const v4i a1 = *reinterpret_cast<const v4i*>(krow + 32);
-        const uint32_t ksw = *reinterpret_cast<const uint32_t*>(ksbase + ((size_t)j * kBk + key) * 4) >> (8 * half);
+        const v4i a1 = *reinterpret_cast<const v4i*>(krow + 16);
+        const uint32_t ksw = *reinterpret_cast<const uint16_t*>(ksbase + ((size_t)j * kBk + key) * 4 + 2 * half);
         v16f acc = {0.f};
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a0), widen(qf4[0]), acc, 4, 4, 0, ksw, 0, qsc);
-        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a1), widen(qf4[1]), acc, 4, 4, 2, ksw, 2, qsc);
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a1), widen(qf4[1]), acc, 4, 4, 1, ksw, 1, qsc);
         s[t] = acc;
       }
     }
@@ -144,15 +145,15 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       if (all16) { s[0] = s16[0]; s[1] = s16[1]; }
       else if (mine16) { s[0] = s16[0]; s[1] = s16[1]; }
     }
-    float gmax;
-    const float alpha = softmax_update(s, lane, TAIL, n_valid, c, st, gmax);
-    rescale(o, alpha);
+    float alpha;
+    uint32_t pb;
+    const bool grew = softmax_update(s, lane, TAIL, n_valid, c, st, alpha, pb);
+    rescale(o, grew, alpha);
     if (!all16) {
-      // heads that took the 16-bit scores contribute nothing on the 4-bit path
+      // heads that took the 16-bit scores contribute nothing on the 4-bit path (zero codes, whatever the scale)
       v16f p4[2] = {s[0], s[1]};
-      float g4 = gmax;
-      if (mine16) { p4[0] = (v16f){0.f}; p4[1] = (v16f){0.f}; g4 = 0.f; }
-      pv_fp4_regs<true>(p4, g4, vsw, 0u, 0u, 0u, vf4[0], vf4[1], vf4[2], vf4[3], o);
+      if (mine16) { p4[0] = (v16f){0.f}; p4[1] = (v16f){0.f}; }
+      pv_fp4_regs<true>(p4, pb, vsw, 0u, 0u, 0u, vf4[0], vf4[1], vf4[2], vf4[3], o);
     }
     if (any16) {
       v16f p16[2] = {s[0], s[1]};

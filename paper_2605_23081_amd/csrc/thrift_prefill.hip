@@ -20,6 +20,8 @@
 // Differences from the kernel the paper sketches for Blackwell (Sec. 3.3): no two-phase split (4-bit
 // tiles first, 16-bit helper afterwards): ascending order keeps the result independent of the schedule
 // and identical to Alg. 1 as written.
+#include <type_traits>
+
 #include "thrift_launch.h"
 #include "thrift_tile.h"
 
@@ -50,8 +52,11 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_
 
 // LDS DMA: the 64 lanes fetch 16 (4) bytes each from base + off and the hardware writes them to the
 // 1 KiB (256 B) of consecutive LDS that starts at lds_base, lane l at lds_base + 16 l (4 l).  base and
-// lds_base are wavefront-uniform.  The instruction takes its LDS base from M0; the compiler has no
-// other use for M0 in this kernel.  Completion is counted by vmcnt like any global load.
+// lds_base are wavefront-uniform.  The instruction takes its LDS base from M0, which each statement sets
+// itself.  M0 is a reserved register for the compiler (it cannot be named as a clobber): it never keeps a
+// value there across statements and loads it right before the few instructions of its own that read it; the
+// build additionally checks that the kernel's listing mentions M0 only inside these statements.
+// Completion is counted by vmcnt like any global load.
 __device__ __forceinline__ void dma_b128(const void* base, uint32_t off, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
 }
@@ -96,9 +101,10 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
 
   // ---- Q fragments ----
   v4i qf4[2];
-  qf4[0] = *reinterpret_cast<const v4i*>(a.q4 + qrow * 64 + half * 16);
-  qf4[1] = *reinterpret_cast<const v4i*>(a.q4 + qrow * 64 + 32 + half * 16);
-  const uint32_t qsc = *reinterpret_cast<const uint32_t*>(a.qs + qrow * 4) >> (8 * half);
+  // fragment kk: d-group 2*half + kk (scores_fp4); its scale is byte kk of qsc
+  qf4[0] = *reinterpret_cast<const v4i*>(a.q4 + qrow * 64 + half * 32);
+  qf4[1] = *reinterpret_cast<const v4i*>(a.q4 + qrow * 64 + half * 32 + 16);
+  const uint32_t qsc = *reinterpret_cast<const uint32_t*>(a.qs + qrow * 4) >> (16 * half);
   const uint8_t* q16head = reinterpret_cast<const uint8_t*>(a.q + qh * Nq * kD);   // wavefront-uniform
 
   const int vis = a.causal ? min(Tk, ((i + a.q_off + 1) * Bq - 1) / kBk + 1) : Tk;
@@ -132,10 +138,14 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
 #pragma unroll
   for (int u = 0; u < KF; ++u) {
     const int f = wave * KF + u;                         // K: fragment (t, kk) = (f>>1, f&1); V: channels 32f .. 32f+31
-    k4off[u] = (uint32_t)(key_of_row(r, f >> 1) * 64 + (2 * (f & 1) + half) * 16);
+    k4off[u] = (uint32_t)(key_of_row(r, f >> 1) * 64 + (2 * half + (f & 1)) * 16);    // d-group 2*half + kk of the key
     v4off[u] = (uint32_t)((32 * f + r) * 32 + half * 16);
   }
   const uint32_t scoff = (uint32_t)lane * 4;
+  // the 256 scale bytes of K ride with the even wavefronts, V's with the odd ones: picked once, in scalar registers
+  const bool v_scales = (wave & 1) != 0;
+  const uint8_t* scbase = v_scales ? vsbase : ksbase;
+  const uint32_t sclds = v_scales ? (uint32_t)kLdsVS : (uint32_t)kLdsKS;
   // 16-bit tiles: one instruction covers 4 rows; lane l writes chunk position l&15 of row l>>4
   // (formed from the lane index where a 16-bit tile is issued, one block in twenty on the headline budget,
   // rather than held in registers through every 4-bit block)
@@ -156,38 +166,41 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
     const int j_ = __builtin_amdgcn_readfirstlane(J), s_ = __builtin_amdgcn_readfirstlane(S); /* scalar operands */ \
     const uint8_t* kt_ = k4base + (size_t)j_ * 4096;                                                           \
     const uint8_t* vt_ = v4base + (size_t)j_ * 4096;                                                           \
-    const uint32_t sl_ = lds0 + kLdsRing + s_ * kSlotStride;                                                   \
+    int wave_ = wave;                                                                                          \
+    asm volatile("" : "+s"(wave_));   /* LDS destinations are formed here from one scalar, not kept per slot and fragment */ \
+    const uint32_t sl_ = lds0 + kLdsRing + s_ * kSlotStride + (uint32_t)(wave_ * (KF * 1024));                 \
     if ((j_ + 1) * kBk <= N) {                                                                                 \
-      _Pragma("unroll") for (int u = 0; u < KF; ++u) dma_b128(kt_, k4off[u], sl_ + kLdsK4 + (wave * KF + u) * 1024); \
-      if (!(wave & 1)) dma_b32(ksbase + (size_t)j_ * 256, scoff, sl_ + kLdsKS);                                \
+      _Pragma("unroll") for (int u = 0; u < KF; ++u) dma_b128(kt_, k4off[u], sl_ + kLdsK4 + u * 1024); \
+      dma_b32(scbase + (size_t)j_ * 256, scoff, sl_ - (uint32_t)(wave_ * (KF * 1024)) + sclds);                                                  \
     } else {                                                                                                   \
       uint32_t last_ = (uint32_t)last_key_row;                                                                 \
       asm volatile("" : "+s"(last_));                                                                          \
       _Pragma("unroll") for (int u = 0; u < KF; ++u)                                                           \
-        dma_b128(kt_, THRIFT_CLAMP_ROWS(k4off[u], 6, last_), sl_ + kLdsK4 + (wave * KF + u) * 1024);           \
-      if (!(wave & 1)) dma_b32(ksbase + (size_t)j_ * 256, THRIFT_CLAMP_ROWS(scoff, 2, last_), sl_ + kLdsKS);   \
+        dma_b128(kt_, THRIFT_CLAMP_ROWS(k4off[u], 6, last_), sl_ + kLdsK4 + u * 1024);                         \
+      /* V scales are stored in whole, zero-padded blocks; K's rows past the last key do not exist */          \
+      dma_b32(scbase + (size_t)j_ * 256, v_scales ? scoff : THRIFT_CLAMP_ROWS(scoff, 2, last_),                \
+              sl_ - (uint32_t)(wave_ * (KF * 1024)) + sclds);                                                  \
     }                                                                                                          \
-    /* V codes and scales: whole blocks; the scale bytes ride with the odd wavefronts, K's with the even ones */ \
-    _Pragma("unroll") for (int u = 0; u < KF; ++u) dma_b128(vt_, v4off[u], sl_ + kLdsV4 + (wave * KF + u) * 1024); \
-    if (wave & 1) dma_b32(vsbase + (size_t)j_ * 256, scoff, sl_ + kLdsVS);                                     \
+    /* V codes: whole blocks */                                                                                \
+    _Pragma("unroll") for (int u = 0; u < KF; ++u) dma_b128(vt_, v4off[u], sl_ + kLdsV4 + u * 1024); \
   } while (0)
   // 16-bit tiles: instruction q_ covers rows 4 q_ .. 4 q_ + 3
 #define THRIFT_ISSUE_TILE16(BASE, J, OFFEXPR, LDSBASE)                                                         \
   do {                                                                                                         \
     const int j_ = __builtin_amdgcn_readfirstlane(J);                                                          \
     const uint8_t* t_ = (BASE) + (size_t)j_ * kTile16;                                                         \
-    int lane16 = lane;                                                                                         \
-    asm volatile("" : "+v"(lane16));   /* offsets are computed here, not carried through the key loop */       \
+    int lane16 = lane, wave_ = wave;                                                                           \
+    asm volatile("" : "+v"(lane16), "+s"(wave_));   /* offsets and destinations are computed here, not carried through the key loop */ \
     if ((j_ + 1) * kBk <= N) {                                                                                 \
       _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                        \
-        const int q_ = u * NW + wave;                                                                          \
+        const int q_ = u * NW + wave_;                                                                         \
         dma_b128(t_ + q_ * 1024, (OFFEXPR), (LDSBASE) + q_ * 1024);                                            \
       }                                                                                                        \
     } else {                                                                                                   \
       uint32_t last_ = (uint32_t)last_key_row;                                                                 \
       asm volatile("" : "+s"(last_));                                                                          \
       _Pragma("unroll") for (int u = 0; u < C16; ++u) {                                                        \
-        const int q_ = u * NW + wave;                                                                          \
+        const int q_ = u * NW + wave_;                                                                         \
         const uint32_t o_ = (uint32_t)(q_ * 1024) + (OFFEXPR);   /* offset from the tile start */              \
         dma_b128(t_, THRIFT_CLAMP_ROWS(o_, 8, last_), (LDSBASE) + q_ * 1024);                                  \
       }                                                                                                        \
@@ -196,7 +209,7 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
 #define THRIFT_ISSUE_V16(J) THRIFT_ISSUE_TILE16(v16base, J, THRIFT_V16OFF(), lds0 + kLdsV16)
 #define THRIFT_ISSUE_K16(J) THRIFT_ISSUE_TILE16(k16base, J, (u * NW >= 8 ? THRIFT_K16OFF() ^ 64u : THRIFT_K16OFF()), lds0 + kLdsK16)
 
-  RowState st = {-INFINITY, 0.f};
+  RowState st = {kEmptyMax, 0.f};
   v16f o[4];
 #pragma unroll
   for (int n = 0; n < 4; ++n) o[n] = (v16f){0.f};
@@ -283,11 +296,12 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
         THRIFT_MASK(j)
         const unsigned char* slot = lds + (j & 1) * kWideSlot;
         v16f s[2];
-        float gmax;
+        float alpha;
+        uint32_t pb;
         scores_fp4(slot, lane, qf4, qsc, s);
-        const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-        rescale(o, alpha);
-        pv_fp4(slot, lane, s, gmax, o);
+        const bool grew = softmax_update(s, lane, mask, n_valid, c, st, alpha, pb);
+        rescale(o, grew, alpha);
+        pv_fp4(slot, lane, s, pb, o);
       }
       if (j < vis_wave) {                                 // j == n0: a promoted block
         THRIFT_SYNC()
@@ -296,9 +310,10 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
         const unsigned char* slot = lds + (j & 1) * kWideSlot;
         v16f s[2];
         scores_16<T>(slot, lane, qf, s);
-        float gmax;
-        const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-        rescale(o, alpha);
+        float alpha;
+        uint32_t pb;
+        const bool grew = softmax_update(s, lane, mask, n_valid, c, st, alpha, pb);
+        rescale(o, grew, alpha);
         pv_16<T, true>(slot + kTile16, lane, s, o);
         THRIFT_NEXT_PROMOTED()
         ++j;
@@ -331,29 +346,36 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
       THRIFT_ISSUE_K16(first_promoted);
       THRIFT_ISSUE_V16(first_promoted);
     }
-    int t = 0;
-    while (j < vis) {                                   // phase A
+    // Phase A, two steps per trip so that the ring slot of each step is a compile-time constant: every LDS
+    // read of the step is then a lane-constant address register plus an immediate offset, no address arithmetic.
+    auto step_a = [&](auto slot_c) __attribute__((always_inline)) {
+      constexpr int SLOT = decltype(slot_c)::value;
       int jn = j + 1;
       while (jn == nx) { ++jn; ++pa; nx = pa < nselv ? sel_at(pa) : 0x7fffffff; }
       THRIFT_SYNC()
       if (jn < vis) {
-        THRIFT_ISSUE4_SLOT(jn, (t + 1) & 1);
+        THRIFT_ISSUE4_SLOT(jn, SLOT ^ 1);
       } else if (nselv > 0) {
         THRIFT_ISSUE_K16(first_promoted);
         THRIFT_ISSUE_V16(first_promoted);
       }
       if (j < vis_wave) {
         THRIFT_MASK(j)
-        const unsigned char* slot = lds + kLdsRing + (t & 1) * kLdsBytes4;
+        const unsigned char* slot = lds + kLdsRing + SLOT * kLdsBytes4;
         v16f s[2];
-        float gmax;
+        float alpha;
+        uint32_t pb;
         scores_fp4(slot, lane, qf4, qsc, s);
-        const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-        rescale(o, alpha);
-        pv_fp4(slot, lane, s, gmax, o);
+        const bool grew = softmax_update(s, lane, mask, n_valid, c, st, alpha, pb);
+        rescale(o, grew, alpha);
+        pv_fp4(slot, lane, s, pb, o);
       }
       j = jn;
-      ++t;
+    };
+    while (j < vis) {                                   // phase A
+      step_a(std::integral_constant<int, 0>{});
+      if (j >= vis) break;
+      step_a(std::integral_constant<int, 1>{});
     }
     // phase B: the promoted blocks follow each other.  The lane's 16-bit query fragments are fetched once and stay
     // in registers for the whole phase (the 4-bit phase, which has no registers to spare, is over: Sec. 3.3 scopes
@@ -385,15 +407,16 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
       }
       THRIFT_MASK(jb)
       v16f s[2];
-      float gmax, alpha = 1.0f;
       if (mine) scores_16<T>(lds + THRIFT_TILE_BUFFER(kbuf), lane, qf, s);
       if (p1) vm_wait<C16>();                           // V(b); K(b+1) may still be on its way
       else vm_wait<0>();
       lds_barrier();                                    // V(b) complete; everyone has its scores, K(b)'s buffer is free
       if (p1) { THRIFT_ISSUE_TILE16(v16base, jb_next, THRIFT_V16OFF(), lds0 + (uint32_t)THRIFT_TILE_BUFFER(kbuf)); }
       if (mine) {
-        alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-        rescale(o, alpha);
+        float alpha;
+        uint32_t pb;
+        const bool grew = softmax_update(s, lane, mask, n_valid, c, st, alpha, pb);
+        rescale(o, grew, alpha);
         pv_16<T, true>(lds + THRIFT_TILE_BUFFER(vbuf), lane, s, o);
       }
       kbuf = kbuf_next;
@@ -421,17 +444,19 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
       THRIFT_MASK(j)
       const unsigned char* slot = lds + kLdsRing + (j & 1) * kLdsBytes4;
       v16f s[2];
-      float gmax;
+      float alpha;
+      uint32_t pb;
       scores_fp4(slot, lane, qf4, qsc, s);
-      const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-      rescale(o, alpha);
-      pv_fp4(slot, lane, s, gmax, o);
+      const bool grew = softmax_update(s, lane, mask, n_valid, c, st, alpha, pb);
+      rescale(o, grew, alpha);
+      pv_fp4(slot, lane, s, pb, o);
       late_v = false;
     }
     if (j < vis_wave) {                                 // j == n0: a promoted block
       const bool p1 = j + 1 == n1 && j + 1 < vis;
       v16f s[2];
-      float gmax;
+      float alpha;
+      uint32_t pb;
       THRIFT_SYNC()
       THRIFT_ISSUE(j, true, j + 1 == n1)
       if (late_v) THRIFT_ISSUE_V16(j);
@@ -445,8 +470,8 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
         lds_barrier();
         THRIFT_ISSUE_K16(j + 1);
       }
-      const float alpha = softmax_update(s, lane, mask, n_valid, c, st, gmax);
-      rescale(o, alpha);
+      const bool grew = softmax_update(s, lane, mask, n_valid, c, st, alpha, pb);
+      rescale(o, grew, alpha);
       if (late_v) {                                     // this block's V tile was issued in this step
         if (p1) vm_wait<C16>();
         else vm_wait<0>();

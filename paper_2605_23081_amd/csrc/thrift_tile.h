@@ -43,15 +43,6 @@ __device__ __forceinline__ int key_of_row(int rho, int t) {
   return 32 * ((rho >> 2) & 1) + 16 * t + 4 * (rho >> 3) + (rho & 3);
 }
 
-// Byte offset inside the K4 LDS region of the 16-byte chunk (key, c4) of the global [64 keys][64 B] tile:
-// fragment (t, kk) is the contiguous 1 KiB that one MFMA reads, lane-major.
-__device__ __forceinline__ int k4_fragment_offset(int key, int c4) {
-  const int t = (key >> 4) & 1, hp = key >> 5, a = (key >> 2) & 3, c = key & 3;
-  const int rho = 8 * a + 4 * hp + c;
-  const int kk = c4 >> 1, hk = c4 & 1;
-  return ((t * 2 + kk) * 64 + 32 * hk + rho) * 16;
-}
-
 __device__ __forceinline__ v8i widen(v4i x) { return __builtin_shufflevector(x, x, 0, 1, 2, 3, -1, -1, -1, -1); }
 
 struct RowState {
@@ -59,18 +50,21 @@ struct RowState {
   float l;      // this lane's partial row sum (the two halves of a query add up at the end)
 };
 
-// S^T for a 4-bit tile.  qf: the lane's two Q fragments (D halves), qsc: its Q scale bytes already
-// shifted so that byte 2*kk belongs to fragment kk.
+// S^T for a 4-bit tile.  The two MFMAs of a sub-tile split D = 128 so that lane half h contracts d-group
+// 2h + kk in MFMA kk (any split works as long as K and Q agree): the lane's two K scale bytes are then
+// neighbours in the [key][d-group] scale row and arrive with one 16-bit LDS read, byte kk for MFMA kk.
+// qf: the lane's two Q fragments (d-groups 2*half + kk), qsc: its Q scale bytes, byte kk for fragment kk.
 __device__ __forceinline__ void scores_fp4(const unsigned char* lds, int lane, const v4i (&qf)[2], uint32_t qsc, v16f (&s)[2]) {
   const int half = lane >> 5, r = lane & 31;
+  const unsigned char* ksrow = lds + kLdsKS + 4 * key_of_row(r, 0) + 2 * half;   // sub-tile 1: 16 keys = 64 bytes further
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    const uint32_t ksw = *reinterpret_cast<const uint32_t*>(lds + kLdsKS + 4 * key_of_row(r, t)) >> (8 * half);
+    const uint32_t ksw = *reinterpret_cast<const uint16_t*>(ksrow + 64 * t);
     const v4i a0 = *reinterpret_cast<const v4i*>(lds + kLdsK4 + ((t * 2 + 0) * 64 + lane) * 16);
     const v4i a1 = *reinterpret_cast<const v4i*>(lds + kLdsK4 + ((t * 2 + 1) * 64 + lane) * 16);
     v16f acc = {0.f};
     acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a0), widen(qf[0]), acc, 4, 4, 0, ksw, 0, qsc);
-    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a1), widen(qf[1]), acc, 4, 4, 2, ksw, 2, qsc);
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a1), widen(qf[1]), acc, 4, 4, 1, ksw, 1, qsc);
     s[t] = acc;
   }
 }
@@ -94,15 +88,23 @@ __device__ __forceinline__ void scores_16(const unsigned char* ktile, int lane, 
   }
 }
 
+// Running maximum of a row that has seen no key yet: a large negative finite number instead of -inf, so that
+// neither m - m nor m * c needs a guard (an exponent argument of -inf still gives probability 0).
+constexpr float kEmptyMax = -1.0e30f;
+
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }   // one v_max3_f32
+
 // Online-softmax update for the lane's 32 scores (Alg. 1 steps 10-12 / 16-17): masks, raises the
-// running maximum, turns s into the unnormalised probabilities exp(scale*(s - m_new)) in place, adds
-// them to the partial row sum and returns alpha = exp(scale*(m_old - m_new)) — exactly 1 in every lane,
-// with no arithmetic spent on it, when no row of the wavefront raised its maximum (the common case
-// once the first blocks are behind).  group_max receives the largest probability of the lane's 32-key
-// group (the MXFP4 scale of P derives from it).
+// running maximum, turns s into the unnormalised probabilities exp(scale*(s - m_new)) in place and adds
+// them to the partial row sum.  Returns true, for the whole wavefront, when some row raised its maximum:
+// only then does alpha hold exp(scale*(m_old - m_new)) (Alg. 1 steps 11 / 16), the row sum is already
+// scaled by it and the caller must rescale its accumulators; otherwise alpha is 1 everywhere and no
+// arithmetic was spent on it (the common case once the first blocks are behind).
+// pbyte receives the E8M0 byte of the lane's 32-key group of P (Alg. 1 step 19 with a power-of-two scale):
+// floor(log2(largest probability of the group)) - 2 + 127, at least 1 so that the scale is a normal float.
 //   c = softmax_scale * log2(e);  n_valid = number of leading keys of the block this query may see.
-__device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mask, int n_valid, float c, RowState& st,
-                                                float& group_max) {
+__device__ __forceinline__ bool softmax_update(v16f (&s)[2], int lane, bool mask, int n_valid, float c, RowState& st,
+                                               float& alpha, uint32_t& pbyte) {
   const int half = lane >> 5;
   if (mask) {
     int lim = n_valid - 32 * half;                      // the lane's keys 16t + i at or past lim are masked
@@ -113,41 +115,63 @@ __device__ __forceinline__ float softmax_update(v16f (&s)[2], int lane, bool mas
       for (int i = 0; i < 16; ++i)
         if (16 * t + i >= lim) s[t][i] = -INFINITY;
   }
-  float mloc = s[0][0];
+  float mloc = max3(s[0][0], s[0][1], s[0][2]);
 #pragma unroll
-  for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, s[0][i]);
+  for (int i = 3; i < 15; i += 2) mloc = max3(mloc, s[0][i], s[0][i + 1]);
+  mloc = max3(mloc, s[0][15], s[1][0]);
 #pragma unroll
-  for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, s[1][i]);
-  const float m_new = fmaxf(st.m, fmaxf(mloc, other_half(mloc)));
-  const float m_safe = m_new == -INFINITY ? 0.f : m_new;       // a row that has seen nothing stays empty
-  float alpha = 1.0f;
-  const bool grew = __builtin_amdgcn_ballot_w64(m_new != st.m) != 0ULL;
-  if (grew) alpha = fast_exp2((st.m - m_safe) * c);
+  for (int i = 1; i < 15; i += 2) mloc = max3(mloc, s[1][i], s[1][i + 1]);
+  mloc = fmaxf(mloc, s[1][15]);
+  // the other half of the row lives 32 lanes away: after the swap of two copies one register holds the lower
+  // half's maximum in every lane and the other the upper half's
+  uint32_t lo = __float_as_uint(mloc), hi = lo;
+  {
+    auto sw = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+    lo = sw[0]; hi = sw[1];
+  }
+  const float m_old = st.m;
+  const float m_new = max3(m_old, __uint_as_float(lo), __uint_as_float(hi));
+  const bool grew = __builtin_amdgcn_ballot_w64(m_new != m_old) != 0ULL;
+  if (grew) {
+    float d = m_old - m_new;
+    asm volatile("" : "+v"(d));                                    // keeps the exponential inside the branch
+    alpha = fast_exp2(d * c);
+    float l = st.l;
+    // stays inside the branch (no select on the common path).  The wait states are for the hand-written consumer of
+    // a transcendental result: the compiler spaces its own instructions, not the inside of an asm statement.
+    asm volatile("s_nop 1\n\tv_mul_f32 %0, %1, %0" : "+v"(l) : "v"(alpha));
+    st.l = l;
+  }
+  st.m = m_new;
   // Elements use one fused multiply-add, s*c - m*c; its rounding residue (a few 1e-7 relative on p) is
-  // harmless for the codes and the row sum.  The group maximum, which fixes the power-of-two scale of
-  // the P quantiser, is formed as (s - m)*c instead: the row maximum then maps to exactly 2^0 and can
-  // never slip under the binade boundary (where the floor scale rule would saturate it to 0.75).
-  const float mc = m_safe * c;
-  float sum = 0.f;
+  // harmless for the codes and the row sum.  The exponent of the group maximum, which fixes the power-of-two
+  // scale of the P quantiser, is formed from (s - m)*c instead: the row maximum then maps to exactly 2^0 and
+  // can never slip under the binade boundary (where the floor rule would scale it to 8 and saturate it to 6).
+  int e;
+  {
+    const float x = (mloc - m_new) * c;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(e) : "v"(x));        // floor; -inf (nothing visible) saturates to INT_MIN
+  }
+  pbyte = (uint32_t)max(e + 125, 1);
+  const float mc = m_new * c;
+  float sum;
 #pragma unroll
   for (int t = 0; t < 2; ++t)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float p = fast_exp2(__builtin_fmaf(s[t][i], c, -mc));
       s[t][i] = p;
-      sum += p;
+      sum = (t == 0 && i == 0) ? p : sum + p;
     }
-  group_max = fast_exp2((mloc - m_safe) * c);
-  st.l = grew ? st.l * alpha + sum : st.l + sum;
-  st.m = m_new;
-  return alpha;
+  st.l += sum;
+  return grew;
 }
 
-__device__ __forceinline__ void rescale(v16f (&o)[4], float alpha) {
+__device__ __forceinline__ void rescale(v16f (&o)[4], bool grew, float alpha) {
   // Skipping is exact: alpha == 1 leaves every accumulator unchanged.  The multiplies are written as
   // in-place instructions so that the accumulators keep their registers on both sides of the branch
   // (otherwise the skip path pays 64 register copies per key block).
-  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0ULL) {
+  if (grew) {
 #pragma unroll
     for (int n = 0; n < 4; ++n)
 #pragma unroll
@@ -162,18 +186,18 @@ __device__ __forceinline__ void rescale(v16f (&o)[4], float alpha) {
 
 // 4-bit P.V (Alg. 1 steps 19-20 with the first-level scale equal to 1): quantise the lane's 32
 // probabilities as one MXFP4 group and accumulate O^T += V^T . P^T on the scaled MFMA.  v0..v3: the
-// lane's V^T fragments (channel 32n + r, tokens 32*half .. +31).  Their scale bytes come either packed
+// lane's V^T fragments (channel 32n + r, tokens 32*half .. +31).  pb: the E8M0 byte of the lane's P group
+// (softmax_update).  The V scale bytes come either packed
 // in one register (PACKED: byte n of vs0) or one per register (byte 0 of vs0..vs3).
 template <bool PACKED>
-__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], float group_max, uint32_t vs0, uint32_t vs1, uint32_t vs2,
+__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], uint32_t pb, uint32_t vs0, uint32_t vs1, uint32_t vs2,
                                             uint32_t vs3, v4i v0, v4i v1, v4i v2, v4i v3, v16f (&o)[4]) {
-  uint32_t ef = __float_as_uint(group_max) >> 23;
-  const uint32_t pb = ef >= 3u ? ef - 2u : 1u;                 // E8M0 byte, kept >= 1 so the scale is a normal float
-  const float pscale = __uint_as_float(pb << 23);
+  const float pscale = __uint_as_float(pb << 23);              // pb: E8M0 byte of the group, >= 1 (a normal float)
   v4i pq;
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
-    uint32_t o32 = 0;
+    uint32_t o32;
+    asm volatile("" : "=v"(o32));                              // all four bytes are written below: no initial value needed
     const int t = w >> 1, i0 = 8 * (w & 1);                    // slots 8w .. 8w+7 = p[t][i0 .. i0+7]
     o32 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o32, p[t][i0 + 0], p[t][i0 + 1], pscale, 0);
     o32 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o32, p[t][i0 + 2], p[t][i0 + 3], pscale, 1);
@@ -196,11 +220,11 @@ __device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], float group_max,
 }
 
 // The same with V^T fragments and scales taken from a staged LDS slot.
-__device__ __forceinline__ void pv_fp4(const unsigned char* slot, int lane, const v16f (&p)[2], float group_max, v16f (&o)[4]) {
+__device__ __forceinline__ void pv_fp4(const unsigned char* slot, int lane, const v16f (&p)[2], uint32_t pb, v16f (&o)[4]) {
   const int half = lane >> 5, r = lane & 31;
   const unsigned char* vs = slot + kLdsVS + half * kD + r;
   const unsigned char* vbase = slot + kLdsV4 + lane * 16;
-  pv_fp4_regs<false>(p, group_max, vs[0], vs[32], vs[64], vs[96], *reinterpret_cast<const v4i*>(vbase),
+  pv_fp4_regs<false>(p, pb, vs[0], vs[32], vs[64], vs[96], *reinterpret_cast<const v4i*>(vbase),
                      *reinterpret_cast<const v4i*>(vbase + 1024), *reinterpret_cast<const v4i*>(vbase + 2048),
                      *reinterpret_cast<const v4i*>(vbase + 3072), o);
 }
