@@ -23,8 +23,10 @@
  *   - No global state: calls on different streams are independent.
  *   - Tensors are contiguous, last index fastest.  16-bit tensors are IEEE fp16 (THRIFT_F16) or
  *     bfloat16 (THRIFT_BF16).
- *   - Shape limits of this version: D == 128, Bk == 64, Bq in {64, 128} (prefill), N a multiple of
- *     Bq and of Bk, Hq a multiple of Hkv, at most 4096 key blocks per row.  Anything else returns
+ *   - Shape limits of this version: D == 128, Bk == 64, Bq in {64, 128} (prefill), Hq a multiple of Hkv,
+ *     at most 4096 key blocks per row (N <= 262144), a GQA group of at most 32 heads in decode, a decode
+ *     cache capacity Nkv that is a multiple of Bk.  Sequence lengths need NOT be multiples of Bq or Bk (a
+ *     short last block is handled as the entry points below describe).  Anything else returns
  *     THRIFT_ERR_SHAPE.
  *
  * MXFP4 as used here (OCP Microscaling v1.0 conversion)
@@ -228,8 +230,9 @@ thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const vo
  * (thrift_attention_forward_workspace(...) bytes, 256-byte aligned, device), which may be reused by the next call
  * on the same stream.  q [B,Hq,N,D], k, v [B,Hkv,N,D] 16-bit (dt); out [B,Hq,N,D] in out_dt; lse nullable [B,Hq,N].
  * budget / fixed_k as in thrift_select_topk; tile_order as in thrift_attn_prefill_ordered (0: Alg. 1's order, 1: the
- * order of the kernel in Sec. 3.3, the faster one); softmax_scale <= 0 means 1/sqrt(D).  A stage that rejects its arguments
- * ends the chain with that stage's status; the stages before it have then already been enqueued.
+ * order of the kernel in Sec. 3.3, the faster one); softmax_scale <= 0 means 1/sqrt(D).  All arguments are
+ * validated before the first stage is enqueued: on a status other than THRIFT_OK nothing has run (THRIFT_ERR_LAUNCH
+ * excepted, which reports a launch the HIP runtime refused).
  */
 size_t thrift_attention_forward_workspace(int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, double budget, int fixed_k);
 thrift_status thrift_attention_forward(const void* q, const void* k, const void* v, thrift_dtype dt,
@@ -257,7 +260,11 @@ size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int 
  *     been quantised from those tokens alone (what thrift_kv_cache_append, or the pre-pass on a tensor of that
  *     length, produces).  Cache contents past that block are never read.  A sequence of length 0 yields zeros.
  *     Split-K: the full key blocks are cut into the partitions; a partly filled last block is a partition of its own.
- *   split_blocks: key blocks per partition (> 0)
+ *   split_blocks: key blocks per workgroup (> 0, a multiple of 4).  The four wavefronts of a workgroup each run
+ *     Alg. 1 over a contiguous quarter and write one partial, so the recurrence (and with it the rounding of P on the
+ *     4-bit path, which follows the running maximum) restarts every split_blocks / 4 key blocks: the result equals
+ *     split-K with partitions of split_blocks / 4 blocks merged by log-sum-exp.  In exact arithmetic the cut points
+ *     do not matter.
  *   out [B,Hq,D] in out_dt
  *   idx_out (nullable) [B,Hq,kmax_out], cnt_out (nullable) [B,Hq]: the selection that was used
  *     (kmax_out >= thrift_select_kmax(1, Nkv/Bk, 1, Bk, 0, budget, fixed_k, 0))

@@ -98,6 +98,32 @@ def _dev(t: torch.Tensor, dtype=None) -> torch.Tensor:
     return t
 
 
+def _prefill_shapes(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq: int) -> None:
+    """The C side sees pointers only: check here that every tensor has the dtype and the exact shape the kernel indexes."""
+    B, Hq, Nq, D = q.shape
+    _, Hkv, Nkv, _ = k.shape
+    assert q.dtype == k.dtype == v.dtype and q.dtype in (torch.float16, torch.bfloat16), (q.dtype, k.dtype, v.dtype)
+    assert k.shape == v.shape == (B, Hkv, Nkv, D), (k.shape, v.shape)
+    Tq, Tv = -(-Nq // Bq), -(-Nkv // 64)
+    u8, i32 = torch.uint8, torch.int32
+    for name, t, shape, dt in (("q4", q4, (B, Hq, Nq, D // 2), u8), ("qs", qs, (B, Hq, Nq, D // 32), u8),
+                               ("k4", k4, (B, Hkv, Nkv, D // 2), u8), ("ks", ks, (B, Hkv, Nkv, D // 32), u8),
+                               ("v4", v4, (B, Hkv, Tv, D, 32), u8), ("vs", vs, (B, Hkv, 2 * Tv, D), u8),
+                               ("cnt", cnt, (B, Hq, Tq), i32)):
+        assert tuple(t.shape) == shape and t.dtype == dt, (name, tuple(t.shape), shape, t.dtype)
+    assert idx.dtype == i32 and idx.dim() == 4 and tuple(idx.shape[:3]) == (B, Hq, Tq) and idx.shape[3] >= 1, tuple(idx.shape)
+
+
+def _cache_shapes(k16, v16, k4, ks, v4, vs, kmean, Bk: int) -> None:
+    B, Hkv, Nkv, D = k16.shape
+    assert k16.dtype == v16.dtype and k16.dtype in (torch.float16, torch.bfloat16) and v16.shape == k16.shape
+    u8 = torch.uint8
+    for name, t, shape, dt in (("k4", k4, (B, Hkv, Nkv, D // 2), u8), ("ks", ks, (B, Hkv, Nkv, D // 32), u8),
+                               ("v4", v4, (B, Hkv, Nkv // 64, D, 32), u8), ("vs", vs, (B, Hkv, Nkv // 32, D), u8),
+                               ("kmean", kmean, (B, Hkv, Nkv // Bk, D), torch.float32)):
+        assert tuple(t.shape) == shape and t.dtype == dt, (name, tuple(t.shape), shape, t.dtype)
+
+
 # ---- host helpers ----
 
 def row_budget(visible: int, budget: float, fixed_k: int = -1) -> int:
@@ -187,10 +213,12 @@ def thrift_attn_prefill(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq: int, Bk: 
                         out_dtype: Optional[torch.dtype] = None, lse: Optional[torch.Tensor] = None) -> torch.Tensor:
     for t in (q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt):
         _dev(t)
+    _prefill_shapes(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq)
     B, Hq, N, D = q.shape
     Hkv = k.shape[1]
     if out is None:
         out = torch.empty(B, Hq, N, D, dtype=out_dtype or q.dtype, device=q.device)
+    assert tuple(out.shape) == (B, Hq, N, D) and (lse is None or (tuple(lse.shape) == (B, Hq, N) and lse.dtype == torch.float32))
     kmax = idx.shape[-1]
     ws_bytes = lib().thrift_attn_prefill_workspace(B, Hq, Hkv, N, D, Bq, Bk, kmax)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=q.device) if ws_bytes else None
@@ -209,10 +237,12 @@ def thrift_attn_prefill_chunk(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq: int
     2 / 3: ascending order with the staging schedule fixed (see include/thrift.h)."""
     for t in (q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt):
         _dev(t)
+    _prefill_shapes(q, k, v, q4, qs, k4, ks, v4, vs, idx, cnt, Bq)
     B, Hq, Nq, D = q.shape
     Hkv, Nkv = k.shape[1], k.shape[2]
     if out is None:
         out = torch.empty(B, Hq, Nq, D, dtype=out_dtype or q.dtype, device=q.device)
+    assert tuple(out.shape) == (B, Hq, Nq, D) and (lse is None or (tuple(lse.shape) == (B, Hq, Nq) and lse.dtype == torch.float32))
     kmax = idx.shape[-1]
     _check(lib().thrift_attn_prefill_ordered(_ptr(q), _ptr(k), _ptr(v), _DT[q.dtype], _ptr(q4), _ptr(qs), _ptr(k4), _ptr(ks),
                                              _ptr(v4), _ptr(vs), _ptr(idx), _ptr(cnt), kmax, B, Hq, Hkv, Nq, int(q_block_offset),
@@ -232,10 +262,16 @@ def thrift_attn_decode(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budget: floa
                        group_shared: bool = False):
     for t in (q, k16, v16, k4, ks, v4, vs, kmean):
         _dev(t)
+    _cache_shapes(k16, v16, k4, ks, v4, vs, kmean, Bk)
     B, Hq, D = q.shape
     _, Hkv, Nkv, _ = k16.shape
+    assert q.dtype == k16.dtype and k16.shape[0] == B and k16.shape[3] == D
+    if seqlens is not None:
+        _dev(seqlens, torch.int32)
+        assert tuple(seqlens.shape) == (B,)
     if out is None:
         out = torch.empty(B, Hq, D, dtype=out_dtype or q.dtype, device=q.device)
+    assert tuple(out.shape) == (B, Hq, D)
     if workspace is None:
         workspace = torch.empty(max(decode_workspace_bytes(B, Hq, Hkv, Nkv, D, Bk, split_blocks), 16), dtype=torch.uint8,
                                 device=q.device)
@@ -265,8 +301,15 @@ def thrift_attn_decode_static(q, k16, v16, k4, ks, v4, vs, kmean, Bk: int, budge
     wants the selection back); neither this wrapper nor the C call allocates."""
     for t in (q, k16, v16, k4, ks, v4, vs, kmean, out):
         _dev(t)
+    _cache_shapes(k16, v16, k4, ks, v4, vs, kmean, Bk)
     B, Hq, D = q.shape
     _, Hkv, Nkv, _ = k16.shape
+    assert q.dtype == k16.dtype and k16.shape[0] == B and k16.shape[3] == D and tuple(out.shape) == (B, Hq, D)
+    if seqlens is not None:
+        _dev(seqlens, torch.int32)
+        assert tuple(seqlens.shape) == (B,)
+    if idx is not None:
+        assert idx.dtype == torch.int32 and tuple(idx.shape[:2]) == (B, Hq) and cnt is not None and tuple(cnt.shape) == (B, Hq)
     kmax = 0 if idx is None else idx.shape[-1]
     _check(lib().thrift_attn_decode_static(_ptr(q), _DT[q.dtype], _ptr(k16), _ptr(v16), _ptr(k4), _ptr(ks), _ptr(v4), _ptr(vs),
                                            _ptr(kmean), _ptr(seqlens), B, Hq, Hkv, Nkv, D, Bk, float(budget), int(fixed_k),
@@ -315,9 +358,12 @@ def thrift_kv_cache_append(k_new, v_new, seqlens, k16, v16, k4, ks, v4, vs, kmea
     _dev(seqlens, torch.int32)
     if new_lens is not None:
         _dev(new_lens, torch.int32)
-    assert k_new.shape == v_new.shape and k_new.dtype == k16.dtype == v16.dtype
+    assert k_new.shape == v_new.shape and k_new.dtype == v_new.dtype == k16.dtype == v16.dtype
+    _cache_shapes(k16, v16, k4, ks, v4, vs, kmean, Bk)
     B, Hkv, n_new, D = k_new.shape
     _, _, Nkv, _ = k16.shape
+    assert tuple(k16.shape[:2]) == (B, Hkv) and k16.shape[3] == D and tuple(seqlens.shape) == (B,)
+    assert new_lens is None or tuple(new_lens.shape) == (B,)
     _check(lib().thrift_kv_cache_append(_ptr(k_new), _ptr(v_new), _DT[k_new.dtype], n_new, _ptr(seqlens), _ptr(new_lens),
                                         _ptr(k16), _ptr(v16), _ptr(k4), _ptr(ks), _ptr(v4), _ptr(vs), _ptr(kmean),
                                         B, Hkv, Nkv, D, Bk, _stream()), "thrift_kv_cache_append")
@@ -378,6 +424,7 @@ def thrift_attention(q, k, v, causal: bool = True, Bq: int = 128, Bk: int = 64, 
         _dev(t)
     B, Hq, N, D = q.shape
     Hkv = k.shape[1]
+    assert q.dtype == k.dtype == v.dtype and k.shape == v.shape == (B, Hkv, N, D), (q.dtype, k.dtype, v.dtype, k.shape, v.shape)
     need = int(lib().thrift_attention_forward_workspace(B, Hq, Hkv, N, D, Bq, Bk, int(causal), float(budget), int(fixed_k)))
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)

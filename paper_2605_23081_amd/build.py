@@ -27,14 +27,23 @@ def scratch_in_loops(asm_text: str):
     walk and reloaded after it costs nothing.  The compiler's listing marks every basic block that belongs to a
     loop in the comment of its label line."""
     bad, kernel, in_loop = set(), None, False
+    kernels, blocks, loop_blocks = 0, 0, 0
     for line in asm_text.splitlines():
         t = line.strip()
         if t.startswith("_Z") and t.split(":")[0].isidentifier() and ":" in t:
             kernel, in_loop = t.split(":")[0], False
+            kernels += 1
         elif t.startswith(".LBB") or t.startswith("; %bb."):
             in_loop = "Loop" in t
+            blocks += 1
+            loop_blocks += in_loop
         elif t.startswith("scratch_") and in_loop and kernel:
             bad.add(kernel)
+    # The labels are the compiler's listing format, not a stable interface: a listing in which no kernel, no basic
+    # block or no loop annotation is recognised cannot be checked and must not pass for clean.
+    if kernels == 0 or blocks == 0 or loop_blocks == 0:
+        raise RuntimeError("the prefill kernel's listing has no recognisable kernel labels / basic blocks / loop annotations: "
+                           "the spill check cannot read this compiler's output")
     return sorted(bad)
 
 
@@ -44,15 +53,23 @@ def m0_outside_inline_asm(asm_text: str) -> int:
     The LDS DMA instruction takes its LDS base from M0, which the inline assembly sets without the compiler knowing.
     That is sound only while the compiler itself never keeps a value in M0 across those statements: the fused
     kernel's listing must mention M0 nowhere but between the ASMSTART / ASMEND markers."""
-    inside, count = False, 0
+    inside, count, statements, seen_inside = False, 0, 0, 0
     for line in asm_text.splitlines():
         t = line.strip()
         if t.startswith(";;#ASMSTART"):
             inside = True
+            statements += 1
         elif t.startswith(";;#ASMEND"):
             inside = False
-        elif not inside and not t.startswith(";") and "m0" in t.replace(",", " ").split():
-            count += 1
+        elif not t.startswith(";") and "m0" in t.replace(",", " ").split():
+            if inside:
+                seen_inside += 1
+            else:
+                count += 1
+    # the kernel does set M0 in its DMA statements: a listing in which that cannot be seen is in a format this check cannot read
+    if statements == 0 or seen_inside == 0:
+        raise RuntimeError("the prefill kernel's listing shows no inline-assembly markers around its M0 writes: "
+                           "the M0 check cannot read this compiler's output")
     return count
 
 

@@ -415,9 +415,14 @@ thrift_status thrift_attention_forward(const void* q, const void* k, const void*
   if (!q || !k || !v || !out) return THRIFT_ERR_NULL;
   if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
   if (!fused_shape_ok(B, Hq, Hkv, N, D, Bq, Bk)) return THRIFT_ERR_SHAPE;
+  if (tile_order < 0 || tile_order > 3) return THRIFT_ERR_SHAPE;          // before the first stage is enqueued
   if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
   const FusedLayout L = fused_layout(B, Hq, Hkv, N, Bq, Bk, causal, budget, fixed_k);
   if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & 255) != 0) return THRIFT_ERR_WORKSPACE;
+  // the grid-size limits of the stages, so that none of them can refuse after an earlier one has been enqueued
+  if ((long)B * Hq * L.Tq > 0x7fffffffL || (long)B * Hkv * L.Tk > 0x7fffffffL || (long)B * Hq * ((long)N / 64 + 1) > 0x7fffffffL)
+    return THRIFT_ERR_SHAPE;
+  if (thrift_status s0 = check_arch()) return s0;
   char* ws = (char*)workspace;
   float* qmean = (float*)(ws + L.qmean);
   float* kmean = (float*)(ws + L.kmean);
@@ -425,7 +430,7 @@ thrift_status thrift_attention_forward(const void* q, const void* k, const void*
   int32_t* cnt = (int32_t*)(ws + L.cnt);
   uint8_t *q4 = (uint8_t*)(ws + L.q4), *qs = (uint8_t*)(ws + L.qs), *k4 = (uint8_t*)(ws + L.k4), *ks = (uint8_t*)(ws + L.ks),
           *v4 = (uint8_t*)(ws + L.v4), *vs = (uint8_t*)(ws + L.vs);
-  // every stage validates its own arguments before it launches; the first failure ends the chain
+  // every stage validates its own arguments again before it launches (the checks above cover all of them)
   thrift_status s;
   if ((s = thrift_block_means(q, dt, B, Hq, N, D, Bq, qmean, stream)) != THRIFT_OK) return s;                 // Alg. 1 step 3
   if ((s = thrift_block_means(k, dt, B, Hkv, N, D, Bk, kmean, stream)) != THRIFT_OK) return s;

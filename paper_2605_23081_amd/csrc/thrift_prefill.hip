@@ -1,25 +1,25 @@
 // Fused mixed-precision flash attention for prefill (Algorithm 1 steps 4-23; Sec. 3.3).
 //
 // One workgroup = one (batch, query head, query block); wavefront w owns query rows 32w .. 32w+31 of
-// the block and keeps Q, the online-softmax state and the O^T accumulators in registers.  Key blocks are
-// visited in ascending order (the order of Alg. 1) and dispatched per tile to the scaled-FP4 or the
-// 16-bit MFMA path.
+// the block and keeps Q, the online-softmax state and the O^T accumulators in registers.  Two walks over
+// the key blocks are built, both dispatching per tile to the scaled-FP4 or the 16-bit MFMA path:
+//   ORDER 0  ascending block order, Alg. 1 as written (a second staging schedule, WIDE, serves high budgets);
+//   ORDER 1  the order of the kernel in Sec. 3.3: every 4-bit block first, then the promoted blocks with the
+//            16-bit query fragments in registers only for that phase.  This is the benchmarked walk.
 //
 // The kernel is bound by the vector ALU work of the softmax and the P quantiser (exp and the FP4
-// converter run at a third of the plain rate), and one wavefront can issue vector instructions at only
+// converter run at a quarter of the plain rate), and one wavefront can issue vector instructions at only
 // about half the rate its SIMD can execute them.  Everything is therefore sized for THREE workgroups per
 // CU (three wavefronts per SIMD): at most 168 vector registers and a third of the LDS per workgroup.
 //   * Every block is staged once into LDS for all wavefronts by LDS DMA (global loads that write LDS
 //     directly: no staging registers, no LDS write instructions), one block ahead of the arithmetic:
 //     MXFP4 codes + scales into one of two 8.5 KiB slots, the 16-bit K and V tiles of a block listed in
-//     the row's TopK set into one K and one V buffer.
-//   * One workgroup barrier per key block orders the traffic.  Two promoted blocks in a row share the
-//     16-bit buffers: the second K tile is fetched after the score phase of the first, the second V tile
-//     at the start of its own step, each behind one more barrier.
+//     the row's TopK set into 16 KiB tile buffers.
+//   * One workgroup barrier per 4-bit key block orders the traffic, two per promoted block.
 //
-// Differences from the kernel the paper sketches for Blackwell (Sec. 3.3): no two-phase split (4-bit
-// tiles first, 16-bit helper afterwards): ascending order keeps the result independent of the schedule
-// and identical to Alg. 1 as written.
+// Differences from the kernel the paper sketches for Blackwell (Sec. 3.3): MXFP4 instead of NVFP4, 32x32
+// MFMA tiles in transposed form (one query per lane column) instead of warp-level MMA tiles, LDS regions
+// per precision instead of one aliased region (three workgroups per CU are worth more than the aliasing).
 #include <type_traits>
 
 #include "thrift_launch.h"

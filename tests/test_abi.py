@@ -80,6 +80,15 @@ def test_validation_errors_come_before_any_launch():
                                                   C.c_float(0.0), fake, 1, None, kw.get("ws", fake), kw.get("wsb", 16), None)
     assert fwd(q=None) == NULL and fwd(dt=2) == DTYPE and fwd(Hkv=3) == SHAPE and fwd(N=0) == SHAPE and fwd(Bq=32) == SHAPE
     assert fwd(budget=1.5) == BUDGET and fwd(ws=None) == WORKSPACE and fwd(wsb=16) == WORKSPACE
+    # an unknown tile order is refused before the first stage of the chain is enqueued (it reaches only the last stage)
+    assert L.thrift_attention_forward(fake, fake, fake, 1, 1, 4, 2, 300, 128, 128, 64, 1, C.c_double(0.05), -1, 7, C.c_float(0.0),
+                                      fake, 1, None, fake, 1 << 30, None) == SHAPE
+    # the entry point without a workspace argument: sizes are checked against its static array first
+    sta = lambda **kw: L.thrift_attn_decode_static(fake, 0, fake, fake, fake, fake, fake, fake, fake, None, kw.get("B", 1), 4, 2,
+                                                   kw.get("N", 1024), 128, 64, C.c_double(0.05), -1, kw.get("split", 8), C.c_float(0.0),
+                                                   fake, 0, None, None, 0, None)
+    assert sta(split=0) == SHAPE and sta(N=1000) == SHAPE
+    assert sta(B=4096, N=131072, split=256) == WORKSPACE
     wsq = L.thrift_attention_forward_workspace
     assert wsq(1, 4, 2, 300, 128, 128, 64, 1, C.c_double(0.05), -1) > 300 * 128 * 6 // 2
     assert wsq(1, 4, 2, 300, 64, 128, 64, 1, C.c_double(0.05), -1) == 0 and wsq(1, 4, 2, 300, 128, 128, 64, 1, C.c_double(-1.0), -1) == 0
@@ -119,6 +128,17 @@ def test_spill_check_reads_the_compiler_listing():
         "\ts_endpgm",
     ])
     assert scratch_in_loops(listing) == ["_ZN6thrift3badEv"]
+
+
+def test_listing_checks_refuse_a_format_they_cannot_read():
+    """A listing without the labels the checks rely on must not pass for clean."""
+    from paper_2605_23081_amd.build import m0_outside_inline_asm, scratch_in_loops
+    for text in ("", "kernel_without_mangled_name:\n\tscratch_load_dword v1, off, off\n\ts_endpgm",
+                 "_ZN6thrift4walkEv:\n\tv_add_f32_e32 v0, v0, v1\n\ts_endpgm"):          # no basic blocks, no loop annotation
+        with pytest.raises(RuntimeError):
+            scratch_in_loops(text)
+    with pytest.raises(RuntimeError):
+        m0_outside_inline_asm("\ts_mov_b32 m0, s10\n\tglobal_load_lds_dwordx4 v1, s[2:3]")   # no inline-assembly markers
 
 
 def test_m0_check_reads_the_compiler_listing():
