@@ -447,3 +447,116 @@ def test_ragged_lengths_pins(oracle, N, Bq, causal):
             d4s = oracle.attn_thrift_decode(qlb, kb, vb, dt, None, None, 64, scale, sb, seqlens=np.array([N], np.int32),
                                             force_path=0, quantize_p=False)
             assert np.abs(d4s - d4).max() < 1e-10
+
+
+# ------------------------------------------------------------------ Alg. 1 step 19 as printed (NVFP4 study variant)
+
+def _e2m1_rne(y):
+    """Nearest value of the E2M1 grid, ties to the even code, magnitudes above 6 saturate (brute force over the grid)."""
+    a = np.abs(y)
+    out = np.empty_like(a)
+    for i, x in enumerate(a.ravel()):
+        d = np.abs(E2M1 - min(x, 6.0))
+        best = np.flatnonzero(d == d.min())
+        out.ravel()[i] = E2M1[best[0] if len(best) == 1 or best[0] % 2 == 0 else best[1]]
+    return np.sign(y) * out
+
+
+def _e4m3(x):
+    """Round to E4M3 with torch's float8 type (saturating at 448, which torch does not do by itself)."""
+    return float(torch.tensor(min(x, 448.0), dtype=torch.float64).to(torch.float32).to(torch.float8_e4m3fn).to(torch.float64))
+
+
+def _nvfp4_groups_np(x):
+    """E2M1 elements with one E4M3 scale (group maximum / 6) per 16 consecutive values of the last axis."""
+    flat = x.reshape(-1, 16)
+    out = np.zeros_like(flat)
+    for g, grp in enumerate(flat):
+        s = _e4m3(np.abs(grp).max() / 6.0)
+        if s > 0:
+            out[g] = _e2m1_rne(grp / s) * s
+    return out.reshape(x.shape)
+
+
+def _nvfp4_attention_np(qd, kd, vd, scale, Bk=64, p_level1=448.0 * 6.0):
+    """Alg. 1 steps 15-20 on the 4-bit path, written out in numpy for non-causal inputs that are already
+    quantised-dequantised: per key block, scores, running maximum, P = exp(S - m), row sum from the unquantised P,
+    then the two-level quantisation of P of step 19 (s1 = rowmax(P) / (448 * 6), NVFP4 groups of 16 keys on P / s1)
+    and O += s1 * P_hat V."""
+    Nq, D = qd.shape
+    m = np.full(Nq, -np.inf); l = np.zeros(Nq); O = np.zeros((Nq, D))
+    for j in range(kd.shape[0] // Bk):
+        S = (qd @ kd[j * Bk:(j + 1) * Bk].T) * scale
+        m_new = np.maximum(m, S.max(axis=1))
+        alpha = np.where(np.isinf(m), 0.0, np.exp(m - m_new))
+        P = np.exp(S - m_new[:, None])
+        l = alpha * l + P.sum(axis=1)
+        s1 = P.max(axis=1) / p_level1
+        Ph = _nvfp4_groups_np(P / s1[:, None]) * s1[:, None]
+        O = alpha[:, None] * O + Ph @ vd[j * Bk:(j + 1) * Bk]
+        m = m_new
+    return O / l[:, None]
+
+
+def test_two_level_p_quantisation_of_alg1_step19_against_numpy(oracle):
+    """The NVFP4 branch of the oracle's tile step against an independent numpy version of Alg. 1 step 19, element by
+    element, on two key blocks (so that the running maximum, the rescale and the level-1 scale all matter).  The E4M3
+    scale rounding comes from torch's float8 type, the E2M1 rounding from a brute-force search of the grid.  A level-1
+    scale of rowmax(P)/448 instead of rowmax(P)/(448*6) must NOT reproduce the oracle."""
+    w = W.scaled(W.TINY, N=128, Hq=2, Hkv=1, Bq=64, Bk=64, seed=9, planted_blocks=1, sink_tokens=0)
+    q, k, v, _, _ = W.make_prefill(w)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    units = _all_units(1, w.Hq, w.N // 64)
+    got = oracle.attn_thrift_prefill(qb, kb, vb, dt, None, None, 64, 64, False, scale, units, force_path=0, fmt=1)
+    got = got.reshape(w.Hq, w.N, w.D)
+    kd = _nvfp4_groups_np(k.double().numpy()[0, 0])
+    vd = _nvfp4_groups_np(np.ascontiguousarray(v.double().numpy()[0, 0].T)).T          # groups of 16 along the tokens
+    worst_wrong = 0.0
+    for h in range(w.Hq):
+        qd = _nvfp4_groups_np(q.double().numpy()[0, h])
+        want = _nvfp4_attention_np(qd, kd, vd, scale)
+        assert np.abs(got[h] - want).max() < 1e-12
+        wrong = _nvfp4_attention_np(qd, kd, vd, scale, p_level1=448.0)
+        worst_wrong = max(worst_wrong, np.abs(got[h] - wrong).max())
+    assert worst_wrong > 1e-4          # the factor 6 of the level-1 scale is visible: dropping it changes the result
+
+
+# ------------------------------------------------------------------ Eq. (4)
+
+def test_error_bound_rhs_against_direct_evaluation_and_first_order_inequality(oracle):
+    """Eq. (4): RHS = sum_j |eps_j| p_j ||v_j - o||, evaluated directly in numpy on one row (eps from the dequantised
+    MXFP4 query and keys), must equal the oracle's value; and the bound must hold to first order: with the exact
+    values and scores perturbed by eps, ||o' - o|| <= RHS up to a second-order term, and o' - o equals Eq. (3)'s
+    sum_j eps_j p_j (v_j - o) to the same order."""
+    w = W.scaled(W.TINY, N=512, Hq=1, Hkv=1, Bq=64, Bk=64, seed=4, planted_blocks=1, sink_tokens=0, outlier_channels=0,
+                 query_mean_gain=0.0)
+    q, k, v, _, _ = W.make_prefill(w)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(w.D)
+    c, s = oracle.quantize_mxfp4(qb, dt, 0); qq = oracle.dequantize_mxfp4(c, s, 0)[0, 0]
+    c, s = oracle.quantize_mxfp4(kb, dt, 0); kq = oracle.dequantize_mxfp4(c, s, 0)[0, 0]
+    qd, kd, vd = q.double().numpy()[0, 0], k.double().numpy()[0, 0], v.double().numpy()[0, 0]
+    for t in (70, 300, 511):
+        n = t + 1
+        sc = (kd[:n] @ qd[t]) * scale
+        eps = (kq[:n] @ qq[t]) * scale - sc
+        p = np.exp(sc - sc.max()); p /= p.sum()
+        o = p @ vd[:n]
+        dist = np.linalg.norm(vd[:n] - o, axis=1)
+        terms = np.abs(eps) * p * dist
+        total, per = oracle.error_bound_rhs(qb[0, 0, t], kb[0, 0], vb[0, 0], dt, 64, n, scale)
+        assert abs(total - terms.sum()) <= 1e-12 * terms.sum()
+        want_per = np.zeros(w.N // 64)
+        np.add.at(want_per, np.arange(n) // 64, terms)
+        assert np.abs(per - want_per).max() <= 1e-12 * terms.sum()
+        # first order: shrink the perturbation until the second-order term is small, then compare
+        for shrink in (1.0, 0.1):
+            e = eps * shrink
+            p2 = np.exp(sc + e - (sc + e).max()); p2 /= p2.sum()
+            delta = p2 @ vd[:n] - o
+            first_order = (e * p) @ (vd[:n] - o)
+            rhs = terms.sum() * shrink
+            second = np.abs(e).max() * rhs * 4.0                     # generous bound on the neglected term
+            assert np.linalg.norm(delta - first_order) <= second
+            assert np.linalg.norm(delta) <= rhs + second
