@@ -47,7 +47,16 @@
 extern "C" {
 #endif
 
-typedef enum {
+/* Callers in any language pass these as plain ints.  In C++ an enumeration without a fixed underlying type may only
+ * hold values in the range of its enumerators (loading anything else is undefined behaviour), and the library, which
+ * is C++, must be able to receive an invalid code in order to refuse it: hence the fixed underlying type there. */
+#ifdef __cplusplus
+#define THRIFT_ENUM_INT : int
+#else
+#define THRIFT_ENUM_INT
+#endif
+
+typedef enum THRIFT_ENUM_INT {
   THRIFT_OK = 0,
   THRIFT_ERR_NULL = 1,      /* a required pointer is NULL */
   THRIFT_ERR_SHAPE = 2,     /* unsupported or inconsistent sizes */
@@ -58,7 +67,7 @@ typedef enum {
   THRIFT_ERR_LAUNCH = 7     /* the HIP runtime refused a launch */
 } thrift_status;
 
-typedef enum { THRIFT_F16 = 0, THRIFT_BF16 = 1, THRIFT_F32 = 2 /* outputs only */ } thrift_dtype;
+typedef enum THRIFT_ENUM_INT { THRIFT_F16 = 0, THRIFT_BF16 = 1, THRIFT_F32 = 2 /* outputs only */ } thrift_dtype;
 
 /* Host: static string for a status code. */
 const char* thrift_status_string(thrift_status s);
@@ -129,7 +138,7 @@ thrift_status thrift_select_topk_shared(const float* qmean, const float* kmean, 
  *   THRIFT_SELECT_DIAGONAL  the k_i visible blocks closest to the causal diagonal (the largest ids).
  * The result feeds thrift_attn_prefill like any other selection.  Unknown selector: THRIFT_ERR_SHAPE.
  */
-typedef enum { THRIFT_SELECT_RANDOM = 1, THRIFT_SELECT_DIAGONAL = 2 } thrift_selector;
+typedef enum THRIFT_ENUM_INT { THRIFT_SELECT_RANDOM = 1, THRIFT_SELECT_DIAGONAL = 2 } thrift_selector;
 thrift_status thrift_select_ablation(int selector, uint64_t seed, int B, int Hq, int Tq, int Tk, int Bq, int Bk,
                                      int causal, double budget, int fixed_k, int q_block_offset,
                                      int32_t* idx, int32_t* cnt, int kmax, void* stream);

@@ -43,6 +43,15 @@ thrift_status after_launch() { return hipGetLastError() == hipSuccess ? THRIFT_O
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// True when a, b, c are positive and a * b * c fits a 32-bit signed integer (grid sizes and row counts); the
+// product is never formed when it could overflow.
+bool fits_int(long a, long b, long c = 1) {
+  const long lim = 0x7fffffffL;
+  if (a <= 0 || b <= 0 || c <= 0 || a > lim || b > lim || c > lim) return false;
+  if (a > lim / b) return false;
+  return a * b <= lim / c;
+}
+
 constexpr int kMaxDevices = 64;
 std::mutex scratch_mutex;
 void* scratch_address[kMaxDevices] = {nullptr};
@@ -177,8 +186,7 @@ thrift_status thrift_block_means(const void* x, thrift_dtype dt, int B, int H, i
   if (!x || !means) return THRIFT_ERR_NULL;
   if (!is16(dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || H <= 0 || N <= 0 || D != kHeadDim || block <= 0) return THRIFT_ERR_SHAPE;
-  const long n_blocks = (long)B * H * (((long)N + block - 1) / block);
-  if (n_blocks > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (!fits_int(B, H, ((long)N + block - 1) / block)) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   launch_block_means(x, dt, (long)B * H, N, block, means, (hipStream_t)stream);
   return after_launch();
@@ -193,7 +201,7 @@ static thrift_status select_topk_impl(const float* qmean, const float* kmean, in
     return THRIFT_ERR_SHAPE;
   if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
   if (kmax < thrift_select_kmax(Tq, Tk, Bq, Bk, causal, budget, fixed_k, q_block_offset)) return THRIFT_ERR_BUDGET;
-  if ((long)B * Hkv * (((long)Tq * (Hq / Hkv) + 3) / 4) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (!fits_int(B, Hq, Tq)) return THRIFT_ERR_SHAPE;                 // rows; the grid, one workgroup per 4 rows of a KV head, is smaller
   if (thrift_status s = check_arch()) return s;
   SelectArgs a;
   a.shared = shared;
@@ -224,10 +232,9 @@ thrift_status thrift_select_ablation(int selector, uint64_t seed, int B, int Hq,
   if (selector != THRIFT_SELECT_RANDOM && selector != THRIFT_SELECT_DIAGONAL) return THRIFT_ERR_SHAPE;
   if (B <= 0 || Hq <= 0 || Tq <= 0 || Tk <= 0 || Tk > kMaxKeyBlocks || Bq <= 0 || Bk <= 0 || q_block_offset < 0 || kmax <= 0)
     return THRIFT_ERR_SHAPE;
-  if ((long)B * Hq * Tq > 0x7fffffffL) return THRIFT_ERR_SHAPE;    // the row index is the high word of the random counter
+  if (!fits_int(B, Hq, Tq)) return THRIFT_ERR_SHAPE;               // the row index is the high word of the random counter
   if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
   if (kmax < thrift_select_kmax(Tq, Tk, Bq, Bk, causal, budget, fixed_k, q_block_offset)) return THRIFT_ERR_BUDGET;
-  if ((long)B * Hq * (((long)Tq + 3) / 4) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   SelectArgs a;
   a.qmean = nullptr; a.kmean = nullptr; a.idx = idx; a.cnt = cnt;
@@ -243,9 +250,9 @@ thrift_status thrift_quantize_mxfp4(const void* x, thrift_dtype dt, int B, int H
   if (!x || !codes || !scales) return THRIFT_ERR_NULL;
   if (!is16(dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || H <= 0 || N <= 0 || D != kHeadDim || (axis != 0 && axis != 1)) return THRIFT_ERR_SHAPE;
+  // axis 1: one workgroup per 64-token block; axis 0: one thread per 32-group, 256 threads per workgroup
+  if (!fits_int(B, H, ((long)N + 63) / 64)) return THRIFT_ERR_SHAPE;
   const long bh = (long)B * H;
-  if (axis == 1 && bh * (((long)N + 63) / 64) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
-  if (axis == 0 && ((size_t)bh * N * (kHeadDim / 32) + 255) / 256 > 0x7fffffffUL) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   launch_quantize(x, dt, bh, N, axis, codes, scales, (hipStream_t)stream);
   return after_launch();
@@ -270,7 +277,7 @@ thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const vo
     return THRIFT_ERR_SHAPE;
   // causal: the chunk must lie inside the sequence (its last query at or before the last key)
   if (causal && ((long)q_block_offset * Bq + Nq > (long)Nkv)) return THRIFT_ERR_SHAPE;
-  if ((long)B * Hq * ((Nq + Bq - 1) / Bq) > 0x7fffffffL) return THRIFT_ERR_SHAPE;
+  if (!fits_int(B, Hq, (Nq + Bq - 1) / Bq)) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   PrefillArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
@@ -307,7 +314,8 @@ thrift_status thrift_attn_prefill(const void* q, const void* k, const void* v, t
 }
 
 size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int Bk, int split_blocks) {
-  if (B <= 0 || Hq <= 0 || Hkv <= 0 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock || split_blocks <= 0 || Nkv % Bk != 0)
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock || split_blocks <= 0 || Nkv % Bk != 0 ||
+      Nkv / Bk > kMaxKeyBlocks || !fits_int(B, Hq, 64))
     return 0;
   return decode_layout(B, Hq, Nkv, Bk, split_blocks).total;
 }
@@ -322,7 +330,7 @@ static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void
   if (!q || !k16 || !v16 || !k4 || !ks || !v4 || !vs || !kmean || !out) return THRIFT_ERR_NULL;
   if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Hq / Hkv > 32 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock ||
-      Nkv % Bk != 0 || Nkv / Bk > kMaxKeyBlocks || split_blocks <= 0 || split_blocks % 4 != 0)
+      Nkv % Bk != 0 || Nkv / Bk > kMaxKeyBlocks || split_blocks <= 0 || split_blocks % 4 != 0 || !fits_int(B, Hq, 64))
     return THRIFT_ERR_SHAPE;
   if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
   const int Tk = Nkv / Bk;
@@ -398,7 +406,7 @@ thrift_status thrift_attn_decode_static(const void* q, thrift_dtype dt, const vo
 
 static bool fused_shape_ok(int B, int Hq, int Hkv, int N, int D, int Bq, int Bk) {
   return B > 0 && Hq > 0 && Hkv > 0 && Hq % Hkv == 0 && N > 0 && D == kHeadDim && Bk == kKeyBlock && (Bq == 64 || Bq == 128) &&
-         (N + Bk - 1) / Bk <= kMaxKeyBlocks;
+         (N + Bk - 1) / Bk <= kMaxKeyBlocks && fits_int(B, Hq, (long)N / 64 + 1);
 }
 
 size_t thrift_attention_forward_workspace(int B, int Hq, int Hkv, int N, int D, int Bq, int Bk, int causal, double budget, int fixed_k) {
@@ -420,8 +428,7 @@ thrift_status thrift_attention_forward(const void* q, const void* k, const void*
   const FusedLayout L = fused_layout(B, Hq, Hkv, N, Bq, Bk, causal, budget, fixed_k);
   if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & 255) != 0) return THRIFT_ERR_WORKSPACE;
   // the grid-size limits of the stages, so that none of them can refuse after an earlier one has been enqueued
-  if ((long)B * Hq * L.Tq > 0x7fffffffL || (long)B * Hkv * L.Tk > 0x7fffffffL || (long)B * Hq * ((long)N / 64 + 1) > 0x7fffffffL)
-    return THRIFT_ERR_SHAPE;
+  if (!fits_int(B, Hq, (long)N / 64 + 1) || !fits_int(B, Hkv, L.Tk)) return THRIFT_ERR_SHAPE;
   if (thrift_status s0 = check_arch()) return s0;
   char* ws = (char*)workspace;
   float* qmean = (float*)(ws + L.qmean);
