@@ -257,6 +257,30 @@ def test_decode_parity(T, oracle, budget):
     assert err <= (TOL16 if budget == 1.0 else TOLMIX)
 
 
+def test_decode_against_the_partition_size_as_stated(T, oracle):
+    """split_blocks names the key blocks per partition.  The kernel evaluates a partition as four consecutive quarters
+    (exact agreement with the oracle at that granularity is what the other decode tests check); against the oracle with
+    one recurrence per stated partition the result differs only by where the 4-bit rounding of P restarts, and must
+    meet the mixed-output bar."""
+    wl = W.scaled(W.DECODE_131K, B=2, N=8192, Hq=8, Hkv=2)
+    q, k, v = W.make_decode(wl)
+    qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
+    scale = 1 / math.sqrt(wl.D)
+    km = oracle.block_means(kb, dt, wl.Bk)
+    qm = q.float().numpy().reshape(wl.B, wl.Hq, 1, wl.D)
+    kg, vg = k.cuda(), v.cuda()
+    k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    kmean = T.thrift_block_means(kg, wl.Bk)
+    for split in (32, 128):
+        idx_r, cnt_r = oracle.select_topk(qm, km, 1, wl.Bk, False, 0.05)
+        idx_r, cnt_r = idx_r[:, :, 0], cnt_r[:, :, 0]
+        got = to_np(T.thrift_attn_decode(q.cuda(), kg, vg, k4, ks, v4, vs, kmean, wl.Bk, 0.05, split_blocks=split, out_dtype=torch.float32))
+        stated = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, scale, split)
+        err = np.abs(got - stated).max()
+        _say(f"decode split_blocks={split}: max abs err against the oracle at {split} blocks per partition {err:.3e}")
+        assert err <= TOLMIX
+
+
 def test_decode_variants(T, oracle):
     _say("decode bf16, group of 1, ragged partition, seqlens, fixed_k")
     wl = W.scaled(W.DECODE_131K, B=2, N=2560, Hq=4, Hkv=4, dtype="bf16")
