@@ -339,6 +339,25 @@ thrift_status thrift_kv_cache_append(const void* k_new, const void* v_new, thrif
                                      void* k16, void* v16, uint8_t* k4, uint8_t* ks, uint8_t* v4, uint8_t* vs, float* kmean,
                                      int B, int Hkv, int Nkv, int D, int Bk, void* stream);
 
+/*
+ * Measurement helper (not a step of the method): one launch of a microbenchmark of a hardware rate that the
+ * roofline figures of the attention kernels are priced against.  The caller times the launch (events on `stream`)
+ * and divides *work by the duration.
+ *   THRIFT_PEAK_MFMA_MXFP4    scaled-FP4 32x32x64 matrix instructions back to back        *work = flops
+ *   THRIFT_PEAK_MFMA_16       16-bit 32x32x16 matrix instructions (dt: fp16 or bf16)      *work = flops
+ *   THRIFT_PEAK_HBM_READ      one streaming read of `buffer` (use >= 1 GiB)                *work = bytes read
+ *   THRIFT_PEAK_VALU_SOFTMAX  the vector-ALU part of one 4-bit 32-query x 64-key wave-tile of the fused kernel
+ *                             (online-softmax update + P quantiser, no matrix instructions, no staging), at the
+ *                             fused kernel's occupancy                                    *work = wave-tiles
+ *   THRIFT_PEAK_TILE_MIX      the same plus the tile's eight matrix instructions           *work = wave-tiles
+ * buffer (device): at least 1 MiB (scratch for results; for THRIFT_PEAK_HBM_READ the data that is read, whatever it
+ * holds; its last 64 KiB are not read).  iters >= 1: loop trips per wavefront (ignored by the HBM probe).
+ * Unknown kind, iters < 1 or a buffer below 1 MiB: THRIFT_ERR_SHAPE.
+ */
+typedef enum THRIFT_ENUM_INT { THRIFT_PEAK_MFMA_MXFP4 = 0, THRIFT_PEAK_MFMA_16 = 1, THRIFT_PEAK_HBM_READ = 2,
+                               THRIFT_PEAK_VALU_SOFTMAX = 3, THRIFT_PEAK_TILE_MIX = 4 } thrift_peak_kind;
+thrift_status thrift_peak_probe(int kind, thrift_dtype dt, int iters, void* buffer, size_t bytes, double* work, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

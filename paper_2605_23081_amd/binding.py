@@ -25,7 +25,7 @@ EXPORTS = (
     "thrift_attn_prefill_workspace", "thrift_attn_prefill", "thrift_attn_prefill_chunk", "thrift_attn_prefill_ordered",
     "thrift_attn_decode_workspace", "thrift_attn_decode", "thrift_attn_decode_shared", "thrift_attn_decode_static",
     "thrift_kv_cache_append",
-    "thrift_attention_forward_workspace", "thrift_attention_forward",
+    "thrift_attention_forward_workspace", "thrift_attention_forward", "thrift_peak_probe",
 )
 
 _lib = None
@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
         L.thrift_attention_forward_workspace.restype = sz
         L.thrift_attention_forward_workspace.argtypes = [i, i, i, i, i, i, i, i, d, i]
         L.thrift_attention_forward.argtypes = [p, p, p, i, i, i, i, i, i, i, i, i, d, i, i, f, p, i, p, p, sz, p]
+        L.thrift_peak_probe.argtypes = [i, i, i, p, sz, C.POINTER(C.c_double), p]
         _lib = L
     return _lib
 
@@ -367,6 +368,19 @@ def thrift_kv_cache_append(k_new, v_new, seqlens, k16, v16, k4, ks, v4, vs, kmea
     _check(lib().thrift_kv_cache_append(_ptr(k_new), _ptr(v_new), _DT[k_new.dtype], n_new, _ptr(seqlens), _ptr(new_lens),
                                         _ptr(k16), _ptr(v16), _ptr(k4), _ptr(ks), _ptr(v4), _ptr(vs), _ptr(kmean),
                                         B, Hkv, Nkv, D, Bk, _stream()), "thrift_kv_cache_append")
+
+
+PEAK_MFMA_MXFP4, PEAK_MFMA_16, PEAK_HBM_READ, PEAK_VALU_SOFTMAX, PEAK_TILE_MIX = range(5)
+
+
+def thrift_peak_probe(kind: int, buffer: torch.Tensor, iters: int = 2000, dtype: torch.dtype = torch.bfloat16) -> float:
+    """Enqueue one measurement microbenchmark (see include/thrift.h) on the current stream; returns the work of the
+    launch (flops, bytes or wave-tiles).  The caller times it."""
+    _dev(buffer, torch.uint8)
+    work = C.c_double(0.0)
+    _check(lib().thrift_peak_probe(int(kind), _DT[dtype], int(iters), _ptr(buffer), buffer.numel(), C.byref(work), _stream()),
+           "thrift_peak_probe")
+    return float(work.value)
 
 
 # ---- Alg. 1 end to end: the user-level form of the paper's signature ----

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libthrift_hip.so")
-SOURCES = ["thrift_api.hip", "thrift_prepass.hip", "thrift_prefill.hip", "thrift_decode.hip", "thrift_cache.hip"]
+SOURCES = ["thrift_api.hip", "thrift_prepass.hip", "thrift_prefill.hip", "thrift_decode.hip", "thrift_cache.hip", "thrift_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # NaN inputs are outside the contract (include/thrift.h); without this every maximum of matrix-unit results
          # is preceded by instructions that only quiet signalling NaNs

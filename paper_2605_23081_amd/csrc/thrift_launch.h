@@ -89,4 +89,7 @@ struct CacheAppendArgs {
 };
 void launch_cache_append(const CacheAppendArgs& a, thrift_dtype dt, hipStream_t st);
 
+// measurement microbenchmarks (thrift_peak_probe): returns the work of the launch, 0 for an unknown kind
+double launch_peak_probe(int kind, thrift_dtype dt, int iters, void* buffer, size_t bytes, hipStream_t st);
+
 }  // namespace thrift

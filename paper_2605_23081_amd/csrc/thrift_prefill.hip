@@ -38,32 +38,6 @@ constexpr int kWideSlot = 2 * kTile16;                       // 32768
 constexpr int kLdsPrefillWide = 2 * kWideSlot;               // 65536: two workgroups per CU
 constexpr int kWidePercent = 15;                             // list length / key blocks (in %) from which the wide schedule is used
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
-// load (a full fence), which would wait for the tiles in flight at every key block; here only this
-// wavefront's LDS reads must have completed before the rendezvous.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
-// Wait until at most N of this wavefront's global loads (LDS DMA included) are still in flight.
-template <int N>
-__device__ __forceinline__ void vm_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
-typedef __attribute__((address_space(3))) void* lds_void_ptr;
-__device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)(p); }
-
-// LDS DMA: the 64 lanes fetch 16 (4) bytes each from base + off and the hardware writes them to the
-// 1 KiB (256 B) of consecutive LDS that starts at lds_base, lane l at lds_base + 16 l (4 l).  base and
-// lds_base are wavefront-uniform.  The instruction takes its LDS base from M0, which each statement sets
-// itself.  M0 is a reserved register for the compiler (it cannot be named as a clobber): it never keeps a
-// value there across statements and loads it right before the few instructions of its own that read it; the
-// build additionally checks that the kernel's listing mentions M0 only inside these statements.
-// Completion is counted by vmcnt like any global load.
-__device__ __forceinline__ void dma_b128(const void* base, uint32_t off, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
-}
-__device__ __forceinline__ void dma_b32(const void* base, uint32_t off, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
-}
-
 template <typename T, int NW, int ORDER, int WIDE>
 __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillArgs a) {
   constexpr int KF = 4 / NW;                 // 1 KiB fragments of a 4-bit K (and of a V) tile per wavefront

@@ -45,6 +45,34 @@ __device__ __forceinline__ int key_of_row(int rho, int t) {
 
 __device__ __forceinline__ v8i widen(v4i x) { return __builtin_shufflevector(x, x, 0, 1, 2, 3, -1, -1, -1, -1); }
 
+// ---- staging primitives shared by the prefill and the decode kernels ----
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global
+// load (a full fence), which would wait for the tiles in flight at every key block; here only this
+// wavefront's LDS reads must have completed before the rendezvous.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Wait until at most N of this wavefront's global loads (LDS DMA included) are still in flight.
+template <int N>
+__device__ __forceinline__ void vm_wait() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+__device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)(lds_void_ptr)(p); }
+
+// LDS DMA: the 64 lanes fetch 16 (4) bytes each from base + off and the hardware writes them to the
+// 1 KiB (256 B) of consecutive LDS that starts at lds_base, lane l at lds_base + 16 l (4 l).  base and
+// lds_base are wavefront-uniform.  The instruction takes its LDS base from M0, which each statement sets
+// itself.  M0 is a reserved register for the compiler (it cannot be named as a clobber): it never keeps a
+// value there across statements and loads it right before the few instructions of its own that read it; the
+// build additionally checks that the kernel's listing mentions M0 only inside these statements.
+// Completion is counted by vmcnt like any global load.
+__device__ __forceinline__ void dma_b128(const void* base, uint32_t off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void dma_b32(const void* base, uint32_t off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+}
+
 struct RowState {
   float m;      // running maximum of the raw (unscaled) scores of this lane's query
   float l;      // this lane's partial row sum (the two halves of a query add up at the end)
@@ -189,9 +217,8 @@ __device__ __forceinline__ void rescale(v16f (&o)[4], bool grew, float alpha) {
 // lane's V^T fragments (channel 32n + r, tokens 32*half .. +31).  pb: the E8M0 byte of the lane's P group
 // (softmax_update).  The V scale bytes come either packed
 // in one register (PACKED: byte n of vs0) or one per register (byte 0 of vs0..vs3).
-template <bool PACKED>
-__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], uint32_t pb, uint32_t vs0, uint32_t vs1, uint32_t vs2,
-                                            uint32_t vs3, v4i v0, v4i v1, v4i v2, v4i v3, v16f (&o)[4]) {
+// Alg. 1 step 19: the lane's 32 probabilities as one MXFP4 group, 16 code bytes in MFMA operand order.
+__device__ __forceinline__ v4i quantize_p_group(const v16f (&p)[2], uint32_t pb) {
   const float pscale = __uint_as_float(pb << 23);              // pb: E8M0 byte of the group, >= 1 (a normal float)
   v4i pq;
 #pragma unroll
@@ -205,7 +232,13 @@ __device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], uint32_t pb, uin
     o32 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(o32, p[t][i0 + 6], p[t][i0 + 7], pscale, 3);
     pq[w] = (int)o32;
   }
-  const v8i pb8 = widen(pq);
+  return pq;
+}
+
+template <bool PACKED>
+__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], uint32_t pb, uint32_t vs0, uint32_t vs1, uint32_t vs2,
+                                            uint32_t vs3, v4i v0, v4i v1, v4i v2, v4i v3, v16f (&o)[4]) {
+  const v8i pb8 = widen(quantize_p_group(p, pb));
   if (PACKED) {
     o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v0), pb8, o[0], 4, 4, 0, vs0, 0, pb);
     o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v1), pb8, o[1], 4, 4, 1, vs0, 0, pb);
