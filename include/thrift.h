@@ -269,11 +269,9 @@ size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int 
  *     been quantised from those tokens alone (what thrift_kv_cache_append, or the pre-pass on a tensor of that
  *     length, produces).  Cache contents past that block are never read.  A sequence of length 0 yields zeros.
  *     Split-K: the full key blocks are cut into the partitions; a partly filled last block is a partition of its own.
- *   split_blocks: key blocks per workgroup (> 0, a multiple of 4).  The four wavefronts of a workgroup each run
- *     Alg. 1 over a contiguous quarter and write one partial, so the recurrence (and with it the rounding of P on the
- *     4-bit path, which follows the running maximum) restarts every split_blocks / 4 key blocks: the result equals
- *     split-K with partitions of split_blocks / 4 blocks merged by log-sum-exp.  In exact arithmetic the cut points
- *     do not matter.
+ *   split_blocks: key blocks per partition (> 0): each (query head, partition) is one recurrence of Alg. 1 over the
+ *     partition's key blocks in ascending order; the rounding of P on the 4-bit path follows the running maximum, so
+ *     the result depends on the partition size at the level of the quantisation noise (in exact arithmetic it does not)
  *   out [B,Hq,D] in out_dt
  *   idx_out (nullable) [B,Hq,kmax_out], cnt_out (nullable) [B,Hq]: the selection that was used
  *     (kmax_out >= thrift_select_kmax(1, Nkv/Bk, 1, Bk, 0, budget, fixed_k, 0))

@@ -10,6 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libthrift_hip.so")
 SOURCES = ["thrift_api.hip", "thrift_prepass.hip", "thrift_prefill.hip", "thrift_decode.hip", "thrift_cache.hip", "thrift_probe.hip"]
+DMA_SOURCES = ["thrift_prefill.hip", "thrift_decode.hip"]      # kernels whose inline assembly sets M0 and keeps DMA in flight
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # NaN inputs are outside the contract (include/thrift.h); without this every maximum of matrix-unit results
          # is preceded by instructions that only quiet signalling NaNs
@@ -81,10 +82,12 @@ def build(verbose: bool = False, extra=()):
         cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
-    # the device listing of the fused kernel, for the spill check (runs beside the object builds)
-    listing = os.path.join(CSRC, "thrift_prefill.gfx950.s")
-    lcmd = ["hipcc", *FLAGS, *extra, "-S", "--cuda-device-only", os.path.join(CSRC, "thrift_prefill.hip"), "-o", listing]
-    lproc = subprocess.Popen(lcmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    # the device listings of the kernels that stage by LDS DMA, for the spill and M0 checks (run beside the object builds)
+    listings = []
+    for src in DMA_SOURCES:
+        listing = os.path.join(CSRC, src.replace(".hip", ".gfx950.s"))
+        lcmd = ["hipcc", *FLAGS, *extra, "-S", "--cuda-device-only", os.path.join(CSRC, src), "-o", listing]
+        listings.append((src, listing, lcmd, subprocess.Popen(lcmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for cmd, p in procs:
         out, _ = p.communicate()
         out = "\n".join(l for l in out.splitlines() if "not a recognized feature for this target" not in l)
@@ -93,18 +96,19 @@ def build(verbose: bool = False, extra=()):
             raise RuntimeError("hipcc failed: " + " ".join(cmd))
         if verbose and out.strip():
             print(out)
-    lout, _ = lproc.communicate()
-    if lproc.returncode != 0:
-        sys.stderr.write(lout + "\n")
-        raise RuntimeError("hipcc failed: " + " ".join(lcmd))
-    with open(listing) as f:
-        text = f.read()
-    os.remove(listing)
-    spilling = scratch_in_loops(text)
-    if spilling:
-        raise RuntimeError("prefill kernel reloads spilled registers inside a loop: " + ", ".join(spilling))
-    if m0_outside_inline_asm(text):
-        raise RuntimeError("the compiler uses M0 in the prefill kernel: the LDS DMA statements would clobber it")
+    for src, listing, lcmd, lproc in listings:
+        lout, _ = lproc.communicate()
+        if lproc.returncode != 0:
+            sys.stderr.write(lout + "\n")
+            raise RuntimeError("hipcc failed: " + " ".join(lcmd))
+        with open(listing) as f:
+            text = f.read()
+        os.remove(listing)
+        spilling = scratch_in_loops(text)
+        if spilling:
+            raise RuntimeError(f"{src}: spilled registers are reloaded inside a loop: " + ", ".join(spilling))
+        if m0_outside_inline_asm(text):
+            raise RuntimeError(f"{src}: the compiler uses M0: the LDS DMA statements would clobber it")
     cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     subprocess.run(cmd, check=True)
     return LIB

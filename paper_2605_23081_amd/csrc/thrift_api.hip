@@ -82,7 +82,7 @@ DecodeLayout decode_layout(int B, int Hq, int Nkv, int Bk, int split_blocks) {
   DecodeLayout L;
   const int Tk = Nkv / Bk;
   L.nsplit = (Tk + split_blocks - 1) / split_blocks;
-  L.nparts = L.nsplit * 4 + 1;                   // one partial per wavefront of a partition's workgroup + one for a partly filled last block
+  L.nparts = L.nsplit + 1;                       // one partial per partition + one for a partly filled last block
   L.words = (Tk + 63) / 64;
   size_t off = 0;
   L.keys = off; off += align256((size_t)B * Hq * Tk * sizeof(uint64_t));
@@ -330,7 +330,7 @@ static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void
   if (!q || !k16 || !v16 || !k4 || !ks || !v4 || !vs || !kmean || !out) return THRIFT_ERR_NULL;
   if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Hq / Hkv > 32 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock ||
-      Nkv % Bk != 0 || Nkv / Bk > kMaxKeyBlocks || split_blocks <= 0 || split_blocks % 4 != 0 || !fits_int(B, Hq, 64))
+      Nkv % Bk != 0 || Nkv / Bk > kMaxKeyBlocks || split_blocks <= 0 || !fits_int(B, Hq, 64))
     return THRIFT_ERR_SHAPE;
   if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
   const int Tk = Nkv / Bk;

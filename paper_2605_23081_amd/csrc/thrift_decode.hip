@@ -1,54 +1,536 @@
 // Split-K decode over the dual MXFP4 / 16-bit KV cache (Sec. 4.1 and Sec. 5 of the paper describe the
 // dual cache; the algorithm is Algorithm 1 with a one-token query block).
 //
-// One workgroup = one (sequence, KV head, partition of split_blocks key blocks).  Its four wavefronts
-// each take a contiguous quarter of the partition and run Alg. 1 over it from a fresh (m, l, O) for all
-// query heads of the GQA group at once: the group's G <= 32 heads are the "query rows" of the same
-// transposed 32x32 MFMA tiles the prefill kernel uses (columns >= G carry zeros and are never stored).
-// The kernel is bandwidth bound: each wavefront streams its key blocks straight from HBM into MFMA
-// operand registers — 4-bit codes and scales for every block that some head of the group has not
-// promoted, the 16-bit K/V rows for blocks that some head has promoted — so every cache byte is read
-// once per KV head, not once per query head.  A head for which the block is promoted takes its scores
-// and P.V from the 16-bit path, the others from the 4-bit path; both feed the same online softmax.
-// Each wavefront writes one unnormalised partial (m, l, O); a second kernel merges the partials of a
-// (sequence, head) by their log-sum-exp.
+// One workgroup = one (sequence, KV head, partition of split_blocks key blocks) and ONE recurrence of Alg. 1
+// per query head over the whole partition.  The group's heads are dealt to the four wavefronts (head g goes to
+// wavefront g mod 4, column g / 4 of that wavefront's transposed 32x32 MFMA tiles; the other columns carry zeros
+// and are never stored), so every wavefront walks every key block of the partition for its own heads.
+// The kernel is bandwidth bound.  Each key block is brought from HBM once per workgroup by LDS DMA and read from
+// LDS by all four wavefronts: the 4-bit codes and scales of every block into a ring of five slots, four blocks
+// ahead of the arithmetic; the 16-bit K and V tiles of a block that some head of the group has promoted into one
+// tile buffer each, one block ahead.  A head for which the block is promoted takes its scores and P.V from the
+// 16-bit tiles, the others from the 4-bit slot; both feed the same online softmax.  Each (head, partition) writes
+// one unnormalised partial (m, l, O); a second kernel merges the partials of a (sequence, head) by their
+// log-sum-exp.  A partly filled last block (a cache that is still growing) is a partition of its own, computed by
+// a small second instantiation with masking, so that the main walk carries none.
+#include <type_traits>
+
 #include "thrift_launch.h"
 #include "thrift_tile.h"
 
 namespace thrift {
 
-constexpr int kDecodeLdsPerWave = kBk * kRow16;   // one 16-bit V tile per wavefront (transposing reads)
+constexpr int kDecRing = 5;                                   // 4-bit slots: block j sits in slot j mod 5, fetched 4 blocks ahead
+constexpr int kDecAhead = kDecRing - 1;
+constexpr int kDecLdsK16 = kDecRing * kLdsBytes4;             // one swizzled 16-bit K tile
+constexpr int kDecLdsV16 = kDecLdsK16 + kTile16;              // one swizzled 16-bit V tile
+constexpr int kDecLds = kDecLdsV16 + kTile16;                 // 76288 B: two workgroups per CU
+constexpr int kDmaPer4 = 3;                                   // DMA instructions one wavefront issues per 4-bit block
+constexpr int kBmWin = 8;                                     // 64-block words of each head's selection bitmap cached in LDS
 
-// TAIL_ONLY = false: the full key blocks of every sequence, the instantiation that carries the traffic.
-// TAIL_ONLY = true: one wavefront per (sequence, KV head) for the one key block a length that is not a multiple of
-// the block size leaves partly filled: its keys past the length are masked, the staging of its 16-bit V rows stops
-// at the last valid row, and the result is one more partial (the last slot) for the merge.  Kept out of the main
-// instantiation so that its hot loop carries none of the masking.
-template <typename T, bool TAIL_ONLY>
-__global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
-  __shared__ __align__(16) unsigned char lds_all[4 * kDecodeLdsPerWave];
+// Wait until at most n (0, 3, 6 or 9) of this wavefront's DMA instructions are in flight.
+__device__ __forceinline__ void vm_wait_dyn(int n) {
+  if (n >= 9) vm_wait<9>();
+  else if (n >= 6) vm_wait<6>();
+  else if (n >= 3) vm_wait<3>();
+  else vm_wait<0>();
+}
+
+// ---- one query row per wavefront: the row layout ----
+// With a single head per wavefront the transposed tiles of the prefill kernel would spend a whole wavefront
+// instruction on each of the row's 64 scores.  Here the score tiles are formed the other way round, S = Q . K^T
+// with the query in rows 0 and 4 of the A operand (all other rows zero): accumulator register 0 of lane (half, r)
+// is row 4*half, column r, i.e. the query against key r of the 32-key sub-tile.  Taking sub-tile 0 from the lower 32
+// lanes and sub-tile 1 from the upper ones leaves ONE register with the score of key `lane` of the block in every
+// lane: the online softmax of Alg. 1 then costs one exponential per block, its maxima come from lane permutes, and
+// the probabilities are gathered into lanes 0 and 32 (the B-operand column of the query in O^T += V^T . P^T, 32 keys
+// = one MXFP4 group per lane) by a few more permutes.
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u(uint32_t x) { return __builtin_amdgcn_update_dpp(0u, x, CTRL, 0xf, 0xf, true); }
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x) { return __uint_as_float(dpp_u<CTRL>(__float_as_uint(x))); }
+constexpr int kDppSwap1 = 0xb1;        // quad_perm [1,0,3,2]: lane ^ 1
+constexpr int kDppSwap2 = 0x4e;        // quad_perm [2,3,0,1]: lane ^ 2
+constexpr int kDppQuadHi = 0xee;       // quad_perm [2,3,2,3]: lanes 0,1 of a quad read lanes 2,3
+constexpr int kDppHalfMirror = 0x141;  // lane i of each 8 reads lane 7 - i
+constexpr int kDppMirror = 0x140;      // lane i of each 16 reads lane 15 - i
+constexpr int kDppShl4 = 0x104;        // lane i reads lane i + 4 of its 16-lane row
+constexpr int kDppShl8 = 0x108;        // lane i reads lane i + 8 of its 16-lane row
+
+// natural key order for the row layout: fragment (t, kk) of lane (half, r) = key 32t + r, d-group 2*half + kk
+__device__ __forceinline__ K4Tile load_k4_rows(const unsigned char* slot, int lane) {
+  const int half = lane >> 5, r = lane & 31;
+  const unsigned char* ksrow = slot + kLdsKS + 4 * r + 2 * half;        // sub-tile 1: 32 keys = 128 bytes further
+  K4Tile k;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    k.ks[t] = *reinterpret_cast<const uint16_t*>(ksrow + 128 * t);
+    k.a[2 * t] = *reinterpret_cast<const v4i*>(slot + kLdsK4 + ((t * 2 + 0) * 64 + lane) * 16);
+    k.a[2 * t + 1] = *reinterpret_cast<const v4i*>(slot + kLdsK4 + ((t * 2 + 1) * 64 + lane) * 16);
+  }
+  return k;
+}
+// Score of key `lane` of the block (Alg. 1 step 15 for the one-token query block).  qf / qsc: the query's fragments
+// and scale bytes in lanes r = 0 and r = 4, zeros elsewhere.
+__device__ __forceinline__ float scores4_row(const K4Tile& k, int lane, const v4i (&qf)[2], uint32_t qsc) {
+  float st[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    v16f acc = {0.f};
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(qf[0]), widen(k.a[2 * t]), acc, 4, 4, 0, qsc, 0, k.ks[t]);
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(qf[1]), widen(k.a[2 * t + 1]), acc, 4, 4, 1, qsc, 1, k.ks[t]);
+    st[t] = acc[0];
+  }
+  return (lane >> 5) ? st[1] : st[0];
+}
+// The same from the 16-bit K tile (Alg. 1 step 9).  Tile rows are keys in natural order, 256 B each, the 16-byte chunk c
+// of row `row` stored at chunk position c ^ (row & 7) (eight neighbouring lanes read eight different positions).
+// qf[s8]: the query's elements d = 16*s8 + 8*half + [0,8) in lanes r = 0 and r = 4, zeros elsewhere.
+template <typename T>
+__device__ __forceinline__ float scores16_row(const unsigned char* ktile, int lane, const v8s (&qf)[8]) {
+  const int half = lane >> 5, r = lane & 31;
+  float st[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const unsigned char* row = ktile + (32 * t + r) * 256;
+    v16f acc = {0.f};
+#pragma unroll
+    for (int s8 = 0; s8 < 8; ++s8) {
+      const v8s kf = *reinterpret_cast<const v8s*>(row + 16 * ((2 * s8 + half) ^ (r & 7)));
+      acc = T::mfma(qf[s8], kf, acc);
+    }
+    st[t] = acc[0];
+  }
+  return half ? st[1] : st[0];
+}
+// Online softmax of Alg. 1 (steps 10-12 / 16-17) on the row layout: sv = this lane's raw score.  st.m is the running
+// maximum (the same in every lane), st.l this lane's share of the row sum.  Returns (for the whole wavefront) whether
+// the maximum rose; only then does alpha hold exp(scale * (m_old - m_new)) and must the accumulators be rescaled.
+// p: this lane's unnormalised probability; pbyte: the E8M0 byte of the lane's 32-key group of P (as in softmax_update).
+__device__ __forceinline__ bool softmax_row(float sv, float c, RowState& st, float& alpha, uint32_t& pbyte, float& p) {
+  float v = sv;
+  v = fmaxf(v, dpp_f<kDppSwap1>(v));
+  v = fmaxf(v, dpp_f<kDppSwap2>(v));
+  v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
+  v = fmaxf(v, dpp_f<kDppMirror>(v));                               // maximum of the lane's 16
+  const uint32_t vb = __float_as_uint(v);
+  const auto s16 = __builtin_amdgcn_permlane16_swap(vb, vb, false, false);   // [0]: the even 16's value on both 16s of a 32, [1]: the odd's
+  const float gmax = fmaxf(__uint_as_float(s16[0]), __uint_as_float(s16[1]));  // maximum of the lane's 32-key group
+  const uint32_t gb = __float_as_uint(gmax);
+  const auto s32 = __builtin_amdgcn_permlane32_swap(gb, gb, false, false);
+  const float m_old = st.m;
+  const float m_new = max3(m_old, __uint_as_float(s32[0]), __uint_as_float(s32[1]));
+  const bool grew = __builtin_amdgcn_ballot_w64(m_new != m_old) != 0ULL;
+  if (grew) {
+    float d = m_old - m_new;
+    asm volatile("" : "+v"(d));                                    // keeps the exponential inside the branch
+    alpha = fast_exp2(d * c);
+    float l = st.l;
+    asm volatile("s_nop 1\n\tv_mul_f32 %0, %1, %0" : "+v"(l) : "v"(alpha));   // wait states: a transcendental result read by hand-written code
+    st.l = l;
+  }
+  st.m = m_new;
+  int e;
+  {
+    const float x = (gmax - m_new) * c;                            // the group maximum maps to exactly 2^floor(x) or above
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(e) : "v"(x));
+  }
+  pbyte = (uint32_t)max(e + 125, 1);
+  p = fast_exp2(__builtin_fmaf(sv, c, -(m_new * c)));
+  st.l += p;
+  return grew;
+}
+// Alg. 1 step 19 on the row layout: every lane turns its probability into an E2M1 code under its group's scale and the
+// 32 codes of a group are collected, in key order, into the four registers of lane 0 (keys 0-31) / lane 32 (keys 32-63);
+// the other lanes end up with codes that belong to no query (their MFMA columns are never stored).
+__device__ __forceinline__ v4i gather_p4(float p, uint32_t pb) {
+  const float pscale = __uint_as_float(pb << 23);
+  const float nb = dpp_f<kDppSwap1>(p);
+  // even lanes: one byte = the codes of keys (lane, lane + 1)
+  const uint32_t b8 = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, p, nb, pscale, 0);
+  const uint32_t b16 = b8 | (dpp_u<kDppQuadHi>(b8) << 8);          // lanes 4q: keys 4q .. 4q+3
+  const uint32_t b32 = b16 | (dpp_u<kDppShl4>(b16) << 16);         // lanes 8q: keys 8q .. 8q+7
+  const auto sw = __builtin_amdgcn_permlane16_swap(b32, b32, false, false);
+  // lane 0 of a 32: sw[0] = its own word (keys 0-7), sw[1] = lane 16's (keys 16-23); lane 8: keys 8-15 and 24-31
+  return (v4i){(int)sw[0], (int)dpp_u<kDppShl8>(sw[0]), (int)sw[1], (int)dpp_u<kDppShl8>(sw[1])};
+}
+// Alg. 1 step 13 on the row layout: the probabilities rounded to the input dtype and collected through a 128-byte LDS
+// row of the wavefront's own: pf[s] of lane (half, *) = keys 32*half + 8s .. + 7 (the order pv_16_rounded contracts in).
+template <typename T>
+__device__ __forceinline__ void gather_p16(uint16_t* prow, int lane, float p, v8s (&pf)[4]) {
+  prow[lane] = T::from_float(p);
+#pragma unroll
+  for (int s = 0; s < 4; ++s) pf[s] = *reinterpret_cast<const v8s*>(prow + 32 * (lane >> 5) + 8 * s);
+}
+// sum over the 64 lanes, in every lane
+__device__ __forceinline__ float wave_sum(float x) {
+  x += dpp_f<kDppSwap1>(x);
+  x += dpp_f<kDppSwap2>(x);
+  x += dpp_f<kDppHalfMirror>(x);
+  x += dpp_f<kDppMirror>(x);
+  const uint32_t xb = __float_as_uint(x);
+  const auto s16 = __builtin_amdgcn_permlane16_swap(xb, xb, false, false);
+  x = __uint_as_float(s16[0]) + __uint_as_float(s16[1]);
+  return x + other_half(x);
+}
+
+// MULTI = false: at most one head per wavefront (a group of up to four heads, the usual GQA ratios): the path of a
+// block is a wavefront-uniform choice and the 16-bit query fragments stay in registers.  MULTI = true: up to eight heads
+// per wavefront, which may split over the two paths of a block: both tiles are computed and each lane keeps its own
+// head's; the 16-bit query fragments are re-read at each promoted block (that instantiation has no registers to spare).
+template <typename T, bool MULTI>
+__global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(DecodeArgs a) {
+  __shared__ __align__(1024) unsigned char lds[kDecLds];
+  __shared__ unsigned long long bmw[32 * kBmWin];              // [head of the group][word of the window]
+  __shared__ __align__(16) uint16_t qrow[MULTI ? 8 : 4 * kD];  // !MULTI: the 16-bit query row of each wavefront's head
+  __shared__ __align__(16) uint16_t prow[MULTI ? 8 : 4 * 64];  // !MULTI: a row of rounded probabilities per wavefront
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
-  unsigned char* lds = lds_all + wave * kDecodeLdsPerWave;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform
   const int G = a.Hq / a.Hkv;
-  const int part = TAIL_ONLY ? 0 : blockIdx.x % a.nsplit;
-  const int unit = TAIL_ONLY ? blockIdx.x : blockIdx.x / a.nsplit;
+  const int part = blockIdx.x % a.nsplit, unit = blockIdx.x / a.nsplit;
   const int b = unit / a.Hkv, kvh = unit % a.Hkv;
-  // cached tokens of this sequence; the last key block may still be filling up
   const int len = a.seqlens ? min(a.Nkv, max(0, a.seqlens[b])) : a.Nkv;
-  const int Tk = TAIL_ONLY ? (len + kBk - 1) / kBk : len / kBk;
-  const bool real = r < G;                                   // this lane's column is a real query head
-  const int hq = kvh * G + (real ? r : 0);
-  const size_t qh = (size_t)b * a.Hq + hq, kh = (size_t)b * a.Hkv + kvh;
+  const int Tk = len / kBk;                                    // full key blocks; a partly filled one is the other kernel's
+  const int j_begin = min(Tk, part * a.split_blocks), j_end = min(Tk, j_begin + a.split_blocks);
+  const int n = j_end - j_begin;                               // key blocks of this partition (workgroup-uniform)
 
-  // contiguous quarter of the partition for this wavefront
-  const int quarter = a.split_blocks / 4;
-  const int j_begin = TAIL_ONLY ? len / kBk : part * a.split_blocks + wave * quarter;
-  const int j_end = TAIL_ONLY ? Tk : min(Tk, j_begin + quarter);
+  // this wavefront's heads: column r carries head wave + 4r of the group
+  const int my_heads = G > wave ? (G - wave + 3) / 4 : 0;
+  const bool real = r < my_heads;
+  const size_t group0 = (size_t)b * a.Hq + (size_t)kvh * G;    // first query head of the group
+  const size_t qh = group0 + (MULTI ? (real ? wave + 4 * r : 0) : (my_heads > 0 ? wave : 0));   // one head: every lane's
+  const size_t kh = (size_t)b * a.Hkv + kvh;
+  const unsigned long long my_mask = my_heads >= 32 ? 0xffffffffULL : ((1ULL << my_heads) - 1ULL);
 
   // ---- Q fragments (zeros for padding columns): the lane quantises its own two MXFP4 groups of the query,
   // d-group 2*half + kk (channels 64*half + 32*kk .. +31) for fragment kk (Alg. 1 step 2 for the one-token
-  // query block) ----
+  // query block); the 16-bit fragments of the same row stay in registers for the promoted blocks ----
+  v4i qf4[2] = {(v4i){0, 0, 0, 0}, (v4i){0, 0, 0, 0}};
+  uint32_t qsc = 0x7f7f7f7fu;
+  const uint16_t* q16row = a.q + qh * kD + 8 * half;
+  // lanes that carry the query: its column in the transposed tiles, or rows 0 and 4 of the row layout
+  const bool qlane = MULTI ? real : (my_heads > 0 && (r == 0 || r == 4));
+  if (qlane) {
+    uint32_t sb[2];
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const uint4* src = reinterpret_cast<const uint4*>(a.q + qh * kD + 64 * half + 32 * kk);
+      uint32_t pair[16], codes[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint4 w = src[t];
+        pair[4 * t] = w.x; pair[4 * t + 1] = w.y; pair[4 * t + 2] = w.z; pair[4 * t + 3] = w.w;
+      }
+      sb[kk] = quantize_group32<T>(pair, codes);
+      qf4[kk] = (v4i){(int)codes[0], (int)codes[1], (int)codes[2], (int)codes[3]};
+    }
+    qsc = sb[0] | (sb[1] << 8);                              // byte kk: the scale of fragment kk
+  }
+  // !MULTI: the 16-bit row of the wavefront's head is parked in LDS (each wavefront writes and reads only its own row)
+  // and read back at each promoted block: a global read inside the walk would wait for every tile DMA in flight, and
+  // the walk has no 32 registers to spare for it.
+  if constexpr (!MULTI) {
+    if (lane < 16) {
+      uint4 w = make_uint4(0u, 0u, 0u, 0u);
+      if (my_heads > 0) w = *reinterpret_cast<const uint4*>(a.q + (group0 + wave) * kD + 8 * lane);
+      *reinterpret_cast<uint4*>(qrow + wave * kD + 8 * lane) = w;
+    }
+  }
+
+  const uint8_t* k4base = a.k4 + kh * a.Nkv * 64;
+  const uint8_t* v4base = a.v4 + kh * (size_t)(a.Nkv / 64) * 4096;
+  const uint8_t* k16base = reinterpret_cast<const uint8_t*>(a.k16 + kh * a.Nkv * kD);
+  const uint8_t* v16base = reinterpret_cast<const uint8_t*>(a.v16 + kh * a.Nkv * kD);
+  // the 256 scale bytes of K ride with the even wavefronts, V's with the odd ones
+  const bool v_scales = (wave & 1) != 0;
+  const uint8_t* scbase = v_scales ? a.vs + kh * (size_t)(a.Nkv / 32) * kD : a.ks + kh * a.Nkv * 4;
+  const uint32_t sclds = v_scales ? (uint32_t)kLdsVS : (uint32_t)kLdsKS;
+
+  // ---- staging: per-lane source offsets of this wavefront's DMA instructions (the LDS side of a DMA is linear
+  // in the lane index, so the MFMA fragment order of the 4-bit tiles and the chunk swizzle of the 16-bit tiles are
+  // expressed in the global offsets) ----
+  const uint32_t lds0 = lds_address(lds);
+  // K fragment (t, kk) = (wave>>1, wave&1): keys in the row permutation of the transposed tiles, or in natural order
+  const uint32_t k4off = (uint32_t)((MULTI ? key_of_row(r, wave >> 1) : 32 * (wave >> 1) + r) * 64 + (2 * half + (wave & 1)) * 16);
+  const uint32_t v4off = (uint32_t)((32 * wave + r) * 32 + half * 16);                               // V channels 32*wave .. +31
+  const uint32_t scoff = (uint32_t)lane * 4;
+  const uint32_t v16off = (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ v16_swizzle(lane >> 4)) * 16);
+  // instruction q = 4u + wave covers rows 4q .. 4q+3.  Transposed tiles: k16_swizzle (rows 32..63: chunk ^ 4 more);
+  // row layout: chunk ^ (row & 7), and row & 7 = 4*(wave & 1) + (lane >> 4) for every u
+  const uint32_t k16off = MULTI ? (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ (lane >> 4)) * 16)
+                                : (uint32_t)((lane >> 4) * 256 + ((lane & 15) ^ (4 * (wave & 1) + (lane >> 4))) * 16);
+  auto issue4 = [&](int j, int slot_index) {            // block j (absolute id) into ring slot slot_index
+    const int j_ = __builtin_amdgcn_readfirstlane(j);
+    const uint32_t slot = lds0 + (uint32_t)(__builtin_amdgcn_readfirstlane(slot_index) * kLdsBytes4);
+    dma_b128(k4base + (size_t)j_ * 4096, k4off, slot + kLdsK4 + wave * 1024);
+    dma_b32(scbase + (size_t)j_ * 256, scoff, slot + sclds);
+    dma_b128(v4base + (size_t)j_ * 4096, v4off, slot + kLdsV4 + wave * 1024);
+  };
+  auto issue16k = [&](int j) {                          // the 16-bit K tile of block j: instruction q covers rows 4q .. 4q+3
+    const int j_ = __builtin_amdgcn_readfirstlane(j);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q_ = u * 4 + wave;
+      dma_b128(k16base + (size_t)j_ * kTile16 + q_ * 1024, (MULTI && u >= 2) ? k16off ^ 64u : k16off, lds0 + kDecLdsK16 + q_ * 1024);
+    }
+  };
+  auto issue16v = [&](int j) {                          // the 16-bit V tile of block j
+    const int j_ = __builtin_amdgcn_readfirstlane(j);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q_ = u * 4 + wave;
+      dma_b128(v16base + (size_t)j_ * kTile16 + q_ * 1024, v16off, lds0 + kDecLdsV16 + q_ * 1024);
+    }
+  };
+
+  // ---- selection bitmaps.  Staging decisions need the whole group's votes on a block (identical in all four
+  // wavefronts); the arithmetic needs this lane's own head.  The walk reads them from a window of kBmWin 64-block
+  // words per head kept in LDS: a global read inside the walk would make the compiler wait for every load in
+  // flight, the tile DMAs included, at each key block. ----
+  int win0 = 0;                                         // first word of the window (workgroup-uniform)
+  int wcur = -1;                                        // word index the cached words (below) belong to
+  auto refill = [&](int word0) {                        // called by all threads at the same point of the walk
+    lds_barrier();                                      // nobody still reads the old window
+    for (int e = tid; e < G * kBmWin; e += 256) {
+      const int h = e / kBmWin, wi = word0 + e % kBmWin;
+      bmw[e] = wi < a.bitmap_words ? a.bitmap[(group0 + h) * a.bitmap_words + wi] : 0ULL;
+    }
+    lds_barrier();
+    win0 = word0;
+  };
+  // Per 64-block word: the OR of the group's words (some head has promoted the block) in scalar registers and this
+  // wavefront's own word(s).  Formed once per 64 key blocks, so that a step of the walk only tests bits.
+  auto scalar_word = [&](int index) -> unsigned long long {      // bmw[index], index wavefront-uniform
+    const unsigned long long w = bmw[index];
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)w), hi = __builtin_amdgcn_readfirstlane((uint32_t)(w >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+  };
+  unsigned long long gor = 0;                           // group OR of word wcur
+  unsigned long long own_s = 0;                         // !MULTI: the word of this wavefront's one head (scalar)
+  unsigned long long own_v = 0;                         // MULTI: the word of this lane's head
+  // Flags of block x of the partition (x may run past the end: all clear): bit 0 of the result = some head of the
+  // group has promoted it (wavefront-uniform); mine = this lane's head has.  Blocks are asked for in ascending order.
+  auto flags = [&](int x, bool& mine) -> int {
+    mine = false;
+    if (x >= n) return 0;
+    const int j = j_begin + x, w = j >> 6;
+    if (w != wcur) {
+      if (w >= win0 + kBmWin || wcur < 0) refill(w);
+      gor = 0;
+      for (int g = 0; g < G; ++g) gor |= scalar_word(g * kBmWin + (w - win0));
+      if constexpr (MULTI) own_v = real ? bmw[(wave + 4 * r) * kBmWin + (w - win0)] : 0ULL;
+      else own_s = my_heads > 0 ? scalar_word(wave * kBmWin + (w - win0)) : 0ULL;
+      wcur = w;
+    }
+    if constexpr (MULTI) mine = ((own_v >> (j & 63)) & 1ULL) != 0ULL;
+    else mine = ((own_s >> (j & 63)) & 1ULL) != 0ULL;
+    return (int)((gor >> (j & 63)) & 1ULL);
+  };
+
+  RowState st = {kEmptyMax, 0.f};
+  v16f o[4];
+#pragma unroll
+  for (int nn = 0; nn < 4; ++nn) o[nn] = (v16f){0.f};
+  const float c = a.scale * 1.4426950408889634f;
+
+  // ---- the walk, software-pipelined over the key blocks: step t (t = -1 .. n-1) finishes block t (softmax, P.V) and
+  // forms the scores of block t+1 in between, so that the matrix unit works on one block while the vector unit works
+  // on its neighbour and no LDS read is waited for where it is issued.
+  // Residency at step t: 4-bit slots of blocks t (V) and t+1 (K) in use, t+2 and t+3 in flight, t+4 issued into the
+  // slot block t-1 has left; the K tile buffer holds block t+1's 16-bit keys, the V tile buffer block t's values.
+  // A 16-bit tile is fetched one step before its use when its buffer is idle then (the neighbouring block is not
+  // promoted), otherwise at the step of its use, which then waits for it.
+  // P?/M?: promoted-by-the-group / promoted-for-this-head flags of blocks t-1 (a), t (b), t+1 (c), t+2 (d). ----
+  int Pa = 0, Pb = 0, Pc, Pd;
+  bool Mb = false, Mc, Md;
+  Pc = flags(0, Mc);
+  Pd = flags(1, Md);
+  if (Pc) issue16k(j_begin);
+  for (int x = 0; x < 3 && x < n; ++x) issue4(j_begin + x, x);
+  int slot_a = 3, slot_b = 4, slot_c = 0;               // ring slots of blocks t-1, t, t+1 at t = -1
+  int early_prev = 0;                                   // the step before fetched 16-bit tiles ahead of its 4-bit block
+
+  // Staging part of step t: waits for what the step reads, then issues what later steps will read.
+  auto stage = [&](int t) {
+    const int j = j_begin + t;
+    // in flight and not yet needed: the 4-bit blocks t+2 and t+3 (where they exist); after 16-bit tiles fetched ahead in
+    // the step before, only that step's 4-bit block t+3
+    const int newer = early_prev ? (t + 3 < n ? kDmaPer4 : 0) : kDmaPer4 * max(0, min(n - 2 - t, 2));
+    vm_wait_dyn(newer);
+    lds_barrier();                                      // block t+1 (and block t's V tile) complete in LDS; step t-1 is behind everyone
+    const int lateK = Pc & Pb, lateV = Pb & Pa;         // the buffer was busy during the step before
+    if (lateK) issue16k(j + 1);
+    if (lateV) issue16v(j);
+    if (lateK | lateV) {
+      vm_wait<0>();
+      lds_barrier();
+    }
+    const int earlyK = Pd & (Pc ^ 1), earlyV = Pc & (Pb ^ 1);
+    if (earlyK) issue16k(j + 2);
+    if (earlyV) issue16v(j + 1);
+    if (t + kDecAhead < n) issue4(j + kDecAhead, slot_a);
+    early_prev = earlyK | earlyV;
+  };
+  if constexpr (!MULTI) {
+    // ---- one head per wavefront: the row layout; its (scalar) selection bit decides the path of a block ----
+    // score of key `lane` of the block in ring slot `slot` / in the K tile buffer
+    auto score16 = [&]() -> float {
+      // the lane-dependent LDS addresses of the 16-bit tiles are formed at the promoted block, from a copy of the lane
+      // index the compiler cannot see through: formed once ahead of the walk they would occupy registers at every step
+      int lane_ = lane;
+      asm volatile("" : "+v"(lane_));
+      const int half_ = lane_ >> 5;
+      v8s q16[8];
+#pragma unroll
+      for (int s8 = 0; s8 < 8; ++s8)
+        q16[s8] = qlane ? *reinterpret_cast<const v8s*>(qrow + wave * kD + 16 * s8 + 8 * half_) : (v8s){0, 0, 0, 0, 0, 0, 0, 0};
+      return scores16_row<T>(lds + kDecLdsK16, lane_, q16);
+    };
+    float sv = 0.f;                                     // raw score of key `lane` of block t on entry to step t
+    stage(-1);                                          // step -1: only the scores of block 0
+    if (my_heads > 0 && n > 0) sv = Mc ? score16() : scores4_row(load_k4_rows(lds + slot_c * kLdsBytes4, lane), lane, qf4, qsc);
+    slot_a = slot_b; slot_b = slot_c; slot_c = 1;
+    // One step; WITH_NEXT (a compile-time flag): block t+1 exists.
+    auto step = [&](int t, auto with_next) {
+      Pa = Pb; Pb = Pc; Pc = Pd; Mb = Mc; Mc = Md;      // shift the flags; block t+2's are new
+      Pd = flags(t + 2, Md);
+      stage(t);
+      if (my_heads > 0) {
+        const unsigned char* slot_v = lds + slot_b * kLdsBytes4;     // block t
+        constexpr bool kNext = decltype(with_next)::value;
+        // the K fragments of a 4-bit block t+1 are asked for first and arrive while the softmax of block t runs; its
+        // score MFMAs go between the quantisation and the P.V MFMAs of block t
+        const bool next4 = kNext && !Mc;
+        K4Tile kt;
+        if (next4) kt = load_k4_rows(lds + slot_c * kLdsBytes4, lane);
+        float alpha, p;
+        uint32_t pb;
+        const bool grew = softmax_row(sv, c, st, alpha, pb, p);
+        rescale(o, grew, alpha);
+        if (!Mb) {
+          const v4i pq = gather_p4(p, pb);
+          if (next4) sv = scores4_row(kt, lane, qf4, qsc);
+          pv_fp4_codes(slot_v, lane, pq, pb, o);
+        } else {
+          v8s pf[4];
+          gather_p16<T>(prow + wave * 64, lane, p, pf);
+          if (next4) sv = scores4_row(kt, lane, qf4, qsc);
+          int lane_ = lane;
+          asm volatile("" : "+v"(lane_));
+          pv_16_rounded<T, true>(lds + kDecLdsV16, lane_, pf, o);
+        }
+        if (kNext && Mc) sv = score16();
+      }
+      slot_a = slot_b; slot_b = slot_c; slot_c = slot_c + 1 == kDecRing ? 0 : slot_c + 1;
+    };
+    for (int t = 0; t + 1 < n; ++t) step(t, std::true_type{});
+    if (n > 0) step(n - 1, std::false_type{});
+  } else {
+    // ---- several heads per wavefront: the transposed tiles of the prefill kernel, head wave + 4r in column r.  The heads
+    // may split over the two paths of a block: both tiles are computed and each lane keeps its own head's. ----
+    auto scores = [&](int slot, bool mine, bool any, bool all, v16f (&s)[2]) {
+      if (!all) scores_fp4(lds + slot * kLdsBytes4, lane, qf4, qsc, s);
+      if (any) {
+        int lane_ = lane;
+        asm volatile("" : "+v"(lane_));                 // no address of the 16-bit tile kept in registers across steps
+        v8s q16[8];
+#pragma unroll
+        for (int s8 = 0; s8 < 8; ++s8)
+          q16[s8] = real ? *reinterpret_cast<const v8s*>(q16row + 16 * s8) : (v8s){0, 0, 0, 0, 0, 0, 0, 0};
+        if (all) {
+          scores_16<T>(lds + kDecLdsK16, lane_, q16, s);
+        } else {
+          v16f s16[2];
+          scores_16<T>(lds + kDecLdsK16, lane_, q16, s16);
+          if (mine) { s[0] = s16[0]; s[1] = s16[1]; }
+        }
+      }
+    };
+    // this wavefront's votes on a block the group has promoted: bit 0 = some head of the wavefront, bit 1 = all of them
+    auto votes = [&](int P, bool mine) -> int {
+      const unsigned long long v = P ? (__builtin_amdgcn_ballot_w64(mine) & my_mask) : 0ULL;
+      return (v != 0ULL ? 1 : 0) | (v == my_mask ? 2 : 0);
+    };
+    v16f s[2];                                          // raw scores of block t on entry to step t
+    stage(-1);                                          // step -1: only the scores of block 0
+    if (my_heads > 0 && n > 0) {
+      const int vc = votes(Pc, Mc);
+      scores(slot_c, Mc, (vc & 1) != 0, (vc & 2) != 0, s);
+    }
+    slot_a = slot_b; slot_b = slot_c; slot_c = 1;
+    // One step; WITH_NEXT (a compile-time flag): block t+1 exists.  The last step is a separate instantiation so that the
+    // score registers are simply overwritten in every other one (no merge of old and new values at each step).
+    auto step = [&](int t, auto with_next) {
+      Pa = Pb; Pb = Pc; Pc = Pd; Mb = Mc; Mc = Md;
+      Pd = flags(t + 2, Md);
+      stage(t);
+      if (my_heads > 0) {
+        const unsigned char* slot_v = lds + slot_b * kLdsBytes4;     // block t
+        float alpha;
+        uint32_t pb;
+        const bool grew = softmax_update(s, lane, false, kBk, c, st, alpha, pb);
+        rescale(o, grew, alpha);
+        const int vb = votes(Pb, Mb), vc = votes(Pc, Mc);
+        const bool any_b = (vb & 1) != 0, all_b = (vb & 2) != 0;
+        // each lane contributes nothing on the path its head did not take (zero codes / zero probabilities)
+        if (!all_b) {
+          v4i pq = quantize_p_group(s, pb);
+          if (Mb) pq = (v4i){0, 0, 0, 0};
+          pv_fp4_codes(slot_v, lane, pq, pb, o);
+        }
+        if (any_b) {
+          if (!Mb) { s[0] = (v16f){0.f}; s[1] = (v16f){0.f}; }
+          int lane_ = lane;
+          asm volatile("" : "+v"(lane_));
+          pv_16<T, true>(lds + kDecLdsV16, lane_, s, o);
+        }
+        if constexpr (decltype(with_next)::value) scores(slot_c, Mc, (vc & 1) != 0, (vc & 2) != 0, s);
+      }
+      slot_a = slot_b; slot_b = slot_c; slot_c = slot_c + 1 == kDecRing ? 0 : slot_c + 1;
+    };
+    for (int t = 0; t + 1 < n; ++t) step(t, std::true_type{});
+    if (n > 0) step(n - 1, std::false_type{});
+  }
+  vm_wait<0>();
+
+  // ---- partial (m, l, O) of this (head, partition): accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
+  // the row sum: the two halves of a column, or all 64 lanes of the row layout
+  const float l = MULTI ? st.l + other_half(st.l) : wave_sum(st.l);
+  if (real) {
+    float* po = a.part_o + (qh * a.nparts + part) * kD;
+#pragma unroll
+    for (int nn = 0; nn < 4; ++nn)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4)
+        *reinterpret_cast<float4*>(po + 32 * nn + 8 * g4 + 4 * half) =
+            make_float4(o[nn][4 * g4], o[nn][4 * g4 + 1], o[nn][4 * g4 + 2], o[nn][4 * g4 + 3]);
+    if (half == 0) {
+      a.part_ml[(qh * a.nparts + part) * 2] = st.m;
+      a.part_ml[(qh * a.nparts + part) * 2 + 1] = l;
+    }
+  }
+}
+
+// The one key block that a length which is not a multiple of the block size leaves partly filled: one wavefront per
+// (sequence, KV head) for all heads of the group (columns of the same tiles), operands straight from global memory,
+// the keys past the length masked, the staging of the 16-bit V rows stopping at the last valid row.  Its result is
+// one more partial (the last slot) for the merge.
+constexpr int kDecodeTailLds = kBk * kRow16;      // one 16-bit V tile (padded rows, transposing reads)
+
+template <typename T>
+__global__ void __launch_bounds__(64) decode_tail_kernel(DecodeArgs a) {
+  __shared__ __align__(16) unsigned char lds[kDecodeTailLds];
+  const int lane = threadIdx.x & 63, half = lane >> 5, r = lane & 31;
+  const int G = a.Hq / a.Hkv;
+  const int unit = blockIdx.x;
+  const int b = unit / a.Hkv, kvh = unit % a.Hkv;
+  const int len = a.seqlens ? min(a.Nkv, max(0, a.seqlens[b])) : a.Nkv;
+  const bool real = r < G;                                   // this lane's column is a real query head
+  const int hq = kvh * G + (real ? r : 0);
+  const size_t qh = (size_t)b * a.Hq + hq, kh = (size_t)b * a.Hkv + kvh;
+  const int j_begin = len / kBk, j_end = (len + kBk - 1) / kBk;   // zero or one block
+
   v4i qf4[2] = {(v4i){0, 0, 0, 0}, (v4i){0, 0, 0, 0}};
   uint32_t qsc = 0x7f7f7f7fu;
   if (real) {
@@ -65,7 +547,7 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       sb[kk] = quantize_group32<T>(pair, codes);
       qf4[kk] = (v4i){(int)codes[0], (int)codes[1], (int)codes[2], (int)codes[3]};
     }
-    qsc = sb[0] | (sb[1] << 8);                              // byte kk: the scale of fragment kk
+    qsc = sb[0] | (sb[1] << 8);
   }
 
   const uint8_t* k4base = a.k4 + kh * a.Nkv * 64;
@@ -83,29 +565,23 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   const float c = a.scale * 1.4426950408889634f;
   const unsigned long long group_mask = G >= 32 ? 0xffffffffULL : ((1ULL << G) - 1ULL);
 
-  unsigned long long word = 0;
-  int word_id = -1;
   for (int j = j_begin; j < j_end; ++j) {
-    constexpr bool TAIL = TAIL_ONLY;
-    if ((j >> 6) != word_id) { word_id = j >> 6; word = real ? bm[word_id] : 0ULL; }
+    const unsigned long long word = real ? bm[j >> 6] : 0ULL;
     const bool mine16 = (word >> (j & 63)) & 1ULL;           // promoted for this lane's head
     const unsigned long long votes = __builtin_amdgcn_ballot_w64(mine16) & group_mask;
     const bool any16 = votes != 0ULL;
     const bool all16 = votes == group_mask;
-    const int n_valid = TAIL ? len - j * kBk : kBk;
+    const int n_valid = len - j * kBk;
 
     v16f s[2];
     v4i vf4[4];
     uint32_t vsw = 0;
     if (!all16) {
-      // the block's 4-bit V fragments and scales are requested together with its K rows: one memory round trip
-      // per block instead of two (they are used after the softmax)
       const uint8_t* vt = v4base + (size_t)j * 4096 + r * 32 + half * 16;
       const uint8_t* vsr = vsbase + ((size_t)j * 2 + half) * kD + r;
 #pragma unroll
       for (int n = 0; n < 4; ++n) vf4[n] = *reinterpret_cast<const v4i*>(vt + 1024 * n);
       vsw = (uint32_t)vsr[0] | ((uint32_t)vsr[32] << 8) | ((uint32_t)vsr[64] << 16) | ((uint32_t)vsr[96] << 24);
-      // ---- 4-bit scores straight from global memory ----
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int key = key_of_row(r, t);
@@ -120,14 +596,13 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       }
     }
     if (any16) {
-      // ---- 16-bit scores; the V tile goes through this wavefront's LDS slice for the transposing reads ----
 #pragma unroll
       for (int u = 0; u < 16; ++u) {
         // rows past the cached tokens are never written by anyone: stage the last valid row in their place
         // (their probabilities are zero, but zero times an arbitrary bit pattern need not be)
         const int chunk = lane + 64 * u, row = chunk >> 4, col = chunk & 15;
         *reinterpret_cast<uint4*>(lds + row * kRow16 + col * 16) =
-            *reinterpret_cast<const uint4*>(v16base + ((size_t)j * kBk + (TAIL ? min(row, n_valid - 1) : row)) * kD + col * 8);
+            *reinterpret_cast<const uint4*>(v16base + ((size_t)j * kBk + min(row, n_valid - 1)) * kD + col * 8);
       }
       v8s qf16[8];
 #pragma unroll
@@ -136,21 +611,20 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       v16f s16[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        const uint16_t* krow = k16base + ((size_t)j * kBk + key_of_row(r, t)) * kD + 8 * half;
+        // key rows past the length are not read either: the last valid row stands in, its scores are masked below
+        const uint16_t* krow = k16base + ((size_t)j * kBk + min(key_of_row(r, t), n_valid - 1)) * kD + 8 * half;
         v16f acc = {0.f};
 #pragma unroll
         for (int s8 = 0; s8 < 8; ++s8) acc = T::mfma(*reinterpret_cast<const v8s*>(krow + 16 * s8), qf16[s8], acc);
         s16[t] = acc;
       }
-      if (all16) { s[0] = s16[0]; s[1] = s16[1]; }
-      else if (mine16) { s[0] = s16[0]; s[1] = s16[1]; }
+      if (all16 || mine16) { s[0] = s16[0]; s[1] = s16[1]; }
     }
     float alpha;
     uint32_t pb;
-    const bool grew = softmax_update(s, lane, TAIL, n_valid, c, st, alpha, pb);
+    const bool grew = softmax_update(s, lane, true, n_valid, c, st, alpha, pb);
     rescale(o, grew, alpha);
     if (!all16) {
-      // heads that took the 16-bit scores contribute nothing on the 4-bit path (zero codes, whatever the scale)
       v16f p4[2] = {s[0], s[1]};
       if (mine16) { p4[0] = (v16f){0.f}; p4[1] = (v16f){0.f}; }
       pv_fp4_regs<true>(p4, pb, vsw, 0u, 0u, 0u, vf4[0], vf4[1], vf4[2], vf4[3], o);
@@ -164,10 +638,9 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
     }
   }
 
-  // ---- partial (m, l, O) of this wavefront: accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
   const float l = st.l + other_half(st.l);
   if (real) {
-    const int pid = TAIL_ONLY ? a.nparts - 1 : part * 4 + wave;
+    const int pid = a.nparts - 1;
     float* po = a.part_o + (qh * a.nparts + pid) * kD;
 #pragma unroll
     for (int n = 0; n < 4; ++n)
@@ -409,12 +882,18 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
 
 void launch_decode(const DecodeArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((long)a.B * a.Hkv * a.nsplit);
-  if (a.dt == THRIFT_F16) decode_partial_kernel<F16, false><<<dim3(grid), dim3(256), 0, st>>>(a);
-  else decode_partial_kernel<BF16, false><<<dim3(grid), dim3(256), 0, st>>>(a);
+  const bool multi = a.Hq / a.Hkv > 4;                 // more than one head per wavefront
+  if (a.dt == THRIFT_F16) {
+    if (multi) decode_partial_kernel<F16, true><<<dim3(grid), dim3(256), 0, st>>>(a);
+    else decode_partial_kernel<F16, false><<<dim3(grid), dim3(256), 0, st>>>(a);
+  } else {
+    if (multi) decode_partial_kernel<BF16, true><<<dim3(grid), dim3(256), 0, st>>>(a);
+    else decode_partial_kernel<BF16, false><<<dim3(grid), dim3(256), 0, st>>>(a);
+  }
   if (a.seqlens != nullptr) {                          // without lengths every sequence fills the cache: no partly filled block
     const unsigned tail_grid = (unsigned)((long)a.B * a.Hkv);
-    if (a.dt == THRIFT_F16) decode_partial_kernel<F16, true><<<dim3(tail_grid), dim3(64), 0, st>>>(a);
-    else decode_partial_kernel<BF16, true><<<dim3(tail_grid), dim3(64), 0, st>>>(a);
+    if (a.dt == THRIFT_F16) decode_tail_kernel<F16><<<dim3(tail_grid), dim3(64), 0, st>>>(a);
+    else decode_tail_kernel<BF16><<<dim3(tail_grid), dim3(64), 0, st>>>(a);
   }
   decode_merge_kernel<<<dim3((unsigned)((long)a.B * a.Hq)), dim3(128), 0, st>>>(a);
 }

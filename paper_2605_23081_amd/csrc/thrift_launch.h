@@ -60,7 +60,7 @@ struct DecodeArgs {
   float* part_o;          // [B,Hq,nparts,D] unnormalised partial outputs
   float* part_ml;         // [B,Hq,nparts,2] running max (raw score units) and row sum of each partial
   int bitmap_words, B, Hq, Hkv, Nkv, split_blocks, nsplit;
-  int nparts;             // partial slots per (sequence, query head): 4 per partition + 1 for a partly filled last block
+  int nparts;             // partial slots per (sequence, query head): 1 per partition + 1 for a partly filled last block
   int nmerge;             // slots the merge reads (the last one only when lengths were given)
   float scale;
   thrift_dtype dt, out_dt;

@@ -82,19 +82,33 @@ struct RowState {
 // 2h + kk in MFMA kk (any split works as long as K and Q agree): the lane's two K scale bytes are then
 // neighbours in the [key][d-group] scale row and arrive with one 16-bit LDS read, byte kk for MFMA kk.
 // qf: the lane's two Q fragments (d-groups 2*half + kk), qsc: its Q scale bytes, byte kk for fragment kk.
-__device__ __forceinline__ void scores_fp4(const unsigned char* lds, int lane, const v4i (&qf)[2], uint32_t qsc, v16f (&s)[2]) {
+struct K4Tile {
+  v4i a[4];            // fragment (t, kk) at index 2t + kk
+  uint32_t ks[2];      // the lane's two K scale bytes of sub-tile t
+};
+__device__ __forceinline__ K4Tile load_k4(const unsigned char* lds, int lane) {
   const int half = lane >> 5, r = lane & 31;
   const unsigned char* ksrow = lds + kLdsKS + 4 * key_of_row(r, 0) + 2 * half;   // sub-tile 1: 16 keys = 64 bytes further
+  K4Tile k;
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    const uint32_t ksw = *reinterpret_cast<const uint16_t*>(ksrow + 64 * t);
-    const v4i a0 = *reinterpret_cast<const v4i*>(lds + kLdsK4 + ((t * 2 + 0) * 64 + lane) * 16);
-    const v4i a1 = *reinterpret_cast<const v4i*>(lds + kLdsK4 + ((t * 2 + 1) * 64 + lane) * 16);
+    k.ks[t] = *reinterpret_cast<const uint16_t*>(ksrow + 64 * t);
+    k.a[2 * t] = *reinterpret_cast<const v4i*>(lds + kLdsK4 + ((t * 2 + 0) * 64 + lane) * 16);
+    k.a[2 * t + 1] = *reinterpret_cast<const v4i*>(lds + kLdsK4 + ((t * 2 + 1) * 64 + lane) * 16);
+  }
+  return k;
+}
+__device__ __forceinline__ void scores_fp4_regs(const K4Tile& k, const v4i (&qf)[2], uint32_t qsc, v16f (&s)[2]) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
     v16f acc = {0.f};
-    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a0), widen(qf[0]), acc, 4, 4, 0, ksw, 0, qsc);
-    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(a1), widen(qf[1]), acc, 4, 4, 1, ksw, 1, qsc);
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(k.a[2 * t]), widen(qf[0]), acc, 4, 4, 0, k.ks[t], 0, qsc);
+    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(k.a[2 * t + 1]), widen(qf[1]), acc, 4, 4, 1, k.ks[t], 1, qsc);
     s[t] = acc;
   }
+}
+__device__ __forceinline__ void scores_fp4(const unsigned char* lds, int lane, const v4i (&qf)[2], uint32_t qsc, v16f (&s)[2]) {
+  scores_fp4_regs(load_k4(lds, lane), qf, qsc, s);
 }
 
 // S^T for a 16-bit tile.  ktile: the swizzled [64 keys][256 B] LDS tile; qf[s8]: the lane's query
@@ -235,10 +249,11 @@ __device__ __forceinline__ v4i quantize_p_group(const v16f (&p)[2], uint32_t pb)
   return pq;
 }
 
+// O^T += V^T . P^T for a group of P already quantised (pq: quantize_p_group's codes).
 template <bool PACKED>
-__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], uint32_t pb, uint32_t vs0, uint32_t vs1, uint32_t vs2,
-                                            uint32_t vs3, v4i v0, v4i v1, v4i v2, v4i v3, v16f (&o)[4]) {
-  const v8i pb8 = widen(quantize_p_group(p, pb));
+__device__ __forceinline__ void pv_fp4_codes_regs(v4i pq, uint32_t pb, uint32_t vs0, uint32_t vs1, uint32_t vs2, uint32_t vs3,
+                                                  v4i v0, v4i v1, v4i v2, v4i v3, v16f (&o)[4]) {
+  const v8i pb8 = widen(pq);
   if (PACKED) {
     o[0] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v0), pb8, o[0], 4, 4, 0, vs0, 0, pb);
     o[1] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(v1), pb8, o[1], 4, 4, 1, vs0, 0, pb);
@@ -252,31 +267,44 @@ __device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], uint32_t pb, uin
   }
 }
 
-// The same with V^T fragments and scales taken from a staged LDS slot.
-__device__ __forceinline__ void pv_fp4(const unsigned char* slot, int lane, const v16f (&p)[2], uint32_t pb, v16f (&o)[4]) {
+template <bool PACKED>
+__device__ __forceinline__ void pv_fp4_regs(const v16f (&p)[2], uint32_t pb, uint32_t vs0, uint32_t vs1, uint32_t vs2,
+                                            uint32_t vs3, v4i v0, v4i v1, v4i v2, v4i v3, v16f (&o)[4]) {
+  pv_fp4_codes_regs<PACKED>(quantize_p_group(p, pb), pb, vs0, vs1, vs2, vs3, v0, v1, v2, v3, o);
+}
+
+// The same with V^T fragments and scales taken from a staged LDS slot: from the codes, or from the probabilities.
+__device__ __forceinline__ void pv_fp4_codes(const unsigned char* slot, int lane, v4i pq, uint32_t pb, v16f (&o)[4]) {
   const int half = lane >> 5, r = lane & 31;
   const unsigned char* vs = slot + kLdsVS + half * kD + r;
   const unsigned char* vbase = slot + kLdsV4 + lane * 16;
-  pv_fp4_regs<false>(p, pb, vs[0], vs[32], vs[64], vs[96], *reinterpret_cast<const v4i*>(vbase),
-                     *reinterpret_cast<const v4i*>(vbase + 1024), *reinterpret_cast<const v4i*>(vbase + 2048),
-                     *reinterpret_cast<const v4i*>(vbase + 3072), o);
+  pv_fp4_codes_regs<false>(pq, pb, vs[0], vs[32], vs[64], vs[96], *reinterpret_cast<const v4i*>(vbase),
+                           *reinterpret_cast<const v4i*>(vbase + 1024), *reinterpret_cast<const v4i*>(vbase + 2048),
+                           *reinterpret_cast<const v4i*>(vbase + 3072), o);
+}
+__device__ __forceinline__ void pv_fp4(const unsigned char* slot, int lane, const v16f (&p)[2], uint32_t pb, v16f (&o)[4]) {
+  pv_fp4_codes(slot, lane, quantize_p_group(p, pb), pb, o);
 }
 
 // 16-bit P.V (Alg. 1 step 13): P rounded to the input dtype; V^T fragments come straight out of the
 // row-major LDS tile `vtile` through the transposing 64-bit LDS read (each 16-lane group turns a
 // 4-key x 16-channel patch into 4 consecutive keys of one channel per lane).  SWZ: the tile has unpadded
 // 256-byte rows with swizzled chunks (v16_swizzle), otherwise rows of kRow16 bytes.
-template <typename T, bool SWZ>
-__device__ __forceinline__ void pv_16(const unsigned char* vtile, int lane, const v16f (&p)[2], v16f (&o)[4]) {
-  const int half = lane >> 5, r = lane & 31, g = r >> 4, i16 = r & 15;
-  constexpr int kRow = SWZ ? 2 * kD : kRow16;
-  v8s pf[4];
+// P rounded to the input dtype, in the B-operand order of the 16-bit P.V MFMAs (slot group s = keys 8s .. 8s+7 of the lane's 32).
+template <typename T>
+__device__ __forceinline__ void round_p16(const v16f (&p)[2], v8s (&pf)[4]) {
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     const int t = s >> 1, i0 = 8 * (s & 1);
 #pragma unroll
     for (int e = 0; e < 8; ++e) pf[s][e] = (short)T::from_float(p[t][i0 + e]);
   }
+}
+
+template <typename T, bool SWZ>
+__device__ __forceinline__ void pv_16_rounded(const unsigned char* vtile, int lane, const v8s (&pf)[4], v16f (&o)[4]) {
+  const int half = lane >> 5, r = lane & 31, g = r >> 4, i16 = r & 15;
+  constexpr int kRow = SWZ ? 2 * kD : kRow16;
   typedef v4s __attribute__((address_space(3))) * lds_v4s_ptr;
   // keys 32*half + 8*s + 4*u + (i16>>2), channels 32*n + 16*g + 4*(i16&3); the swizzle term of all these
   // rows is 4*((i16>>2)&3), which turns the 64-byte step of n into an XOR
@@ -293,6 +321,13 @@ __device__ __forceinline__ void pv_16(const unsigned char* vtile, int lane, cons
       o[n] = T::mfma(a, pf[s], o[n]);
     }
   }
+}
+
+template <typename T, bool SWZ>
+__device__ __forceinline__ void pv_16(const unsigned char* vtile, int lane, const v16f (&p)[2], v16f (&o)[4]) {
+  v8s pf[4];
+  round_p16<T>(p, pf);
+  pv_16_rounded<T, SWZ>(vtile, lane, pf, o);
 }
 
 }  // namespace thrift

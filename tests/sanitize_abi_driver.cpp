@@ -26,7 +26,7 @@ int main() {
   EXPECT(thrift_attn_prefill(fake, fake, fake, THRIFT_F16, fu, fu, fu, fu, fu, fu, fi, fi, 4, 1, 4, 2, 256, 128, 64, 64, 1, 0.f, nullptr, THRIFT_F16, nullptr, nullptr, 0, nullptr), THRIFT_ERR_NULL);
   EXPECT(thrift_attn_prefill_chunk(fake, fake, fake, THRIFT_F16, fu, fu, fu, fu, fu, fu, fi, fi, 4, 1, 4, 2, 256, 3, 256, 128, 64, 64, 1, 0.f, fake, THRIFT_F16, nullptr, nullptr, 0, nullptr), THRIFT_ERR_SHAPE);
   EXPECT(thrift_attn_prefill_ordered(fake, fake, fake, THRIFT_F16, fu, fu, fu, fu, fu, fu, fi, fi, 4, 1, 4, 2, 256, 0, 256, 128, 64, 64, 1, 9, 0.f, fake, THRIFT_F16, nullptr, nullptr, 0, nullptr), THRIFT_ERR_SHAPE);
-  EXPECT(thrift_attn_decode(fake, THRIFT_F16, fake, fake, fu, fu, fu, fu, ff, nullptr, 1, 4, 2, 1024, 128, 64, 0.05, -1, 6, 0.f, fake, THRIFT_F16, nullptr, nullptr, 0, fake, 1 << 30, nullptr), THRIFT_ERR_SHAPE);
+  EXPECT(thrift_attn_decode(fake, THRIFT_F16, fake, fake, fu, fu, fu, fu, ff, nullptr, 1, 4, 2, 1024, 128, 64, 0.05, -1, 0, 0.f, fake, THRIFT_F16, nullptr, nullptr, 0, fake, 1 << 30, nullptr), THRIFT_ERR_SHAPE);
   EXPECT(thrift_attn_decode(fake, THRIFT_F16, fake, fake, fu, fu, fu, fu, ff, nullptr, 1, 4, 2, 1024, 128, 64, 0.05, -1, 8, 0.f, fake, THRIFT_F16, nullptr, nullptr, 0, fake, 16, nullptr), THRIFT_ERR_WORKSPACE);
   EXPECT(thrift_attn_decode_shared(fake, THRIFT_F16, fake, fake, fu, fu, fu, fu, ff, nullptr, 1, 4, 2, 1024, 128, 64, 2.0, -1, 8, 0.f, fake, THRIFT_F16, nullptr, nullptr, 0, fake, 1 << 30, nullptr), THRIFT_ERR_BUDGET);
   EXPECT(thrift_attn_decode_static(fake, THRIFT_F16, fake, fake, fu, fu, fu, fu, ff, nullptr, 4096, 4, 2, 131072, 128, 64, 0.05, -1, 256, 0.f, fake, THRIFT_F16, nullptr, nullptr, 0, nullptr), THRIFT_ERR_WORKSPACE);

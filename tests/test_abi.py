@@ -66,7 +66,7 @@ def test_validation_errors_come_before_any_launch():
     dec = lambda **kw: L.thrift_attn_decode(fake, 0, fake, fake, fake, fake, fake, fake, fake, None, 1, 4, 2, kw.get("N", 1024), 128, 64,
                                             C.c_double(kw.get("budget", 0.05)), -1, kw.get("split", 8), C.c_float(0.0), fake, 0,
                                             None, None, 0, kw.get("ws", fake), kw.get("wsb", 1 << 30), None)
-    assert dec(split=0) == SHAPE and dec(split=6) == SHAPE and dec(N=1000) == SHAPE
+    assert dec(split=0) == SHAPE and dec(N=1000) == SHAPE
     assert dec(budget=2.0) == BUDGET
     assert dec(ws=None) == WORKSPACE and dec(wsb=16) == WORKSPACE
     app = lambda **kw: L.thrift_kv_cache_append(kw.get("k", fake), fake, kw.get("dt", 0), kw.get("n", 1), kw.get("sl", fake), None,

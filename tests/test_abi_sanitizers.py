@@ -12,7 +12,10 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 CSRC = os.path.join(ROOT, "paper_2605_23081_amd", "csrc")
-KERNEL_OBJECTS = ["thrift_prepass.o", "thrift_prefill.o", "thrift_decode.o", "thrift_cache.o"]
+from paper_2605_23081_amd.build import SOURCES
+
+# every object of the library except the C ABI itself, which this test compiles with the sanitizers on its host side
+KERNEL_OBJECTS = [src.replace(".hip", ".o") for src in SOURCES if src != "thrift_api.hip"]
 CLANGXX = "/opt/rocm/lib/llvm/bin/clang++"
 
 

@@ -229,9 +229,8 @@ def _decode_case(T, oracle, wl, budget, split_blocks, seqlens=None, fixed_k=-1):
         tkb = Tk if sl is None else sl[b] // wl.Bk
         i_b, c_b = oracle.select_topk(qm[b:b + 1], km[b:b + 1, :, :tkb], 1, wl.Bk, False, budget, fixed_k)
         idx_r[b, :, :i_b.shape[-1]] = i_b[0, :, 0]; cnt_r[b] = c_b[0, :, 0]
-    # the library runs each partition as four consecutive sub-partitions (one per wavefront): split-K
-    # with partitions of split_blocks / 4 key blocks
-    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, scale, split_blocks // 4, seqlens=sl)
+    # one recurrence of Alg. 1 per partition of split_blocks key blocks, on both sides
+    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, scale, split_blocks, seqlens=sl)
     kg, vg = k.cuda(), v.cuda()
     k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
     kmean = T.thrift_block_means(kg, wl.Bk)
@@ -257,11 +256,10 @@ def test_decode_parity(T, oracle, budget):
     assert err <= (TOL16 if budget == 1.0 else TOLMIX)
 
 
-def test_decode_against_the_partition_size_as_stated(T, oracle):
-    """split_blocks names the key blocks per partition.  The kernel evaluates a partition as four consecutive quarters
-    (exact agreement with the oracle at that granularity is what the other decode tests check); against the oracle with
-    one recurrence per stated partition the result differs only by where the 4-bit rounding of P restarts, and must
-    meet the mixed-output bar."""
+def test_decode_partition_sizes(T, oracle):
+    """split_blocks names the key blocks per partition: one recurrence of Alg. 1 per partition, partitions merged by
+    log-sum-exp.  Sizes that are not multiples of four, a size larger than the cache (one partition), and the size of
+    the benchmark configuration."""
     wl = W.scaled(W.DECODE_131K, B=2, N=8192, Hq=8, Hkv=2)
     q, k, v = W.make_decode(wl)
     qb, dt = oracle.bits_of(q); kb, _ = oracle.bits_of(k); vb, _ = oracle.bits_of(v)
@@ -271,13 +269,13 @@ def test_decode_against_the_partition_size_as_stated(T, oracle):
     kg, vg = k.cuda(), v.cuda()
     k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
     kmean = T.thrift_block_means(kg, wl.Bk)
-    for split in (32, 128):
-        idx_r, cnt_r = oracle.select_topk(qm, km, 1, wl.Bk, False, 0.05)
-        idx_r, cnt_r = idx_r[:, :, 0], cnt_r[:, :, 0]
+    idx_r, cnt_r = oracle.select_topk(qm, km, 1, wl.Bk, False, 0.05)
+    idx_r, cnt_r = idx_r[:, :, 0], cnt_r[:, :, 0]
+    for split in (1, 3, 7, 32, 128, 256):
         got = to_np(T.thrift_attn_decode(q.cuda(), kg, vg, k4, ks, v4, vs, kmean, wl.Bk, 0.05, split_blocks=split, out_dtype=torch.float32))
-        stated = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, scale, split)
-        err = np.abs(got - stated).max()
-        _say(f"decode split_blocks={split}: max abs err against the oracle at {split} blocks per partition {err:.3e}")
+        want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, scale, split)
+        err = np.abs(got - want).max()
+        _say(f"decode split_blocks={split}: max abs err {err:.3e}")
         assert err <= TOLMIX
 
 
@@ -519,7 +517,7 @@ def test_decode_shared_selection(T, oracle, budget):
     qm = q.float().numpy().reshape(B, Hq, 1, wl.D)
     idx_r, cnt_r = oracle.select_topk(qm, km, 1, wl.Bk, False, budget, group_shared=True)
     idx_r, cnt_r = idx_r[:, :, 0], cnt_r[:, :, 0]
-    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, 1 / math.sqrt(wl.D), 16 // 4)
+    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, wl.Bk, 1 / math.sqrt(wl.D), 16)
     kg, vg = k.cuda(), v.cuda()
     k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
     kmean = T.thrift_block_means(kg, wl.Bk)
@@ -749,7 +747,7 @@ def test_decode_at_any_length(T, oracle, budget, shared):
             sc = np.repeat(sc.reshape(Hkv, Hq // Hkv, -1).sum(1), Hq // Hkv, axis=0)
         scores[b, :, :sc.shape[-1]] = sc
     sl = np.asarray(lens, np.int32)
-    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, 64, 1 / math.sqrt(wl.D), split // 4, seqlens=sl)
+    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, 64, 1 / math.sqrt(wl.D), split, seqlens=sl)
     got, idx_g, cnt_g = T.thrift_attn_decode(q.cuda(), cache.k16, cache.v16, cache.k4, cache.ks, cache.v4, cache.vs, cache.kmean,
                                              64, budget, -1, split, seqlens=cache.seqlens, out_dtype=torch.float32,
                                              return_selection=True, group_shared=shared)
@@ -897,7 +895,7 @@ def test_decode_random_shapes(T, oracle, case):
         if shared:
             sc = np.repeat(sc.reshape(Hkv, Hq // Hkv, -1).sum(1), Hq // Hkv, axis=0)
         scores[b, :, :sc.shape[-1]] = sc
-    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, 64, 1 / math.sqrt(wl.D), split // 4, seqlens=np.asarray(lens, np.int32))
+    want = oracle.attn_thrift_decode(qb, kb, vb, dt, idx_r, cnt_r, 64, 1 / math.sqrt(wl.D), split, seqlens=np.asarray(lens, np.int32))
     got, idx_g, cnt_g = T.thrift_attn_decode(q.cuda(), cache.k16, cache.v16, cache.k4, cache.ks, cache.v4, cache.vs, cache.kmean,
                                              64, budget, -1, split, seqlens=cache.seqlens, out_dtype=torch.float32,
                                              return_selection=True, group_shared=shared)
