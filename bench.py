@@ -231,6 +231,12 @@ def main() -> int:
                                                              Bq, Bk, True, 0, out=plan.out, tile_order=other_order), 3)
         result["prefill"]["other_tile_order"] = {"order": ORDER_NAMES[other_order], "ms_fused_kernel": round(ms_other, 3),
                                                  "kernel_tflops": round(flops / (ms_other * 1e-3) / 1e12, 2)}
+        if args.tile_order == 1:
+            # the same tile order from a persistent launch (three workgroups per CU taking items from a device counter)
+            ms_pers = timed(lambda: T.thrift_attn_prefill_chunk(q, k, v, plan.q4, plan.qs, plan.k4, plan.ks, plan.v4, plan.vs, plan.idx, plan.cnt,
+                                                                Bq, Bk, True, 0, out=plan.out, tile_order=4), 3)
+            result["prefill"]["persistent_launch"] = {"ms_fused_kernel": round(ms_pers, 3), "kernel_tflops": round(flops / (ms_pers * 1e-3) / 1e12, 2),
+                                                      "note": "tile_order 4: same arithmetic, items from a device counter instead of one workgroup per item"}
         sweep = {}
         for f in (0.10, 0.25):
             p2 = T.PrefillPlan(B, Hq, Hkv, N, D, Bq, Bk, True, f, q.dtype, dev, tile_order=args.tile_order)

@@ -221,6 +221,12 @@ thrift_status thrift_attn_prefill_chunk(const void* q, const void* k, const void
  *                 workgroups per CU, every block a whole step ahead and the 16-bit query rows in registers,
  *                 Bq = 128 only, else it falls back to 2).  0 picks 3 when kmax is at least 15 % of the key
  *                 blocks, where the promoted blocks dominate the time.  The results of 0, 2 and 3 are bit-identical.
+ *   tile_order 4: the order of 1 from a persistent launch: as many workgroups as the device holds at once (three
+ *                 per CU) take the (head, query block) items, heaviest first, from a counter in device memory
+ *                 instead of one workgroup being launched per item.  Bit-identical to 1; Bq = 128 only, else it
+ *                 is 1.  The counter is one per device: two launches with tile_order 4 must not overlap on a device.
+ *                 (Measured slower than 1 on the 131k layer: the hardware dispatcher already hands out the
+ *                 heaviest-first launch order dynamically.  Kept for measurement.)
  * Other values: THRIFT_ERR_SHAPE.
  */
 thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const void* v, thrift_dtype dt,

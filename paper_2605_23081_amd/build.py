@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -27,18 +28,24 @@ def scratch_in_loops(asm_text: str):
     same in-order memory queue and wait for those transfers at every block.  A spill that is stored before the
     walk and reloaded after it costs nothing.  The compiler's listing marks every basic block that belongs to a
     loop in the comment of its label line."""
-    bad, kernel, in_loop = set(), None, False
+    bad, kernel, depth = set(), None, 0
     kernels, blocks, loop_blocks = 0, 0, 0
     for line in asm_text.splitlines():
         t = line.strip()
         if t.startswith("_Z") and t.split(":")[0].isidentifier() and ":" in t:
-            kernel, in_loop = t.split(":")[0], False
+            kernel, depth = t.split(":")[0], 0
             kernels += 1
         elif t.startswith(".LBB") or t.startswith("; %bb."):
-            in_loop = "Loop" in t
+            depths = [int(d) for d in re.findall(r"Depth=(\d+)", t)]
+            depth = max(depths) if depths else 0
             blocks += 1
-            loop_blocks += in_loop
-        elif t.startswith("scratch_") and in_loop and kernel:
+            loop_blocks += depth > 0
+        elif t.startswith(";") and "Loop" in t and "Depth=" in t:
+            # continuation lines of a label's comment: a nested loop's header names its parent first, itself below
+            depth = max([depth] + [int(d) for d in re.findall(r"Depth=(\d+)", t)])
+        elif t.startswith("scratch_") and kernel and depth >= (2 if "persistent" in kernel else 1):
+            # in a persistent kernel the outermost loop is the loop over work items: a reload at an item's start or end
+            # is outside the walk over the key blocks, like a reload before or after the walk of the other kernels
             bad.add(kernel)
     # The labels are the compiler's listing format, not a stable interface: a listing in which no kernel, no basic
     # block or no loop annotation is recognised cannot be checked and must not pass for clean.

@@ -269,7 +269,7 @@ thrift_status thrift_attn_prefill_ordered(const void* q, const void* k, const vo
                                           void* out, thrift_dtype out_dt, float* lse,
                                           void* workspace, size_t workspace_bytes, void* stream) {
   (void)workspace; (void)workspace_bytes;
-  if (tile_order < 0 || tile_order > 3) return THRIFT_ERR_SHAPE;
+  if (tile_order < 0 || tile_order > 4) return THRIFT_ERR_SHAPE;
   if (!q || !k || !v || !q4 || !qs || !k4 || !ks || !v4 || !vs || !idx || !cnt || !out) return THRIFT_ERR_NULL;
   if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0 || Nq <= 0 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock ||
@@ -423,7 +423,7 @@ thrift_status thrift_attention_forward(const void* q, const void* k, const void*
   if (!q || !k || !v || !out) return THRIFT_ERR_NULL;
   if (!is16(dt) || !is_out(out_dt)) return THRIFT_ERR_DTYPE;
   if (!fused_shape_ok(B, Hq, Hkv, N, D, Bq, Bk)) return THRIFT_ERR_SHAPE;
-  if (tile_order < 0 || tile_order > 3) return THRIFT_ERR_SHAPE;          // before the first stage is enqueued
+  if (tile_order < 0 || tile_order > 4) return THRIFT_ERR_SHAPE;          // before the first stage is enqueued
   if (fixed_k < 0 && !(budget >= 0.0 && budget <= 1.0)) return THRIFT_ERR_BUDGET;
   const FusedLayout L = fused_layout(B, Hq, Hkv, N, Bq, Bk, causal, budget, fixed_k);
   if (!workspace || workspace_bytes < L.total || ((uintptr_t)workspace & 255) != 0) return THRIFT_ERR_WORKSPACE;

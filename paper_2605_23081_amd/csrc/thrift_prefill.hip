@@ -38,12 +38,13 @@ constexpr int kWideSlot = 2 * kTile16;                       // 32768
 constexpr int kLdsPrefillWide = 2 * kWideSlot;               // 65536: two workgroups per CU
 constexpr int kWidePercent = 15;                             // list length / key blocks (in %) from which the wide schedule is used
 
+// One work item: a (sequence, query head, query block) and all its key blocks.  `work` is the item's position in the
+// launch order (what blockIdx.x is in the one-item-per-workgroup launch).
 template <typename T, int NW, int ORDER, int WIDE>
-__global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillArgs a) {
+__device__ __forceinline__ void prefill_item(const PrefillArgs& a, unsigned char* lds, unsigned work) {
   constexpr int KF = 4 / NW;                 // 1 KiB fragments of a 4-bit K (and of a V) tile per wavefront
   constexpr int C16 = 16 / NW;               // ... for one 16-bit K or V tile
   constexpr int kSlotStride = WIDE ? kWideSlot : kLdsBytes4;
-  __shared__ __align__(1024) unsigned char lds[WIDE ? kLdsPrefillWide : kLdsPrefill];
 
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: loop bounds stay scalar
@@ -55,12 +56,12 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
   const int units = a.B * a.Hkv, per_unit = G * Tq;
   int unit, within;
   if ((units & 7) == 0) {
-    const int xcd = blockIdx.x & 7, t = blockIdx.x >> 3;
+    const int xcd = work & 7, t = work >> 3;
     unit = xcd + 8 * (t / per_unit);
     within = t % per_unit;
   } else {
-    unit = blockIdx.x / per_unit;
-    within = blockIdx.x % per_unit;
+    unit = work / per_unit;
+    within = work % per_unit;
   }
   const int b = unit / a.Hkv, kvh = unit % a.Hkv;
   const int i = Tq - 1 - within / G;
@@ -531,6 +532,35 @@ __global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillA
 #undef THRIFT_ROW_AGAIN
 }
 
+template <typename T, int NW, int ORDER, int WIDE>
+__global__ void __launch_bounds__(NW * 64, WIDE ? 2 : 3) prefill_kernel(PrefillArgs a) {
+  __shared__ __align__(1024) unsigned char lds[WIDE ? kLdsPrefillWide : kLdsPrefill];
+  prefill_item<T, NW, ORDER, WIDE>(a, lds, blockIdx.x);
+}
+
+// The same items from a persistent launch: as many workgroups as the chip holds at once, each taking the next item
+// (heaviest first, like the launch order above) from a device counter until none is left.  An item of this kernel
+// leaves no DMA in flight and the barriers below keep the LDS of one item apart from the next.
+static __device__ unsigned int prefill_next_item[64];       // one counter per launch in flight would be needed: see launch_prefill
+
+__global__ void prefill_reset_counter_kernel() { prefill_next_item[0] = 0u; }
+
+template <typename T, int NW, int ORDER>
+__global__ void __launch_bounds__(NW * 64, 3) prefill_persistent_kernel(PrefillArgs a, unsigned items) {
+  __shared__ __align__(1024) unsigned char lds[kLdsPrefill];
+  __shared__ unsigned next;
+  // the workgroup's position on its XCD decides nothing here: items keep the XCD of their KV head only while the
+  // counter hands consecutive items to consecutive workgroups, which it does at the start and loses later
+  for (;;) {
+    if (threadIdx.x == 0) next = atomicAdd(&prefill_next_item[0], 1u);
+    __syncthreads();
+    const unsigned work = next;
+    __syncthreads();
+    if (work >= items) break;
+    prefill_item<T, NW, ORDER, 0>(a, lds, work);
+  }
+}
+
 // The wide schedule pays for itself once promoted blocks are frequent: their 32 KiB of 16-bit tiles then
 // arrive a whole step ahead instead of half a step, at the price of two instead of three workgroups per CU
 // for the 4-bit blocks.  The per-row list length bounds the promoted share from above.
@@ -543,9 +573,20 @@ static bool wide_schedule(const PrefillArgs& a) {
 
 void launch_prefill(const PrefillArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((long)a.B * a.Hq * ((a.Nq + a.Bq - 1) / a.Bq));
+  if (a.tile_order == 4 && a.Bq == 128) {
+    // persistent launch of the Sec. 3.3 order: three workgroups per CU.  One counter per device: two such launches
+    // must not overlap on a device.  The counter is cleared by a kernel (a memset node misbehaves under graph capture).
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const unsigned resident = (unsigned)min((long)grid, 3L * cus);
+    prefill_reset_counter_kernel<<<dim3(1), dim3(1), 0, st>>>();
+    if (a.dt == THRIFT_F16) prefill_persistent_kernel<F16, 4, 1><<<dim3(resident), dim3(256), 0, st>>>(a, grid);
+    else prefill_persistent_kernel<BF16, 4, 1><<<dim3(resident), dim3(256), 0, st>>>(a, grid);
+    return;
+  }
 #define THRIFT_LAUNCH(T, NW)                                                                                   \
   do {                                                                                                         \
-    if (a.tile_order == 1) prefill_kernel<T, NW, 1, 0><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);               \
+    if (a.tile_order == 1 || a.tile_order == 4) prefill_kernel<T, NW, 1, 0><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);               \
     else prefill_kernel<T, NW, 0, 0><<<dim3(grid), dim3(NW * 64), 0, st>>>(a);                                 \
   } while (0)
   if (wide_schedule(a)) {

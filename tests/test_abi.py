@@ -128,6 +128,24 @@ def test_spill_check_reads_the_compiler_listing():
         "\ts_endpgm",
     ])
     assert scratch_in_loops(listing) == ["_ZN6thrift3badEv"]
+    # a persistent kernel's outermost loop runs over work items: a reload at an item's start is outside the walk, one in
+    # a nested loop (whose header line names the parent first and itself on the comment line below) is inside it
+    def persistent(name, reload_in_walk):
+        return "\n".join([
+            name + ":",
+            ".LBB2_1:                                ; =>This Loop Header: Depth=1",
+            "\tscratch_load_dword v1, off, off offset:8 ; 4-byte Folded Reload",
+            ".LBB2_2:                                ;   Parent Loop BB2_1 Depth=1",
+            "                                        ; =>  This Inner Loop Header: Depth=2",
+            "\tscratch_load_dword v2, off, off ; 4-byte Folded Reload" if reload_in_walk else "\tv_add_f32_e32 v0, v0, v1",
+            "\ts_cbranch_scc1 .LBB2_2",
+            "; %bb.3:                                ;   in Loop: Header=BB2_1 Depth=1",
+            "\ts_cbranch_scc1 .LBB2_1",
+            "\ts_endpgm",
+        ])
+    assert scratch_in_loops(persistent("_ZN6thrift17persistent_kernelEv", False)) == []
+    assert scratch_in_loops(persistent("_ZN6thrift17persistent_kernelEv", True)) == ["_ZN6thrift17persistent_kernelEv"]
+    assert scratch_in_loops(persistent("_ZN6thrift5otherEv", False)) == ["_ZN6thrift5otherEv"]
 
 
 def test_listing_checks_refuse_a_format_they_cannot_read():

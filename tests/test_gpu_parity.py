@@ -562,8 +562,14 @@ def test_prefill_two_phase_order(T, oracle, wl, budget, causal):
         asc = T.thrift_attn_prefill(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, out_dtype=torch.float32)
         torch.cuda.synchronize()
         assert torch.equal(asc, got)
+    # the same order from the persistent launch (items taken from a device counter): the same bits, twice in a row
+    for _ in range(2):
+        pers = T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0,
+                                           out_dtype=torch.float32, tile_order=4)
+        torch.cuda.synchronize()
+        assert torch.equal(pers, got)
     with pytest.raises(T.ThriftError) as e:
-        T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0, tile_order=4)
+        T.thrift_attn_prefill_chunk(qg, kg, vg, q4, qs, k4, ks, v4, vs, ig, cg, wl.Bq, wl.Bk, causal, 0, tile_order=5)
     assert e.value.code == 2
 
 
