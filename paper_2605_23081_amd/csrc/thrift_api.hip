@@ -477,6 +477,7 @@ thrift_status thrift_peak_probe(int kind, thrift_dtype dt, int iters, void* buff
   if (((uintptr_t)buffer & 15) != 0) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;
   *work = launch_peak_probe(kind, dt, iters, buffer, bytes, (hipStream_t)stream);
+  if (*work < 0.0) return THRIFT_ERR_SHAPE;               // a buffer the probe cannot cover in one launch: nothing was launched
   return after_launch();
 }
 

@@ -56,7 +56,6 @@ constexpr int kDppQuadHi = 0xee;       // quad_perm [2,3,2,3]: lanes 0,1 of a qu
 constexpr int kDppHalfMirror = 0x141;  // lane i of each 8 reads lane 7 - i
 constexpr int kDppMirror = 0x140;      // lane i of each 16 reads lane 15 - i
 constexpr int kDppShl4 = 0x104;        // lane i reads lane i + 4 of its 16-lane row
-constexpr int kDppShl8 = 0x108;        // lane i reads lane i + 8 of its 16-lane row
 
 // natural key order for the row layout: fragment (t, kk) of lane (half, r) = key 32t + r, d-group 2*half + kk
 __device__ __forceinline__ K4Tile load_k4_rows(const unsigned char* slot, int lane) {
@@ -71,38 +70,40 @@ __device__ __forceinline__ K4Tile load_k4_rows(const unsigned char* slot, int la
   }
   return k;
 }
-// Score of key `lane` of the block (Alg. 1 step 15 for the one-token query block).  qf / qsc: the query's fragments
-// and scale bytes in lanes r = 0 and r = 4, zeros elsewhere.
-__device__ __forceinline__ float scores4_row(const K4Tile& k, int lane, const v4i (&qf)[2], uint32_t qsc) {
-  float st[2];
+// Scores of key `lane` of the block for the wavefront's NH heads (Alg. 1 step 15 for the one-token query block).
+// qf / qsc: the fragments and scale bytes of head u in lanes r = u and r = u + 4 (u < 4), zeros elsewhere: accumulator
+// register u is then row u + 4*half, head u against key r.
+template <int NH>
+__device__ __forceinline__ void scores4_row(const K4Tile& k, int lane, const v4i (&qf)[2], uint32_t qsc, float (&sv)[NH]) {
+  v16f acc[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
-    v16f acc = {0.f};
-    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(qf[0]), widen(k.a[2 * t]), acc, 4, 4, 0, qsc, 0, k.ks[t]);
-    acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(qf[1]), widen(k.a[2 * t + 1]), acc, 4, 4, 1, qsc, 1, k.ks[t]);
-    st[t] = acc[0];
+    acc[t] = (v16f){0.f};
+    acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(qf[0]), widen(k.a[2 * t]), acc[t], 4, 4, 0, qsc, 0, k.ks[t]);
+    acc[t] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(qf[1]), widen(k.a[2 * t + 1]), acc[t], 4, 4, 1, qsc, 1, k.ks[t]);
   }
-  return (lane >> 5) ? st[1] : st[0];
+#pragma unroll
+  for (int u = 0; u < NH; ++u) sv[u] = (lane >> 5) ? acc[1][u] : acc[0][u];
 }
 // The same from the 16-bit K tile (Alg. 1 step 9).  Tile rows are keys in natural order, 256 B each, the 16-byte chunk c
 // of row `row` stored at chunk position c ^ (row & 7) (eight neighbouring lanes read eight different positions).
-// qf[s8]: the query's elements d = 16*s8 + 8*half + [0,8) in lanes r = 0 and r = 4, zeros elsewhere.
-template <typename T>
-__device__ __forceinline__ float scores16_row(const unsigned char* ktile, int lane, const v8s (&qf)[8]) {
+// qf[s8]: head u's elements d = 16*s8 + 8*half + [0,8) in lanes r = u and r = u + 4, zeros elsewhere.
+template <typename T, int NH>
+__device__ __forceinline__ void scores16_row(const unsigned char* ktile, int lane, const v8s (&qf)[8], float (&sv)[NH]) {
   const int half = lane >> 5, r = lane & 31;
-  float st[2];
+  v16f acc[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
     const unsigned char* row = ktile + (32 * t + r) * 256;
-    v16f acc = {0.f};
+    acc[t] = (v16f){0.f};
 #pragma unroll
     for (int s8 = 0; s8 < 8; ++s8) {
       const v8s kf = *reinterpret_cast<const v8s*>(row + 16 * ((2 * s8 + half) ^ (r & 7)));
-      acc = T::mfma(qf[s8], kf, acc);
+      acc[t] = T::mfma(qf[s8], kf, acc[t]);
     }
-    st[t] = acc[0];
   }
-  return half ? st[1] : st[0];
+#pragma unroll
+  for (int u = 0; u < NH; ++u) sv[u] = half ? acc[1][u] : acc[0][u];
 }
 // Online softmax of Alg. 1 (steps 10-12 / 16-17) on the row layout: sv = this lane's raw score.  st.m is the running
 // maximum (the same in every lane), st.l this lane's share of the row sum.  Returns (for the whole wavefront) whether
@@ -142,9 +143,11 @@ __device__ __forceinline__ bool softmax_row(float sv, float c, RowState& st, flo
   return grew;
 }
 // Alg. 1 step 19 on the row layout: every lane turns its probability into an E2M1 code under its group's scale and the
-// 32 codes of a group are collected, in key order, into the four registers of lane 0 (keys 0-31) / lane 32 (keys 32-63);
-// the other lanes end up with codes that belong to no query (their MFMA columns are never stored).
+// 32 codes of a group are collected, in key order, into the four registers of lane U (keys 0-31) / lane 32 + U (keys
+// 32-63), the B-operand column of head U; what the other lanes receive belongs to no query.
+template <int U>
 __device__ __forceinline__ v4i gather_p4(float p, uint32_t pb) {
+  static_assert(U >= 0 && U < 4, "the head's column must lie in the first four lanes");
   const float pscale = __uint_as_float(pb << 23);
   const float nb = dpp_f<kDppSwap1>(p);
   // even lanes: one byte = the codes of keys (lane, lane + 1)
@@ -152,8 +155,11 @@ __device__ __forceinline__ v4i gather_p4(float p, uint32_t pb) {
   const uint32_t b16 = b8 | (dpp_u<kDppQuadHi>(b8) << 8);          // lanes 4q: keys 4q .. 4q+3
   const uint32_t b32 = b16 | (dpp_u<kDppShl4>(b16) << 16);         // lanes 8q: keys 8q .. 8q+7
   const auto sw = __builtin_amdgcn_permlane16_swap(b32, b32, false, false);
-  // lane 0 of a 32: sw[0] = its own word (keys 0-7), sw[1] = lane 16's (keys 16-23); lane 8: keys 8-15 and 24-31
-  return (v4i){(int)sw[0], (int)dpp_u<kDppShl8>(sw[0]), (int)sw[1], (int)dpp_u<kDppShl8>(sw[1])};
+  // lane 0 of a 32: sw[0] = its own word (keys 0-7), sw[1] = lane 16's (keys 16-23); lane 8: keys 8-15 and 24-31.
+  // Lane U reads lane 0 (a shift right by U) and lane 8 (a shift left by 8 - U) of its 16.
+  constexpr int kFrom0 = 0x110 | U, kFrom8 = 0x100 | (8 - U);
+  if constexpr (U == 0) return (v4i){(int)sw[0], (int)dpp_u<kFrom8>(sw[0]), (int)sw[1], (int)dpp_u<kFrom8>(sw[1])};
+  else return (v4i){(int)dpp_u<kFrom0>(sw[0]), (int)dpp_u<kFrom8>(sw[0]), (int)dpp_u<kFrom0>(sw[1]), (int)dpp_u<kFrom8>(sw[1])};
 }
 // Alg. 1 step 13 on the row layout: the probabilities rounded to the input dtype and collected through a 128-byte LDS
 // row of the wavefront's own: pf[s] of lane (half, *) = keys 32*half + 8s .. + 7 (the order pv_16_rounded contracts in).
@@ -175,16 +181,19 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x + other_half(x);
 }
 
-// MULTI = false: at most one head per wavefront (a group of up to four heads, the usual GQA ratios): the path of a
-// block is a wavefront-uniform choice and the 16-bit query fragments stay in registers.  MULTI = true: up to eight heads
-// per wavefront, which may split over the two paths of a block: both tiles are computed and each lane keeps its own
-// head's; the 16-bit query fragments are re-read at each promoted block (that instantiation has no registers to spare).
-template <typename T, bool MULTI>
-__global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(DecodeArgs a) {
+// HPW = 1 or 2: at most HPW heads per wavefront (groups of up to 4 / 8 heads, the usual GQA ratios), in the row layout;
+// the path of a block is a scalar choice per head.  HPW = 0: up to eight heads per wavefront in the transposed tiles of
+// the prefill kernel (head wave + 4r in column r), which cost a wavefront instruction per score and key but no more for
+// eight heads than for one; the heads may split over the two paths of a block, both tiles are then computed and each
+// lane keeps its own head's.
+template <typename T, int HPW>
+__global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(DecodeArgs a) {
+  constexpr bool MULTI = HPW == 0;
+  constexpr int NH = MULTI ? 1 : HPW;
   __shared__ __align__(1024) unsigned char lds[kDecLds];
   __shared__ unsigned long long bmw[32 * kBmWin];              // [head of the group][word of the window]
-  __shared__ __align__(16) uint16_t qrow[MULTI ? 8 : 4 * kD];  // !MULTI: the 16-bit query row of each wavefront's head
-  __shared__ __align__(16) uint16_t prow[MULTI ? 8 : 4 * 64];  // !MULTI: a row of rounded probabilities per wavefront
+  __shared__ __align__(16) uint16_t qrow[MULTI ? 8 : 4 * NH * kD];   // row layout: the 16-bit query rows of each wavefront's heads
+  __shared__ __align__(16) uint16_t prow[MULTI ? 8 : 4 * 64];        // row layout: a row of rounded probabilities per wavefront
   const int tid = threadIdx.x, lane = tid & 63, half = lane >> 5, r = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform
   const int G = a.Hq / a.Hkv;
@@ -199,7 +208,7 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
   const int my_heads = G > wave ? (G - wave + 3) / 4 : 0;
   const bool real = r < my_heads;
   const size_t group0 = (size_t)b * a.Hq + (size_t)kvh * G;    // first query head of the group
-  const size_t qh = group0 + (MULTI ? (real ? wave + 4 * r : 0) : (my_heads > 0 ? wave : 0));   // one head: every lane's
+  const size_t qh = group0 + (real ? wave + 4 * r : 0);       // the head whose result this lane stores (column r)
   const size_t kh = (size_t)b * a.Hkv + kvh;
   const unsigned long long my_mask = my_heads >= 32 ? 0xffffffffULL : ((1ULL << my_heads) - 1ULL);
 
@@ -209,13 +218,15 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
   v4i qf4[2] = {(v4i){0, 0, 0, 0}, (v4i){0, 0, 0, 0}};
   uint32_t qsc = 0x7f7f7f7fu;
   const uint16_t* q16row = a.q + qh * kD + 8 * half;
-  // lanes that carry the query: its column in the transposed tiles, or rows 0 and 4 of the row layout
-  const bool qlane = MULTI ? real : (my_heads > 0 && (r == 0 || r == 4));
+  // lanes that carry a query as an MFMA operand: its column in the transposed tiles; rows u and u + 4 for head u of
+  // the row layout
+  const bool qlane = MULTI ? real : (r < 8 && (r & 3) < min(my_heads, NH));
+  const size_t qhq = MULTI ? qh : group0 + (qlane ? wave + 4 * (r & 3) : 0);
   if (qlane) {
     uint32_t sb[2];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
-      const uint4* src = reinterpret_cast<const uint4*>(a.q + qh * kD + 64 * half + 32 * kk);
+      const uint4* src = reinterpret_cast<const uint4*>(a.q + qhq * kD + 64 * half + 32 * kk);
       uint32_t pair[16], codes[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
@@ -227,14 +238,14 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
     }
     qsc = sb[0] | (sb[1] << 8);                              // byte kk: the scale of fragment kk
   }
-  // !MULTI: the 16-bit row of the wavefront's head is parked in LDS (each wavefront writes and reads only its own row)
-  // and read back at each promoted block: a global read inside the walk would wait for every tile DMA in flight, and
-  // the walk has no 32 registers to spare for it.
+  // Row layout: the 16-bit rows of the wavefront's heads are parked in LDS (each wavefront writes and reads only its own
+  // rows) and read back at each promoted block: a global read inside the walk would wait for every tile DMA in flight.
   if constexpr (!MULTI) {
-    if (lane < 16) {
+    if (lane < 16 * NH) {
+      const int u = lane >> 4;
       uint4 w = make_uint4(0u, 0u, 0u, 0u);
-      if (my_heads > 0) w = *reinterpret_cast<const uint4*>(a.q + (group0 + wave) * kD + 8 * lane);
-      *reinterpret_cast<uint4*>(qrow + wave * kD + 8 * lane) = w;
+      if (u < my_heads) w = *reinterpret_cast<const uint4*>(a.q + (group0 + wave + 4 * u) * kD + 8 * (lane & 15));
+      *reinterpret_cast<uint4*>(qrow + (wave * NH + u) * kD + 8 * (lane & 15)) = w;
     }
   }
 
@@ -307,28 +318,42 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
     return ((unsigned long long)hi << 32) | lo;
   };
   unsigned long long gor = 0;                           // group OR of word wcur
-  unsigned long long own_s = 0;                         // !MULTI: the word of this wavefront's one head (scalar)
-  unsigned long long own_v = 0;                         // MULTI: the word of this lane's head
+  unsigned long long own_s[NH];                         // row layout: the words of this wavefront's heads (scalar)
+#pragma unroll
+  for (int u = 0; u < NH; ++u) own_s[u] = 0ULL;
+  unsigned long long own_v = 0;                         // transposed tiles: the word of this lane's head
   // Flags of block x of the partition (x may run past the end: all clear): bit 0 of the result = some head of the
-  // group has promoted it (wavefront-uniform); mine = this lane's head has.  Blocks are asked for in ascending order.
-  auto flags = [&](int x, bool& mine) -> int {
-    mine = false;
+  // group has promoted it (wavefront-uniform); mine = this lane's head has (transposed tiles) / bit u = head u of this
+  // wavefront has (row layout, scalar).  Blocks are asked for in ascending order.
+  using Mine = std::conditional_t<MULTI, bool, int>;
+  auto flags = [&](int x, Mine& mine) -> int {
+    mine = Mine(0);
     if (x >= n) return 0;
     const int j = j_begin + x, w = j >> 6;
     if (w != wcur) {
       if (w >= win0 + kBmWin || wcur < 0) refill(w);
       gor = 0;
       for (int g = 0; g < G; ++g) gor |= scalar_word(g * kBmWin + (w - win0));
-      if constexpr (MULTI) own_v = real ? bmw[(wave + 4 * r) * kBmWin + (w - win0)] : 0ULL;
-      else own_s = my_heads > 0 ? scalar_word(wave * kBmWin + (w - win0)) : 0ULL;
+      if constexpr (MULTI) {
+        own_v = real ? bmw[(wave + 4 * r) * kBmWin + (w - win0)] : 0ULL;
+      } else {
+#pragma unroll
+        for (int u = 0; u < NH; ++u) own_s[u] = u < my_heads ? scalar_word((wave + 4 * u) * kBmWin + (w - win0)) : 0ULL;
+      }
       wcur = w;
     }
-    if constexpr (MULTI) mine = ((own_v >> (j & 63)) & 1ULL) != 0ULL;
-    else mine = ((own_s >> (j & 63)) & 1ULL) != 0ULL;
+    if constexpr (MULTI) {
+      mine = ((own_v >> (j & 63)) & 1ULL) != 0ULL;
+    } else {
+#pragma unroll
+      for (int u = 0; u < NH; ++u) mine |= (int)((own_s[u] >> (j & 63)) & 1ULL) << u;
+    }
     return (int)((gor >> (j & 63)) & 1ULL);
   };
 
-  RowState st = {kEmptyMax, 0.f};
+  RowState st[NH];                                      // row layout: one per head; transposed tiles: this lane's column
+#pragma unroll
+  for (int u = 0; u < NH; ++u) st[u] = {kEmptyMax, 0.f};
   v16f o[4];
 #pragma unroll
   for (int nn = 0; nn < 4; ++nn) o[nn] = (v16f){0.f};
@@ -343,7 +368,7 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
   // promoted), otherwise at the step of its use, which then waits for it.
   // P?/M?: promoted-by-the-group / promoted-for-this-head flags of blocks t-1 (a), t (b), t+1 (c), t+2 (d). ----
   int Pa = 0, Pb = 0, Pc, Pd;
-  bool Mb = false, Mc, Md;
+  Mine Mb = Mine(0), Mc, Md;
   Pc = flags(0, Mc);
   Pd = flags(1, Md);
   if (Pc) issue16k(j_begin);
@@ -373,23 +398,34 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
     early_prev = earlyK | earlyV;
   };
   if constexpr (!MULTI) {
-    // ---- one head per wavefront: the row layout; its (scalar) selection bit decides the path of a block ----
-    // score of key `lane` of the block in ring slot `slot` / in the K tile buffer
-    auto score16 = [&]() -> float {
+    // ---- up to NH heads per wavefront in the row layout; the (scalar) selection bit of a head decides its path ----
+    const int all_heads = (1 << min(my_heads, NH)) - 1;          // mask of this wavefront's heads
+    // scores of key `lane` of the block in the K tile buffer, for every head
+    auto score16 = [&](float (&sv)[NH]) {
       // the lane-dependent LDS addresses of the 16-bit tiles are formed at the promoted block, from a copy of the lane
       // index the compiler cannot see through: formed once ahead of the walk they would occupy registers at every step
       int lane_ = lane;
       asm volatile("" : "+v"(lane_));
-      const int half_ = lane_ >> 5;
+      const int half_ = lane_ >> 5, r_ = lane_ & 31;
       v8s q16[8];
 #pragma unroll
       for (int s8 = 0; s8 < 8; ++s8)
-        q16[s8] = qlane ? *reinterpret_cast<const v8s*>(qrow + wave * kD + 16 * s8 + 8 * half_) : (v8s){0, 0, 0, 0, 0, 0, 0, 0};
-      return scores16_row<T>(lds + kDecLdsK16, lane_, q16);
+        q16[s8] = qlane ? *reinterpret_cast<const v8s*>(qrow + (wave * NH + (r_ & 3)) * kD + 16 * s8 + 8 * half_) : (v8s){0, 0, 0, 0, 0, 0, 0, 0};
+      scores16_row<T, NH>(lds + kDecLdsK16, lane_, q16, sv);
     };
-    float sv = 0.f;                                     // raw score of key `lane` of block t on entry to step t
+    // scores of block x (flags Mx) from its slot and / or the K tile buffer: each head keeps its own path's
+    auto scores = [&](int slot, int Mx, float (&sv)[NH]) {
+      float s4[NH], s16[NH];
+      if (Mx != all_heads) scores4_row<NH>(load_k4_rows(lds + slot * kLdsBytes4, lane), lane, qf4, qsc, s4);
+      if (Mx != 0) score16(s16);
+#pragma unroll
+      for (int u = 0; u < NH; ++u) sv[u] = ((Mx >> u) & 1) ? s16[u] : s4[u];
+    };
+    float sv[NH];                                       // raw score of key `lane` of block t on entry to step t, per head
+#pragma unroll
+    for (int u = 0; u < NH; ++u) sv[u] = 0.f;
     stage(-1);                                          // step -1: only the scores of block 0
-    if (my_heads > 0 && n > 0) sv = Mc ? score16() : scores4_row(load_k4_rows(lds + slot_c * kLdsBytes4, lane), lane, qf4, qsc);
+    if (my_heads > 0 && n > 0) scores(slot_c, Mc, sv);
     slot_a = slot_b; slot_b = slot_c; slot_c = 1;
     // One step; WITH_NEXT (a compile-time flag): block t+1 exists.
     auto step = [&](int t, auto with_next) {
@@ -401,26 +437,58 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
         constexpr bool kNext = decltype(with_next)::value;
         // the K fragments of a 4-bit block t+1 are asked for first and arrive while the softmax of block t runs; its
         // score MFMAs go between the quantisation and the P.V MFMAs of block t
-        const bool next4 = kNext && !Mc;
+        const bool next4 = kNext && Mc != all_heads, next16 = kNext && Mc != 0;
         K4Tile kt;
         if (next4) kt = load_k4_rows(lds + slot_c * kLdsBytes4, lane);
-        float alpha, p;
-        uint32_t pb;
-        const bool grew = softmax_row(sv, c, st, alpha, pb, p);
-        rescale(o, grew, alpha);
-        if (!Mb) {
-          const v4i pq = gather_p4(p, pb);
-          if (next4) sv = scores4_row(kt, lane, qf4, qsc);
-          pv_fp4_codes(slot_v, lane, pq, pb, o);
-        } else {
-          v8s pf[4];
-          gather_p16<T>(prow + wave * 64, lane, p, pf);
-          if (next4) sv = scores4_row(kt, lane, qf4, qsc);
+        // softmax of every head; the accumulators of head u are column u: its rescale factor goes to lanes r = u
+        float p[NH], alpha_lane = 1.f;
+        uint32_t pb[NH];
+        bool grew = false;
+#pragma unroll
+        for (int u = 0; u < NH; ++u) {
+          float alpha;
+          const bool g = softmax_row(sv[u], c, st[u], alpha, pb[u], p[u]);
+          if (g) alpha_lane = (NH == 1 || r == u) ? alpha : alpha_lane;
+          grew |= g;
+        }
+        rescale(o, grew, alpha_lane);
+        // P operands: head u's codes / rounded probabilities in lanes r = u, zeros for the path it does not take
+        v4i pq = {0, 0, 0, 0};
+        uint32_t pb_lane = 127u;
+        v8s pf[4];
+#pragma unroll
+        for (int s4i = 0; s4i < 4; ++s4i) pf[s4i] = (v8s){0, 0, 0, 0, 0, 0, 0, 0};
+        auto place = [&](auto uc) {
+          constexpr int u = decltype(uc)::value;
+          if (((Mb >> u) & 1) == 0) {
+            const v4i mine4 = gather_p4<u>(p[u], pb[u]);
+            if constexpr (NH == 1) { pq = mine4; pb_lane = pb[u]; }
+            else if (r == u) { pq = mine4; pb_lane = pb[u]; }
+          } else {
+            v8s mine16[4];
+            gather_p16<T>(prow + wave * 64, lane, p[u], mine16);
+            if (NH == 1 || r == u) {
+#pragma unroll
+              for (int s4i = 0; s4i < 4; ++s4i) pf[s4i] = mine16[s4i];
+            }
+          }
+        };
+        place(std::integral_constant<int, 0>{});
+        if constexpr (NH > 1) place(std::integral_constant<int, 1>{});
+        static_assert(NH <= 2, "one place() call per head");
+        float s4[NH], s16[NH];
+        if (next4) scores4_row<NH>(kt, lane, qf4, qsc, s4);
+        if (Mb != all_heads) pv_fp4_codes(slot_v, lane, pq, pb_lane, o);
+        if (Mb != 0) {
           int lane_ = lane;
           asm volatile("" : "+v"(lane_));
           pv_16_rounded<T, true>(lds + kDecLdsV16, lane_, pf, o);
         }
-        if (kNext && Mc) sv = score16();
+        if (next16) score16(s16);
+        if constexpr (kNext) {
+#pragma unroll
+          for (int u = 0; u < NH; ++u) sv[u] = ((Mc >> u) & 1) ? s16[u] : s4[u];
+        }
       }
       slot_a = slot_b; slot_b = slot_c; slot_c = slot_c + 1 == kDecRing ? 0 : slot_c + 1;
     };
@@ -469,7 +537,7 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
         const unsigned char* slot_v = lds + slot_b * kLdsBytes4;     // block t
         float alpha;
         uint32_t pb;
-        const bool grew = softmax_update(s, lane, false, kBk, c, st, alpha, pb);
+        const bool grew = softmax_update(s, lane, false, kBk, c, st[0], alpha, pb);
         rescale(o, grew, alpha);
         const int vb = votes(Pb, Mb), vc = votes(Pc, Mc);
         const bool any_b = (vb & 1) != 0, all_b = (vb & 2) != 0;
@@ -495,8 +563,20 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
   vm_wait<0>();
 
   // ---- partial (m, l, O) of this (head, partition): accumulator i of tile n is channel 32n + 8(i/4) + 4*half + i%4 ----
-  // the row sum: the two halves of a column, or all 64 lanes of the row layout
-  const float l = MULTI ? st.l + other_half(st.l) : wave_sum(st.l);
+  // the row sum and maximum of this lane's column: the two halves of a column of the transposed tiles; all 64 lanes of
+  // head r's register in the row layout
+  float l, m;
+  if constexpr (MULTI) {
+    l = st[0].l + other_half(st[0].l);
+    m = st[0].m;
+  } else {
+    l = 0.f; m = kEmptyMax;
+#pragma unroll
+    for (int u = 0; u < NH; ++u) {
+      const float lu = wave_sum(st[u].l);
+      if (r == u) { l = lu; m = st[u].m; }
+    }
+  }
   if (real) {
     float* po = a.part_o + (qh * a.nparts + part) * kD;
 #pragma unroll
@@ -506,7 +586,7 @@ __global__ void __launch_bounds__(256, MULTI ? 1 : 2) decode_partial_kernel(Deco
         *reinterpret_cast<float4*>(po + 32 * nn + 8 * g4 + 4 * half) =
             make_float4(o[nn][4 * g4], o[nn][4 * g4 + 1], o[nn][4 * g4 + 2], o[nn][4 * g4 + 3]);
     if (half == 0) {
-      a.part_ml[(qh * a.nparts + part) * 2] = st.m;
+      a.part_ml[(qh * a.nparts + part) * 2] = m;
       a.part_ml[(qh * a.nparts + part) * 2 + 1] = l;
     }
   }
@@ -882,14 +962,17 @@ __global__ void __launch_bounds__(128) decode_merge_kernel(DecodeArgs a) {
 
 void launch_decode(const DecodeArgs& a, hipStream_t st) {
   const unsigned grid = (unsigned)((long)a.B * a.Hkv * a.nsplit);
-  const bool multi = a.Hq / a.Hkv > 4;                 // more than one head per wavefront
-  if (a.dt == THRIFT_F16) {
-    if (multi) decode_partial_kernel<F16, true><<<dim3(grid), dim3(256), 0, st>>>(a);
-    else decode_partial_kernel<F16, false><<<dim3(grid), dim3(256), 0, st>>>(a);
-  } else {
-    if (multi) decode_partial_kernel<BF16, true><<<dim3(grid), dim3(256), 0, st>>>(a);
-    else decode_partial_kernel<BF16, false><<<dim3(grid), dim3(256), 0, st>>>(a);
-  }
+  // heads per wavefront: one or two in the row layout (groups of up to 4 / 8 heads), else the transposed tiles
+  const int G = a.Hq / a.Hkv;
+#define THRIFT_LAUNCH_PARTIAL(T)                                                             \
+  do {                                                                                       \
+    if (G <= 4) decode_partial_kernel<T, 1><<<dim3(grid), dim3(256), 0, st>>>(a);            \
+    else if (G <= 8) decode_partial_kernel<T, 2><<<dim3(grid), dim3(256), 0, st>>>(a);       \
+    else decode_partial_kernel<T, 0><<<dim3(grid), dim3(256), 0, st>>>(a);                   \
+  } while (0)
+  if (a.dt == THRIFT_F16) THRIFT_LAUNCH_PARTIAL(F16);
+  else THRIFT_LAUNCH_PARTIAL(BF16);
+#undef THRIFT_LAUNCH_PARTIAL
   if (a.seqlens != nullptr) {                          // without lengths every sequence fills the cache: no partly filled block
     const unsigned tail_grid = (unsigned)((long)a.B * a.Hkv);
     if (a.dt == THRIFT_F16) decode_tail_kernel<F16><<<dim3(tail_grid), dim3(64), 0, st>>>(a);

@@ -40,16 +40,18 @@ __global__ void __launch_bounds__(256, 3) peak_mfma_kernel(float* out, int iters
 }
 
 __global__ void __launch_bounds__(256) peak_hbm_read_kernel(const uint4* __restrict__ src, size_t n16, float* out) {
-  // grid-stride over 16-byte chunks, four independent loads in flight per lane
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  // Each workgroup streams one contiguous 16 KiB segment, four independent 16-byte loads per lane, marked as not to be
+  // kept in the caches: the shape that read the fastest of those tried (grid-stride sweeps and fewer, longer segments
+  // were 2 to 12 % slower).
+  typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+  const u4* p = reinterpret_cast<const u4*>(src) + (size_t)blockIdx.x * 1024 + threadIdx.x;
   uint32_t acc = 0;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    const uint4 x0 = src[i], x1 = src[i + stride], x2 = src[i + 2 * stride], x3 = src[i + 3 * stride];
-    acc ^= x0.x ^ x0.y ^ x0.z ^ x0.w ^ x1.x ^ x1.y ^ x1.z ^ x1.w ^ x2.x ^ x2.y ^ x2.z ^ x2.w ^ x3.x ^ x3.y ^ x3.z ^ x3.w;
+  if (((size_t)blockIdx.x + 1) * 1024 <= n16) {
+    const u4 x0 = __builtin_nontemporal_load(p), x1 = __builtin_nontemporal_load(p + 256), x2 = __builtin_nontemporal_load(p + 512),
+             x3 = __builtin_nontemporal_load(p + 768);
+    acc = x0.x ^ x0.y ^ x0.z ^ x0.w ^ x1.x ^ x1.y ^ x1.z ^ x1.w ^ x2.x ^ x2.y ^ x2.z ^ x2.w ^ x3.x ^ x3.y ^ x3.z ^ x3.w;
   }
-  for (; i < n16; i += stride) { const uint4 x = src[i]; acc ^= x.x ^ x.y ^ x.z ^ x.w; }
-  if (acc == 0x9e3779b9u) out[blockIdx.x] = 1.f;      // practically never: keeps the loads alive without a store per thread
+  if (acc == 0x9e3779b9u) out[blockIdx.x & 255] = 1.f;      // practically never: keeps the loads alive without a store per thread
 }
 
 template <bool WITH_MFMA>
@@ -119,9 +121,11 @@ double launch_peak_probe(int kind, thrift_dtype dt, int iters, void* buffer, siz
       return (double)kGrid * 4 * iters * 16 * (2.0 * 32 * 32 * 16);
     case THRIFT_PEAK_HBM_READ: {
       const size_t tail = 65536;                        // the last 64 KiB are the (never read) output region
-      const size_t n16 = (bytes - tail) / 16;
-      peak_hbm_read_kernel<<<dim3(256 * 8), dim3(256), 0, st>>>((const uint4*)buffer, n16, (float*)((char*)buffer + (bytes - tail)));
-      return (double)n16 * 16.0;
+      const size_t segments = (bytes - tail) / 16384;   // whole 16 KiB segments only
+      if (segments == 0 || segments > 0x7fffffffu) return -1.0;
+      peak_hbm_read_kernel<<<dim3((unsigned)segments), dim3(256), 0, st>>>((const uint4*)buffer, segments * 1024,
+                                                                           (float*)((char*)buffer + (bytes - tail)));
+      return (double)segments * 16384.0;
     }
     case THRIFT_PEAK_VALU_SOFTMAX:
       peak_tile_mix_kernel<false><<<dim3(kGrid), dim3(256), 0, st>>>(out, iters, 0.1275f);
