@@ -3,16 +3,20 @@
 //
 // One workgroup = one (sequence, KV head, partition of split_blocks key blocks) and ONE recurrence of Alg. 1
 // per query head over the whole partition.  The group's heads are dealt to the four wavefronts (head g goes to
-// wavefront g mod 4, column g / 4 of that wavefront's transposed 32x32 MFMA tiles; the other columns carry zeros
-// and are never stored), so every wavefront walks every key block of the partition for its own heads.
-// The kernel is bandwidth bound.  Each key block is brought from HBM once per workgroup by LDS DMA and read from
-// LDS by all four wavefronts: the 4-bit codes and scales of every block into a ring of five slots, four blocks
-// ahead of the arithmetic; the 16-bit K and V tiles of a block that some head of the group has promoted into one
-// tile buffer each, one block ahead.  A head for which the block is promoted takes its scores and P.V from the
-// 16-bit tiles, the others from the 4-bit slot; both feed the same online softmax.  Each (head, partition) writes
-// one unnormalised partial (m, l, O); a second kernel merges the partials of a (sequence, head) by their
-// log-sum-exp.  A partly filled last block (a cache that is still growing) is a partition of its own, computed by
-// a small second instantiation with masking, so that the main walk carries none.
+// wavefront g mod 4), so every wavefront walks every key block of the partition for its own heads.
+// The kernel is bandwidth bound.  Each key block is brought from HBM once per workgroup by LDS DMA (with the
+// streaming hint: nothing of the cache is read twice) and read from LDS by all four wavefronts: the 4-bit codes and
+// scales of every block into a ring of five slots, up to three blocks ahead of the arithmetic; the 16-bit K and V
+// tiles of a block that some head of the group has promoted into one tile buffer each, one step ahead when the
+// buffer is idle then.  A head for which the block is promoted takes its scores and P.V from the 16-bit tiles, the
+// others from the 4-bit slot; both feed the same online softmax.  The walk is software-pipelined: the scores of
+// block t+1 are formed between the softmax and the P.V of block t.
+// With one or two heads per wavefront (head groups of up to 8) the score tiles are formed as Q.K^T with each query
+// in two rows, which leaves one register with a head's 64 scores of the block across the lanes (the row layout
+// below); larger groups use the transposed tiles of the prefill kernel, head wave + 4r in column r.
+// Each (head, partition) writes one unnormalised partial (m, l, O); a second kernel merges the partials of a
+// (sequence, head) by their log-sum-exp.  A partly filled last block (a cache that is still growing) is a partition
+// of its own, computed by a small second kernel with masking, so that the main walk carries none.
 #include <type_traits>
 
 #include "thrift_launch.h"
@@ -274,16 +278,16 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
   auto issue4 = [&](int j, int slot_index) {            // block j (absolute id) into ring slot slot_index
     const int j_ = __builtin_amdgcn_readfirstlane(j);
     const uint32_t slot = lds0 + (uint32_t)(__builtin_amdgcn_readfirstlane(slot_index) * kLdsBytes4);
-    dma_b128(k4base + (size_t)j_ * 4096, k4off, slot + kLdsK4 + wave * 1024);
-    dma_b32(scbase + (size_t)j_ * 256, scoff, slot + sclds);
-    dma_b128(v4base + (size_t)j_ * 4096, v4off, slot + kLdsV4 + wave * 1024);
+    dma_b128<true>(k4base + (size_t)j_ * 4096, k4off, slot + kLdsK4 + wave * 1024);
+    dma_b32<true>(scbase + (size_t)j_ * 256, scoff, slot + sclds);
+    dma_b128<true>(v4base + (size_t)j_ * 4096, v4off, slot + kLdsV4 + wave * 1024);
   };
   auto issue16k = [&](int j) {                          // the 16-bit K tile of block j: instruction q covers rows 4q .. 4q+3
     const int j_ = __builtin_amdgcn_readfirstlane(j);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int q_ = u * 4 + wave;
-      dma_b128(k16base + (size_t)j_ * kTile16 + q_ * 1024, (MULTI && u >= 2) ? k16off ^ 64u : k16off, lds0 + kDecLdsK16 + q_ * 1024);
+      dma_b128<true>(k16base + (size_t)j_ * kTile16 + q_ * 1024, (MULTI && u >= 2) ? k16off ^ 64u : k16off, lds0 + kDecLdsK16 + q_ * 1024);
     }
   };
   auto issue16v = [&](int j) {                          // the 16-bit V tile of block j
@@ -291,7 +295,7 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int q_ = u * 4 + wave;
-      dma_b128(v16base + (size_t)j_ * kTile16 + q_ * 1024, v16off, lds0 + kDecLdsV16 + q_ * 1024);
+      dma_b128<true>(v16base + (size_t)j_ * kTile16 + q_ * 1024, v16off, lds0 + kDecLdsV16 + q_ * 1024);
     }
   };
 
@@ -770,11 +774,15 @@ __global__ void __launch_bounds__(256) decode_scores_kernel(const uint16_t* __re
   const float* kunit = kmean + (size_t)unit * Tk * kD;
   // the chunk after the one being scored travels through registers, so its latency hides behind the arithmetic
   float4 pre[8];
+  typedef float f4v __attribute__((ext_vector_type(4)));
 #define THRIFT_LOAD_CHUNK(C)                                                                                     \
   _Pragma("unroll") for (int u = 0; u < 8; ++u) {                                                                \
     const int c4 = tid + 256 * u, row = c4 >> 5, col = (c4 & 31) * 4;                                            \
-    pre[u] = (C) * 64 + row < Tk ? *reinterpret_cast<const float4*>(kunit + ((size_t)(C) * 64 + row) * kD + col) \
-                                 : make_float4(0.f, 0.f, 0.f, 0.f);                                              \
+    pre[u] = make_float4(0.f, 0.f, 0.f, 0.f);                                                                    \
+    if ((C) * 64 + row < Tk) {   /* read once by the whole grid: streaming hint */                               \
+      const f4v t = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(kunit + ((size_t)(C) * 64 + row) * kD + col)); \
+      pre[u] = make_float4(t.x, t.y, t.z, t.w);                                                                  \
+    }                                                                                                            \
   }
   THRIFT_LOAD_CHUNK(chunk0)
   // the query token is its own block mean (one-token block): the 16-bit value widened exactly

@@ -66,11 +66,22 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_
 // value there across statements and loads it right before the few instructions of its own that read it; the
 // build additionally checks that the kernel's listing mentions M0 only inside these statements.
 // Completion is counted by vmcnt like any global load.
+// STREAM: the bytes are read once by the whole grid (the decode kernel's cache tiles): the load carries the non-temporal
+// hint, so that it does not displace what other kernels' data the caches hold and streams at the higher rate measured for
+// such loads.
+template <bool STREAM = false>
 __device__ __forceinline__ void dma_b128(const void* base, uint32_t off, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
 }
+template <bool STREAM = false>
 __device__ __forceinline__ void dma_b32(const void* base, uint32_t off, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+  if constexpr (STREAM)
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 nt" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(base), "s"(lds_base) : "memory");
 }
 
 struct RowState {
