@@ -16,7 +16,6 @@ recovery at 5 / 10 / 25 % over one query head of every KV group.
 from __future__ import annotations
 
 import argparse
-import glob
 import hashlib
 import json
 import math
@@ -47,8 +46,8 @@ ALU_PEAK = 1024 * 64 * 2.4e9 / ALU_CYCLES * (4 * 128) / 1e12   # TFLOP/s
 # (FETCH_SIZE, WRITE_SIZE; scaled by what the same counters read for the 1 GiB calibration copy below: x2.0 and
 # x1.0); the summary of those runs is profiles/prefill_decode_hbm_traffic_pmc.txt.  Counters cannot be read from
 # inside this process, so the figures belong to the kernel sources they were measured on: `source_sha` is the hash of
-# paper_2605_23081_amd/csrc at that time, and a build from other sources reports no traffic.
-MEASURED_TRAFFIC_GB = {"source_sha": "a3271f150645",
+# the two kernels' sources (KERNEL_SOURCES below) at that time, and a build from other sources reports no traffic.
+MEASURED_TRAFFIC_GB = {"source_sha": "4a1f0712ddee",
                        "prefill_131k_f0.05_order1": {"fetched": 22.72, "written": 1.107},
                        "prefill_131k_f0.05_order0": {"fetched": 36.66, "written": 1.074},
                        "decode_16x131k_f0.05": {"fetched": 3.834, "written": 0.0022}}
@@ -63,12 +62,15 @@ def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+KERNEL_SOURCES = ("thrift_device.h", "thrift_tile.h", "thrift_launch.h", "thrift_prefill.hip", "thrift_decode.hip")
+
+
 def kernel_source_sha() -> str:
-    """Hash of the kernel sources this build was made from (what measured traffic figures are tied to)."""
+    """Hash of the sources of the fused prefill kernel and of the decode kernels (what measured traffic figures are tied to)."""
     h = hashlib.sha256()
-    for path in sorted(glob.glob(os.path.join(ROOT, "paper_2605_23081_amd", "csrc", "*.h*"))):
-        with open(path, "rb") as f:
-            h.update(os.path.basename(path).encode() + b"\0" + f.read())
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2605_23081_amd", "csrc", name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
     return h.hexdigest()[:12]
 
 
@@ -134,11 +136,11 @@ def main() -> int:
 
         # every launch lasts tens of milliseconds, like the kernels it is compared with: the clock under a sustained
         # matrix / vector load is well below the one a short burst sees
-        mfma4 = rate(T.PEAK_MFMA_MXFP4, 50000, 2) / 1e12
-        mfma16 = rate(T.PEAK_MFMA_16, 50000, 2) / 1e12
+        mfma4 = rate(T.PEAK_MFMA_MXFP4, 3000, 2) / 1e12
+        mfma16 = rate(T.PEAK_MFMA_16, 3000, 2) / 1e12
         hbm = rate(T.PEAK_HBM_READ, 1, 100) / 1e9
-        valu = rate(T.PEAK_VALU_SOFTMAX, 50000, 2) * FLOP_PER_WAVE_TILE / 1e12
-        mix = rate(T.PEAK_TILE_MIX, 50000, 2) * FLOP_PER_WAVE_TILE / 1e12
+        valu = rate(T.PEAK_VALU_SOFTMAX, 3000, 2) * FLOP_PER_WAVE_TILE / 1e12
+        mix = rate(T.PEAK_TILE_MIX, 3000, 2) * FLOP_PER_WAVE_TILE / 1e12
         measured = {"mfma_mxfp4": round(mfma4, 1), "mfma_16bit": round(mfma16, 1), "hbm_read_GBps": round(hbm, 1),
                     "valu_softmax_part": round(valu, 1), "tile_mix": round(mix, 1), "unit": "TFLOP/s unless named",
                     "how": "thrift_peak_probe microbenchmarks, three workgroups per CU like the fused kernel; valu_softmax_part / tile_mix: "

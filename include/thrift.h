@@ -354,9 +354,9 @@ thrift_status thrift_kv_cache_append(const void* k_new, const void* v_new, thrif
  *                             (online-softmax update + P quantiser, no matrix instructions, no staging), at the
  *                             fused kernel's occupancy                                    *work = wave-tiles
  *   THRIFT_PEAK_TILE_MIX      the same plus the tile's eight matrix instructions           *work = wave-tiles
- * buffer (device): at least 1 MiB (scratch for results; for THRIFT_PEAK_HBM_READ the data that is read, whatever it
+ * buffer (device): at least 16 MiB (scratch for results; for THRIFT_PEAK_HBM_READ the data that is read, whatever it
  * holds; its last 64 KiB are not read).  iters >= 1: loop trips per wavefront (ignored by the HBM probe).
- * Unknown kind, iters < 1 or a buffer below 1 MiB: THRIFT_ERR_SHAPE.
+ * Unknown kind, iters < 1 or a buffer below 16 MiB: THRIFT_ERR_SHAPE.
  */
 typedef enum THRIFT_ENUM_INT { THRIFT_PEAK_MFMA_MXFP4 = 0, THRIFT_PEAK_MFMA_16 = 1, THRIFT_PEAK_HBM_READ = 2,
                                THRIFT_PEAK_VALU_SOFTMAX = 3, THRIFT_PEAK_TILE_MIX = 4 } thrift_peak_kind;

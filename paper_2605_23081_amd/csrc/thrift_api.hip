@@ -472,7 +472,7 @@ thrift_status thrift_kv_cache_append(const void* k_new, const void* v_new, thrif
 
 thrift_status thrift_peak_probe(int kind, thrift_dtype dt, int iters, void* buffer, size_t bytes, double* work, void* stream) {
   if (!buffer || !work) return THRIFT_ERR_NULL;
-  if (kind < THRIFT_PEAK_MFMA_MXFP4 || kind > THRIFT_PEAK_TILE_MIX || iters < 1 || bytes < ((size_t)1 << 20)) return THRIFT_ERR_SHAPE;
+  if (kind < THRIFT_PEAK_MFMA_MXFP4 || kind > THRIFT_PEAK_TILE_MIX || iters < 1 || bytes < ((size_t)16 << 20)) return THRIFT_ERR_SHAPE;
   if (kind == THRIFT_PEAK_MFMA_16 && !is16(dt)) return THRIFT_ERR_DTYPE;
   if (((uintptr_t)buffer & 15) != 0) return THRIFT_ERR_SHAPE;
   if (thrift_status s = check_arch()) return s;

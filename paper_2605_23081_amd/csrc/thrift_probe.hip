@@ -78,6 +78,7 @@ __global__ void __launch_bounds__(256, 3) peak_tile_mix_kernel(float* out, int i
       // S^T of the tile: four scaled-FP4 MFMAs on register operands (scores far below the running maximum)
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
+        asm volatile("" : "+v"(kf[t]));               // a new K fragment as far as the compiler knows: the MFMAs stay in the loop
         v16f acc = {0.f};
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(kf[t]), widen(qf[0]), acc, 4, 4, 0, 0x70707070, 0, 0x70707070);
         acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(kf[t ^ 1]), widen(qf[1]), acc, 4, 4, 1, 0x70707070, 1, 0x70707070);
@@ -109,7 +110,9 @@ __global__ void __launch_bounds__(256, 3) peak_tile_mix_kernel(float* out, int i
 
 // Returns the work of one launch: flops (MFMA kinds), bytes (HBM), wave-tiles (tile mixes); 0 for an unknown kind.
 double launch_peak_probe(int kind, thrift_dtype dt, int iters, void* buffer, size_t bytes, hipStream_t st) {
-  constexpr int kGrid = 256 * 3;                        // three workgroups per CU
+  // 48 workgroups per CU in all: the CUs are refilled as workgroups retire and hold three at a time on average, like
+  // under the fused kernel's long grid (a grid of exactly three per CU was placed unevenly and ran at two per SIMD)
+  constexpr int kGrid = 256 * 3 * 16;
   float* out = (float*)buffer;                          // every probe but the HBM one writes kGrid * 256 floats
   switch (kind) {
     case THRIFT_PEAK_MFMA_MXFP4:
