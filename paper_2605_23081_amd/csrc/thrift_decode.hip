@@ -24,17 +24,21 @@
 
 namespace thrift {
 
-constexpr int kDecRing = 5;                                   // 4-bit slots: block j sits in slot j mod 5, fetched 4 blocks ahead
-constexpr int kDecAhead = kDecRing - 1;
+constexpr int kDecRing = 5;                                   // 4-bit slots: block t of the partition sits in slot t mod kDecRing
+constexpr int kDecAhead = kDecRing - 1;                       // step t issues block t + kDecAhead into the slot block t-1 has left
+constexpr int kDecFlight = kDecRing - 3;                      // blocks in flight and not yet needed at a step: t+2 .. t+kDecRing-2
 constexpr int kDecLdsK16 = kDecRing * kLdsBytes4;             // one swizzled 16-bit K tile
 constexpr int kDecLdsV16 = kDecLdsK16 + kTile16;              // one swizzled 16-bit V tile
 constexpr int kDecLds = kDecLdsV16 + kTile16;                 // 76288 B: two workgroups per CU
 constexpr int kDmaPer4 = 3;                                   // DMA instructions one wavefront issues per 4-bit block
 constexpr int kBmWin = 8;                                     // 64-block words of each head's selection bitmap cached in LDS
 
-// Wait until at most n (0, 3, 6 or 9) of this wavefront's DMA instructions are in flight.
+// Wait until at most n (a multiple of kDmaPer4 = 3) of this wavefront's DMA instructions are in flight.
 __device__ __forceinline__ void vm_wait_dyn(int n) {
-  if (n >= 9) vm_wait<9>();
+  static_assert(kDecFlight <= 5, "one case per possible count");
+  if (n >= 15) vm_wait<15>();
+  else if (n >= 12) vm_wait<12>();
+  else if (n >= 9) vm_wait<9>();
   else if (n >= 6) vm_wait<6>();
   else if (n >= 3) vm_wait<3>();
   else vm_wait<0>();
@@ -366,7 +370,7 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
   // ---- the walk, software-pipelined over the key blocks: step t (t = -1 .. n-1) finishes block t (softmax, P.V) and
   // forms the scores of block t+1 in between, so that the matrix unit works on one block while the vector unit works
   // on its neighbour and no LDS read is waited for where it is issued.
-  // Residency at step t: 4-bit slots of blocks t (V) and t+1 (K) in use, t+2 and t+3 in flight, t+4 issued into the
+  // Residency at step t (kDecRing = 5): 4-bit slots of blocks t (V) and t+1 (K) in use, t+2 and t+3 in flight, t+4 issued into the
   // slot block t-1 has left; the K tile buffer holds block t+1's 16-bit keys, the V tile buffer block t's values.
   // A 16-bit tile is fetched one step before its use when its buffer is idle then (the neighbouring block is not
   // promoted), otherwise at the step of its use, which then waits for it.
@@ -376,16 +380,16 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
   Pc = flags(0, Mc);
   Pd = flags(1, Md);
   if (Pc) issue16k(j_begin);
-  for (int x = 0; x < 3 && x < n; ++x) issue4(j_begin + x, x);
-  int slot_a = 3, slot_b = 4, slot_c = 0;               // ring slots of blocks t-1, t, t+1 at t = -1
+  for (int x = 0; x < kDecRing - 2 && x < n; ++x) issue4(j_begin + x, x);
+  int slot_a = kDecRing - 2, slot_b = kDecRing - 1, slot_c = 0;   // ring slots of blocks t-1, t, t+1 at t = -1
   int early_prev = 0;                                   // the step before fetched 16-bit tiles ahead of its 4-bit block
 
   // Staging part of step t: waits for what the step reads, then issues what later steps will read.
   auto stage = [&](int t) {
     const int j = j_begin + t;
-    // in flight and not yet needed: the 4-bit blocks t+2 and t+3 (where they exist); after 16-bit tiles fetched ahead in
-    // the step before, only that step's 4-bit block t+3
-    const int newer = early_prev ? (t + 3 < n ? kDmaPer4 : 0) : kDmaPer4 * max(0, min(n - 2 - t, 2));
+    // in flight and not yet needed: the 4-bit blocks t+2 .. t+kDecRing-2 (where they exist); after 16-bit tiles fetched
+    // ahead in the step before, only that step's 4-bit block t+kDecRing-2
+    const int newer = early_prev ? (t + kDecRing - 2 < n ? kDmaPer4 : 0) : kDmaPer4 * max(0, min(n - 2 - t, kDecFlight));
     vm_wait_dyn(newer);
     lds_barrier();                                      // block t+1 (and block t's V tile) complete in LDS; step t-1 is behind everyone
     const int lateK = Pc & Pb, lateV = Pb & Pa;         // the buffer was busy during the step before
