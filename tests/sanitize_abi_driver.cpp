@@ -35,6 +35,14 @@ int main() {
   EXPECT(thrift_kv_cache_append(fake, fake, THRIFT_F16, 2000, fi, nullptr, fake, fake, fu, fu, fu, fu, ff, 1, 2, 1024, 128, 64, nullptr), THRIFT_ERR_SHAPE);
   EXPECT(thrift_attention_forward(fake, fake, fake, THRIFT_BF16, 1, 4, 2, 300, 128, 128, 64, 1, 0.05, -1, 7, 0.f, fake, THRIFT_BF16, nullptr, fake, (size_t)1 << 30, nullptr), THRIFT_ERR_SHAPE);
   EXPECT(thrift_attention_forward(fake, fake, fake, THRIFT_BF16, 1, 4, 2, 300, 128, 128, 64, 1, 0.05, -1, 0, 0.f, fake, THRIFT_BF16, nullptr, fake, 16, nullptr), THRIFT_ERR_WORKSPACE);
+  {
+    double work = 0.0;
+    EXPECT(thrift_peak_probe(THRIFT_PEAK_TILE_MIX, THRIFT_BF16, 10, nullptr, (size_t)1 << 30, &work, nullptr), THRIFT_ERR_NULL);
+    EXPECT(thrift_peak_probe(9, THRIFT_BF16, 10, fake, (size_t)1 << 30, &work, nullptr), THRIFT_ERR_SHAPE);
+    EXPECT(thrift_peak_probe(THRIFT_PEAK_TILE_MIX, THRIFT_BF16, 0, fake, (size_t)1 << 30, &work, nullptr), THRIFT_ERR_SHAPE);
+    EXPECT(thrift_peak_probe(THRIFT_PEAK_HBM_READ, THRIFT_BF16, 1, fake, (size_t)1 << 20, &work, nullptr), THRIFT_ERR_SHAPE);
+    EXPECT(thrift_peak_probe(THRIFT_PEAK_MFMA_16, THRIFT_F32, 10, fake, (size_t)1 << 30, &work, nullptr), THRIFT_ERR_DTYPE);
+  }
   // host helpers over wide argument ranges (integer arithmetic, no overflow)
   long acc = 0;
   for (int vis = 0; vis <= 4096; vis += 7) for (double f = 0.0; f <= 1.0; f += 0.125) acc += thrift_row_budget(vis, f, -1) + thrift_row_budget(vis, f, 5);

@@ -98,6 +98,19 @@ def test_validation_errors_come_before_any_launch():
     assert "gfx950" in T.status_string(6)
 
 
+def test_peak_probe_validates_before_launching():
+    L = T.lib()
+    fake, work = C.c_void_p(0x1000), C.c_double(0.0)
+    probe = lambda kind=4, dt=1, iters=10, buf=fake, size=1 << 30: L.thrift_peak_probe(kind, dt, iters, buf, C.c_size_t(size), C.byref(work), None)
+    assert probe(buf=None) == 1
+    assert probe(kind=5) == 2 and probe(kind=-1) == 2
+    assert probe(iters=0) == 2
+    assert probe(size=(16 << 20) - 1) == 2                 # smaller than the probes' result region
+    assert probe(buf=C.c_void_p(0x1008)) == 2              # not 16-byte aligned
+    assert probe(kind=1, dt=2) == 3                        # the 16-bit MFMA probe needs fp16 or bf16
+    assert L.thrift_peak_probe(4, 1, 10, fake, C.c_size_t(1 << 30), None, None) == 1
+
+
 def test_without_a_gpu_valid_calls_fail_loudly():
     import torch
     if torch.cuda.is_available():

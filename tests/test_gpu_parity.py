@@ -999,3 +999,21 @@ def test_prefill_degenerate_inputs(T, oracle, order):
         # ties everywhere: the selection takes the smallest ids, on both sides
         idx_g, cnt_g = T.thrift_select_topk(T.thrift_block_means(z.cuda(), Bq), T.thrift_block_means(zk.cuda(), 64), Bq, 64, True, 0.25)
         assert np.array_equal(to_np(idx_g)[..., :idx.shape[-1]], idx) and np.array_equal(to_np(cnt_g), cnt)
+
+
+# ------------------------------------------------------------------ measurement microbenchmarks
+def test_peak_probes_run_and_report_their_work(T):
+    """Every thrift_peak_probe kind launches, leaves the device healthy and reports the work its launch did (the figure
+    bench.py divides by the measured time)."""
+    _say("peak probes")
+    buf = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    grid, iters = 256 * 3 * 16, 20
+    want = {T.PEAK_MFMA_MXFP4: grid * 4 * iters * 16 * 2.0 * 32 * 32 * 64, T.PEAK_MFMA_16: grid * 4 * iters * 16 * 2.0 * 32 * 32 * 16,
+            T.PEAK_HBM_READ: float(((64 << 20) - 65536) // 16384 * 16384), T.PEAK_VALU_SOFTMAX: float(grid * 4 * iters),
+            T.PEAK_TILE_MIX: float(grid * 4 * iters)}
+    for kind, work in want.items():
+        for dtype in ((torch.bfloat16, torch.float16) if kind == T.PEAK_MFMA_16 else (torch.bfloat16,)):
+            got = T.thrift_peak_probe(kind, buf, iters, dtype)
+            torch.cuda.synchronize()
+            assert got == work, (kind, got, work)
+    assert torch.all(buf[-65536 - (1 << 20):-65536] == 1)      # the HBM probe only reads; the others write at the front
