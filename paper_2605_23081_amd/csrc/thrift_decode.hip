@@ -389,8 +389,12 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
     const int j = j_begin + t;
     // in flight and not yet needed: the 4-bit blocks t+2 .. t+kDecRing-2 (where they exist); after 16-bit tiles fetched
     // ahead in the step before, only that step's 4-bit block t+kDecRing-2
-    const int newer = early_prev ? (t + kDecRing - 2 < n ? kDmaPer4 : 0) : kDmaPer4 * max(0, min(n - 2 - t, kDecFlight));
-    vm_wait_dyn(newer);
+    if (!early_prev && t + kDecRing - 2 < n) {
+      vm_wait<kDmaPer4 * kDecFlight>();                 // the steady state of the walk: one scalar test
+    } else {
+      const int newer = early_prev ? (t + kDecRing - 2 < n ? kDmaPer4 : 0) : kDmaPer4 * max(0, min(n - 2 - t, kDecFlight));
+      vm_wait_dyn(newer);
+    }
     lds_barrier();                                      // block t+1 (and block t's V tile) complete in LDS; step t-1 is behind everyone
     const int lateK = Pc & Pb, lateV = Pb & Pa;         // the buffer was busy during the step before
     if (lateK) issue16k(j + 1);
