@@ -193,9 +193,10 @@ __device__ __forceinline__ float wave_sum(float x) {
 // the path of a block is a scalar choice per head.  HPW = 0: up to eight heads per wavefront in the transposed tiles of
 // the prefill kernel (head wave + 4r in column r), which cost a wavefront instruction per score and key but no more for
 // eight heads than for one; the heads may split over the two paths of a block, both tiles are then computed and each
-// lane keeps its own head's.
+// lane keeps its own head's.  That form finishes a block within its step (scores, softmax, P.V) instead of forming the
+// next block's scores ahead: it has no registers to carry them.
 template <typename T, int HPW>
-__global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(DecodeArgs a) {
+__global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   constexpr bool MULTI = HPW == 0;
   constexpr int NH = MULTI ? 1 : HPW;
   __shared__ __align__(1024) unsigned char lds[kDecLds];
@@ -379,7 +380,10 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
   Mine Mb = Mine(0), Mc, Md;
   Pc = flags(0, Mc);
   Pd = flags(1, Md);
-  if (Pc) issue16k(j_begin);
+  // The K tile buffer holds block t + kKShift's keys at step t: the row layout forms the scores of block t+1 at step t,
+  // the transposed tiles (which have no registers to carry scores from one step to the next) those of block t itself.
+  constexpr int kKShift = MULTI ? 0 : 1;
+  if (kKShift == 1 && Pc) issue16k(j_begin);
   for (int x = 0; x < kDecRing - 2 && x < n; ++x) issue4(j_begin + x, x);
   int slot_a = kDecRing - 2, slot_b = kDecRing - 1, slot_c = 0;   // ring slots of blocks t-1, t, t+1 at t = -1
   int early_prev = 0;                                   // the step before fetched 16-bit tiles ahead of its 4-bit block
@@ -396,15 +400,16 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
       vm_wait_dyn(newer);
     }
     lds_barrier();                                      // block t+1 (and block t's V tile) complete in LDS; step t-1 is behind everyone
-    const int lateK = Pc & Pb, lateV = Pb & Pa;         // the buffer was busy during the step before
-    if (lateK) issue16k(j + 1);
+    const int Kprev = kKShift ? Pb : Pa, Kcur = kKShift ? Pc : Pb, Knext = kKShift ? Pd : Pc;   // promoted flags of blocks t + kKShift - 1, +0, +1
+    const int lateK = Kcur & Kprev, lateV = Pb & Pa;    // the buffer was busy during the step before
+    if (lateK) issue16k(j + kKShift);
     if (lateV) issue16v(j);
     if (lateK | lateV) {
       vm_wait<0>();
       lds_barrier();
     }
-    const int earlyK = Pd & (Pc ^ 1), earlyV = Pc & (Pb ^ 1);
-    if (earlyK) issue16k(j + 2);
+    const int earlyK = Knext & (Kcur ^ 1), earlyV = Pc & (Pb ^ 1);
+    if (earlyK) issue16k(j + kKShift + 1);
     if (earlyV) issue16v(j + 1);
     if (t + kDecAhead < n) issue4(j + kDecAhead, slot_a);
     early_prev = earlyK | earlyV;
@@ -532,27 +537,23 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
       const unsigned long long v = P ? (__builtin_amdgcn_ballot_w64(mine) & my_mask) : 0ULL;
       return (v != 0ULL ? 1 : 0) | (v == my_mask ? 2 : 0);
     };
-    v16f s[2];                                          // raw scores of block t on entry to step t
-    stage(-1);                                          // step -1: only the scores of block 0
-    if (my_heads > 0 && n > 0) {
-      const int vc = votes(Pc, Mc);
-      scores(slot_c, Mc, (vc & 1) != 0, (vc & 2) != 0, s);
-    }
+    stage(-1);                                          // step -1: staging only
     slot_a = slot_b; slot_b = slot_c; slot_c = 1;
-    // One step; WITH_NEXT (a compile-time flag): block t+1 exists.  The last step is a separate instantiation so that the
-    // score registers are simply overwritten in every other one (no merge of old and new values at each step).
-    auto step = [&](int t, auto with_next) {
+    for (int t = 0; t < n; ++t) {
       Pa = Pb; Pb = Pc; Pc = Pd; Mb = Mc; Mc = Md;
       Pd = flags(t + 2, Md);
       stage(t);
       if (my_heads > 0) {
-        const unsigned char* slot_v = lds + slot_b * kLdsBytes4;     // block t
+        // the whole of block t in this step: scores, softmax, P.V (nothing is carried over to the next step)
+        const unsigned char* slot_v = lds + slot_b * kLdsBytes4;
+        const int vb = votes(Pb, Mb);
+        const bool any_b = (vb & 1) != 0, all_b = (vb & 2) != 0;
+        v16f s[2];
+        scores(slot_b, Mb, any_b, all_b, s);
         float alpha;
         uint32_t pb;
         const bool grew = softmax_update(s, lane, false, kBk, c, st[0], alpha, pb);
         rescale(o, grew, alpha);
-        const int vb = votes(Pb, Mb), vc = votes(Pc, Mc);
-        const bool any_b = (vb & 1) != 0, all_b = (vb & 2) != 0;
         // each lane contributes nothing on the path its head did not take (zero codes / zero probabilities)
         if (!all_b) {
           v4i pq = quantize_p_group(s, pb);
@@ -565,12 +566,9 @@ __global__ void __launch_bounds__(256, HPW == 0 ? 1 : 2) decode_partial_kernel(D
           asm volatile("" : "+v"(lane_));
           pv_16<T, true>(lds + kDecLdsV16, lane_, s, o);
         }
-        if constexpr (decltype(with_next)::value) scores(slot_c, Mc, (vc & 1) != 0, (vc & 2) != 0, s);
       }
       slot_a = slot_b; slot_b = slot_c; slot_c = slot_c + 1 == kDecRing ? 0 : slot_c + 1;
-    };
-    for (int t = 0; t + 1 < n; ++t) step(t, std::true_type{});
-    if (n > 0) step(n - 1, std::false_type{});
+    }
   }
   vm_wait<0>();
 
