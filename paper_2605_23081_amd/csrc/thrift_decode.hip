@@ -854,13 +854,18 @@ struct DecodeSelectArgs {
   long long ppm;
 };
 
-// One wavefront per row, no barriers: lane l keeps key blocks l, l+64, ... in registers; the k-th largest
-// key is found by a 64-step bitwise search whose counts are ballots + scalar popcounts.
+// One workgroup per row: thread t keeps key blocks t, t+256, ... in registers; the k-th largest key is found by a
+// bitwise search from the top bit (64 steps at most, typically 25-30: it stops once a candidate has exactly k keys at or
+// above it; two bits per step were slower, the steps are bound by the ballots, not by the barrier).  A step counts per lane, sums a wavefront by the ballots of the count's bits and the four wavefronts
+// through LDS (one barrier per step; the slots alternate so that a step's values outlive the next step's writes).
+// With one wavefront per row the 512 rows of the benchmark occupied a quarter of the chip and took 21 us.
 template <int MAXC>
 __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, long n_rows) {
-  const int lane = threadIdx.x & 63;
-  const long row = (long)blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  if (row >= n_rows) return;
+  __shared__ int cross[2][4];
+  __shared__ int tcnt[MAXC][4], scnt[MAXC][4];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const long row = blockIdx.x;
   const int b = (int)(row / p.Hq);
   const int vis = p.seqlens ? min(p.Tk, (max(0, p.seqlens[b]) + kBk - 1) / kBk) : p.Tk;
   int k;
@@ -873,25 +878,29 @@ __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, 
   uint64_t key[MAXC];
 #pragma unroll
   for (int c = 0; c < MAXC; ++c) {
-    const int j = c * 64 + lane;
+    const int j = c * 256 + tid;
     key[c] = j < vis ? p.keys[row * p.Tk + j] : 0ULL;
   }
   unsigned long long* bm = p.bitmap + row * p.words;
   int32_t* out = p.idx_out ? p.idx_out + row * p.kmax_out : nullptr;
-  if (p.cnt_out && lane == 0) p.cnt_out[row] = k;
-  if (k <= 0) {
-    for (int w = lane; w < p.words; w += 64) bm[w] = 0ULL;
-    if (out) for (int t = lane; t < p.kmax_out; t += 64) out[t] = -1;
+  if (p.cnt_out && tid == 0) p.cnt_out[row] = k;
+  if (k <= 0) {                                              // uniform over the workgroup
+    for (int w = tid; w < p.words; w += 256) bm[w] = 0ULL;
+    if (out) for (int t = tid; t < p.kmax_out; t += 256) out[t] = -1;
     return;
   }
-  // Invalid slots hold key 0, and every candidate below is >= 1, so they never count.  Each lane counts
-  // its own keys (at most MAXC <= 64, seven bits); the wavefront total is the weighted popcount of the
-  // ballots of those seven bits.
-  auto wave_total = [&](int n_lane) -> int {
+  // Invalid slots hold key 0, and every candidate below is >= 1, so they never count.  Each lane counts its own keys
+  // (at most MAXC <= 16, five bits); the wavefront total is the weighted popcount of the ballots of those bits.
+  int parity = 0;
+  auto row_total = [&](int n_lane) -> int {                  // called by all threads at the same point
     int tot = 0;
 #pragma unroll
-    for (int b7 = 0; b7 < 7; ++b7) tot += __popcll(__ballot((n_lane >> b7) & 1)) << b7;
-    return tot;
+    for (int b5 = 0; b5 < 5; ++b5) tot += __popcll(__ballot((n_lane >> b5) & 1)) << b5;
+    if (lane == 0) cross[parity][wave] = tot;
+    __syncthreads();
+    const int n = cross[parity][0] + cross[parity][1] + cross[parity][2] + cross[parity][3];
+    parity ^= 1;
+    return n;
   };
   uint64_t T = 0;
   for (int bit = 63; bit >= 0; --bit) {
@@ -899,7 +908,7 @@ __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, 
     int n_lane = 0;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) n_lane += key[c] >= cand ? 1 : 0;
-    const int n = wave_total(n_lane);
+    const int n = row_total(n_lane);
     if (n >= k) T = cand;
     if (n == k) break;                                       // exactly the k largest lie at or above cand: done
   }
@@ -908,28 +917,45 @@ __global__ void __launch_bounds__(256) decode_select_kernel(DecodeSelectArgs p, 
     int n_lane = 0;
 #pragma unroll
     for (int c = 0; c < MAXC; ++c) n_lane += key[c] > T ? 1 : 0;
-    n_gt = wave_total(n_lane);
+    n_gt = row_total(n_lane);
   }
   const int need_ties = k - n_gt;                            // keys equal to T, taken from the smallest id up (0 after an early exit above a gap)
+  // Ids ascend with (c, wavefront, lane).  First the tie counts of every (c, wavefront), then the selection, then the
+  // output positions: two barriers in all.
   const uint64_t lt_mask = (1ULL << lane) - 1ULL;
-  int written = 0, ties_seen = 0;
+  uint64_t tie_b[MAXC];
 #pragma unroll
   for (int c = 0; c < MAXC; ++c) {
-    if (c * 64 < vis) {
-      const bool valid = c * 64 + lane < vis;
-      const bool tie = valid && key[c] == T;
-      const uint64_t tie_b = __ballot(tie);
-      const bool sel = valid && (key[c] > T || (tie && ties_seen + __popcll(tie_b & lt_mask) < need_ties));
-      const uint64_t sel_b = __ballot(sel);
-      if (sel && out) out[written + __popcll(sel_b & lt_mask)] = c * 64 + lane;
-      written += __popcll(sel_b);
-      ties_seen += __popcll(tie_b);
-      if (lane == 0) bm[c] = sel_b;
-    } else if (lane == 0 && c < p.words) {
-      bm[c] = 0ULL;
-    }
+    tie_b[c] = __ballot(c * 256 + tid < vis && key[c] == T);
+    if (lane == 0) tcnt[c][wave] = __popcll(tie_b[c]);
   }
-  if (out) for (int t = k + lane; t < p.kmax_out; t += 64) out[t] = -1;
+  __syncthreads();
+  uint64_t sel_b[MAXC];
+  int ties_before = 0;                                       // ties in earlier chunks and earlier wavefronts of this chunk
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    int before = ties_before;
+    for (int w = 0; w < wave; ++w) before += tcnt[c][w];
+    const bool valid = c * 256 + tid < vis;
+    const bool tie = valid && key[c] == T;
+    const bool sel = valid && (key[c] > T || (tie && before + __popcll(tie_b[c] & lt_mask) < need_ties));
+    sel_b[c] = __ballot(sel);
+    if (lane == 0) scnt[c][wave] = __popcll(sel_b[c]);
+    ties_before += tcnt[c][0] + tcnt[c][1] + tcnt[c][2] + tcnt[c][3];
+  }
+  __syncthreads();
+  int written = 0;
+#pragma unroll
+  for (int c = 0; c < MAXC; ++c) {
+    int before = written;
+    for (int w = 0; w < wave; ++w) before += scnt[c][w];
+    if (out && ((sel_b[c] >> lane) & 1ULL)) out[before + __popcll(sel_b[c] & lt_mask)] = c * 256 + tid;
+    const int word = c * 4 + wave;
+    if (lane == 0 && word < p.words) bm[word] = sel_b[c];
+    written += scnt[c][0] + scnt[c][1] + scnt[c][2] + scnt[c][3];
+  }
+  for (int w = MAXC * 4 + tid; w < p.words; w += 256) bm[w] = 0ULL;
+  if (out) for (int t = k + tid; t < p.kmax_out; t += 256) out[t] = -1;
 }
 
 void launch_decode_select(const uint16_t* q16, int q_is_bf16, const float* kmean, const int32_t* seqlens, uint64_t* keys,
@@ -942,11 +968,11 @@ void launch_decode_select(const uint16_t* q16, int q_is_bf16, const float* kmean
   p.keys = keys; p.seqlens = seqlens; p.bitmap = bitmap; p.idx_out = idx_out; p.cnt_out = cnt_out;
   p.Hq = Hq; p.Tk = Tk; p.words = words; p.kmax_out = kmax_out; p.fixed_k = fixed_k; p.ppm = ppm;
   const long n_rows = (long)B * Hq;
-  const dim3 grid((unsigned)((n_rows + 3) / 4)), block(256);
-  if (chunks <= 8) decode_select_kernel<8><<<grid, block, 0, st>>>(p, n_rows);
-  else if (chunks <= 16) decode_select_kernel<16><<<grid, block, 0, st>>>(p, n_rows);
-  else if (chunks <= 32) decode_select_kernel<32><<<grid, block, 0, st>>>(p, n_rows);
-  else decode_select_kernel<64><<<grid, block, 0, st>>>(p, n_rows);
+  const dim3 grid((unsigned)n_rows), block(256);
+  if (chunks <= 8) decode_select_kernel<2><<<grid, block, 0, st>>>(p, n_rows);            // 256 key blocks per register slot
+  else if (chunks <= 16) decode_select_kernel<4><<<grid, block, 0, st>>>(p, n_rows);
+  else if (chunks <= 32) decode_select_kernel<8><<<grid, block, 0, st>>>(p, n_rows);
+  else decode_select_kernel<16><<<grid, block, 0, st>>>(p, n_rows);
 }
 
 // Log-sum-exp merge of the partials of one (sequence, query head): 128 threads, one per channel.
