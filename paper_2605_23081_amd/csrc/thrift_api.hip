@@ -74,11 +74,11 @@ thrift_status static_scratch(void** ptr) {
 }
 
 struct DecodeLayout {
-  size_t keys, bitmap, part_o, part_ml, total;
-  int nsplit, nparts, words;
+  size_t keys, bitmap, part_o, part_ml, order, total;
+  int nsplit, nparts, words, order_items;
 };
 
-DecodeLayout decode_layout(int B, int Hq, int Nkv, int Bk, int split_blocks) {
+DecodeLayout decode_layout(int B, int Hq, int Hkv, int Nkv, int Bk, int split_blocks) {
   DecodeLayout L;
   const int Tk = Nkv / Bk;
   L.nsplit = (Tk + split_blocks - 1) / split_blocks;
@@ -89,6 +89,8 @@ DecodeLayout decode_layout(int B, int Hq, int Nkv, int Bk, int split_blocks) {
   L.bitmap = off; off += align256((size_t)B * Hq * L.words * sizeof(unsigned long long));
   L.part_o = off; off += align256((size_t)B * Hq * L.nparts * kHeadDim * sizeof(float));
   L.part_ml = off; off += align256((size_t)B * Hq * L.nparts * 2 * sizeof(float));
+  L.order_items = decode_order_items(B, Hkv, L.nsplit);
+  L.order = off; off += align256((size_t)L.order_items * sizeof(int));
   L.total = off;
   return L;
 }
@@ -317,7 +319,7 @@ size_t thrift_attn_decode_workspace(int B, int Hq, int Hkv, int Nkv, int D, int 
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || Nkv <= 0 || D != kHeadDim || Bk != kKeyBlock || split_blocks <= 0 || Nkv % Bk != 0 ||
       Nkv / Bk > kMaxKeyBlocks || !fits_int(B, Hq, 64))
     return 0;
-  return decode_layout(B, Hq, Nkv, Bk, split_blocks).total;
+  return decode_layout(B, Hq, Hkv, Nkv, Bk, split_blocks).total;
 }
 
 static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void* k16, const void* v16,
@@ -337,7 +339,7 @@ static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void
   const int kneed = thrift_row_budget(Tk, budget, fixed_k);
   if (idx_out && (kmax_out < kneed || kmax_out <= 0)) return THRIFT_ERR_BUDGET;
   if (idx_out && !cnt_out) return THRIFT_ERR_NULL;
-  const DecodeLayout L = decode_layout(B, Hq, Nkv, Bk, split_blocks);
+  const DecodeLayout L = decode_layout(B, Hq, Hkv, Nkv, Bk, split_blocks);
   if (!workspace) return THRIFT_ERR_WORKSPACE;
   if (workspace_bytes < L.total) return THRIFT_ERR_WORKSPACE;
   if (((uintptr_t)workspace & 15) != 0) return THRIFT_ERR_WORKSPACE;
@@ -356,6 +358,7 @@ static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void
   a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.seqlens = seqlens;
   a.bitmap = bitmap; a.bitmap_words = L.words;
   a.out = out; a.part_o = (float*)(ws + L.part_o); a.part_ml = (float*)(ws + L.part_ml);
+  a.order = L.order_items > 0 ? (int*)(ws + L.order) : nullptr;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Nkv = Nkv; a.split_blocks = split_blocks; a.nsplit = L.nsplit; a.nparts = L.nparts; a.nmerge = seqlens ? L.nparts : L.nparts - 1;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
   a.dt = dt; a.out_dt = out_dt;

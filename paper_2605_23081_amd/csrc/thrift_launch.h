@@ -59,6 +59,7 @@ struct DecodeArgs {
   void* out;
   float* part_o;          // [B,Hq,nparts,D] unnormalised partial outputs
   float* part_ml;         // [B,Hq,nparts,2] running max (raw score units) and row sum of each partial
+  int* order;             // nullable [B*Hkv*nsplit]: scratch for the launch order of the split-K workgroups (heaviest first)
   int bitmap_words, B, Hq, Hkv, Nkv, split_blocks, nsplit;
   int nparts;             // partial slots per (sequence, query head): 1 per partition + 1 for a partly filled last block
   int nmerge;             // slots the merge reads (the last one only when lengths were given)
@@ -66,6 +67,8 @@ struct DecodeArgs {
   thrift_dtype dt, out_dt;
 };
 void launch_decode(const DecodeArgs& a, hipStream_t st);
+// entries of DecodeArgs::order that launch_decode wants; 0 = so many workgroups that their order does not matter (pass nullptr)
+int decode_order_items(int B, int Hkv, int nsplit);
 // decode-time selection: scores of the cached key-block means against the query heads, then per-row TopK
 // as a bitmap ([B*Hq][words], bit j%64 of word j/64) and optionally as ascending id lists
 void launch_decode_select(const uint16_t* q16, int q_is_bf16, const float* kmean, const int32_t* seqlens, uint64_t* keys,

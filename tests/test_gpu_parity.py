@@ -379,6 +379,43 @@ def test_decode_is_deterministic_and_keeps_guards(T, oracle):
     assert torch.all(buf[:256] == 777.0) and torch.all(buf[256 + n:] == 777.0)
 
 
+def test_decode_launch_order_is_a_permutation_heaviest_first(T, oracle):
+    """The split-K workgroups take their (sequence, KV head, partition) from a list the call writes into the last array
+    of its workspace: every item exactly once, by descending bytes to stage (1 per key block + 4 per block that some head
+    of the group has promoted).  A list that missed an item would leave that item's partial unwritten."""
+    wl = W.scaled(W.DECODE_131K, B=3, N=4096, Hq=8, Hkv=2)
+    split, Tk, G = 16, wl.N // wl.Bk, wl.Hq // wl.Hkv
+    q, k, v = W.make_decode(wl)
+    kg, vg = k.cuda(), v.cuda()
+    k4, ks = T.thrift_quantize_mxfp4(kg, 0); v4, vs = T.thrift_quantize_mxfp4(vg, 1)
+    kmean = T.thrift_block_means(kg, wl.Bk)
+    sl = np.array([4096, 1500, 0], np.int32)
+    nbytes = T.decode_workspace_bytes(wl.B, wl.Hq, wl.Hkv, wl.N, wl.D, wl.Bk, split)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    _, idx, cnt = T.thrift_attn_decode(q.cuda(), kg, vg, k4, ks, v4, vs, kmean, wl.Bk, 0.1, split_blocks=split,
+                                       seqlens=torch.from_numpy(sl).cuda(), workspace=ws, return_selection=True)
+    torch.cuda.synchronize()
+    nsplit = (Tk + split - 1) // split
+    items = wl.B * wl.Hkv * nsplit
+    region = (4 * items + 255) // 256 * 256
+    order = ws[nbytes - region:nbytes - region + 4 * items].cpu().numpy().view(np.int32)
+    assert np.array_equal(np.sort(order), np.arange(items))
+    idx, cnt = to_np(idx), to_np(cnt)
+    weight = np.zeros(items, np.int64)
+    for b in range(wl.B):
+        full = min(int(sl[b]), wl.N) // wl.Bk
+        for kvh in range(wl.Hkv):
+            promoted = np.zeros(Tk, bool)
+            for h in range(kvh * G, (kvh + 1) * G):
+                promoted[idx[b, h, :cnt[b, h]]] = True
+            for part in range(nsplit):
+                lo, hi = min(full, part * split), min(full, (part + 1) * split)
+                weight[(b * wl.Hkv + kvh) * nsplit + part] = (hi - lo) + 4 * int(promoted[lo:hi].sum())
+    assert 5 * split < 1023            # every weight has a bin of its own at this partition size: the order is exact
+    assert np.all(np.diff(weight[order]) <= 0)
+    assert weight.max() > weight.min()
+
+
 # ------------------------------------------------------------------ App. A ablation selectors
 @pytest.mark.parametrize("selector", [1, 2])
 def test_select_ablation_bit_exact(T, oracle, selector):
