@@ -169,19 +169,24 @@ __device__ __forceinline__ uint64_t splitmix64_output(uint64_t seed, uint64_t n)
   return z ^ (z >> 31);
 }
 
-template <int MAXC>
-__global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
-  constexpr int kStride = kD + 4;                       // padded fp32 row of a staged key mean
-  __shared__ __align__(16) float kst[64 * kStride];
-  __shared__ __align__(16) double qsd[4][kD];           // the row's query mean (shared mode: summed over the group's heads)
+template <int MAXC, int NW>
+__global__ void __launch_bounds__(NW * 64) select_topk_kernel(SelectArgs p) {
+  constexpr int kQuarter = kD / 4;                      // channels staged at a time
+  constexpr int kStride = kQuarter + 4;                 // padded fp32 quarter row of a staged key mean: conflict-free 16-byte reads
+  constexpr int kPer = 2048 / (NW * 64);                // 16-byte pieces of a staged piece per thread
+  __shared__ __align__(16) float kst[256 * kStride];
+  __shared__ __align__(16) double qsd[NW][kD];          // the row's query mean (shared mode: summed over the group's heads)
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int G = p.Hq / p.Hkv;
   const int GR = p.shared ? 1 : G;                      // selection rows per query block and KV head
   const int nheads = p.shared ? G : 1;                  // heads that receive a row's result
   const int rows_per_unit = p.Tq * GR;                  // rows of one (b, kv head), ordered (i, head in group)
-  const int wgs_per_unit = (rows_per_unit + 3) / 4;
-  const int unit = blockIdx.x / wgs_per_unit;
-  const int row0 = (blockIdx.x % wgs_per_unit) * 4;
+  const int wgs_per_unit = (rows_per_unit + NW - 1) / NW;
+  // Grid order: the last (under a causal mask: longest) rows of every (b, kv head) first, the units interleaved, so
+  // that the launch does not end on its longest workgroups and a KV head's means stay in one XCD's L2 (8 units)
+  const int units = p.B * p.Hkv;
+  const int unit = blockIdx.x % units;
+  const int row0 = (wgs_per_unit - 1 - (int)(blockIdx.x / units)) * NW;
   const int b = unit / p.Hkv, kvh = unit % p.Hkv;
   const int row = row0 + wave;
   const bool active = row < rows_per_unit;
@@ -190,7 +195,7 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
   const int cap = p.Tk;
   const int vis = active ? min(cap, visible_blocks_dev(i, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset)) : 0;
   const int k = row_budget_dev(vis, p.ppm, p.fixed_k);
-  const int last_row = min(row0 + 3, rows_per_unit - 1);
+  const int last_row = min(row0 + NW - 1, rows_per_unit - 1);
   const int vis_max = min(cap, visible_blocks_dev(last_row / GR, p.Tk, p.Bq, p.Bk, p.causal, p.q_block_offset));
   const size_t rowid = ((size_t)b * p.Hq + hq) * p.Tq + i;
 
@@ -207,41 +212,71 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
   }
   const float* kbase = p.kmean + ((size_t)b * p.Hkv + kvh) * p.Tk * kD;
 
+  // Scoring is bound by LDS bandwidth (one pipe per CU): every step of a key's chain reads the key mean (per lane) and
+  // the query mean (the same address in all lanes, but a full read all the same).  So a lane walks the chains of four
+  // keys (one of each of four 64-key chunks) side by side and reads the query mean once for the four: half the LDS reads
+  // per score.  256 key means are staged a quarter of their channels at a time (36 KiB), fetched into registers while
+  // the quarter before is being scored and handed to LDS between two barriers; the workgroup's rows share every
+  // staged piece (16 rows: a quarter of the L2 reads of 4).
+  float4 nx[kPer];
+  auto fetch = [&](int t) {                              // piece t: keys 256*(t/4) .. +255, channels 32*(t%4) .. +31
+    const int key0 = (t >> 2) * 256, ch0 = (t & 3) * kQuarter;
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int chunk = tid + NW * 64 * u;               // 2048 pieces of 4 floats
+      const int r = chunk >> 3, col = (chunk & 7) * 4;
+      nx[u] = key0 + r < p.Tk ? *reinterpret_cast<const float4*>(kbase + (size_t)(key0 + r) * kD + ch0 + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+
   uint64_t key[MAXC];
 #pragma unroll
-  for (int c = 0; c < MAXC; ++c) {
-    key[c] = 0;
-    if (p.selector != 0) {
-      // Ablation selectors (App. A): the same k-th-largest search over other keys.  Random: output
-      // number n+1 of the SplitMix64 stream of `seed`, n = rowid * 2^32 + j; diagonal: the block id.
+  for (int c = 0; c < MAXC; ++c) key[c] = 0;
+  if (p.selector != 0) {
+    // Ablation selectors (App. A): the same k-th-largest search over other keys.  Random: output
+    // number n+1 of the SplitMix64 stream of `seed`, n = rowid * 2^32 + j; diagonal: the block id.
+#pragma unroll
+    for (int c = 0; c < MAXC; ++c) {
       const int j = c * 64 + lane;
       if (j < vis) key[c] = p.selector == 1 ? splitmix64_output(p.seed, (((uint64_t)rowid << 32) | (uint64_t)j) + 1ULL) : (uint64_t)j + 1ULL;
-    } else if (c * 64 < vis_max) {                       // uniform over the workgroup
-      __syncthreads();
-      // stage 64 key means (rows beyond Tk are not read)
+    }
+  } else {
+    if (vis_max > 0) fetch(0);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int chunk = tid + 256 * u;                 // 2048 chunks of 4 floats
-        const int r = chunk >> 5, col = (chunk & 31) * 4;
-        if (c * 64 + r < p.Tk)
-          *reinterpret_cast<float4*>(&kst[r * kStride + col]) =
-              *reinterpret_cast<const float4*>(kbase + (size_t)(c * 64 + r) * kD + col);
-      }
-      __syncthreads();
-      const int j = c * 64 + lane;
-      if (j < vis) {
-        double s = 0.0;
-#pragma unroll 8
-        for (int d = 0; d < kD; d += 4) {
-          float4 kv = *reinterpret_cast<const float4*>(&kst[lane * kStride + d]);
-          const double2 qa = *reinterpret_cast<const double2*>(&qsd[wave][d]);
-          const double2 qb = *reinterpret_cast<const double2*>(&qsd[wave][d + 2]);
-          s = fma(qa.x, (double)kv.x, s);
-          s = fma(qa.y, (double)kv.y, s);
-          s = fma(qb.x, (double)kv.z, s);
-          s = fma(qb.y, (double)kv.w, s);
+    for (int cg = 0; cg < MAXC / 4; ++cg) {
+      if (cg * 256 < vis_max) {                          // uniform over the workgroup
+        double sc[4] = {0.0, 0.0, 0.0, 0.0};             // the chains of keys 256*cg + 64*cc + lane
+#pragma unroll 1
+        for (int h = 0; h < 4; ++h) {
+          __syncthreads();                               // the piece before has been scored by every row
+#pragma unroll
+          for (int u = 0; u < kPer; ++u) {
+            const int chunk = tid + NW * 64 * u;
+            const int r = chunk >> 3, col = (chunk & 7) * 4;
+            *reinterpret_cast<float4*>(&kst[r * kStride + col]) = nx[u];      // rows beyond Tk: zeros, never used
+          }
+          const int t1 = cg * 4 + h + 1;
+          if (t1 < MAXC && (t1 >> 2) * 256 < vis_max) fetch(t1);              // uniform over the workgroup
+          __syncthreads();
+          if (cg * 256 < vis) {                          // uniform over the wavefront; keys past `vis` are scored and dropped
+#pragma unroll
+            for (int d = 0; d < kQuarter; d += 4) {
+              const double2 qa = *reinterpret_cast<const double2*>(&qsd[wave][h * kQuarter + d]);
+              const double2 qb = *reinterpret_cast<const double2*>(&qsd[wave][h * kQuarter + d + 2]);
+#pragma unroll
+              for (int cc = 0; cc < 4; ++cc) {
+                const float4 kv = *reinterpret_cast<const float4*>(&kst[(cc * 64 + lane) * kStride + d]);
+                sc[cc] = fma(qa.x, (double)kv.x, sc[cc]);
+                sc[cc] = fma(qa.y, (double)kv.y, sc[cc]);
+                sc[cc] = fma(qb.x, (double)kv.z, sc[cc]);
+                sc[cc] = fma(qb.y, (double)kv.w, sc[cc]);
+              }
+            }
+          }
         }
-        key[c] = order_key(s);
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+          if ((cg * 4 + cc) * 64 + lane < vis) key[cg * 4 + cc] = order_key(sc[cc]);
       }
     }
   }
@@ -293,13 +328,21 @@ __global__ void __launch_bounds__(256) select_topk_kernel(SelectArgs p) {
 
 void launch_select_topk(const SelectArgs& p, hipStream_t st) {
   const int G = p.shared ? 1 : p.Hq / p.Hkv;
-  const int wgs_per_unit = (p.Tq * G + 3) / 4;
-  const unsigned grid = (unsigned)((long)p.B * p.Hkv * wgs_per_unit);
   const int chunks = (p.Tk + 63) / 64;
-  if (chunks <= 8) select_topk_kernel<8><<<dim3(grid), dim3(256), 0, st>>>(p);
-  else if (chunks <= 16) select_topk_kernel<16><<<dim3(grid), dim3(256), 0, st>>>(p);
-  else if (chunks <= 32) select_topk_kernel<32><<<dim3(grid), dim3(256), 0, st>>>(p);
-  else select_topk_kernel<64><<<dim3(grid), dim3(256), 0, st>>>(p);
+  // 16 rows per workgroup where a (b, kv head) has that many and the keys of a row fit 128 registers per lane
+  const int nw = (p.Tq * G >= 16 && chunks <= 32) ? 16 : 4;
+  const int wgs_per_unit = (p.Tq * G + nw - 1) / nw;
+  const dim3 grid((unsigned)((long)p.B * p.Hkv * wgs_per_unit));
+  if (nw == 16) {
+    if (chunks <= 8) select_topk_kernel<8, 16><<<grid, dim3(1024), 0, st>>>(p);
+    else if (chunks <= 16) select_topk_kernel<16, 16><<<grid, dim3(1024), 0, st>>>(p);
+    else select_topk_kernel<32, 16><<<grid, dim3(1024), 0, st>>>(p);
+  } else {
+    if (chunks <= 8) select_topk_kernel<8, 4><<<grid, dim3(256), 0, st>>>(p);
+    else if (chunks <= 16) select_topk_kernel<16, 4><<<grid, dim3(256), 0, st>>>(p);
+    else if (chunks <= 32) select_topk_kernel<32, 4><<<grid, dim3(256), 0, st>>>(p);
+    else select_topk_kernel<64, 4><<<grid, dim3(256), 0, st>>>(p);
+  }
 }
 
 }  // namespace thrift

@@ -348,6 +348,27 @@ def test_select_single_row_and_offset(T, oracle):
         assert np.array_equal(to_np(idx_g)[..., :idx_r.shape[-1]], idx_r) and np.array_equal(to_np(cnt_g), cnt_r)
 
 
+@pytest.mark.parametrize("Hq,Hkv,Tq,Tk,causal,off", [
+    (4, 2, 9, 300, False, 0),          # 18 rows per KV head: a full workgroup of 16 rows and a ragged one; 5 chunks (a part group of 4)
+    (2, 1, 20, 2048, True, 2008 * 64), # 40 rows, 32 chunks, a causal frontier that differs from row to row
+    (1, 1, 5, 2100, False, 0),         # more than 2048 key blocks: the 4-row kernel with 64 key registers
+    (8, 2, 3, 70, False, 0),           # fewer than 16 rows per KV head: the 4-row kernel, ragged
+    (2, 2, 33, 257, True, 225 * 64)])  # one key past a staged group of 256
+def test_select_topk_kernel_shapes(T, oracle, Hq, Hkv, Tq, Tk, causal, off):
+    """Every instantiation of the selection kernel (rows per workgroup, key registers per lane) against the oracle,
+    bit for bit, per-head and group-shared."""
+    _say(f"select shapes Hq={Hq} Hkv={Hkv} Tq={Tq} Tk={Tk} causal={causal} off={off}")
+    g = torch.Generator().manual_seed(1000 * Tq + Tk)
+    qm = torch.randn(1, Hq, Tq, 128, generator=g)
+    km = torch.randn(1, Hkv, Tk, 128, generator=g)
+    for shared in (False, True):
+        idx_r, cnt_r = oracle.select_topk(qm.numpy(), km.numpy(), 64, 64, causal, 0.07, q_block_offset=off, group_shared=shared)
+        idx_g, cnt_g = T.thrift_select_topk(qm.cuda(), km.cuda(), 64, 64, causal, 0.07, q_block_offset=off, group_shared=shared)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(cnt_g), cnt_r)
+        assert np.array_equal(to_np(idx_g)[..., :idx_r.shape[-1]], idx_r) and np.all(to_np(idx_g)[..., idx_r.shape[-1]:] == -1)
+
+
 # head groups of every kernel shape: one head per wavefront (G <= 4, some wavefronts without a head at G = 3), two (G <= 8,
 # some with one at G = 5, 6, 7), more (the transposed tiles: G = 12, 32)
 @pytest.mark.parametrize("Hq,Hkv,B,N,split", [(32, 1, 1, 1024, 16), (4, 4, 1, 640, 64), (16, 2, 2, 1536, 4), (12, 2, 2, 1024, 8),
