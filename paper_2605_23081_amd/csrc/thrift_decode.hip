@@ -770,7 +770,8 @@ __global__ void __launch_bounds__(256) decode_scores_kernel(const uint16_t* __re
   __shared__ __align__(16) float kst[64 * kStride];
   __shared__ __align__(16) float qst[32 * kD];
   __shared__ __align__(16) double qsum[kD];            // shared mode: the group's query vectors added up (fp64, head order)
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform: the loop over the heads stays scalar
   const int G = Hq / Hkv, chunks = (Tk + 63) / 64;
   const int groups = (chunks + kScoreChunksPerWg - 1) / kScoreChunksPerWg;
   const int chunk0 = (blockIdx.x % groups) * kScoreChunksPerWg, unit = blockIdx.x / groups;
@@ -1005,6 +1006,7 @@ __global__ void __launch_bounds__(1024) decode_order_kernel(DecodeArgs a, int n_
       const unsigned long long* bm = a.bitmap + ((size_t)b * a.Hq + (size_t)kvh * G) * a.bitmap_words;
       for (int w = j_begin >> 6; w <= (j_end - 1) >> 6; ++w) {
         unsigned long long any = 0ULL;
+#pragma unroll 4
         for (int h = 0; h < G; ++h) any |= bm[(size_t)h * a.bitmap_words + w];
         const int lo = max(j_begin - 64 * w, 0), hi = min(j_end - 64 * w, 64);          // bits lo .. hi-1 of this word
         any >>= lo;
