@@ -47,9 +47,9 @@ ALU_PEAK = 1024 * 64 * 2.4e9 / ALU_CYCLES * (4 * 128) / 1e12   # TFLOP/s
 # x1.0); the summary of those runs is profiles/prefill_decode_hbm_traffic_pmc.txt.  Counters cannot be read from
 # inside this process, so the figures belong to the kernel sources they were measured on: `source_sha` is the hash of
 # the two kernels' sources (KERNEL_SOURCES below) at that time, and a build from other sources reports no traffic.
-MEASURED_TRAFFIC_GB = {"source_sha": "c2373a3f0aa9",
-                       "prefill_131k_f0.05_order1": {"fetched": 22.53, "written": 1.107},
-                       "prefill_131k_f0.05_order0": {"fetched": 36.69, "written": 1.074},
+MEASURED_TRAFFIC_GB = {"source_sha": "1a2827b0c1c8",
+                       "prefill_131k_f0.05_order1": {"fetched": 22.72, "written": 1.107},
+                       "prefill_131k_f0.05_order0": {"fetched": 36.67, "written": 1.074},
                        "decode_16x131k_f0.05": {"fetched": 3.834, "written": 0.0022}}
 PAPER_CONTEXT = {"gap_recovery_pct_at_5_10_25": [89.1, 91.8, 92.4], "e2e_speedup_at_131k": 2.0,
                  "hardware": "RTX PRO 6000 Blackwell, NVFP4+FP16 (context only, not a target)"}

@@ -390,30 +390,34 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
   int early_prev = 0;                                   // the step before fetched 16-bit tiles ahead of its 4-bit block
 
   // Staging part of step t: waits for what the step reads, then issues what later steps will read.
-  auto stage = [&](int t) {
+  // `plain` (workgroup-uniform): the caller has seen that none of the decisions below can come out true (row layout:
+  // the group has promoted none of the blocks t .. t+2, no 16-bit tile was fetched ahead, block t+kDecAhead exists).
+  auto stage = [&](int t, bool plain) {
     const int j = j_begin + t;
     // in flight and not yet needed: the 4-bit blocks t+2 .. t+kDecRing-2 (where they exist); after 16-bit tiles fetched
     // ahead in the step before, only that step's 4-bit block t+kDecRing-2
-    if (!early_prev && t + kDecRing - 2 < n) {
+    if (plain || (!early_prev && t + kDecRing - 2 < n)) {
       vm_wait<kDmaPer4 * kDecFlight>();                 // the steady state of the walk: one scalar test
     } else {
       const int newer = early_prev ? (t + kDecRing - 2 < n ? kDmaPer4 : 0) : kDmaPer4 * max(0, min(n - 2 - t, kDecFlight));
       vm_wait_dyn(newer);
     }
     lds_barrier();                                      // block t+1 (and block t's V tile) complete in LDS; step t-1 is behind everyone
-    const int Kprev = kKShift ? Pb : Pa, Kcur = kKShift ? Pc : Pb, Knext = kKShift ? Pd : Pc;   // promoted flags of blocks t + kKShift - 1, +0, +1
-    const int lateK = Kcur & Kprev, lateV = Pb & Pa;    // the buffer was busy during the step before
-    if (lateK) issue16k(j + kKShift);
-    if (lateV) issue16v(j);
-    if (lateK | lateV) {
-      vm_wait<0>();
-      lds_barrier();
+    if (!plain) {
+      const int Kprev = kKShift ? Pb : Pa, Kcur = kKShift ? Pc : Pb, Knext = kKShift ? Pd : Pc;   // promoted flags of blocks t + kKShift - 1, +0, +1
+      const int lateK = Kcur & Kprev, lateV = Pb & Pa;  // the buffer was busy during the step before
+      if (lateK) issue16k(j + kKShift);
+      if (lateV) issue16v(j);
+      if (lateK | lateV) {
+        vm_wait<0>();
+        lds_barrier();
+      }
+      const int earlyK = Knext & (Kcur ^ 1), earlyV = Pc & (Pb ^ 1);
+      if (earlyK) issue16k(j + kKShift + 1);
+      if (earlyV) issue16v(j + 1);
+      early_prev = earlyK | earlyV;                     // a plain step leaves it at 0
     }
-    const int earlyK = Knext & (Kcur ^ 1), earlyV = Pc & (Pb ^ 1);
-    if (earlyK) issue16k(j + kKShift + 1);
-    if (earlyV) issue16v(j + 1);
-    if (t + kDecAhead < n) issue4(j + kDecAhead, slot_a);
-    early_prev = earlyK | earlyV;
+    if (plain || t + kDecAhead < n) issue4(j + kDecAhead, slot_a);
   };
   if constexpr (!MULTI) {
     // ---- up to NH heads per wavefront in the row layout; the (scalar) selection bit of a head decides its path ----
@@ -442,14 +446,15 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
     float sv[NH];                                       // raw score of key `lane` of block t on entry to step t, per head
 #pragma unroll
     for (int u = 0; u < NH; ++u) sv[u] = 0.f;
-    stage(-1);                                          // step -1: only the scores of block 0
+    stage(-1, false);                                   // step -1: only the scores of block 0
     if (my_heads > 0 && n > 0) scores(slot_c, Mc, sv);
     slot_a = slot_b; slot_b = slot_c; slot_c = 1;
     // One step; WITH_NEXT (a compile-time flag): block t+1 exists.
     auto step = [&](int t, auto with_next) {
       Pa = Pb; Pb = Pc; Pc = Pd; Mb = Mc; Mc = Md;      // shift the flags; block t+2's are new
       Pd = flags(t + 2, Md);
-      stage(t);
+      // most steps have no promoted block in sight: they skip the buffer decisions (3.6 % of an all-4-bit pass)
+      stage(t, (Pb | Pc | Pd | early_prev) == 0 && t + kDecAhead < n);
       if (my_heads > 0) {
         const unsigned char* slot_v = lds + slot_b * kLdsBytes4;     // block t
         constexpr bool kNext = decltype(with_next)::value;
@@ -538,12 +543,12 @@ __global__ void __launch_bounds__(256, 2) decode_partial_kernel(DecodeArgs a) {
       const unsigned long long v = P ? (__builtin_amdgcn_ballot_w64(mine) & my_mask) : 0ULL;
       return (v != 0ULL ? 1 : 0) | (v == my_mask ? 2 : 0);
     };
-    stage(-1);                                          // step -1: staging only
+    stage(-1, false);                                   // step -1: staging only
     slot_a = slot_b; slot_b = slot_c; slot_c = 1;
     for (int t = 0; t < n; ++t) {
       Pa = Pb; Pb = Pc; Pc = Pd; Mb = Mc; Mc = Md;
       Pd = flags(t + 2, Md);
-      stage(t);
+      stage(t, false);
       if (my_heads > 0) {
         // the whole of block t in this step: scores, softmax, P.V (nothing is carried over to the next step)
         const unsigned char* slot_v = lds + slot_b * kLdsBytes4;
@@ -980,10 +985,10 @@ void launch_decode_select(const uint16_t* q16, int q_is_bf16, const float* kmean
 // Launch order of the split-K workgroups: heaviest first.  A workgroup's duration follows the bytes it stages (8.5 KiB
 // per key block, 32 KiB more for a block that some head of the group has promoted), the selections differ between
 // partitions and sequences differ in length, and a grid of a few workgroups per CU slot has no later rounds to even
-// that out: with the items in natural order the pass ends when the unluckiest slot does (measured: 11 % above the mean
-// for two rounds of workgroups whose bytes scatter by 5 %).  Handing the heaviest items out first pairs them with the
-// lightest.  One workgroup: weight of every item from the selection bitmaps, counting sort into kOrderBins bins,
-// descending; items of one bin come out in no particular order (the results do not depend on the order at all).
+// that out: in natural order the pass ends when the unluckiest slot does.  Handing the heaviest items out first pairs
+// them with the lightest (measured on two rounds of workgroups whose bytes scatter by +-17 %: 1 to 3 % of the pass).
+// One workgroup: weight of every item from the selection bitmaps, counting sort into kOrderBins bins, descending; items
+// of one bin come out in no particular order (the results do not depend on the order at all).
 constexpr int kOrderMaxItems = 8192;     // beyond this many items the grid has rounds enough: natural order
 constexpr int kOrderBins = 1024;       // = the threads of the ordering workgroup
 
