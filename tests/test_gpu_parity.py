@@ -374,7 +374,10 @@ def test_select_topk_kernel_shapes(T, oracle, Hq, Hkv, Tq, Tk, causal, off):
 @pytest.mark.parametrize("Hq,Hkv,B,N,split", [(32, 1, 1, 1024, 16), (4, 4, 1, 640, 64), (16, 2, 2, 1536, 4), (12, 2, 2, 1024, 8),
                                               (5, 1, 1, 1024, 16), (3, 1, 2, 1024, 3), (24, 2, 1, 1024, 8), (7, 1, 2, 1536, 5),
                                               # partitions longer than the kernel's window of cached selection words (8 x 64 blocks)
-                                              (8, 2, 1, 69632, 1088), (16, 1, 1, 40960, 640), (24, 1, 1, 36864, 576)])
+                                              (8, 2, 1, 69632, 1088), (16, 1, 1, 40960, 640), (24, 1, 1, 36864, 576),
+                                              # launch order: 2048 items (two per thread of the ordering workgroup); 16384 items
+                                              # (more than it sorts: natural order)
+                                              (8, 2, 2, 65536, 2), (8, 8, 4, 32768, 1)])
 def test_decode_edge_shapes(T, oracle, Hq, Hkv, B, N, split):
     wl = W.scaled(W.DECODE_131K, B=B, N=N, Hq=Hq, Hkv=Hkv)
     _say(f"decode edge B={B} N={N} Hq={Hq} Hkv={Hkv} split={split}")
