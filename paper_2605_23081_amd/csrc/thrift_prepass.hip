@@ -179,7 +179,7 @@ __global__ void __launch_bounds__(NW * 64) select_topk_kernel(SelectArgs p) {
   const int tid = threadIdx.x, lane = tid & 63;
   // wavefront-uniform, and known to the compiler as such: the row, its visible blocks and budget, the threshold and the
   // counts of the search below then live in scalar registers (left as a per-lane value, every count of the search went
-  // through vector registers and a branch per chunk: 3600 vector instructions per row instead of 600)
+  // through vector registers and a branch per chunk: 3600 vector instructions per row instead of 1500)
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int G = p.Hq / p.Hkv;
   const int GR = p.shared ? 1 : G;                      // selection rows per query block and KV head
@@ -216,10 +216,10 @@ __global__ void __launch_bounds__(NW * 64) select_topk_kernel(SelectArgs p) {
   }
   const float* kbase = p.kmean + ((size_t)b * p.Hkv + kvh) * p.Tk * kD;
 
-  // Scoring is bound by LDS bandwidth (one pipe per CU): every step of a key's chain reads the key mean (per lane) and
-  // the query mean (the same address in all lanes, but a full read all the same).  So a lane walks the chains of four
-  // keys (one of each of four 64-key chunks) side by side and reads the query mean once for the four: half the LDS reads
-  // per score.  256 key means are staged a quarter of their channels at a time (36 KiB), fetched into registers while
+  // Every step of a key's chain reads the key mean (per lane) and the query mean (the same address in all lanes, but a
+  // full read all the same); with one chain per lane those reads took most of the CU's one LDS pipe.  So a lane walks the
+  // chains of four keys (one of each of four 64-key chunks) side by side and reads the query mean once for the four:
+  // half the LDS reads per score, and four independent chains of fused multiply-adds.  256 key means are staged a quarter of their channels at a time (36 KiB), fetched into registers while
   // the quarter before is being scored and handed to LDS between two barriers; the workgroup's rows share every
   // staged piece (16 rows: a quarter of the L2 reads of 4).
   float4 nx[kPer];
