@@ -358,7 +358,8 @@ static thrift_status attn_decode_impl(const void* q, thrift_dtype dt, const void
   a.k4 = k4; a.ks = ks; a.v4 = v4; a.vs = vs; a.seqlens = seqlens;
   a.bitmap = bitmap; a.bitmap_words = L.words;
   a.out = out; a.part_o = (float*)(ws + L.part_o); a.part_ml = (float*)(ws + L.part_ml);
-  a.order = L.order_items > 0 ? (int*)(ws + L.order) : nullptr;
+  // heaviest-first launch order of the split-K workgroups; without promoted blocks and without lengths all items weigh the same
+  a.order = (L.order_items > 0 && (kneed > 0 || seqlens != nullptr)) ? (int*)(ws + L.order) : nullptr;
   a.B = B; a.Hq = Hq; a.Hkv = Hkv; a.Nkv = Nkv; a.split_blocks = split_blocks; a.nsplit = L.nsplit; a.nparts = L.nparts; a.nmerge = seqlens ? L.nparts : L.nparts - 1;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)D);
   a.dt = dt; a.out_dt = out_dt;
